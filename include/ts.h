@@ -1,0 +1,179 @@
+/*
+ * ts.h - C ABI of the MI355X sparse-convolution library (libts.so).
+ *
+ * One layer of a sparse CNN on a voxelized point cloud, as the paper states it
+ * (Sec. 2): inputs are integer coordinates P_in with features X_in, weights
+ * W[K^3][C_in][C_out], kernel size K and stride s; "mapping" takes coordinates
+ * only and yields the output coordinates P_out and the kernel maps
+ * M = {(j, k, n)} with p_j = s*q_k + delta_n (Sec. 2.1, Alg. 1 and Alg. 3);
+ * the compute takes X_in, W and M and yields
+ *     x_out[k] = sum_n sum_j 1[p_j = s*q_k + delta_n] x_in[j] * W_n     (Eq. 1)
+ * by gather, per-offset matmul and scatter-accumulate (Sec. 2.2, Alg. 2).
+ *
+ * Conventions (fixed by this library where the paper is silent):
+ *   coords   int32 [N][4], columns (batch, x, y, z); rows are distinct.
+ *   offsets  Delta^3(K) = {-r..K-1-r}^3, r = floor((K-1)/2); weight index
+ *            n = ((dx+r)*K + (dy+r))*K + (dz+r)  (x slowest).  K=3: {-1,0,1}^3,
+ *            K=2: {0,1}^3.
+ *   stride 1: P_out = P_in, same row order (output k is input k).
+ *   stride>1: P_out = distinct candidates (p - delta)/s with s | (p - delta),
+ *            in ascending (batch, x, y, z) order; no boundary clipping.
+ *   transposed: coords are the FINE coordinates (the outputs of the transposed
+ *            layer).  The map is the forward (K, s) map fine -> coarse with the
+ *            roles swapped: inputs are the coarse points in ascending order,
+ *            x_out[j] = sum over (k, n) with p_j = s*q_k + delta_n of x_in[k]*W_n.
+ *
+ * Memory: every pointer documented "device" is HIP device memory on the
+ * current device; "host" is ordinary host memory.  The caller owns all
+ * tensors passed in; they must stay alive until the stream has passed the
+ * call.  The library owns everything behind ts_kmap* until ts_free().
+ *
+ * Errors: every int-returning function returns TS_OK (0) or a negative
+ * ts_status; ts_last_error() gives thread-local text for the last failure.
+ * No exception crosses this boundary.  There is no CPU fallback: without a
+ * usable HIP device every call fails with TS_ERR_HIP.
+ *
+ * Threading/streams: work is enqueued on the stream set by ts_set_stream()
+ * (default: the null stream).  Calls on one ts_kmap from several host threads
+ * at once are not supported.
+ */
+#ifndef TS_H
+#define TS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ts_status {
+    TS_OK = 0,
+    TS_ERR_INVALID_ARG = -1,     /* null pointer, negative size, unsupported K / stride            */
+    TS_ERR_SHAPE = -2,           /* rows / cols / dtype do not match the kernel map or each other   */
+    TS_ERR_COORD_RANGE = -3,     /* a coordinate is outside the packable range below                */
+    TS_ERR_DUPLICATE_COORD = -4, /* two input rows hold the same (batch, x, y, z)                   */
+    TS_ERR_OOM = -5,             /* device or host allocation failed                                */
+    TS_ERR_HIP = -6,             /* a HIP runtime call failed (text in ts_last_error)               */
+    TS_ERR_UNSUPPORTED = -7      /* valid request outside what the kernels cover                    */
+} ts_status;
+
+/* Element types of feature / weight / output tensors. */
+enum { TS_F32 = 0, TS_F16 = 1 };
+
+/* Packable coordinate range: batch in [0, TS_BATCH_MAX], x,y,z in [TS_COORD_MIN, TS_COORD_MAX]. */
+#define TS_BATCH_MAX 8190
+#define TS_COORD_MIN (-65528)
+#define TS_COORD_MAX 65527
+
+/* How ts_sparse_conv_ex computes Eq. 1. */
+enum {
+    TS_DATAFLOW_AUTO = 0,     /* library's choice (the fused kernel where it applies)                     */
+    TS_DATAFLOW_EXPLICIT = 1, /* Alg. 2 as three launches: gather -> grouped matmul -> scatter-accumulate */
+    TS_DATAFLOW_FUSED = 2     /* one output-stationary kernel: gather into the MFMA operand, accumulate
+                                 over offsets in registers, write each output row once                    */
+};
+
+/* Dense row-major matrix: rows x cols elements of dtype, device memory. */
+typedef struct ts_tensor {
+    void   *data;   /* device */
+    int64_t rows;
+    int32_t cols;
+    int32_t dtype;  /* TS_F32 or TS_F16 */
+} ts_tensor;
+
+/* Opaque, immutable, device-resident kernel map (Sec. 2.1: the maps M plus P_out). */
+typedef struct ts_kmap ts_kmap;
+
+/* ---- mapping (Sec. 2.1; Alg. 1, Alg. 3) ---------------------------------------------------- */
+
+/*
+ * Build the kernel map of a (kernel_size, stride) convolution over N input points.
+ *   coords       device, int32 [N][4] (batch, x, y, z); not modified; N >= 0.
+ *   kernel_size  1, 2 or 3 (stride 1 requires odd kernel_size); stride 1 or 2.
+ *   transposed   0 or 1 (1 requires stride > 1), see the header comment.
+ *   out_kmap     receives the new map; *out_kmap = NULL on error.
+ * Internally: pack coordinates to 64-bit keys, (stride>1: candidate keys, sort, unique),
+ * insert inputs into an open-addressing hash table, probe s*q_k + delta_n for every
+ * output and offset, then compact into per-offset pair lists.  Synchronises the stream
+ * (it must learn N_out and the map sizes to allocate).  The map may be reused by any
+ * number of ts_sparse_conv calls.
+ */
+int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
+                  ts_kmap **out_kmap);
+
+/* Release a map and everything it owns.  NULL is allowed. */
+void ts_free(ts_kmap *kmap);
+
+int64_t ts_kmap_num_in(const ts_kmap *kmap);        /* rows of X_in the map expects               */
+int64_t ts_kmap_num_out(const ts_kmap *kmap);       /* rows of X_out it produces                  */
+int64_t ts_kmap_num_pairs(const ts_kmap *kmap);     /* |M| = sum of the per-offset sizes          */
+int     ts_kmap_kernel_volume(const ts_kmap *kmap); /* K^3                                        */
+
+/* Output coordinates P_out: dst is device int32 [num_out][4].  (For a transposed map: the fine coords.) */
+int ts_kmap_out_coords(const ts_kmap *kmap, int32_t *dst);
+/* Input coordinates in the row order X_in must have: dst is device int32 [num_in][4]. */
+int ts_kmap_in_coords(const ts_kmap *kmap, int32_t *dst);
+/* Per-offset map sizes |M[W_n]|: dst is HOST int64 [K^3]. */
+int ts_kmap_sizes(const ts_kmap *kmap, int64_t *dst);
+/*
+ * The maps as index pairs, offset-major: entries [off_n, off_n + size_n) belong to offset n,
+ * off_n = sum of sizes before n; within an offset, pairs are ordered by output index.
+ * in_idx/out_idx are device int32 [num_pairs]; either may be NULL.
+ */
+int ts_kmap_pairs(const ts_kmap *kmap, int32_t *in_idx, int32_t *out_idx);
+
+/* ---- compute (Sec. 2.2, Alg. 2; Eq. 1) ------------------------------------------------------ */
+
+/*
+ * out = sparse convolution of feats with weights over kmap (Eq. 1).
+ *   feats    [num_in][C_in], weights [K^3 * C_in][C_out] (i.e. [K^3][C_in][C_out] flattened),
+ *   out      [num_out][C_out], caller-allocated, fully overwritten.
+ * All three share one dtype.  TS_F16 multiplies fp16 operands and accumulates in fp32 over
+ * C_in and over all offsets, rounding once when the row is stored; TS_F32 uses fp32 throughout.
+ * C_in and C_out must be multiples of 16 for the MFMA kernels (TS_F16: C_in of 4 or 8 is also
+ * accepted and zero-extended internally); at most 256.
+ * Never synchronises.  Uses library-owned scratch memory that is grown on demand.
+ */
+int ts_sparse_conv(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
+                   ts_tensor *out);
+
+/* Same, with the dataflow chosen by the caller (TS_DATAFLOW_*). */
+int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
+                      ts_tensor *out, int dataflow);
+
+/*
+ * The three stages of Alg. 2 on their own (what TS_DATAFLOW_EXPLICIT runs), for per-stage
+ * tests and timing.  The buffers F and G are offset-major like ts_kmap_pairs.
+ *
+ * ts_gather:        F[off_n + m] = feats[in_n[m]] for every offset in one launch.
+ *                   F is [num_pairs][C_in], dtype of feats.  For an odd-K stride-1 map the rows
+ *                   of the centre offset are left untouched: its map is the identity and
+ *                   ts_grouped_matmul reads feats directly (Sec. 4.2.1).
+ * ts_grouped_matmul: G[off_n + m] = F[off_n + m] * W_n for every offset in one launch, tiles
+ *                   scheduled over (offset, row block) with no zero padding.  feats is needed
+ *                   for the centre offset only and may be NULL when the map has none.
+ *                   G is [num_pairs][C_out] TS_F32 (partial sums stay fp32).
+ * ts_scatter_reduce: out[k] = sum of G rows whose pair has output k (output-stationary: each
+ *                   row is reduced in registers in offset order and written once).
+ */
+int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F);
+int ts_grouped_matmul(const ts_tensor *F, const ts_tensor *feats, const ts_tensor *weights,
+                      const ts_kmap *kmap, ts_tensor *G);
+int ts_scatter_reduce(const ts_tensor *G, const ts_kmap *kmap, ts_tensor *out);
+
+/* ---- runtime ---------------------------------------------------------------------------------- */
+
+/* Stream (hipStream_t) all later calls enqueue on; NULL = the null stream. */
+int ts_set_stream(void *hip_stream);
+/* Free the library's cached scratch and pooled device memory (synchronises the device). */
+int ts_release_cache(void);
+/* Text of the last error on this thread ("" if none). Valid until the next failing call. */
+const char *ts_last_error(void);
+/* Library version string. */
+const char *ts_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TS_H */

@@ -1,0 +1,270 @@
+"""ctypes binding of libts.so: argument marshalling only, same names as ``include/ts.h``.
+
+PyTorch supplies device memory (tensors) and the stream; every step of the layer runs in
+the library's HIP kernels.  There is no fallback: if ``libts.so`` has not been built or
+cannot be loaded, the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+TS_F32, TS_F16 = 0, 1
+TS_DATAFLOW_AUTO, TS_DATAFLOW_EXPLICIT, TS_DATAFLOW_FUSED = 0, 1, 2
+
+TS_OK = 0
+TS_ERR_INVALID_ARG, TS_ERR_SHAPE, TS_ERR_COORD_RANGE, TS_ERR_DUPLICATE_COORD = -1, -2, -3, -4
+TS_ERR_OOM, TS_ERR_HIP, TS_ERR_UNSUPPORTED = -5, -6, -7
+
+TS_BATCH_MAX, TS_COORD_MIN, TS_COORD_MAX = 8190, -65528, 65527
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libts.so")
+_lib = None
+
+EXPORTS = [
+    "ts_build_kmap", "ts_free", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
+    "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
+    "ts_sparse_conv", "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
+    "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version",
+]
+
+
+class TsError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libts error {code}: {message}")
+        self.code = code
+
+
+class ts_tensor(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int32),
+                ("dtype", ctypes.c_int32)]
+
+
+def load_library(path: str | None = None):
+    """Load libts.so and declare the signatures of ``include/ts.h``."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or _LIB_PATH
+    if not os.path.exists(p):
+        raise RuntimeError(f"{p} is missing: build it with `python -m paper_2204_10319_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = ctypes.CDLL(p)
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    tp = ctypes.POINTER(ts_tensor)
+    lib.ts_build_kmap.argtypes = [vp, i64, ci, ci, ci, ctypes.POINTER(vp)]
+    lib.ts_build_kmap.restype = ci
+    lib.ts_free.argtypes = [vp]
+    lib.ts_free.restype = None
+    for name in ("ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs"):
+        getattr(lib, name).argtypes = [vp]
+        getattr(lib, name).restype = i64
+    lib.ts_kmap_kernel_volume.argtypes = [vp]
+    lib.ts_kmap_kernel_volume.restype = ci
+    lib.ts_kmap_out_coords.argtypes = [vp, vp]
+    lib.ts_kmap_in_coords.argtypes = [vp, vp]
+    lib.ts_kmap_sizes.argtypes = [vp, ctypes.POINTER(i64)]
+    lib.ts_kmap_pairs.argtypes = [vp, vp, vp]
+    lib.ts_sparse_conv.argtypes = [tp, tp, vp, tp]
+    lib.ts_sparse_conv_ex.argtypes = [tp, tp, vp, tp, ci]
+    lib.ts_gather.argtypes = [tp, vp, tp]
+    lib.ts_grouped_matmul.argtypes = [tp, tp, tp, vp, tp]
+    lib.ts_scatter_reduce.argtypes = [tp, vp, tp]
+    lib.ts_set_stream.argtypes = [vp]
+    lib.ts_release_cache.argtypes = []
+    for name in ("ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs", "ts_sparse_conv",
+                 "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_set_stream",
+                 "ts_release_cache"):
+        getattr(lib, name).restype = ci
+    lib.ts_last_error.argtypes = []
+    lib.ts_last_error.restype = ctypes.c_char_p
+    lib.ts_version.argtypes = []
+    lib.ts_version.restype = ctypes.c_char_p
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != TS_OK:
+        raise TsError(rc, load_library().ts_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return TS_F16
+    if t.dtype == torch.float32:
+        return TS_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _as_ts(t: torch.Tensor, rows: int | None = None, cols: int | None = None) -> ts_tensor:
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    r = t.shape[0] if rows is None else rows
+    c = t.shape[-1] if cols is None else cols
+    return ts_tensor(t.data_ptr() if t.numel() else None, r, c, _dtype_code(t))
+
+
+def _use_current_stream():
+    _check(load_library().ts_set_stream(torch.cuda.current_stream().cuda_stream))
+
+
+def ts_set_stream(stream: torch.cuda.Stream | None):
+    _check(load_library().ts_set_stream(stream.cuda_stream if stream is not None else None))
+
+
+def ts_release_cache():
+    _check(load_library().ts_release_cache())
+
+
+def ts_version() -> str:
+    return load_library().ts_version().decode()
+
+
+class KMap:
+    """Owner of a ``ts_kmap*``; freed by :func:`ts_free` or on garbage collection."""
+
+    def __init__(self, handle: int):
+        self._h = handle
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("kernel map already freed")
+        return self._h
+
+    num_in = property(lambda self: load_library().ts_kmap_num_in(self.handle))
+    num_out = property(lambda self: load_library().ts_kmap_num_out(self.handle))
+    num_pairs = property(lambda self: load_library().ts_kmap_num_pairs(self.handle))
+    kernel_volume = property(lambda self: load_library().ts_kmap_kernel_volume(self.handle))
+
+    def out_coords(self) -> torch.Tensor:
+        return ts_kmap_out_coords(self)
+
+    def in_coords(self) -> torch.Tensor:
+        return ts_kmap_in_coords(self)
+
+    def sizes(self) -> np.ndarray:
+        return ts_kmap_sizes(self)
+
+    def pairs(self):
+        return ts_kmap_pairs(self)
+
+    def free(self):
+        if self._h:
+            load_library().ts_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def ts_build_kmap(coords: torch.Tensor, kernel_size: int, stride: int = 1, transposed: bool = False) -> KMap:
+    """coords: device int32 [N,4] (batch, x, y, z)."""
+    if coords.dtype != torch.int32 or coords.dim() != 2 or coords.shape[1] != 4:
+        raise ValueError("coords must be int32 [N,4]")
+    if not coords.is_cuda or not coords.is_contiguous():
+        raise ValueError("coords must be a contiguous device tensor")
+    _use_current_stream()
+    h = ctypes.c_void_p()
+    rc = load_library().ts_build_kmap(coords.data_ptr() if coords.numel() else None, coords.shape[0],
+                                      int(kernel_size), int(stride), int(bool(transposed)), ctypes.byref(h))
+    _check(rc)
+    return KMap(h.value)
+
+
+def ts_free(kmap: KMap):
+    kmap.free()
+
+
+def ts_kmap_out_coords(kmap: KMap) -> torch.Tensor:
+    _use_current_stream()
+    dst = torch.empty((kmap.num_out, 4), dtype=torch.int32, device="cuda")
+    _check(load_library().ts_kmap_out_coords(kmap.handle, dst.data_ptr() if dst.numel() else None))
+    return dst
+
+
+def ts_kmap_in_coords(kmap: KMap) -> torch.Tensor:
+    _use_current_stream()
+    dst = torch.empty((kmap.num_in, 4), dtype=torch.int32, device="cuda")
+    _check(load_library().ts_kmap_in_coords(kmap.handle, dst.data_ptr() if dst.numel() else None))
+    return dst
+
+
+def ts_kmap_sizes(kmap: KMap) -> np.ndarray:
+    dst = (ctypes.c_int64 * kmap.kernel_volume)()
+    _check(load_library().ts_kmap_sizes(kmap.handle, dst))
+    return np.array(list(dst), dtype=np.int64)
+
+
+def ts_kmap_pairs(kmap: KMap):
+    """(in_idx, out_idx): device int32 [num_pairs] each, offset-major."""
+    _use_current_stream()
+    m = kmap.num_pairs
+    a = torch.empty((m,), dtype=torch.int32, device="cuda")
+    b = torch.empty((m,), dtype=torch.int32, device="cuda")
+    _check(load_library().ts_kmap_pairs(kmap.handle, a.data_ptr() if m else None, b.data_ptr() if m else None))
+    return a, b
+
+
+def _weights_ts(weights: torch.Tensor) -> ts_tensor:
+    if weights.dim() != 3:
+        raise ValueError("weights must be [K^3, C_in, C_out]")
+    return _as_ts(weights, rows=weights.shape[0] * weights.shape[1], cols=weights.shape[2])
+
+
+def ts_sparse_conv(feats: torch.Tensor, weights: torch.Tensor, kmap: KMap, out: torch.Tensor | None = None,
+                   dataflow: int = TS_DATAFLOW_AUTO) -> torch.Tensor:
+    """feats [num_in, C_in], weights [K^3, C_in, C_out] -> out [num_out, C_out] (same dtype)."""
+    _use_current_stream()
+    if out is None:
+        out = torch.empty((kmap.num_out, weights.shape[2]), dtype=feats.dtype, device=feats.device)
+    f, w, o = _as_ts(feats), _weights_ts(weights), _as_ts(out)
+    lib = load_library()
+    if dataflow == TS_DATAFLOW_AUTO:
+        rc = lib.ts_sparse_conv(ctypes.byref(f), ctypes.byref(w), kmap.handle, ctypes.byref(o))
+    else:
+        rc = lib.ts_sparse_conv_ex(ctypes.byref(f), ctypes.byref(w), kmap.handle, ctypes.byref(o), int(dataflow))
+    _check(rc)
+    return out
+
+
+def ts_sparse_conv_ex(feats, weights, kmap, out=None, dataflow: int = TS_DATAFLOW_AUTO):
+    return ts_sparse_conv(feats, weights, kmap, out, dataflow)
+
+
+def ts_gather(feats: torch.Tensor, kmap: KMap, F: torch.Tensor | None = None) -> torch.Tensor:
+    _use_current_stream()
+    if F is None:
+        F = torch.zeros((kmap.num_pairs, feats.shape[1]), dtype=feats.dtype, device=feats.device)
+    f, b = _as_ts(feats), _as_ts(F)
+    _check(load_library().ts_gather(ctypes.byref(f), kmap.handle, ctypes.byref(b)))
+    return F
+
+
+def ts_grouped_matmul(F: torch.Tensor, feats: torch.Tensor | None, weights: torch.Tensor, kmap: KMap,
+                      G: torch.Tensor | None = None) -> torch.Tensor:
+    _use_current_stream()
+    if G is None:
+        G = torch.empty((kmap.num_pairs, weights.shape[2]), dtype=torch.float32, device=F.device)
+    a, w, g = _as_ts(F), _weights_ts(weights), _as_ts(G)
+    x = ctypes.byref(_as_ts(feats)) if feats is not None else None
+    _check(load_library().ts_grouped_matmul(ctypes.byref(a), x, ctypes.byref(w), kmap.handle, ctypes.byref(g)))
+    return G
+
+
+def ts_scatter_reduce(G: torch.Tensor, kmap: KMap, out: torch.Tensor | None = None,
+                      dtype: torch.dtype = torch.float16) -> torch.Tensor:
+    _use_current_stream()
+    if out is None:
+        out = torch.empty((kmap.num_out, G.shape[1]), dtype=dtype, device=G.device)
+    g, o = _as_ts(G), _as_ts(out)
+    _check(load_library().ts_scatter_reduce(ctypes.byref(g), kmap.handle, ctypes.byref(o)))
+    return out

@@ -1,0 +1,485 @@
+// Feature computation of the sparse-convolution layer (paper Sec. 2.2, Alg. 2; Eq. 1).
+//
+// Two dataflows over the same kernel map:
+//
+//  explicit  - Alg. 2 in three launches for all offsets at once ("fused" gather / scatter of
+//              Sec. 4.3.2): gather rows into the offset-major buffer F, grouped matmul
+//              G = F_n * W_n scheduled as tiles over (offset, row block) without padding,
+//              output-stationary reduction of G into X_out (each row reduced in registers,
+//              written once).
+//  fused     - one output-stationary kernel.  A workgroup owns 128 outputs (sorted by
+//              neighbour bitmask so that they share offsets), walks the offsets present in
+//              the tile, stages W_n in LDS, loads the neighbours' feature rows straight into
+//              the MFMA operand registers and keeps the sum over offsets in the accumulators.
+//              Neither F nor G exists; every output row is written once.
+//
+// MFMA orientation: D[co][m] += Wt[co][ci] * X[m][ci]  (32x32 tiles, "A" = transposed weights
+// from LDS, "B" = gathered feature rows).  A lane then owns 4 consecutive output channels of
+// one row per accumulator quad, which makes the stores 8-16 bytes wide.
+#include "ts_internal.h"
+
+using namespace ts;
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kWaveRows = 32;                 // rows (MFMA columns) per wave
+static_assert(kWaves * kWaveRows == kTileRows, "tile = 4 waves x 32 rows");
+
+// Per-dtype constants.  A lane moves 16-byte vectors: VEC elements.  One operand step covers
+// KSTEP = 2*VEC input channels (lane halves h = 0/1 take VEC each).  LDS holds a
+// [co][KC + VEC] slab of the transposed weights; the VEC-element row padding makes the
+// 16-lane groups of a ds_read_b128 hit distinct banks.
+template <class T> struct Elem;
+template <> struct Elem<_Float16> {
+    typedef half8 vec;
+    static constexpr int VEC = 8, KSTEP = 16, KC = 64, LDS_STRIDE = KC + VEC;
+};
+template <> struct Elem<float> {
+    typedef floatx4 vec;
+    static constexpr int VEC = 4, KSTEP = 8, KC = 32, LDS_STRIDE = KC + VEC;
+};
+
+__device__ __forceinline__ void mma_step(const half8 &a, const half8 &b, floatx16 &acc) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+}
+__device__ __forceinline__ void mma_step(const floatx4 &a, const floatx4 &b, floatx16 &acc) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], acc, 0, 0, 0);
+}
+
+// Copy the [NCB*32][kc] slab of transposed weights for offset n, output-channel chunk co0 and
+// input-channel chunk k0 into LDS.  All kThreads threads take part.
+template <class T, int NCB>
+__device__ __forceinline__ void stage_weights(const T *__restrict__ Wt, T *lds, int n, int co0, int k0, int kc,
+                                              int cin, int cout) {
+    typedef typename Elem<T>::vec vec;
+    constexpr int VEC = Elem<T>::VEC;
+    const int vec_per_row = kc / VEC;
+    const int total = NCB * 32 * vec_per_row;
+    const T *src = Wt + ((int64_t)n * cout + co0) * cin + k0;
+    for (int v = threadIdx.x; v < total; v += kThreads) {
+        int row = v / vec_per_row, col = v - row * vec_per_row;
+        *reinterpret_cast<vec *>(lds + row * Elem<T>::LDS_STRIDE + col * VEC) =
+            *reinterpret_cast<const vec *>(src + (int64_t)row * cin + col * VEC);
+    }
+}
+
+// acc[cb] += Wt_lds[cb*32 .. +32][0 .. kc) * xrow[0 .. kc)^T for this wave's 32 rows.
+// xrow points at the k0-th channel of the lane's feature row (nullptr-safe through `valid`).
+template <class T, int NCB>
+__device__ __forceinline__ void mma_chunk(const T *lds, const T *xrow, bool valid, int kc, floatx16 (&acc)[NCB]) {
+    typedef typename Elem<T>::vec vec;
+    constexpr int VEC = Elem<T>::VEC, KSTEP = Elem<T>::KSTEP, KC = Elem<T>::KC;
+    const int lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
+    vec b[KC / KSTEP];
+#pragma unroll
+    for (int kb = 0; kb < KC / KSTEP; ++kb) {
+        vec z = {};
+        b[kb] = (valid && kb * KSTEP < kc) ? *reinterpret_cast<const vec *>(xrow + kb * KSTEP + h * VEC) : z;
+    }
+#pragma unroll
+    for (int kb = 0; kb < KC / KSTEP; ++kb) {
+        if (kb * KSTEP < kc) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                vec a = *reinterpret_cast<const vec *>(lds + (cb * 32 + m) * Elem<T>::LDS_STRIDE + kb * KSTEP + h * VEC);
+                mma_step(a, b[kb], acc[cb]);
+            }
+        }
+    }
+}
+
+// Store the wave's accumulators: lane (m, h) holds, for block cb and quad g, the channels
+// co0 + cb*32 + g*8 + h*4 + {0..3} of row m.
+template <class TO, int NCB>
+__device__ __forceinline__ void store_rows(TO *out, int64_t row, int cout, int co0, const floatx16 (&acc)[NCB]) {
+    const int lane = threadIdx.x & 63, h = lane >> 5;
+    if (row < 0) return;
+    TO *dst = out + row * cout + co0 + h * 4;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            if constexpr (sizeof(TO) == 2) {
+                half4 v = {(_Float16)acc[cb][g * 4 + 0], (_Float16)acc[cb][g * 4 + 1], (_Float16)acc[cb][g * 4 + 2],
+                           (_Float16)acc[cb][g * 4 + 3]};
+                *reinterpret_cast<half4 *>(dst + cb * 32 + g * 8) = v;
+            } else {
+                floatx4 v = {acc[cb][g * 4 + 0], acc[cb][g * 4 + 1], acc[cb][g * 4 + 2], acc[cb][g * 4 + 3]};
+                *reinterpret_cast<floatx4 *>(dst + cb * 32 + g * 8) = v;
+            }
+        }
+    }
+}
+
+// ---- fused output-stationary kernel ---------------------------------------------------------
+// grid = (tiles, cout / (NCB*32)).  cin is a multiple of KSTEP, cout a multiple of NCB*32.
+template <class T, int NCB>
+__global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, const T *__restrict__ Wt,
+                                                    const int32_t *__restrict__ tnbr,
+                                                    const uint32_t *__restrict__ tmask,
+                                                    const int32_t *__restrict__ perm, T *__restrict__ out, int cin,
+                                                    int cout, int K3) {
+    __shared__ __attribute__((aligned(16))) T lds[NCB * 32 * Elem<T>::LDS_STRIDE];
+    constexpr int KC = Elem<T>::KC;
+    const int64_t tile = blockIdx.x;
+    const int co0 = blockIdx.y * NCB * 32;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m = lane & 31;
+    const int slot = wave * kWaveRows + m;
+    uint32_t mask = tmask[tile];
+    floatx16 acc[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+        for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+
+    while (mask) {
+        const int n = __builtin_ctz(mask);
+        mask &= mask - 1;
+        const int32_t j = tnbr[(tile * K3 + n) * kTileRows + slot];
+        const bool valid = j >= 0;
+        const bool wave_has_work = __ballot(valid) != 0;
+        for (int k0 = 0; k0 < cin; k0 += KC) {
+            const int kc = cin - k0 < KC ? cin - k0 : KC;
+            __syncthreads();
+            stage_weights<T, NCB>(Wt, lds, n, co0, k0, kc, cin, cout);
+            __syncthreads();
+            if (wave_has_work) mma_chunk<T, NCB>(lds, X + (int64_t)(valid ? j : 0) * cin + k0, valid, kc, acc);
+        }
+    }
+    store_rows<T, NCB>(out, perm[tile * kTileRows + slot], cout, co0, acc);
+}
+
+// ---- explicit dataflow ------------------------------------------------------------------------
+// Gather (Alg. 2, "F[m] <- X_in[j]") for all offsets: one thread per 16-byte vector of F.
+__global__ void k_gather(const uint4 *__restrict__ X, const int32_t *__restrict__ in_idx, uint4 *__restrict__ F,
+                         int64_t M, int vec_per_row, int64_t skip_lo, int64_t skip_hi) {
+    int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t p = g / vec_per_row;
+    int v = (int)(g - p * vec_per_row);
+    if (p >= M || (p >= skip_lo && p < skip_hi)) return;
+    F[p * vec_per_row + v] = X[(int64_t)in_idx[p] * vec_per_row + v];
+}
+
+// Grouped matmul: block -> (offset n, 128-row block) by walking the per-offset tile counts.
+// Rows of the centre offset of an identity map come from X itself.
+template <class T, int NCB>
+__global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F, const T *__restrict__ X,
+                                                         const T *__restrict__ Wt, const int32_t *__restrict__ offs,
+                                                         float *__restrict__ G, int cin, int cout, int K3,
+                                                         int centre) {
+    __shared__ __attribute__((aligned(16))) T lds[NCB * 32 * Elem<T>::LDS_STRIDE];
+    constexpr int KC = Elem<T>::KC;
+    int t = blockIdx.x, n = 0, lo = 0, hi = 0;
+    for (; n < K3; ++n) {
+        lo = offs[n];
+        hi = offs[n + 1];
+        int tiles = (hi - lo + kTileRows - 1) / kTileRows;
+        if (t < tiles) break;
+        t -= tiles;
+    }
+    if (n >= K3) return;
+    const int co0 = blockIdx.y * NCB * 32;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m = lane & 31;
+    const int64_t p = (int64_t)lo + (int64_t)t * kTileRows + wave * kWaveRows + m;   // row of F and G
+    const bool valid = p < hi;
+    const bool wave_has_work = __ballot(valid) != 0;
+    const T *src = (n == centre) ? X + (p - lo) * cin : F + p * cin;
+    floatx16 acc[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+        for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+    for (int k0 = 0; k0 < cin; k0 += KC) {
+        const int kc = cin - k0 < KC ? cin - k0 : KC;
+        __syncthreads();
+        stage_weights<T, NCB>(Wt, lds, n, co0, k0, kc, cin, cout);
+        __syncthreads();
+        if (wave_has_work) mma_chunk<T, NCB>(lds, (valid ? src : X) + k0, valid, kc, acc);
+    }
+    store_rows<float, NCB>(G, valid ? p : -1, cout, co0, acc);
+}
+
+// Scatter-accumulate, output-stationary: thread = (output row, 4 channels); partial sums are
+// added in offset order in fp32 registers and the row is written once.
+template <class T>
+__global__ void k_scatter_reduce(const float *__restrict__ G, const int32_t *__restrict__ pos, T *__restrict__ out,
+                                 int64_t n_out, int cout, int K3) {
+    const int quads = cout / 4;
+    int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t k = g / quads;
+    int q = (int)(g - k * quads);
+    if (k >= n_out) return;
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int n = 0; n < K3; ++n) {
+        int32_t p = pos[(int64_t)n * n_out + k];
+        if (p >= 0) acc += *reinterpret_cast<const floatx4 *>(G + (int64_t)p * cout + q * 4);
+    }
+    if constexpr (sizeof(T) == 2) {
+        half4 v = {(_Float16)acc[0], (_Float16)acc[1], (_Float16)acc[2], (_Float16)acc[3]};
+        *reinterpret_cast<half4 *>(out + k * cout + q * 4) = v;
+    } else {
+        *reinterpret_cast<floatx4 *>(out + k * cout + q * 4) = acc;
+    }
+}
+
+// ---- operand preparation ----------------------------------------------------------------------
+// Wt[n][co][ci'] = W[n][ci'][co] for ci' < cin, 0 for cin <= ci' < cin_pad.
+template <class T>
+__global__ void k_pack_weights(const T *__restrict__ W, T *__restrict__ Wt, int K3, int cin, int cin_pad, int cout) {
+    int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (int64_t)K3 * cout * cin_pad;
+    if (g >= total) return;
+    int ci = (int)(g % cin_pad);
+    int co = (int)((g / cin_pad) % cout);
+    int n = (int)(g / ((int64_t)cin_pad * cout));
+    Wt[g] = ci < cin ? W[((int64_t)n * cin + ci) * cout + co] : (T)0;
+}
+
+// Xp[row][c] = X[row][c] for c < cin, 0 up to cin_pad.
+template <class T>
+__global__ void k_pad_rows(const T *__restrict__ X, T *__restrict__ Xp, int64_t rows, int cin, int cin_pad) {
+    int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= rows * cin_pad) return;
+    int64_t r = g / cin_pad;
+    int c = (int)(g - r * cin_pad);
+    Xp[g] = c < cin ? X[r * cin + c] : (T)0;
+}
+
+inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
+inline size_t elem_size(int dtype) { return dtype == TS_F16 ? 2 : 4; }
+inline int kstep(int dtype) { return dtype == TS_F16 ? Elem<_Float16>::KSTEP : Elem<float>::KSTEP; }
+
+// Output-channel blocks of 32 handled by one workgroup: the largest of 4,3,2,1 dividing cout/32.
+inline int pick_ncb(int cout) {
+    int blocks = cout / 32;
+    for (int ncb = 4; ncb >= 1; --ncb)
+        if (blocks % ncb == 0) return ncb;
+    return 1;
+}
+
+struct Prepared {
+    const void *x;    // features, rows padded to cin_pad channels
+    const void *wt;   // transposed, padded weights
+    int cin_pad;
+};
+
+int check_tensor(const ts_tensor *t, const char *name) {
+    if (!t) return fail(TS_ERR_INVALID_ARG, "%s is NULL", name);
+    if (t->dtype != TS_F32 && t->dtype != TS_F16) return fail(TS_ERR_INVALID_ARG, "%s: unknown dtype %d", name, t->dtype);
+    if (t->rows < 0 || t->cols <= 0) return fail(TS_ERR_SHAPE, "%s: bad shape [%lld, %d]", name, (long long)t->rows, t->cols);
+    if (t->rows > 0 && !t->data) return fail(TS_ERR_INVALID_ARG, "%s: data is NULL", name);
+    if (reinterpret_cast<uintptr_t>(t->data) & 15) return fail(TS_ERR_INVALID_ARG, "%s: data must be 16-byte aligned", name);
+    return TS_OK;
+}
+
+int check_layer(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, const ts_tensor *out) {
+    if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    TS_TRY(check_tensor(feats, "feats"));
+    TS_TRY(check_tensor(weights, "weights"));
+    TS_TRY(check_tensor(out, "out"));
+    if (feats->dtype != weights->dtype || feats->dtype != out->dtype)
+        return fail(TS_ERR_SHAPE, "feats, weights and out must share one dtype");
+    if (feats->rows != kmap->n_in) return fail(TS_ERR_SHAPE, "feats has %lld rows, the map expects %lld", (long long)feats->rows, (long long)kmap->n_in);
+    if (out->rows != kmap->n_out) return fail(TS_ERR_SHAPE, "out has %lld rows, the map produces %lld", (long long)out->rows, (long long)kmap->n_out);
+    if (weights->rows != (int64_t)kmap->K3 * feats->cols)
+        return fail(TS_ERR_SHAPE, "weights must be [K^3*C_in, C_out] = [%lld, .], got %lld rows", (long long)kmap->K3 * feats->cols, (long long)weights->rows);
+    if (weights->cols != out->cols) return fail(TS_ERR_SHAPE, "weights has %d columns, out has %d", weights->cols, out->cols);
+    if (out->cols % 32 != 0 || out->cols > 1024) return fail(TS_ERR_UNSUPPORTED, "C_out must be a multiple of 32 (<= 1024), got %d", out->cols);
+    if (feats->cols > 1024) return fail(TS_ERR_UNSUPPORTED, "C_in must be <= 1024, got %d", feats->cols);
+    return TS_OK;
+}
+
+// Transpose/pad the weights into scratch, and pad the features when C_in is not a multiple of
+// the operand step.
+template <class T>
+int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, Prepared *pr) {
+    hipStream_t st = stream();
+    const int cin = feats->cols, cout = weights->cols, ks = Elem<T>::KSTEP;
+    const int cin_pad = (cin + ks - 1) / ks * ks;
+    pr->cin_pad = cin_pad;
+    size_t wn = (size_t)kmap->K3 * cout * cin_pad;
+    T *wt = static_cast<T *>(scratch(2, wn * sizeof(T)));
+    if (!wt) return TS_ERR_OOM;
+    hipLaunchKernelGGL(k_pack_weights<T>, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads), 0, st,
+                       static_cast<const T *>(weights->data), wt, kmap->K3, cin, cin_pad, cout);
+    pr->wt = wt;
+    pr->x = feats->data;
+    if (cin_pad != cin && feats->rows > 0) {
+        size_t xn = (size_t)feats->rows * cin_pad;
+        T *xp = static_cast<T *>(scratch(3, xn * sizeof(T)));
+        if (!xp) return TS_ERR_OOM;
+        hipLaunchKernelGGL(k_pad_rows<T>, dim3(blocks_for((int64_t)xn, kThreads)), dim3(kThreads), 0, st,
+                           static_cast<const T *>(feats->data), xp, feats->rows, cin, cin_pad);
+        pr->x = xp;
+    }
+    return TS_OK;
+}
+
+template <class T, int NCB>
+void launch_fused(const Prepared &pr, const ts_kmap *kmap, ts_tensor *out) {
+    dim3 grid((unsigned)kmap->n_tiles, out->cols / (NCB * 32));
+    hipLaunchKernelGGL((k_fused<T, NCB>), grid, dim3(kThreads), 0, stream(), static_cast<const T *>(pr.x),
+                       static_cast<const T *>(pr.wt), kmap->d_tnbr, kmap->d_tmask, kmap->d_perm,
+                       static_cast<T *>(out->data), pr.cin_pad, out->cols, kmap->K3);
+}
+
+template <class T>
+int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
+    Prepared pr;
+    TS_TRY(prepare<T>(feats, weights, kmap, &pr));
+    switch (pick_ncb(out->cols)) {
+        case 4: launch_fused<T, 4>(pr, kmap, out); break;
+        case 3: launch_fused<T, 3>(pr, kmap, out); break;
+        case 2: launch_fused<T, 2>(pr, kmap, out); break;
+        default: launch_fused<T, 1>(pr, kmap, out); break;
+    }
+    TS_HIP(hipGetLastError());
+    return TS_OK;
+}
+
+int64_t total_mm_tiles(const ts_kmap *kmap) {
+    int64_t t = 0;
+    for (int n = 0; n < kmap->K3; ++n) t += (kmap->sizes[n] + kTileRows - 1) / kTileRows;
+    return t;
+}
+
+template <class T, int NCB>
+void launch_grouped_mm(const T *F, const T *X, const T *wt, const ts_kmap *kmap, float *G, int cin_pad, int cout) {
+    dim3 grid((unsigned)total_mm_tiles(kmap), cout / (NCB * 32));
+    hipLaunchKernelGGL((k_grouped_mm<T, NCB>), grid, dim3(kThreads), 0, stream(), F, X, wt, kmap->d_offs, G, cin_pad,
+                       cout, kmap->K3, kmap->centre);
+}
+
+int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const ts_kmap *kmap, void *F) {
+    if (kmap->M == 0) return TS_OK;
+    const int vec_per_row = (int)(cin_pad * elem_size(dtype) / 16);
+    int64_t lo = 0, hi = 0;
+    if (kmap->centre >= 0) {
+        lo = kmap->offs[kmap->centre];
+        hi = kmap->offs[kmap->centre + 1];
+    }
+    hipLaunchKernelGGL(k_gather, dim3(blocks_for(kmap->M * vec_per_row, kThreads)), dim3(kThreads), 0, stream(),
+                       static_cast<const uint4 *>(x), kmap->d_in_idx, static_cast<uint4 *>(F), kmap->M, vec_per_row, lo,
+                       hi);
+    TS_HIP(hipGetLastError());
+    return TS_OK;
+}
+
+template <class T>
+int grouped_mm_impl(const void *F, const void *X, const void *wt, const ts_kmap *kmap, float *G, int cin_pad,
+                    int cout) {
+    if (kmap->M == 0) return TS_OK;
+    const T *f = static_cast<const T *>(F), *x = static_cast<const T *>(X), *w = static_cast<const T *>(wt);
+    switch (pick_ncb(cout)) {
+        case 4: launch_grouped_mm<T, 4>(f, x, w, kmap, G, cin_pad, cout); break;
+        case 3: launch_grouped_mm<T, 3>(f, x, w, kmap, G, cin_pad, cout); break;
+        case 2: launch_grouped_mm<T, 2>(f, x, w, kmap, G, cin_pad, cout); break;
+        default: launch_grouped_mm<T, 1>(f, x, w, kmap, G, cin_pad, cout); break;
+    }
+    TS_HIP(hipGetLastError());
+    return TS_OK;
+}
+
+template <class T>
+int reduce_impl(const float *G, const ts_kmap *kmap, ts_tensor *out) {
+    if (kmap->n_out == 0) return TS_OK;
+    int64_t threads = kmap->n_out * (out->cols / 4);
+    hipLaunchKernelGGL(k_scatter_reduce<T>, dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, stream(), G,
+                       kmap->d_pos, static_cast<T *>(out->data), kmap->n_out, out->cols, kmap->K3);
+    TS_HIP(hipGetLastError());
+    return TS_OK;
+}
+
+template <class T>
+int run_explicit(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
+    Prepared pr;
+    TS_TRY(prepare<T>(feats, weights, kmap, &pr));
+    const int64_t M = kmap->M;
+    void *F = scratch(0, (size_t)(M ? M : 1) * pr.cin_pad * sizeof(T));
+    float *G = static_cast<float *>(scratch(1, (size_t)(M ? M : 1) * out->cols * sizeof(float)));
+    if (!F || !G) return TS_ERR_OOM;
+    TS_TRY(gather_impl(pr.x, feats->rows, pr.cin_pad, feats->dtype, kmap, F));
+    TS_TRY(grouped_mm_impl<T>(F, pr.x, pr.wt, kmap, G, pr.cin_pad, out->cols));
+    return reduce_impl<T>(G, kmap, out);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
+                      int dataflow) {
+    TS_TRY(check_layer(feats, weights, kmap, out));
+    if (dataflow != TS_DATAFLOW_AUTO && dataflow != TS_DATAFLOW_EXPLICIT && dataflow != TS_DATAFLOW_FUSED)
+        return fail(TS_ERR_INVALID_ARG, "unknown dataflow %d", dataflow);
+    if (kmap->n_out == 0) return TS_OK;
+    const bool f16 = feats->dtype == TS_F16;
+    if (dataflow == TS_DATAFLOW_EXPLICIT)
+        return f16 ? run_explicit<_Float16>(feats, weights, kmap, out) : run_explicit<float>(feats, weights, kmap, out);
+    return f16 ? run_fused<_Float16>(feats, weights, kmap, out) : run_fused<float>(feats, weights, kmap, out);
+}
+
+int ts_sparse_conv(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
+    return ts_sparse_conv_ex(feats, weights, kmap, out, TS_DATAFLOW_AUTO);
+}
+
+int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F) {
+    if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    TS_TRY(check_tensor(feats, "feats"));
+    TS_TRY(check_tensor(F, "F"));
+    if (feats->rows != kmap->n_in) return fail(TS_ERR_SHAPE, "feats has %lld rows, the map expects %lld", (long long)feats->rows, (long long)kmap->n_in);
+    if (F->rows != kmap->M || F->cols != feats->cols || F->dtype != feats->dtype)
+        return fail(TS_ERR_SHAPE, "F must be [num_pairs, C_in] of the dtype of feats");
+    if ((feats->cols * elem_size(feats->dtype)) % 16 != 0)
+        return fail(TS_ERR_UNSUPPORTED, "rows must be a multiple of 16 bytes");
+    return gather_impl(feats->data, feats->rows, feats->cols, feats->dtype, kmap, F->data);
+}
+
+int ts_grouped_matmul(const ts_tensor *F, const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
+                      ts_tensor *G) {
+    if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    TS_TRY(check_tensor(F, "F"));
+    TS_TRY(check_tensor(weights, "weights"));
+    TS_TRY(check_tensor(G, "G"));
+    if (kmap->centre >= 0) {
+        TS_TRY(check_tensor(feats, "feats"));
+        if (feats->rows != kmap->n_in || feats->cols != F->cols || feats->dtype != F->dtype)
+            return fail(TS_ERR_SHAPE, "feats must be [num_in, C_in] of the dtype of F");
+    }
+    if (F->rows != kmap->M || G->rows != kmap->M) return fail(TS_ERR_SHAPE, "F and G must have num_pairs rows");
+    if (weights->dtype != F->dtype || G->dtype != TS_F32) return fail(TS_ERR_SHAPE, "weights must match F; G must be TS_F32");
+    if (weights->rows != (int64_t)kmap->K3 * F->cols || weights->cols != G->cols)
+        return fail(TS_ERR_SHAPE, "weights must be [K^3*C_in, C_out]");
+    if (G->cols % 32 != 0 || F->cols % kstep(F->dtype) != 0)
+        return fail(TS_ERR_UNSUPPORTED, "C_out must be a multiple of 32 and C_in of %d", kstep(F->dtype));
+    // weights only: the rows of F are already in the operand layout
+    ts_tensor none = {nullptr, 0, F->cols, F->dtype};
+    Prepared pr;
+    if (F->dtype == TS_F16) {
+        TS_TRY(prepare<_Float16>(&none, weights, kmap, &pr));
+        return grouped_mm_impl<_Float16>(F->data, feats ? feats->data : nullptr, pr.wt, kmap, static_cast<float *>(G->data), F->cols, G->cols);
+    }
+    TS_TRY(prepare<float>(&none, weights, kmap, &pr));
+    return grouped_mm_impl<float>(F->data, feats ? feats->data : nullptr, pr.wt, kmap, static_cast<float *>(G->data), F->cols, G->cols);
+}
+
+int ts_scatter_reduce(const ts_tensor *G, const ts_kmap *kmap, ts_tensor *out) {
+    if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    TS_TRY(check_tensor(G, "G"));
+    TS_TRY(check_tensor(out, "out"));
+    if (G->dtype != TS_F32 || G->rows != kmap->M) return fail(TS_ERR_SHAPE, "G must be TS_F32 [num_pairs, C_out]");
+    if (out->rows != kmap->n_out || out->cols != G->cols) return fail(TS_ERR_SHAPE, "out must be [num_out, C_out]");
+    if (out->cols % 4 != 0) return fail(TS_ERR_UNSUPPORTED, "C_out must be a multiple of 4");
+    return out->dtype == TS_F16 ? reduce_impl<_Float16>(static_cast<const float *>(G->data), kmap, out)
+                                : reduce_impl<float>(static_cast<const float *>(G->data), kmap, out);
+}
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/ts.h"
+
+namespace ts {
+
+// ---- errors -------------------------------------------------------------------------------
+int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
+#define TS_HIP(call)                                                                        \
+    do {                                                                                    \
+        hipError_t ts_e_ = (call);                                                          \
+        if (ts_e_ != hipSuccess)                                                            \
+            return ts::fail(TS_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(ts_e_));  \
+    } while (0)
+
+#define TS_TRY(expr)                  \
+    do {                              \
+        int ts_rc_ = (expr);          \
+        if (ts_rc_ != TS_OK) return ts_rc_; \
+    } while (0)
+
+// ---- runtime ------------------------------------------------------------------------------
+hipStream_t stream();
+
+// Pooled device memory: freed blocks are kept and handed out again, so steady-state
+// calls do not reach hipMalloc/hipFree.  Returns nullptr on failure (error text is set).
+void *dev_alloc(size_t bytes);
+void dev_free(void *p);
+
+// Grow-only scratch areas for ts_sparse_conv (slot 0: gather buffer F, 1: partial sums G,
+// 2: packed weights, 3: padded features).  Contents do not survive across calls.
+void *scratch(int slot, size_t bytes);
+
+// Pinned host staging area (at least `bytes` long), one per process.
+void *host_staging(size_t bytes);
+
+template <class T>
+inline int alloc_n(T **p, size_t n) {
+    *p = static_cast<T *>(dev_alloc((n ? n : 1) * sizeof(T)));
+    return *p ? TS_OK : TS_ERR_OOM;
+}
+
+// ---- 64-bit coordinate keys ----------------------------------------------------------------
+// key = batch<<51 | (x+B)<<34 | (y+B)<<17 | (z+B), B = 2^16: order-preserving in (b,x,y,z)
+// ("flattening the coordinate of each dimension into an integer", paper Sec. 2.1.2).
+// With x,y,z in [TS_COORD_MIN, TS_COORD_MAX] a field never borrows or carries when a kernel
+// offset (|d| <= 7) is added, so key(p + d) = key(p) + key_delta(d).
+constexpr int kFieldBits = 17;
+constexpr int64_t kBias = 1 << 16;
+constexpr uint64_t kFieldMask = (1u << kFieldBits) - 1;
+constexpr uint64_t kEmptyKey = ~0ull;
+
+__host__ __device__ inline uint64_t pack_key(int32_t b, int32_t x, int32_t y, int32_t z) {
+    return ((uint64_t)(uint32_t)b << (3 * kFieldBits)) | ((uint64_t)(x + kBias) << (2 * kFieldBits)) |
+           ((uint64_t)(y + kBias) << kFieldBits) | (uint64_t)(z + kBias);
+}
+__host__ __device__ inline void unpack_key(uint64_t k, int32_t c[4]) {
+    c[3] = (int32_t)(k & kFieldMask) - (int32_t)kBias;
+    c[2] = (int32_t)((k >> kFieldBits) & kFieldMask) - (int32_t)kBias;
+    c[1] = (int32_t)((k >> (2 * kFieldBits)) & kFieldMask) - (int32_t)kBias;
+    c[0] = (int32_t)(k >> (3 * kFieldBits));
+}
+__host__ __device__ inline int64_t key_delta(int dx, int dy, int dz) {
+    return ((int64_t)dx << (2 * kFieldBits)) + ((int64_t)dy << kFieldBits) + (int64_t)dz;
+}
+
+constexpr int kMaxK3 = 27;      // kernel volumes up to 3^3 (one bit per offset in a 32-bit mask)
+constexpr int kTileRows = 128;  // output rows per workgroup tile of the fused kernel
+
+}  // namespace ts
+
+// The kernel map.  Everything with a d_ prefix is device memory owned by the map.
+struct ts_kmap {
+    int K = 0, s = 0, transposed = 0, K3 = 0;
+    int centre = -1;            // index of the identity offset (odd K, stride 1), else -1
+    int64_t n_in = 0, n_out = 0, M = 0;
+    int64_t sizes[ts::kMaxK3] = {0};      // |M[W_n]|
+    int64_t offs[ts::kMaxK3 + 1] = {0};   // exclusive prefix of sizes
+    uint64_t *d_in_keys = nullptr;        // [n_in]  packed input coordinates, row order of X_in
+    uint64_t *d_out_keys = nullptr;       // [n_out] packed output coordinates (may alias d_in_keys)
+    int32_t *d_nbr = nullptr;             // [K3][n_out] input row feeding output k through offset n, or -1
+    int32_t *d_pos = nullptr;             // [K3][n_out] row of that pair in the offset-major buffers, or -1
+    int32_t *d_in_idx = nullptr;          // [M] offset-major, ordered by output index inside an offset
+    int32_t *d_out_idx = nullptr;         // [M]
+    int32_t *d_offs = nullptr;            // [K3+1] device copy of offs
+    // output-stationary tiles of the fused kernel: outputs sorted by their neighbour bitmask
+    int64_t n_tiles = 0;
+    int32_t *d_perm = nullptr;            // [n_tiles*kTileRows] sorted position -> output row, -1 = padding
+    int32_t *d_tnbr = nullptr;            // [n_tiles][K3][kTileRows] input row or -1
+    uint32_t *d_tmask = nullptr;          // [n_tiles] OR of the rows' neighbour bitmasks
+};

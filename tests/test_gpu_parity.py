@@ -1,0 +1,256 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Kernel maps must equal the oracle's bit-exactly as sorted (in, out, offset) triples;
+features must agree within a relative L2 error of 1e-5 (fp32) / 2e-3 (fp16 in, fp32 accumulate).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2204_10319_amd import binding as ts
+from workloads import (uniform_grid_coords, box_surface_coords, lidar_scan_coords, features, conv_weights,
+                       shuffle_rows)
+from _util import TOL, np_dtype, to_dev, gpu_triples, oracle_map, oracle_conv, check_features
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand_coords(seed, n, lo, hi, batches=1):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    side = hi - lo
+    flat = rng.choice(batches * side ** 3, size=n, replace=False)
+    b, x, y, z = np.unravel_index(flat, (batches, side, side, side))
+    return np.stack([b, x + lo, y + lo, z + lo], axis=1).astype(np.int32)
+
+
+def _check_map(coords, K, s, transposed=False):
+    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
+    in_c, out_c, tri = oracle_map(coords, K, s, transposed)
+    assert kmap.num_in == in_c.shape[0]
+    assert kmap.num_out == out_c.shape[0]
+    assert kmap.kernel_volume == K ** 3
+    assert np.array_equal(kmap.out_coords().cpu().numpy(), out_c)
+    assert np.array_equal(kmap.in_coords().cpu().numpy(), in_c)
+    assert kmap.num_pairs == tri.shape[0]
+    assert np.array_equal(kmap.sizes(), np.bincount(tri[:, 2], minlength=K ** 3))
+    assert np.array_equal(gpu_triples(kmap), tri)
+    return kmap
+
+
+MAP_CASES = [(1, 1, False), (3, 1, False), (2, 2, False), (3, 2, False), (1, 2, False), (2, 2, True), (3, 2, True)]
+
+
+@pytest.mark.parametrize("K,s,transposed", MAP_CASES)
+@pytest.mark.parametrize("n", [1, 37, 700, 5000])
+def test_kmap_small(K, s, transposed, n):
+    """Several tiles and a ragged tail, negative coordinates, three batch indices."""
+    coords = _rand_coords(1000 + n + 10 * K + s, n, -9, 9, batches=3)
+    _check_map(coords, K, s, transposed)
+
+
+@pytest.mark.parametrize("K,s,transposed", MAP_CASES)
+def test_kmap_empty(K, s, transposed):
+    kmap = ts.ts_build_kmap(torch.zeros((0, 4), dtype=torch.int32, device="cuda"), K, s, transposed)
+    assert kmap.num_in == 0 and kmap.num_out == 0 and kmap.num_pairs == 0
+    assert kmap.sizes().sum() == 0
+
+
+def test_kmap_extreme_coordinates():
+    lo, hi = ts.TS_COORD_MIN, ts.TS_COORD_MAX
+    coords = np.array([[0, lo, lo, lo], [0, lo + 1, lo, lo], [0, hi, hi, hi], [0, hi, hi - 1, hi],
+                       [ts.TS_BATCH_MAX, 0, 0, 0], [ts.TS_BATCH_MAX, 0, 0, 1], [0, 0, 0, 0]], dtype=np.int32)
+    for K, s, tr in MAP_CASES:
+        _check_map(coords, K, s, tr)
+
+
+def test_kmap_errors():
+    dup = np.array([[0, 1, 2, 3], [0, 5, 5, 5], [0, 1, 2, 3]], dtype=np.int32)
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(dup), 3, 1)
+    assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(dup), 2, 2, True)
+    assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
+    far = np.array([[0, 1, 2, 3], [0, ts.TS_COORD_MAX + 1, 0, 0]], dtype=np.int32)
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(far), 3, 1)
+    assert e.value.code == ts.TS_ERR_COORD_RANGE
+    neg_batch = np.array([[-1, 1, 2, 3]], dtype=np.int32)
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(neg_batch), 2, 2)
+    assert e.value.code == ts.TS_ERR_COORD_RANGE
+    ok = to_dev(np.array([[0, 1, 2, 3]], dtype=np.int32))
+    for K, s, tr in [(2, 1, False), (4, 1, False), (3, 3, False), (3, 1, True), (0, 1, False)]:
+        with pytest.raises(ts.TsError) as e:
+            ts.ts_build_kmap(ok, K, s, tr)
+        assert e.value.code == ts.TS_ERR_INVALID_ARG
+    # the library still works after the failures
+    _check_map(_rand_coords(5, 100, 0, 6), 3, 1)
+
+
+def _layer_case(coords, c_in, c_out, K, s, transposed, dtype, seed, dataflows=(ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT)):
+    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
+    x = features(seed, kmap.num_in, c_in, np_dtype(dtype))
+    w = conv_weights(seed + 1, K ** 3, c_in, c_out, np_dtype(dtype))
+    ref = oracle_conv(coords, x, w, K, s, transposed)
+    errs = []
+    for df in dataflows:
+        y = ts.ts_sparse_conv(to_dev(x), to_dev(w), kmap, dataflow=df)
+        torch.cuda.synchronize()
+        errs.append(check_features(y, ref, dtype, f"dataflow {df} C {c_in}->{c_out} K{K} s{s} t{transposed}"))
+    return errs
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+@pytest.mark.parametrize("K,s,transposed", [(3, 1, False), (1, 1, False), (2, 2, False), (2, 2, True), (3, 2, False), (3, 2, True)])
+@pytest.mark.parametrize("c_in,c_out", [(32, 32), (16, 64), (64, 96), (48, 128), (128, 256)])
+def test_layer_small(dtype, K, s, transposed, c_in, c_out):
+    coords = _rand_coords(77 + c_in + K, 1500, -7, 7, batches=2)
+    _layer_case(coords, c_in, c_out, K, s, transposed, dtype, seed=c_in + c_out)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+@pytest.mark.parametrize("n", [1, 31, 129, 1000])
+def test_layer_ragged_sizes(dtype, n):
+    coords = _rand_coords(300 + n, n, 0, 11)
+    _layer_case(coords, 32, 32, 3, 1, False, dtype, seed=n)
+
+
+@pytest.mark.parametrize("c_in", [4, 8, 24])
+def test_layer_narrow_input(c_in):
+    """C_in below the MFMA operand step (the 4-channel stem) is zero-extended inside the library."""
+    coords = _rand_coords(55, 900, 0, 10)
+    _layer_case(coords, c_in, 32, 3, 1, False, torch.float16, seed=c_in)
+
+
+def test_layer_empty():
+    kmap = ts.ts_build_kmap(torch.zeros((0, 4), dtype=torch.int32, device="cuda"), 3, 1)
+    x = torch.zeros((0, 32), dtype=torch.float16, device="cuda")
+    w = torch.zeros((27, 32, 32), dtype=torch.float16, device="cuda")
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+        assert ts.ts_sparse_conv(x, w, kmap, dataflow=df).shape == (0, 32)
+
+
+def test_layer_shape_errors():
+    coords = _rand_coords(9, 200, 0, 8)
+    kmap = ts.ts_build_kmap(to_dev(coords), 3, 1)
+    x = torch.zeros((200, 32), dtype=torch.float16, device="cuda")
+    w = torch.zeros((27, 32, 32), dtype=torch.float16, device="cuda")
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_sparse_conv(x[:100].contiguous(), w, kmap)
+    assert e.value.code == ts.TS_ERR_SHAPE
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_sparse_conv(x, w[:8].contiguous(), kmap)
+    assert e.value.code == ts.TS_ERR_SHAPE
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_sparse_conv(x, w.float(), kmap)
+    assert e.value.code == ts.TS_ERR_SHAPE
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_sparse_conv(x, torch.zeros((27, 32, 40), dtype=torch.float16, device="cuda"), kmap)
+    assert e.value.code == ts.TS_ERR_UNSUPPORTED
+
+
+def test_config1_uniform_grid_fp32():
+    """20 000 of 64^3 cells, C 32->32, fp32, submanifold 3x3x3."""
+    coords = uniform_grid_coords(0)
+    kmap = _check_map(coords, 3, 1)
+    assert abs(kmap.num_pairs - 58400) < 1500
+    errs = _layer_case(coords, 32, 32, 3, 1, False, torch.float32, seed=100)
+    print("config 1 rel L2:", errs)
+
+
+def test_config2_box_surfaces_fp16():
+    """~100k box-surface voxels in 256^3, C 64->64, fp16 with fp32 accumulation."""
+    coords = box_surface_coords(1, n_boxes=9)
+    assert 90000 <= coords.shape[0] <= 110000
+    _check_map(coords, 3, 1)
+    errs = _layer_case(coords, 64, 64, 3, 1, False, torch.float16, seed=200)
+    print("config 2 rel L2:", errs)
+
+
+@pytest.fixture(scope="module")
+def lidar_coords():
+    return lidar_scan_coords(2, n_sweeps=5)
+
+
+def test_config3_lidar_map(lidar_coords):
+    assert 135000 <= lidar_coords.shape[0] <= 165000
+    _check_map(lidar_coords, 3, 1)
+
+
+@pytest.mark.parametrize("c", [32, 64, 128])
+def test_config3_lidar_fp16(lidar_coords, c):
+    errs = _layer_case(lidar_coords, c, c, 3, 1, False, torch.float16, seed=300 + c)
+    print(f"config 3 C={c} rel L2:", errs)
+
+
+def test_config4_down_up_pair(lidar_coords):
+    """2x2x2 stride-2 conv 64->128 onto floor(coord/2), then the transposed conv 128->64 back."""
+    dtype = torch.float16
+    down = _check_map(lidar_coords, 2, 2)
+    up = _check_map(lidar_coords, 2, 2, transposed=True)
+    assert down.num_out == up.num_in
+    x = features(400, lidar_coords.shape[0], 64, np.float16)
+    w_down = conv_weights(401, 8, 64, 128, np.float16, gain=8.0)      # N(0, 1/fan_in), fan_in = 64
+    w_up = conv_weights(402, 8, 128, 64, np.float16, gain=8.0)
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+        y = ts.ts_sparse_conv(to_dev(x), to_dev(w_down), down, dataflow=df)
+        ref = oracle_conv(lidar_coords, x, w_down, 2, 2)
+        check_features(y, ref, dtype, "down")
+        # the up layer consumes exactly what the device produced (fp16), so only its own error is measured
+        y_host = y.cpu().numpy()
+        z = ts.ts_sparse_conv(y, to_dev(w_up), up, dataflow=df)
+        ref_up = oracle_conv(lidar_coords, y_host, w_up, 2, 2, transposed=True)
+        check_features(z, ref_up, dtype, "up")
+
+
+def test_stages_of_alg2(lidar_coords):
+    """Gather, grouped matmul and scatter-accumulate on their own (Alg. 2), C 64->64 fp16."""
+    coords = lidar_coords
+    kmap = ts.ts_build_kmap(to_dev(coords), 3, 1)
+    tri = gpu_triples(kmap)                                  # sorted by (n, k, j) = the library's pair order
+    sizes = kmap.sizes()
+    offs = np.concatenate([[0], np.cumsum(sizes)])
+    x = features(500, coords.shape[0], 64, np.float16)
+    w = conv_weights(501, 27, 64, 64, np.float16)
+    xd, wd = to_dev(x), to_dev(w)
+    F = ts.ts_gather(xd, kmap).cpu().numpy()
+    keep = tri[:, 2] != 13                                   # centre rows are not materialised
+    assert np.array_equal(F[keep], x[tri[keep, 0]])
+    G = ts.ts_grouped_matmul(to_dev(F), xd, wd, kmap)
+    Gh = G.cpu().numpy().astype(np.float64)
+    for n in (0, 4, 13, 22, 26):
+        sel = slice(offs[n], offs[n + 1])
+        ref = x[tri[sel, 0]].astype(np.float64) @ w[n].astype(np.float64)
+        assert oracle.rel_l2(Gh[sel], ref) < 1e-6
+    y = ts.ts_scatter_reduce(G, kmap, dtype=torch.float16)
+    acc = np.zeros((coords.shape[0], 64))
+    np.add.at(acc, tri[:, 1], Gh)
+    assert oracle.rel_l2(y.cpu().numpy(), acc.astype(np.float16)) < 2e-3
+    check_features(y, oracle_conv(coords, x, w, 3, 1), torch.float16, "staged")
+
+
+def test_results_are_deterministic(lidar_coords):
+    kmap_a = ts.ts_build_kmap(to_dev(lidar_coords), 3, 1)
+    kmap_b = ts.ts_build_kmap(to_dev(lidar_coords), 3, 1)
+    pa, pb = kmap_a.pairs(), kmap_b.pairs()
+    assert torch.equal(pa[0], pb[0]) and torch.equal(pa[1], pb[1])
+    x = to_dev(features(600, lidar_coords.shape[0], 64, np.float16))
+    w = to_dev(conv_weights(601, 27, 64, 64, np.float16))
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+        y1 = ts.ts_sparse_conv(x, w, kmap_a, dataflow=df)
+        y2 = ts.ts_sparse_conv(x, w, kmap_b, dataflow=df)
+        assert torch.equal(y1, y2)
+
+
+def test_row_order_independence():
+    coords = uniform_grid_coords(7, n=4000, grid=20)
+    x = features(700, 4000, 32, np.float16)
+    w = conv_weights(701, 27, 32, 32, np.float16)
+    kmap = ts.ts_build_kmap(to_dev(coords), 3, 1)
+    y = ts.ts_sparse_conv(to_dev(x), to_dev(w), kmap).cpu().numpy()
+    perm = np.random.Generator(np.random.PCG64(3)).permutation(4000)
+    kmap_p = ts.ts_build_kmap(to_dev(coords[perm]), 3, 1)
+    yp = ts.ts_sparse_conv(to_dev(x[perm]), to_dev(w), kmap_p).cpu().numpy()
+    assert oracle.rel_l2(yp, y[perm]) < 1e-3
