@@ -168,6 +168,15 @@ int ts_scatter_reduce(const ts_tensor *G, const ts_kmap *kmap, ts_tensor *out);
 int ts_set_stream(void *hip_stream);
 /* Free the library's cached scratch and pooled device memory (synchronises the device). */
 int ts_release_cache(void);
+/*
+ * Per-kernel timing for benchmarks.  While enabled, the library brackets each kernel launch
+ * (or library sort) with a hipEvent pair on its stream; `only`, when not NULL/empty, restricts
+ * this to the one kernel of that name.  ts_profile_read synchronises the stream, writes one
+ * line per kernel name, "name launches total_ms\n", into buf (host, cap bytes), and clears
+ * the records.  Not thread-safe; off by default.
+ */
+int ts_profile_enable(int on, const char *only);
+int ts_profile_read(char *buf, size_t cap);
 /* Text of the last error on this thread ("" if none). Valid until the next failing call. */
 const char *ts_last_error(void);
 /* Library version string. */

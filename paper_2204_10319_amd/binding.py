@@ -28,7 +28,7 @@ EXPORTS = [
     "ts_build_kmap", "ts_free", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
-    "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version",
+    "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read",
 ]
 
 
@@ -79,6 +79,10 @@ def load_library(path: str | None = None):
                  "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_set_stream",
                  "ts_release_cache"):
         getattr(lib, name).restype = ci
+    lib.ts_profile_enable.argtypes = [ci, ctypes.c_char_p]
+    lib.ts_profile_enable.restype = ci
+    lib.ts_profile_read.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
+    lib.ts_profile_read.restype = ci
     lib.ts_last_error.argtypes = []
     lib.ts_last_error.restype = ctypes.c_char_p
     lib.ts_version.argtypes = []
@@ -123,6 +127,22 @@ def ts_release_cache():
 
 def ts_version() -> str:
     return load_library().ts_version().decode()
+
+
+def ts_profile_enable(on: bool, only: str | None = None):
+    _check(load_library().ts_profile_enable(int(bool(on)), only.encode() if only else None))
+
+
+def ts_profile_read() -> dict:
+    """{kernel name: (launches, total_ms)} since the last read; synchronises the stream."""
+    _use_current_stream()
+    buf = ctypes.create_string_buffer(1 << 16)
+    _check(load_library().ts_profile_read(buf, len(buf)))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, count, ms = line.split()
+        out[name] = (int(count), float(ms))
+    return out
 
 
 class KMap:

@@ -301,23 +301,20 @@ int check_layer(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap 
 // the operand step.
 template <class T>
 int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, Prepared *pr) {
-    hipStream_t st = stream();
     const int cin = feats->cols, cout = weights->cols, ks = Elem<T>::KSTEP;
     const int cin_pad = (cin + ks - 1) / ks * ks;
     pr->cin_pad = cin_pad;
     size_t wn = (size_t)kmap->K3 * cout * cin_pad;
     T *wt = static_cast<T *>(scratch(2, wn * sizeof(T)));
     if (!wt) return TS_ERR_OOM;
-    hipLaunchKernelGGL(k_pack_weights<T>, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads), 0, st,
-                       static_cast<const T *>(weights->data), wt, kmap->K3, cin, cin_pad, cout);
+    TS_LAUNCH("k_pack_weights", k_pack_weights<T>, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads), static_cast<const T *>(weights->data), wt, kmap->K3, cin, cin_pad, cout);
     pr->wt = wt;
     pr->x = feats->data;
     if (cin_pad != cin && feats->rows > 0) {
         size_t xn = (size_t)feats->rows * cin_pad;
         T *xp = static_cast<T *>(scratch(3, xn * sizeof(T)));
         if (!xp) return TS_ERR_OOM;
-        hipLaunchKernelGGL(k_pad_rows<T>, dim3(blocks_for((int64_t)xn, kThreads)), dim3(kThreads), 0, st,
-                           static_cast<const T *>(feats->data), xp, feats->rows, cin, cin_pad);
+        TS_LAUNCH("k_pad_rows", k_pad_rows<T>, dim3(blocks_for((int64_t)xn, kThreads)), dim3(kThreads), static_cast<const T *>(feats->data), xp, feats->rows, cin, cin_pad);
         pr->x = xp;
     }
     return TS_OK;
@@ -326,9 +323,7 @@ int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kma
 template <class T, int NCB>
 void launch_fused(const Prepared &pr, const ts_kmap *kmap, ts_tensor *out) {
     dim3 grid((unsigned)kmap->n_tiles, out->cols / (NCB * 32));
-    hipLaunchKernelGGL((k_fused<T, NCB>), grid, dim3(kThreads), 0, stream(), static_cast<const T *>(pr.x),
-                       static_cast<const T *>(pr.wt), kmap->d_tnbr, kmap->d_tmask, kmap->d_perm,
-                       static_cast<T *>(out->data), pr.cin_pad, out->cols, kmap->K3);
+    TS_LAUNCH("k_fused", (k_fused<T, NCB>), grid, dim3(kThreads), static_cast<const T *>(pr.x), static_cast<const T *>(pr.wt), kmap->d_tnbr, kmap->d_tmask, kmap->d_perm, static_cast<T *>(out->data), pr.cin_pad, out->cols, kmap->K3);
 }
 
 template <class T>
@@ -354,8 +349,7 @@ int64_t total_mm_tiles(const ts_kmap *kmap) {
 template <class T, int NCB>
 void launch_grouped_mm(const T *F, const T *X, const T *wt, const ts_kmap *kmap, float *G, int cin_pad, int cout) {
     dim3 grid((unsigned)total_mm_tiles(kmap), cout / (NCB * 32));
-    hipLaunchKernelGGL((k_grouped_mm<T, NCB>), grid, dim3(kThreads), 0, stream(), F, X, wt, kmap->d_offs, G, cin_pad,
-                       cout, kmap->K3, kmap->centre);
+    TS_LAUNCH("k_grouped_mm", (k_grouped_mm<T, NCB>), grid, dim3(kThreads), F, X, wt, kmap->d_offs, G, cin_pad, cout, kmap->K3, kmap->centre);
 }
 
 int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const ts_kmap *kmap, void *F) {
@@ -366,9 +360,7 @@ int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const t
         lo = kmap->offs[kmap->centre];
         hi = kmap->offs[kmap->centre + 1];
     }
-    hipLaunchKernelGGL(k_gather, dim3(blocks_for(kmap->M * vec_per_row, kThreads)), dim3(kThreads), 0, stream(),
-                       static_cast<const uint4 *>(x), kmap->d_in_idx, static_cast<uint4 *>(F), kmap->M, vec_per_row, lo,
-                       hi);
+    TS_LAUNCH("k_gather", k_gather, dim3(blocks_for(kmap->M * vec_per_row, kThreads)), dim3(kThreads), static_cast<const uint4 *>(x), kmap->d_in_idx, static_cast<uint4 *>(F), kmap->M, vec_per_row, lo, hi);
     TS_HIP(hipGetLastError());
     return TS_OK;
 }
@@ -392,8 +384,7 @@ template <class T>
 int reduce_impl(const float *G, const ts_kmap *kmap, ts_tensor *out) {
     if (kmap->n_out == 0) return TS_OK;
     int64_t threads = kmap->n_out * (out->cols / 4);
-    hipLaunchKernelGGL(k_scatter_reduce<T>, dim3(blocks_for(threads, kThreads)), dim3(kThreads), 0, stream(), G,
-                       kmap->d_pos, static_cast<T *>(out->data), kmap->n_out, out->cols, kmap->K3);
+    TS_LAUNCH("k_scatter_reduce", k_scatter_reduce<T>, dim3(blocks_for(threads, kThreads)), dim3(kThreads), G, kmap->d_pos, static_cast<T *>(out->data), kmap->n_out, out->cols, kmap->K3);
     TS_HIP(hipGetLastError());
     return TS_OK;
 }

@@ -40,6 +40,20 @@ void *scratch(int slot, size_t bytes);
 // Pinned host staging area (at least `bytes` long), one per process.
 void *host_staging(size_t bytes);
 
+// Optional per-kernel timing (ts_profile_enable): an event pair around the enclosed launches.
+struct ProfScope {
+    explicit ProfScope(const char *name);
+    ~ProfScope();
+    int rec_;
+};
+
+// Launch on the library stream inside a timing scope named after the kernel.
+#define TS_LAUNCH(name, kernel, grid, block, ...)                                   \
+    do {                                                                            \
+        ts::ProfScope ts_ps_(name);                                                 \
+        hipLaunchKernelGGL(kernel, grid, block, 0, ts::stream(), __VA_ARGS__);      \
+    } while (0)
+
 template <class T>
 inline int alloc_n(T **p, size_t n) {
     *p = static_cast<T *>(dev_alloc((n ? n : 1) * sizeof(T)));

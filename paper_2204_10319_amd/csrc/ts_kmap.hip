@@ -336,6 +336,7 @@ int make_table(Temps &tmp, int64_t entries, Table *t) {
     TS_TRY(tmp.get(&t->vals, cap));
     t->mask = (uint32_t)(cap - 1);
     t->shift = 64 - __builtin_ctzll(cap);
+    ProfScope ps("memset_table");
     TS_HIP(hipMemsetAsync(t->keys, 0xFF, cap * sizeof(uint64_t), stream()));
     return TS_OK;
 }
@@ -360,6 +361,7 @@ int sort_keys(Temps &tmp, uint64_t *in, uint64_t *out, size_t n) {
     TS_HIP(rocprim::radix_sort_keys(nullptr, bytes, in, out, n, 0, 64, stream()));
     void *ws;
     TS_TRY(tmp.get((char **)&ws, bytes));
+    ProfScope ps("sort_keys");
     TS_HIP(rocprim::radix_sort_keys(ws, bytes, in, out, n, 0, 64, stream()));
     return TS_OK;
 }
@@ -373,9 +375,8 @@ int finish_map(ts_kmap *m, Temps &tmp, int *d_status) {
     int32_t *blkcnt;
     TS_TRY(tmp.get(&blkcnt, (size_t)K3 * nblk));
     TS_TRY(alloc_n(&m->d_offs, K3 + 1));
-    hipLaunchKernelGGL(k_count, dim3(nblk, K3), dim3(kThreads), 0, st, m->d_nbr, n_out, nblk, blkcnt);
-    hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(kThreads), 0, st, blkcnt, (int64_t)K3 * nblk, nblk, K3,
-                       m->d_offs);
+    TS_LAUNCH("k_count", k_count, dim3(nblk, K3), dim3(kThreads), m->d_nbr, n_out, nblk, blkcnt);
+    TS_LAUNCH("k_scan_counts", k_scan_counts, dim3(1), dim3(kThreads), blkcnt, (int64_t)K3 * nblk, nblk, K3, m->d_offs);
 
     // the one host round trip: status flags and the per-offset starts
     int32_t *h = static_cast<int32_t *>(host_staging((ST_WORDS + kMaxK3 + 1) * sizeof(int32_t)));
@@ -394,8 +395,7 @@ int finish_map(ts_kmap *m, Temps &tmp, int *d_status) {
     TS_TRY(alloc_n(&m->d_in_idx, (size_t)m->M));
     TS_TRY(alloc_n(&m->d_out_idx, (size_t)m->M));
     TS_TRY(alloc_n(&m->d_pos, (size_t)K3 * n_out));
-    hipLaunchKernelGGL(k_compact, dim3(nblk, K3), dim3(kThreads), 0, st, m->d_nbr, n_out, nblk, blkcnt,
-                       m->d_in_idx, m->d_out_idx, m->d_pos);
+    TS_LAUNCH("k_compact", k_compact, dim3(nblk, K3), dim3(kThreads), m->d_nbr, n_out, nblk, blkcnt, m->d_in_idx, m->d_out_idx, m->d_pos);
 
     // tiles: outputs ordered by neighbour bitmask so that a tile's rows share their offsets
     uint32_t *masks, *masks_sorted;
@@ -404,20 +404,21 @@ int finish_map(ts_kmap *m, Temps &tmp, int *d_status) {
     TS_TRY(tmp.get(&masks_sorted, (size_t)n_out));
     TS_TRY(tmp.get(&rows, (size_t)n_out));
     TS_TRY(tmp.get(&rows_sorted, (size_t)n_out));
-    hipLaunchKernelGGL(k_row_masks, dim3(blocks_for(n_out, kThreads)), dim3(kThreads), 0, st, m->d_nbr, n_out,
-                       K3, masks, rows);
+    TS_LAUNCH("k_row_masks", k_row_masks, dim3(blocks_for(n_out, kThreads)), dim3(kThreads), m->d_nbr, n_out, K3, masks, rows);
     size_t bytes = 0;
     TS_HIP(rocprim::radix_sort_pairs(nullptr, bytes, masks, masks_sorted, rows, rows_sorted, (size_t)n_out, 0, K3,
                                      st));
     void *ws;
     TS_TRY(tmp.get((char **)&ws, bytes));
-    TS_HIP(rocprim::radix_sort_pairs(ws, bytes, masks, masks_sorted, rows, rows_sorted, (size_t)n_out, 0, K3, st));
+    {
+        ProfScope ps("sort_masks");
+        TS_HIP(rocprim::radix_sort_pairs(ws, bytes, masks, masks_sorted, rows, rows_sorted, (size_t)n_out, 0, K3, st));
+    }
     m->n_tiles = (n_out + kTileRows - 1) / kTileRows;
     TS_TRY(alloc_n(&m->d_perm, (size_t)m->n_tiles * kTileRows));
     TS_TRY(alloc_n(&m->d_tnbr, (size_t)m->n_tiles * K3 * kTileRows));
     TS_TRY(alloc_n(&m->d_tmask, (size_t)m->n_tiles));
-    hipLaunchKernelGGL(k_build_tiles, dim3((unsigned)m->n_tiles), dim3(kTileRows), 0, st, m->d_nbr, n_out, K3,
-                       masks_sorted, rows_sorted, m->d_perm, m->d_tnbr, m->d_tmask);
+    TS_LAUNCH("k_build_tiles", k_build_tiles, dim3((unsigned)m->n_tiles), dim3(kTileRows), m->d_nbr, n_out, K3, masks_sorted, rows_sorted, m->d_perm, m->d_tnbr, m->d_tmask);
     TS_HIP(hipGetLastError());
     // temporaries go back to the pool when the caller's Temps dies; later work on the same
     // stream is ordered after the kernels above, so reuse is safe without another wait
@@ -442,21 +443,21 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
     uint64_t *given;   // keys of the caller's coordinates
     TS_TRY(alloc_n(&given, (size_t)N));
     m->d_in_keys = given;   // provisional owner, so that an early error frees it
-    hipLaunchKernelGGL(k_pack, dim3(blocks_for(N, kThreads)), dim3(kThreads), 0, st,
-                       reinterpret_cast<const int4 *>(coords), N, given, d_status);
+    TS_LAUNCH("k_pack", k_pack, dim3(blocks_for(N, kThreads)), dim3(kThreads), reinterpret_cast<const int4 *>(coords), N, given, d_status);
 
     Table table;
     if (s == 1) {
         m->n_in = m->n_out = N;
         m->d_out_keys = given;
         TS_TRY(alloc_n(&m->d_nbr, (size_t)K3 * N));
-        TS_HIP(hipMemsetAsync(m->d_nbr, 0xFF, (size_t)K3 * N * sizeof(int32_t), st));
+        {
+            ProfScope ps("memset_nbr");
+            TS_HIP(hipMemsetAsync(m->d_nbr, 0xFF, (size_t)K3 * N * sizeof(int32_t), st));
+        }
         TS_TRY(make_table(tmp, N, &table));
-        hipLaunchKernelGGL(k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), 0, st, given, N, table,
-                           m->d_nbr + (int64_t)m->centre * N, d_status);
+        TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, table, m->d_nbr + (int64_t)m->centre * N, d_status);
         if (K3 > 1)
-            hipLaunchKernelGGL(k_probe_symmetric, dim3(blocks_for(N, kThreads), K3 / 2), dim3(kThreads), 0, st,
-                               given, N, table, K, m->d_nbr);
+            TS_LAUNCH("k_probe_symmetric", k_probe_symmetric, dim3(blocks_for(N, kThreads), K3 / 2), dim3(kThreads), given, N, table, K, m->d_nbr);
     } else {
         // coarse set: candidates -> sort -> unique (the empty key, if present, sorts last)
         const bool one_each = (K == 2 && s == 2);
@@ -468,19 +469,20 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
         TS_TRY(tmp.get(&uniq, n_cand));
         TS_TRY(tmp.get(&d_count, 1));
         if (one_each)
-            hipLaunchKernelGGL(k_candidates_k2s2, dim3(blocks_for(N, kThreads)), dim3(kThreads), 0, st, given, N,
-                               cand);
+            TS_LAUNCH("k_candidates_k2s2", k_candidates_k2s2, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, cand);
         else
-            hipLaunchKernelGGL(k_candidates, dim3(blocks_for(N, kThreads), K3), dim3(kThreads), 0, st, given, N, K,
-                               s, cand);
+            TS_LAUNCH("k_candidates", k_candidates, dim3(blocks_for(N, kThreads), K3), dim3(kThreads), given, N, K, s, cand);
         TS_TRY(sort_keys(tmp, cand, sorted, n_cand));
         size_t bytes = 0;
         TS_HIP(rocprim::unique(nullptr, bytes, sorted, uniq, d_count, n_cand, rocprim::equal_to<uint64_t>(), st));
         void *ws;
         TS_TRY(tmp.get((char **)&ws, bytes));
-        TS_HIP(rocprim::unique(ws, bytes, sorted, uniq, d_count, n_cand, rocprim::equal_to<uint64_t>(), st));
+        {
+            ProfScope ps("unique_keys");
+            TS_HIP(rocprim::unique(ws, bytes, sorted, uniq, d_count, n_cand, rocprim::equal_to<uint64_t>(), st));
+        }
         // the empty key, if any candidate was rejected, is the last unique value: do not count it
-        hipLaunchKernelGGL(k_drop_empty_key, dim3(1), dim3(1), 0, st, uniq, d_count);
+        TS_LAUNCH("k_drop_empty_key", k_drop_empty_key, dim3(1), dim3(1), uniq, d_count);
         int64_t *h = static_cast<int64_t *>(host_staging(64));
         if (!h) return TS_ERR_OOM;
         TS_HIP(hipMemcpyAsync(h, d_count, sizeof(int64_t), hipMemcpyDeviceToHost, st));
@@ -498,10 +500,8 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             }
             TS_TRY(alloc_n(&m->d_nbr, (size_t)K3 * n_coarse));
             TS_TRY(make_table(tmp, N, &table));
-            hipLaunchKernelGGL(k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), 0, st, given, N, table,
-                               (int32_t *)nullptr, d_status);
-            hipLaunchKernelGGL(k_probe_forward, dim3(blocks_for(n_coarse, kThreads), K3), dim3(kThreads), 0, st,
-                               coarse, n_coarse, table, K, s, m->d_nbr);
+            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, table, (int32_t *)nullptr, d_status);
+            TS_LAUNCH("k_probe_forward", k_probe_forward, dim3(blocks_for(n_coarse, kThreads), K3), dim3(kThreads), coarse, n_coarse, table, K, s, m->d_nbr);
         } else {
             m->n_in = n_coarse;
             m->n_out = N;
@@ -512,13 +512,10 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             // duplicates among the fine points are found by inserting them as well
             Table fine_table;
             TS_TRY(make_table(tmp, N, &fine_table));
-            hipLaunchKernelGGL(k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), 0, st, given, N, fine_table,
-                               (int32_t *)nullptr, d_status);
+            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, fine_table, (int32_t *)nullptr, d_status);
             TS_TRY(make_table(tmp, n_coarse, &table));
-            hipLaunchKernelGGL(k_insert, dim3(blocks_for(n_coarse, kThreads)), dim3(kThreads), 0, st, coarse,
-                               n_coarse, table, (int32_t *)nullptr, d_status);
-            hipLaunchKernelGGL(k_probe_transposed, dim3(blocks_for(N, kThreads), K3), dim3(kThreads), 0, st, given, N,
-                               table, K, s, m->d_nbr);
+            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(n_coarse, kThreads)), dim3(kThreads), coarse, n_coarse, table, (int32_t *)nullptr, d_status);
+            TS_LAUNCH("k_probe_transposed", k_probe_transposed, dim3(blocks_for(N, kThreads), K3), dim3(kThreads), given, N, table, K, s, m->d_nbr);
         }
     }
     TS_HIP(hipGetLastError());
@@ -565,8 +562,7 @@ int ts_kmap_out_coords(const ts_kmap *kmap, int32_t *dst) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
     if (kmap->n_out == 0) return TS_OK;
     if (!dst || (reinterpret_cast<uintptr_t>(dst) & 15)) return fail(TS_ERR_INVALID_ARG, "dst is NULL or not 16-byte aligned");
-    hipLaunchKernelGGL(k_unpack, dim3(blocks_for(kmap->n_out, kThreads)), dim3(kThreads), 0, ts::stream(),
-                       kmap->d_out_keys, kmap->n_out, reinterpret_cast<int4 *>(dst));
+    TS_LAUNCH("k_unpack", k_unpack, dim3(blocks_for(kmap->n_out, kThreads)), dim3(kThreads), kmap->d_out_keys, kmap->n_out, reinterpret_cast<int4 *>(dst));
     TS_HIP(hipGetLastError());
     return TS_OK;
 }
@@ -575,8 +571,7 @@ int ts_kmap_in_coords(const ts_kmap *kmap, int32_t *dst) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
     if (kmap->n_in == 0) return TS_OK;
     if (!dst || (reinterpret_cast<uintptr_t>(dst) & 15)) return fail(TS_ERR_INVALID_ARG, "dst is NULL or not 16-byte aligned");
-    hipLaunchKernelGGL(k_unpack, dim3(blocks_for(kmap->n_in, kThreads)), dim3(kThreads), 0, ts::stream(),
-                       kmap->d_in_keys, kmap->n_in, reinterpret_cast<int4 *>(dst));
+    TS_LAUNCH("k_unpack", k_unpack, dim3(blocks_for(kmap->n_in, kThreads)), dim3(kThreads), kmap->d_in_keys, kmap->n_in, reinterpret_cast<int4 *>(dst));
     TS_HIP(hipGetLastError());
     return TS_OK;
 }

@@ -3,10 +3,12 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstring>
 #include <map>
 #include <mutex>
 #include <string>
 #include <unordered_map>
+#include <vector>
 
 namespace ts {
 
@@ -116,9 +118,86 @@ void *host_staging(size_t bytes) {
     return g_host;
 }
 
+// ---- per-kernel timing --------------------------------------------------------------------------
+namespace {
+struct ProfRec {
+    const char *name;
+    hipEvent_t a, b;
+};
+bool g_prof_on = false;
+std::string g_prof_filter;
+std::vector<ProfRec> g_prof_recs;
+std::vector<hipEvent_t> g_prof_free_events;
+
+hipEvent_t prof_event() {
+    if (!g_prof_free_events.empty()) {
+        hipEvent_t e = g_prof_free_events.back();
+        g_prof_free_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+}  // namespace
+
+ProfScope::ProfScope(const char *name) : rec_(-1) {
+    if (!g_prof_on) return;
+    if (!g_prof_filter.empty() && g_prof_filter != name) return;
+    ProfRec r{name, prof_event(), prof_event()};
+    if (!r.a || !r.b) return;
+    (void)hipEventRecord(r.a, g_stream);
+    g_prof_recs.push_back(r);
+    rec_ = (int)g_prof_recs.size() - 1;
+}
+
+ProfScope::~ProfScope() {
+    if (rec_ >= 0) (void)hipEventRecord(g_prof_recs[rec_].b, g_stream);
+}
+
 }  // namespace ts
 
 extern "C" {
+
+int ts_profile_enable(int on, const char *only) {
+    ts::g_prof_on = on != 0;
+    ts::g_prof_filter = only ? only : "";
+    return TS_OK;
+}
+
+int ts_profile_read(char *buf, size_t cap) {
+    if (!buf || cap == 0) return ts::fail(TS_ERR_INVALID_ARG, "buf is NULL or empty");
+    TS_HIP(hipStreamSynchronize(ts::g_stream));
+    std::map<std::string, std::pair<long, double>> agg;
+    std::vector<std::string> order;
+    for (auto &r : ts::g_prof_recs) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) {
+            (void)hipGetLastError();
+            ms = 0.f;
+        }
+        auto it = agg.find(r.name);
+        if (it == agg.end()) {
+            order.push_back(r.name);
+            agg[r.name] = {1, (double)ms};
+        } else {
+            it->second.first += 1;
+            it->second.second += ms;
+        }
+        ts::g_prof_free_events.push_back(r.a);
+        ts::g_prof_free_events.push_back(r.b);
+    }
+    ts::g_prof_recs.clear();
+    std::string text;
+    char line[256];
+    for (auto &name : order) {
+        snprintf(line, sizeof(line), "%s %ld %.6f\n", name.c_str(), agg[name].first, agg[name].second);
+        text += line;
+    }
+    if (text.size() + 1 > cap) return ts::fail(TS_ERR_INVALID_ARG, "buffer too small: need %zu bytes", text.size() + 1);
+    memcpy(buf, text.c_str(), text.size() + 1);
+    return TS_OK;
+}
 
 int ts_set_stream(void *hip_stream) {
     ts::g_stream = static_cast<hipStream_t>(hip_stream);
