@@ -32,18 +32,33 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kWaveRows = 32;                 // rows (MFMA columns) per wave
 static_assert(kWaves * kWaveRows == kTileRows, "tile = 4 waves x 32 rows");
 
-// Per-dtype constants.  A lane moves 16-byte vectors: VEC elements.  One operand step covers
-// KSTEP = 2*VEC input channels (lane halves h = 0/1 take VEC each).  LDS holds a
-// [co][KC + VEC] slab of the transposed weights; the VEC-element row padding makes the
-// 16-lane groups of a ds_read_b128 hit distinct banks.
+// Per-dtype constants.  A lane moves 16-byte vectors of VEC elements.  One operand step covers
+// KSTEP = 2*VEC input channels (lane halves h = 0/1 take VEC each).
 template <class T> struct Elem;
 template <> struct Elem<_Float16> {
     typedef half8 vec;
-    static constexpr int VEC = 8, KSTEP = 16, KC = 64, LDS_STRIDE = KC + VEC;
+    static constexpr int VEC = 8, KSTEP = 16;
 };
 template <> struct Elem<float> {
     typedef floatx4 vec;
-    static constexpr int VEC = 4, KSTEP = 8, KC = 32, LDS_STRIDE = KC + VEC;
+    static constexpr int VEC = 4, KSTEP = 8;
+};
+
+// Kernel shape: NCB blocks of 32 output channels per workgroup, input channels consumed in
+// chunks of KC (KC divides C_in, so every chunk is full and the inner code is branch-free).
+// LDS holds a [NCB*32][KC + VEC] slab of transposed weights; the VEC-element row padding
+// makes the 16 lanes of a ds_read_b128 phase hit distinct bank groups.
+template <class T, int NCB, int KC_>
+struct Shape {
+    typedef typename Elem<T>::vec vec;
+    static constexpr int VEC = Elem<T>::VEC, KSTEP = Elem<T>::KSTEP, KC = KC_;
+    static constexpr int NKB = KC / KSTEP;            // operand steps per chunk
+    static constexpr int STRIDE = KC + VEC;           // LDS row stride in elements
+    static constexpr int VPR = KC / VEC;              // 16-byte vectors per slab row
+    static constexpr int ROWS = NCB * 32;
+    static constexpr int TOTAL = ROWS * VPR;          // vectors per slab
+    static constexpr int WV = (TOTAL + kThreads - 1) / kThreads;   // vectors per thread
+    static constexpr int SLAB = ROWS * STRIDE;        // elements per slab
 };
 
 __device__ __forceinline__ void mma_step(const half8 &a, const half8 &b, floatx16 &acc) {
@@ -56,44 +71,52 @@ __device__ __forceinline__ void mma_step(const floatx4 &a, const floatx4 &b, flo
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], acc, 0, 0, 0);
 }
 
-// Copy the [NCB*32][kc] slab of transposed weights for offset n, output-channel chunk co0 and
-// input-channel chunk k0 into LDS.  All kThreads threads take part.
-template <class T, int NCB>
-__device__ __forceinline__ void stage_weights(const T *__restrict__ Wt, T *lds, int n, int co0, int k0, int kc,
-                                              int cin, int cout) {
-    typedef typename Elem<T>::vec vec;
-    constexpr int VEC = Elem<T>::VEC;
-    const int vec_per_row = kc / VEC;
-    const int total = NCB * 32 * vec_per_row;
+// Global -> registers: this thread's share of the weight slab of (offset n, channels k0..k0+KC).
+// Threads past the end of a small slab repeat its last vector (same value to the same place).
+template <class S, class T>
+__device__ __forceinline__ void load_w_regs(typename S::vec (&wreg)[S::WV], const T *__restrict__ Wt, int n, int co0,
+                                            int k0, int cin, int cout) {
     const T *src = Wt + ((int64_t)n * cout + co0) * cin + k0;
-    for (int v = threadIdx.x; v < total; v += kThreads) {
-        int row = v / vec_per_row, col = v - row * vec_per_row;
-        *reinterpret_cast<vec *>(lds + row * Elem<T>::LDS_STRIDE + col * VEC) =
-            *reinterpret_cast<const vec *>(src + (int64_t)row * cin + col * VEC);
+#pragma unroll
+    for (int i = 0; i < S::WV; ++i) {
+        int v = threadIdx.x + i * kThreads;
+        v = v < S::TOTAL ? v : S::TOTAL - 1;
+        int row = v / S::VPR, col = v % S::VPR;
+        wreg[i] = *reinterpret_cast<const typename S::vec *>(src + (int64_t)row * cin + col * S::VEC);
     }
 }
 
-// acc[cb] += Wt_lds[cb*32 .. +32][0 .. kc) * xrow[0 .. kc)^T for this wave's 32 rows.
-// xrow points at the k0-th channel of the lane's feature row (nullptr-safe through `valid`).
-template <class T, int NCB>
-__device__ __forceinline__ void mma_chunk(const T *lds, const T *xrow, bool valid, int kc, floatx16 (&acc)[NCB]) {
-    typedef typename Elem<T>::vec vec;
-    constexpr int VEC = Elem<T>::VEC, KSTEP = Elem<T>::KSTEP, KC = Elem<T>::KC;
-    const int lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
-    vec b[KC / KSTEP];
+// Registers -> LDS, same mapping.
+template <class S, class T>
+__device__ __forceinline__ void store_w_regs(const typename S::vec (&wreg)[S::WV], T *lds) {
 #pragma unroll
-    for (int kb = 0; kb < KC / KSTEP; ++kb) {
-        vec z = {};
-        b[kb] = (valid && kb * KSTEP < kc) ? *reinterpret_cast<const vec *>(xrow + kb * KSTEP + h * VEC) : z;
+    for (int i = 0; i < S::WV; ++i) {
+        int v = threadIdx.x + i * kThreads;
+        v = v < S::TOTAL ? v : S::TOTAL - 1;
+        int row = v / S::VPR, col = v % S::VPR;
+        *reinterpret_cast<typename S::vec *>(lds + row * S::STRIDE + col * S::VEC) = wreg[i];
     }
+}
+
+// Global -> registers: the lane's operand vectors for channels [k0, k0+KC) of the row at `row`
+// (already offset to the lane's half).  No predication: absent neighbours point at a zero row.
+template <class S, class T>
+__device__ __forceinline__ void load_x_regs(typename S::vec (&b)[S::NKB], const T *row) {
 #pragma unroll
-    for (int kb = 0; kb < KC / KSTEP; ++kb) {
-        if (kb * KSTEP < kc) {
+    for (int kb = 0; kb < S::NKB; ++kb) b[kb] = *reinterpret_cast<const typename S::vec *>(row + kb * S::KSTEP);
+}
+
+// acc[cb] += slab[cb*32 .. +32][0 .. KC) * b^T.
+template <class S, class T, int NCB>
+__device__ __forceinline__ void mma_stage(const T *lds, const typename S::vec (&b)[S::NKB], floatx16 (&acc)[NCB]) {
+    const int lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
+    const T *base = lds + m * S::STRIDE + h * S::VEC;
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-                vec a = *reinterpret_cast<const vec *>(lds + (cb * 32 + m) * Elem<T>::LDS_STRIDE + kb * KSTEP + h * VEC);
-                mma_step(a, b[kb], acc[cb]);
-            }
+    for (int kb = 0; kb < S::NKB; ++kb) {
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            typename S::vec a = *reinterpret_cast<const typename S::vec *>(base + cb * 32 * S::STRIDE + kb * S::KSTEP);
+            mma_step(a, b[kb], acc[cb]);
         }
     }
 }
@@ -122,37 +145,85 @@ __device__ __forceinline__ void store_rows(TO *out, int64_t row, int cout, int c
 }
 
 // ---- fused output-stationary kernel ---------------------------------------------------------
-// grid = (tiles, cout / (NCB*32)).  cin is a multiple of KSTEP, cout a multiple of NCB*32.
-template <class T, int NCB>
+// grid = (tiles, cout / (NCB*32)); cin is a multiple of KC.  A "stage" is one (offset n,
+// channel chunk k0) pair of the tile.  Software pipeline with one barrier per stage: while the
+// MFMAs of stage s read LDS slab `cur` and the operand registers loaded one stage earlier,
+// the global loads of stage s+1 (weight slab, neighbour rows) are in flight; the slab goes to
+// the other LDS buffer after the MFMAs.  All loads are unconditional so that the compiler can
+// count them: rows without a neighbour read `zero_row` instead.
+template <class T, int NCB, int KC>
 __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, const T *__restrict__ Wt,
                                                     const int32_t *__restrict__ tnbr,
                                                     const uint32_t *__restrict__ tmask,
-                                                    const int32_t *__restrict__ perm, T *__restrict__ out, int cin,
-                                                    int cout, int K3) {
-    __shared__ __attribute__((aligned(16))) T lds[NCB * 32 * Elem<T>::LDS_STRIDE];
-    constexpr int KC = Elem<T>::KC;
+                                                    const int32_t *__restrict__ perm, T *__restrict__ out,
+                                                    const T *__restrict__ zero_row, int cin, int cout, int K3) {
+    typedef Shape<T, NCB, KC> S;
+    typedef typename S::vec vec;
+    __shared__ __attribute__((aligned(16))) T lds_w[2][S::SLAB];
+    __shared__ int32_t lds_j[kMaxK3][kTileRows];
     const int64_t tile = blockIdx.x;
     const int co0 = blockIdx.y * NCB * 32;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m = lane & 31;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
     const int slot = wave * kWaveRows + m;
-    uint32_t mask = tmask[tile];
+    const uint32_t mask = tmask[tile];
     floatx16 acc[NCB];
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb)
         for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
 
-    while (mask) {
-        const int n = __builtin_ctz(mask);
-        mask &= mask - 1;
-        const int32_t j = tnbr[(tile * K3 + n) * kTileRows + slot];
-        const bool valid = j >= 0;
-        const bool wave_has_work = __ballot(valid) != 0;
-        for (int k0 = 0; k0 < cin; k0 += KC) {
-            const int kc = cin - k0 < KC ? cin - k0 : KC;
-            __syncthreads();
-            stage_weights<T, NCB>(Wt, lds, n, co0, k0, kc, cin, cout);
-            __syncthreads();
-            if (wave_has_work) mma_chunk<T, NCB>(lds, X + (int64_t)(valid ? j : 0) * cin + k0, valid, kc, acc);
+    if (mask) {
+        // neighbour rows of every offset present in the tile -> LDS (two offsets per pass)
+        {
+            uint32_t mm = mask;
+            int idx = 0;
+            while (mm) {
+                int n = __builtin_ctz(mm);
+                mm &= mm - 1;
+                if ((idx & 1) == (int)(threadIdx.x >> 7))
+                    lds_j[n][threadIdx.x & 127] = tnbr[(tile * K3 + n) * kTileRows + (threadIdx.x & 127)];
+                ++idx;
+            }
+        }
+        uint32_t rem = mask;
+        int n = __builtin_ctz(rem), k0 = 0;
+        rem &= rem - 1;
+        vec wreg[S::WV], bx_a[S::NKB], bx_b[S::NKB];
+        load_w_regs<S, T>(wreg, Wt, n, co0, k0, cin, cout);
+        __syncthreads();   // lds_j complete
+        int32_t j = lds_j[n][slot];
+        load_x_regs<S, T>(bx_a, (j >= 0 ? X + (int64_t)j * cin + k0 : zero_row) + h * S::VEC);
+        store_w_regs<S, T>(wreg, lds_w[0]);
+        int cur = 0;
+        // One stage.  The two operand register sets swap roles between calls, so prefetched
+        // registers are never copied (a copy would wait for the loads at once).
+        auto stage = [&](vec(&b_now)[S::NKB], vec(&b_next)[S::NKB]) -> bool {
+            int n2 = n, k2 = k0 + KC;
+            bool has_next = true;
+            if (k2 >= cin) {
+                k2 = 0;
+                if (rem) {
+                    n2 = __builtin_ctz(rem);
+                    rem &= rem - 1;
+                } else {
+                    has_next = false;
+                    n2 = n;   // harmless reload of the current stage keeps the loads unconditional
+                }
+            }
+            __syncthreads();   // slab `cur` is complete; nobody still reads the other buffer
+            load_w_regs<S, T>(wreg, Wt, n2, co0, k2, cin, cout);
+            const int32_t j2 = lds_j[n2][slot];
+            load_x_regs<S, T>(b_next, (j2 >= 0 ? X + (int64_t)j2 * cin + k2 : zero_row) + h * S::VEC);
+            if (__ballot(j >= 0) != 0) mma_stage<S, T, NCB>(lds_w[cur], b_now, acc);
+            store_w_regs<S, T>(wreg, lds_w[cur ^ 1]);
+            cur ^= 1;
+            n = n2;
+            k0 = k2;
+            j = j2;
+            return has_next;
+        };
+        for (;;) {
+            if (!stage(bx_a, bx_b)) break;
+            if (!stage(bx_b, bx_a)) break;
         }
     }
     store_rows<T, NCB>(out, perm[tile * kTileRows + slot], cout, co0, acc);
@@ -170,14 +241,16 @@ __global__ void k_gather(const uint4 *__restrict__ X, const int32_t *__restrict_
 }
 
 // Grouped matmul: block -> (offset n, 128-row block) by walking the per-offset tile counts.
-// Rows of the centre offset of an identity map come from X itself.
-template <class T, int NCB>
+// Rows of the centre offset of an identity map come from X itself.  Rows past the end of an
+// offset's list read `zero_row` and are not stored.
+template <class T, int NCB, int KC>
 __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F, const T *__restrict__ X,
                                                          const T *__restrict__ Wt, const int32_t *__restrict__ offs,
-                                                         float *__restrict__ G, int cin, int cout, int K3,
-                                                         int centre) {
-    __shared__ __attribute__((aligned(16))) T lds[NCB * 32 * Elem<T>::LDS_STRIDE];
-    constexpr int KC = Elem<T>::KC;
+                                                         float *__restrict__ G, const T *__restrict__ zero_row,
+                                                         int cin, int cout, int K3, int centre) {
+    typedef Shape<T, NCB, KC> S;
+    typedef typename S::vec vec;
+    __shared__ __attribute__((aligned(16))) T lds_w[S::SLAB];
     int t = blockIdx.x, n = 0, lo = 0, hi = 0;
     for (; n < K3; ++n) {
         lo = offs[n];
@@ -188,21 +261,23 @@ __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F
     }
     if (n >= K3) return;
     const int co0 = blockIdx.y * NCB * 32;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m = lane & 31;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
     const int64_t p = (int64_t)lo + (int64_t)t * kTileRows + wave * kWaveRows + m;   // row of F and G
     const bool valid = p < hi;
-    const bool wave_has_work = __ballot(valid) != 0;
-    const T *src = (n == centre) ? X + (p - lo) * cin : F + p * cin;
+    const T *src = !valid ? zero_row : (n == centre ? X + (p - lo) * cin : F + p * cin);
+    const int kstride = valid ? 1 : 0;   // the zero row is one chunk long
     floatx16 acc[NCB];
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb)
         for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+    vec wreg[S::WV], bx[S::NKB];
     for (int k0 = 0; k0 < cin; k0 += KC) {
-        const int kc = cin - k0 < KC ? cin - k0 : KC;
+        load_w_regs<S, T>(wreg, Wt, n, co0, k0, cin, cout);
+        load_x_regs<S, T>(bx, src + k0 * kstride + h * S::VEC);
         __syncthreads();
-        stage_weights<T, NCB>(Wt, lds, n, co0, k0, kc, cin, cout);
+        store_w_regs<S, T>(wreg, lds_w);
         __syncthreads();
-        if (wave_has_work) mma_chunk<T, NCB>(lds, (valid ? src : X) + k0, valid, kc, acc);
+        mma_stage<S, T, NCB>(lds_w, bx, acc);
     }
     store_rows<float, NCB>(G, valid ? p : -1, cout, co0, acc);
 }
@@ -320,22 +395,50 @@ int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kma
     return TS_OK;
 }
 
-template <class T, int NCB>
-void launch_fused(const Prepared &pr, const ts_kmap *kmap, ts_tensor *out) {
-    dim3 grid((unsigned)kmap->n_tiles, out->cols / (NCB * 32));
-    TS_LAUNCH("k_fused", (k_fused<T, NCB>), grid, dim3(kThreads), static_cast<const T *>(pr.x), static_cast<const T *>(pr.wt), kmap->d_tnbr, kmap->d_tmask, kmap->d_perm, static_cast<T *>(out->data), pr.cin_pad, out->cols, kmap->K3);
+// Largest chunk of {8,4,2} operand steps (KC = 64/32/16 for fp16, 32/16/8 for fp32) that divides cin.
+inline int pick_ksteps(int cin, int kstep_elems) {
+    int steps = cin / kstep_elems;
+    if (steps % 4 == 0) return 4;
+    if (steps % 2 == 0) return 2;
+    return 1;
 }
+
+// Run `fn.template operator()<NCB, KSTEPS>()` for the runtime pair (ncb, ksteps).
+template <class Fn>
+void dispatch_shape(int ncb, int ksteps, Fn &&fn) {
+#define TS_CASE(N, K)                     \
+    if (ncb == N && ksteps == K) {        \
+        fn.template operator()<N, K>();   \
+        return;                           \
+    }
+    TS_CASE(1, 1) TS_CASE(1, 2) TS_CASE(1, 4) TS_CASE(2, 1) TS_CASE(2, 2) TS_CASE(2, 4)
+    TS_CASE(3, 1) TS_CASE(3, 2) TS_CASE(3, 4) TS_CASE(4, 1) TS_CASE(4, 2) TS_CASE(4, 4)
+#undef TS_CASE
+}
+
+template <class T>
+struct FusedLaunch {
+    const Prepared &pr;
+    const ts_kmap *kmap;
+    ts_tensor *out;
+    const T *zero;
+    template <int NCB, int KSTEPS>
+    void operator()() const {
+        constexpr int KC = KSTEPS * Elem<T>::KSTEP;
+        dim3 grid((unsigned)kmap->n_tiles, out->cols / (NCB * 32));
+        TS_LAUNCH("k_fused", (k_fused<T, NCB, KC>), grid, dim3(kThreads), static_cast<const T *>(pr.x),
+                  static_cast<const T *>(pr.wt), kmap->d_tnbr, kmap->d_tmask, kmap->d_perm,
+                  static_cast<T *>(out->data), zero, pr.cin_pad, out->cols, kmap->K3);
+    }
+};
 
 template <class T>
 int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
     Prepared pr;
     TS_TRY(prepare<T>(feats, weights, kmap, &pr));
-    switch (pick_ncb(out->cols)) {
-        case 4: launch_fused<T, 4>(pr, kmap, out); break;
-        case 3: launch_fused<T, 3>(pr, kmap, out); break;
-        case 2: launch_fused<T, 2>(pr, kmap, out); break;
-        default: launch_fused<T, 1>(pr, kmap, out); break;
-    }
+    const T *zero = static_cast<const T *>(zero_row());
+    if (!zero) return TS_ERR_OOM;
+    dispatch_shape(pick_ncb(out->cols), pick_ksteps(pr.cin_pad, Elem<T>::KSTEP), FusedLaunch<T>{pr, kmap, out, zero});
     TS_HIP(hipGetLastError());
     return TS_OK;
 }
@@ -346,11 +449,21 @@ int64_t total_mm_tiles(const ts_kmap *kmap) {
     return t;
 }
 
-template <class T, int NCB>
-void launch_grouped_mm(const T *F, const T *X, const T *wt, const ts_kmap *kmap, float *G, int cin_pad, int cout) {
-    dim3 grid((unsigned)total_mm_tiles(kmap), cout / (NCB * 32));
-    TS_LAUNCH("k_grouped_mm", (k_grouped_mm<T, NCB>), grid, dim3(kThreads), F, X, wt, kmap->d_offs, G, cin_pad, cout, kmap->K3, kmap->centre);
-}
+template <class T>
+struct GroupedLaunch {
+    const T *F, *X, *wt;
+    const ts_kmap *kmap;
+    float *G;
+    const T *zero;
+    int cin_pad, cout;
+    template <int NCB, int KSTEPS>
+    void operator()() const {
+        constexpr int KC = KSTEPS * Elem<T>::KSTEP;
+        dim3 grid((unsigned)total_mm_tiles(kmap), cout / (NCB * 32));
+        TS_LAUNCH("k_grouped_mm", (k_grouped_mm<T, NCB, KC>), grid, dim3(kThreads), F, X, wt, kmap->d_offs, G, zero,
+                  cin_pad, cout, kmap->K3, kmap->centre);
+    }
+};
 
 int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const ts_kmap *kmap, void *F) {
     if (kmap->M == 0) return TS_OK;
@@ -369,13 +482,11 @@ template <class T>
 int grouped_mm_impl(const void *F, const void *X, const void *wt, const ts_kmap *kmap, float *G, int cin_pad,
                     int cout) {
     if (kmap->M == 0) return TS_OK;
-    const T *f = static_cast<const T *>(F), *x = static_cast<const T *>(X), *w = static_cast<const T *>(wt);
-    switch (pick_ncb(cout)) {
-        case 4: launch_grouped_mm<T, 4>(f, x, w, kmap, G, cin_pad, cout); break;
-        case 3: launch_grouped_mm<T, 3>(f, x, w, kmap, G, cin_pad, cout); break;
-        case 2: launch_grouped_mm<T, 2>(f, x, w, kmap, G, cin_pad, cout); break;
-        default: launch_grouped_mm<T, 1>(f, x, w, kmap, G, cin_pad, cout); break;
-    }
+    const T *zero = static_cast<const T *>(zero_row());
+    if (!zero) return TS_ERR_OOM;
+    dispatch_shape(pick_ncb(cout), pick_ksteps(cin_pad, Elem<T>::KSTEP),
+                   GroupedLaunch<T>{static_cast<const T *>(F), static_cast<const T *>(X), static_cast<const T *>(wt),
+                                    kmap, G, zero, cin_pad, cout});
     TS_HIP(hipGetLastError());
     return TS_OK;
 }

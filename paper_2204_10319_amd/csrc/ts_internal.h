@@ -37,6 +37,9 @@ void dev_free(void *p);
 // 2: packed weights, 3: padded features).  Contents do not survive across calls.
 void *scratch(int slot, size_t bytes);
 
+// 4 KiB of device zeros (a feature row of any supported width), allocated once.
+const void *zero_row();
+
 // Pinned host staging area (at least `bytes` long), one per process.
 void *host_staging(size_t bytes);
 

@@ -103,6 +103,19 @@ void *scratch(int slot, size_t bytes) {
     return s.p;
 }
 
+const void *zero_row() {
+    static void *z = nullptr;
+    if (z) return z;
+    void *p = nullptr;
+    if (hipMalloc(&p, 4096) != hipSuccess || hipMemset(p, 0, 4096) != hipSuccess) {
+        (void)hipGetLastError();
+        fail(TS_ERR_OOM, "allocating the zero row failed");
+        return nullptr;
+    }
+    z = p;
+    return z;
+}
+
 void *host_staging(size_t bytes) {
     if (g_host_bytes >= bytes) return g_host;
     if (g_host) (void)hipHostFree(g_host);
