@@ -171,7 +171,7 @@ int ts_release_cache(void);
 /*
  * Per-kernel timing for benchmarks.  While enabled, the library brackets each kernel launch
  * (or library sort) with a hipEvent pair on its stream; `only`, when not NULL/empty, restricts
- * this to the one kernel of that name.  ts_profile_read synchronises the stream, writes one
+ * this to the kernels whose name starts with it.  ts_profile_read synchronises the stream, writes one
  * line per kernel name, "name launches total_ms\n", into buf (host, cap bytes), and clears
  * the records.  Not thread-safe; off by default.
  */

@@ -151,7 +151,7 @@ __device__ __forceinline__ void store_rows(TO *out, int64_t row, int cout, int c
 // the global loads of stage s+1 (weight slab, neighbour rows) are in flight; the slab goes to
 // the other LDS buffer after the MFMAs.  All loads are unconditional so that the compiler can
 // count them: rows without a neighbour read `zero_row` instead.
-template <class T, int NCB, int KC>
+template <class T, int NCB, int KC, int G>
 __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, const T *__restrict__ Wt,
                                                     const int32_t *__restrict__ tnbr,
                                                     const uint32_t *__restrict__ tmask,
@@ -159,7 +159,7 @@ __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, con
                                                     const T *__restrict__ zero_row, int cin, int cout, int K3) {
     typedef Shape<T, NCB, KC> S;
     typedef typename S::vec vec;
-    __shared__ __attribute__((aligned(16))) T lds_w[2][S::SLAB];
+    __shared__ __attribute__((aligned(16))) T lds_w[2][G][S::SLAB];
     __shared__ int32_t lds_j[kMaxK3][kTileRows];
     const int64_t tile = blockIdx.x;
     const int co0 = blockIdx.y * NCB * 32;
@@ -172,61 +172,215 @@ __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, con
         for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
 
     if (mask) {
-        // neighbour rows of every offset present in the tile -> LDS (two offsets per pass)
+        // Neighbour rows of the tile -> LDS.  All loads are issued before the first is used
+        // (a load-wait-store loop over the present offsets would pay one memory latency per
+        // offset); entries of absent offsets hold unspecified values and are never read back.
         {
-            uint32_t mm = mask;
-            int idx = 0;
-            while (mm) {
-                int n = __builtin_ctz(mm);
-                mm &= mm - 1;
-                if ((idx & 1) == (int)(threadIdx.x >> 7))
-                    lds_j[n][threadIdx.x & 127] = tnbr[(tile * K3 + n) * kTileRows + (threadIdx.x & 127)];
-                ++idx;
+            constexpr int PER = (kMaxK3 + 1) / 2;
+            const int half = threadIdx.x >> 7, col = threadIdx.x & 127;
+            int32_t v[PER];
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                int n = 2 * i + half;
+                n = n < K3 ? n : K3 - 1;
+                v[i] = tnbr[(tile * K3 + n) * kTileRows + col];
+            }
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                int n = 2 * i + half;
+                n = n < K3 ? n : K3 - 1;
+                lds_j[n][col] = v[i];
             }
         }
+        // Iterator over the tile's (offset, chunk) pairs; a stage takes the next G of them.
+        // Past the end it keeps returning the last pair with live = false (loads stay
+        // unconditional and in bounds, the MFMAs are skipped).
         uint32_t rem = mask;
-        int n = __builtin_ctz(rem), k0 = 0;
+        int it_n = __builtin_ctz(rem), it_k = 0;
+        bool it_live = true;
         rem &= rem - 1;
-        vec wreg[S::WV], bx_a[S::NKB], bx_b[S::NKB];
-        load_w_regs<S, T>(wreg, Wt, n, co0, k0, cin, cout);
+        auto next_pair = [&](int &n, int &k0, bool &live) {
+            n = it_n;
+            k0 = it_k;
+            live = it_live;
+            if (it_k + KC < cin) {
+                it_k += KC;
+            } else if (rem) {
+                it_k = 0;
+                it_n = __builtin_ctz(rem);
+                rem &= rem - 1;
+            } else {
+                it_live = false;
+            }
+        };
+        vec wreg[G][S::WV], bx_a[G][S::NKB], bx_b[G][S::NKB];
+        int32_t j_a[G], j_b[G];
+        bool live_a[G], live_b[G];
+        auto issue_loads = [&](vec(&b)[G][S::NKB], int32_t(&j)[G], bool(&live)[G]) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                int n, k0;
+                next_pair(n, k0, live[g]);
+                load_w_regs<S, T>(wreg[g], Wt, n, co0, k0, cin, cout);
+                j[g] = live[g] ? lds_j[n][slot] : -1;
+                load_x_regs<S, T>(b[g], (j[g] >= 0 ? X + (int64_t)j[g] * cin + k0 : zero_row) + h * S::VEC);
+            }
+        };
         __syncthreads();   // lds_j complete
-        int32_t j = lds_j[n][slot];
-        load_x_regs<S, T>(bx_a, (j >= 0 ? X + (int64_t)j * cin + k0 : zero_row) + h * S::VEC);
-        store_w_regs<S, T>(wreg, lds_w[0]);
+        issue_loads(bx_a, j_a, live_a);
+#pragma unroll
+        for (int g = 0; g < G; ++g) store_w_regs<S, T>(wreg[g], lds_w[0][g]);
         int cur = 0;
         // One stage.  The two operand register sets swap roles between calls, so prefetched
         // registers are never copied (a copy would wait for the loads at once).
-        auto stage = [&](vec(&b_now)[S::NKB], vec(&b_next)[S::NKB]) -> bool {
-            int n2 = n, k2 = k0 + KC;
-            bool has_next = true;
-            if (k2 >= cin) {
-                k2 = 0;
-                if (rem) {
-                    n2 = __builtin_ctz(rem);
-                    rem &= rem - 1;
-                } else {
-                    has_next = false;
-                    n2 = n;   // harmless reload of the current stage keeps the loads unconditional
-                }
-            }
-            __syncthreads();   // slab `cur` is complete; nobody still reads the other buffer
-            load_w_regs<S, T>(wreg, Wt, n2, co0, k2, cin, cout);
-            const int32_t j2 = lds_j[n2][slot];
-            load_x_regs<S, T>(b_next, (j2 >= 0 ? X + (int64_t)j2 * cin + k2 : zero_row) + h * S::VEC);
-            if (__ballot(j >= 0) != 0) mma_stage<S, T, NCB>(lds_w[cur], b_now, acc);
-            store_w_regs<S, T>(wreg, lds_w[cur ^ 1]);
+        auto stage = [&](vec(&b_now)[G][S::NKB], int32_t(&j_now)[G], bool(&live_now)[G], vec(&b_next)[G][S::NKB],
+                         int32_t(&j_next)[G], bool(&live_next)[G]) -> bool {
+            __syncthreads();   // slabs `cur` are complete; nobody still reads the other buffer
+            const bool more = it_live;
+            issue_loads(b_next, j_next, live_next);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if (live_now[g] && __ballot(j_now[g] >= 0) != 0) mma_stage<S, T, NCB>(lds_w[cur][g], b_now[g], acc);
+#pragma unroll
+            for (int g = 0; g < G; ++g) store_w_regs<S, T>(wreg[g], lds_w[cur ^ 1][g]);
             cur ^= 1;
-            n = n2;
-            k0 = k2;
-            j = j2;
-            return has_next;
+            return more;
         };
         for (;;) {
-            if (!stage(bx_a, bx_b)) break;
-            if (!stage(bx_b, bx_a)) break;
+            if (!stage(bx_a, j_a, live_a, bx_b, j_b, live_b)) break;
+            if (!stage(bx_b, j_b, live_b, bx_a, j_a, live_a)) break;
         }
     }
     store_rows<T, NCB>(out, perm[tile * kTileRows + slot], cout, co0, acc);
+}
+
+// ---- fused kernel over 32-row groups with an adaptive split of the offsets -----------------------
+// The time of a wave is its chain of dependent memory round trips, one per offset of its
+// group, so a group with many offsets is shared by 2 or 4 waves (each takes every 2nd / 4th
+// rank) whose partial sums meet in LDS and are added in wave order.  Per 128-row tile the
+// split factor sf follows the largest group: sf = 1 -> one workgroup, a wave per group, direct
+// store; sf = 2 / 4 -> two / four workgroups.  grid.x = 4 * tiles; surplus workgroups exit.
+// Weights are read from global memory in MFMA fragment order (k_pack_weights_frag).
+template <class T, int NCB, int KC>
+__global__ void __launch_bounds__(kThreads) k_fused_group(const T *__restrict__ X, const T *__restrict__ Wf,
+                                                          const int32_t *__restrict__ gnbr,
+                                                          const uint32_t *__restrict__ ghdr,
+                                                          const int32_t *__restrict__ perm, T *__restrict__ out,
+                                                          const T *__restrict__ zero_row,
+                                                          const uint32_t *__restrict__ work,
+                                                          const uint32_t *__restrict__ work_count, int cin, int cout,
+                                                          int K3) {
+    typedef Shape<T, NCB, KC> S;
+    typedef typename S::vec vec;
+    constexpr int NKB = S::NKB, COLS = NCB * 32, RSTRIDE = COLS + 4, QUADS = COLS / 4;
+    __shared__ __attribute__((aligned(16))) float red[kWaves][32][RSTRIDE];
+    static_assert(sizeof(float) * 32 * RSTRIDE >= sizeof(T) * 32 * S::STRIDE, "transposition tile must fit in a wave's slice of red");
+    if (blockIdx.x >= *work_count) return;   // the grid is sized for the worst case
+    const uint32_t item = work[blockIdx.x];
+    const int64_t tile = item >> 4;
+    const int b = (item >> 2) & 3;
+    const int sf = 1 << (item & 3);
+    const int co0 = blockIdx.y * COLS;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
+    const int grp = b * (kWaves / sf) + wave / sf;     // group of this wave within the tile
+    const int part = wave % sf;                        // which ranks it takes
+    const int64_t group = tile * 4 + grp;
+    const uint32_t hv = ghdr[group * 8 + (lane & 7)];  // header words, one per lane
+    const int cnt = __builtin_amdgcn_readlane(hv, 0) & 0xff;
+    const int32_t row_out = perm[group * 32 + m];
+    const int32_t *jbase = gnbr + group * K3 * 32 + m;
+    const int nkb_total = cin / S::KSTEP;
+    floatx16 acc[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+        for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
+
+    // Feature rows are fetched with consecutive lanes on consecutive 16-byte pieces of a row
+    // (few cache lines per load instruction: the texture unit serves about one line per two
+    // cycles) and turned into the MFMA operand layout, one row per lane, through a
+    // wave-private LDS tile with padded rows.
+    constexpr int CPR = KC / S::VEC;          // 16-byte pieces per row chunk
+    constexpr int RPI = 64 / CPR;             // rows per load instruction
+    constexpr int RI = 32 / RPI;              // load instructions per chunk
+    T *xt = reinterpret_cast<T *>(&red[0][0][0]) + wave * (32 * S::STRIDE);   // red is not in use yet
+    const int piece = lane % CPR, rsub = lane / CPR;
+
+    int r = part;
+    int32_t j = jbase[(r < cnt ? r : 0) * 32];
+    while (r < cnt) {
+        const int byte = 1 + r;
+        const int n = (__builtin_amdgcn_readlane(hv, byte >> 2) >> (8 * (byte & 3))) & 0xff;
+        const int r_next = r + sf;
+        const int32_t j_next = jbase[(r_next < cnt ? r_next : r) * 32];
+        const T *wsrc = Wf + (((int64_t)n * (cout / 32) + co0 / 32) * nkb_total) * (64 * S::VEC) + lane * S::VEC;
+        const T *xsrc[RI];
+        int xstep[RI];
+#pragma unroll
+        for (int i = 0; i < RI; ++i) {
+            const int32_t jr = __shfl(j, i * RPI + rsub, 64);
+            xsrc[i] = (jr >= 0 ? X + (int64_t)jr * cin : zero_row) + piece * S::VEC;
+            xstep[i] = jr >= 0 ? KC : 0;   // the zero row is one chunk long
+        }
+        for (int k0 = 0, kc = 0; k0 < cin; k0 += KC, ++kc) {
+            vec wa[NCB][NKB], xv[RI], bx[NKB];
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int kb = 0; kb < NKB; ++kb)
+                    wa[cb][kb] = *reinterpret_cast<const vec *>(wsrc + ((int64_t)cb * nkb_total + kc * NKB + kb) * (64 * S::VEC));
+#pragma unroll
+            for (int i = 0; i < RI; ++i) xv[i] = *reinterpret_cast<const vec *>(xsrc[i] + kc * xstep[i]);
+            // keep every load of the stage ahead of its use: the scheduler would otherwise
+            // interleave them to save registers and pay the memory latency several times
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < RI; ++i)
+                *reinterpret_cast<vec *>(xt + (i * RPI + rsub) * S::STRIDE + piece * S::VEC) = xv[i];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) bx[kb] = *reinterpret_cast<const vec *>(xt + m * S::STRIDE + kb * S::KSTEP + h * S::VEC);
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb) mma_step(wa[cb][kb], bx[kb], acc[cb]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        r = r_next;
+        j = j_next;
+    }
+    if (sf > 1) __syncthreads();   // every wave is done with its transposition tile before red is written
+    if (sf == 1) {
+        store_rows<T, NCB>(out, row_out, cout, co0, acc);
+        return;
+    }
+    // partial sums -> LDS, added in part order by the sf waves of the group
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            floatx4 v = {acc[cb][g * 4 + 0], acc[cb][g * 4 + 1], acc[cb][g * 4 + 2], acc[cb][g * 4 + 3]};
+            *reinterpret_cast<floatx4 *>(&red[wave][m][cb * 32 + g * 8 + h * 4]) = v;
+        }
+    __syncthreads();
+    const int w0 = wave - part;   // first wave of this group
+    for (int e = part * 64 + lane; e < 32 * QUADS; e += sf * 64) {
+        const int rr = e / QUADS, q = e % QUADS;
+        const int32_t ro = perm[group * 32 + rr];
+        if (ro < 0) continue;
+        floatx4 sum = *reinterpret_cast<const floatx4 *>(&red[w0][rr][q * 4]);
+        for (int w = 1; w < sf; ++w) sum += *reinterpret_cast<const floatx4 *>(&red[w0 + w][rr][q * 4]);
+        T *dst = out + (int64_t)ro * cout + co0 + q * 4;
+        if constexpr (sizeof(T) == 2) {
+            half4 v = {(_Float16)sum[0], (_Float16)sum[1], (_Float16)sum[2], (_Float16)sum[3]};
+            *reinterpret_cast<half4 *>(dst) = v;
+        } else {
+            *reinterpret_cast<floatx4 *>(dst) = sum;
+        }
+    }
 }
 
 // ---- explicit dataflow ------------------------------------------------------------------------
@@ -318,6 +472,27 @@ __global__ void k_pack_weights(const T *__restrict__ W, T *__restrict__ Wt, int 
     Wt[g] = ci < cin ? W[((int64_t)n * cin + ci) * cout + co] : (T)0;
 }
 
+// Weights in MFMA fragment order for the split-offset kernel:
+// Wf[n][cb][kb][lane][e] = W[n][ci][co] with co = cb*32 + lane%32, ci = kb*KSTEP + (lane/32)*VEC + e
+// (0 for ci >= cin).  One (n, cb, kb) fragment is 64 lanes x 16 bytes, contiguous.
+template <class T>
+__global__ void k_pack_weights_frag(const T *__restrict__ W, T *__restrict__ Wf, int K3, int cin, int cin_pad,
+                                    int cout) {
+    constexpr int VEC = Elem<T>::VEC, KSTEP = Elem<T>::KSTEP;
+    int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (int64_t)K3 * cout * cin_pad;
+    if (g >= total) return;
+    const int nkb = cin_pad / KSTEP;
+    int e = (int)(g % VEC);
+    int lane = (int)((g / VEC) % 64);
+    int kb = (int)((g / (VEC * 64)) % nkb);
+    int cb = (int)((g / ((int64_t)VEC * 64 * nkb)) % (cout / 32));
+    int n = (int)(g / ((int64_t)VEC * 64 * nkb * (cout / 32)));
+    int co = cb * 32 + (lane & 31);
+    int ci = kb * KSTEP + (lane >> 5) * VEC + e;
+    Wf[g] = ci < cin ? W[((int64_t)n * cin + ci) * cout + co] : (T)0;
+}
+
 // Xp[row][c] = X[row][c] for c < cin, 0 up to cin_pad.
 template <class T>
 __global__ void k_pad_rows(const T *__restrict__ X, T *__restrict__ Xp, int64_t rows, int cin, int cin_pad) {
@@ -375,13 +550,18 @@ int check_layer(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap 
 // Transpose/pad the weights into scratch, and pad the features when C_in is not a multiple of
 // the operand step.
 template <class T>
-int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, Prepared *pr) {
+int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, Prepared *pr,
+            bool fragment_order = false) {
     const int cin = feats->cols, cout = weights->cols, ks = Elem<T>::KSTEP;
     const int cin_pad = (cin + ks - 1) / ks * ks;
     pr->cin_pad = cin_pad;
     size_t wn = (size_t)kmap->K3 * cout * cin_pad;
     T *wt = static_cast<T *>(scratch(2, wn * sizeof(T)));
     if (!wt) return TS_ERR_OOM;
+    if (fragment_order)
+        TS_LAUNCH("k_pack_weights", k_pack_weights_frag<T>, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads),
+                  static_cast<const T *>(weights->data), wt, kmap->K3, cin, cin_pad, cout);
+    else
     TS_LAUNCH("k_pack_weights", k_pack_weights<T>, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads), static_cast<const T *>(weights->data), wt, kmap->K3, cin, cin_pad, cout);
     pr->wt = wt;
     pr->x = feats->data;
@@ -416,6 +596,12 @@ void dispatch_shape(int ncb, int ksteps, Fn &&fn) {
 #undef TS_CASE
 }
 
+// (offset, chunk) pairs per pipeline stage of k_fused: narrow shapes have little MFMA work
+// per pair, so several are batched between barriers to shorten the chain of memory latencies.
+constexpr int fused_group(int ncb, int ksteps) {
+    return ncb * ksteps <= 2 ? 4 : (ncb * ksteps <= 8 ? 3 : 1);
+}
+
 template <class T>
 struct FusedLaunch {
     const Prepared &pr;
@@ -425,16 +611,51 @@ struct FusedLaunch {
     template <int NCB, int KSTEPS>
     void operator()() const {
         constexpr int KC = KSTEPS * Elem<T>::KSTEP;
+        constexpr int G = fused_group(NCB, KSTEPS);
         dim3 grid((unsigned)kmap->n_tiles, out->cols / (NCB * 32));
-        TS_LAUNCH("k_fused", (k_fused<T, NCB, KC>), grid, dim3(kThreads), static_cast<const T *>(pr.x),
+        TS_LAUNCH("k_fused", (k_fused<T, NCB, KC, G>), grid, dim3(kThreads), static_cast<const T *>(pr.x),
                   static_cast<const T *>(pr.wt), kmap->d_tnbr, kmap->d_tmask, kmap->d_perm,
                   static_cast<T *>(out->data), zero, pr.cin_pad, out->cols, kmap->K3);
     }
 };
 
 template <class T>
+struct GroupLaunch {
+    const Prepared &pr;
+    const ts_kmap *kmap;
+    ts_tensor *out;
+    const T *zero;
+    template <int NCB, int KSTEPS>
+    void operator()() const {
+        constexpr int KC = KSTEPS * Elem<T>::KSTEP;
+        dim3 grid((unsigned)kmap->n_tiles * 4, out->cols / (NCB * 32));   // worst case: every tile split 4 ways
+        TS_LAUNCH("k_fused_group", (k_fused_group<T, NCB, KC>), grid, dim3(kThreads), static_cast<const T *>(pr.x),
+                  static_cast<const T *>(pr.wt), kmap->d_gnbr, kmap->d_ghdr, kmap->d_perm,
+                  static_cast<T *>(out->data), zero, kmap->d_work, kmap->d_work + kmap->n_tiles * 4, pr.cin_pad,
+                  out->cols, kmap->K3);
+    }
+};
+
+// Narrow layers (C_in of at most 4 operand steps, C_out <= 64) run the group
+// kernel: little MFMA work per offset, so short per-wave chains and many resident waves win.
+// Wider layers run k_fused, which shares each weight slab among four waves through LDS.
+template <class T>
+bool group_applies(int cin_pad, int cout) {
+    return cin_pad <= 4 * Elem<T>::KSTEP && cout <= 64;
+}
+
+template <class T>
 int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
     Prepared pr;
+    const int cin_pad_guess = (feats->cols + Elem<T>::KSTEP - 1) / Elem<T>::KSTEP * Elem<T>::KSTEP;
+    if (group_applies<T>(cin_pad_guess, out->cols)) {
+        TS_TRY(prepare<T>(feats, weights, kmap, &pr, true));
+        const T *zero = static_cast<const T *>(zero_row());
+        if (!zero) return TS_ERR_OOM;
+        dispatch_shape(pick_ncb(out->cols), pick_ksteps(pr.cin_pad, Elem<T>::KSTEP), GroupLaunch<T>{pr, kmap, out, zero});
+        TS_HIP(hipGetLastError());
+        return TS_OK;
+    }
     TS_TRY(prepare<T>(feats, weights, kmap, &pr));
     const T *zero = static_cast<const T *>(zero_row());
     if (!zero) return TS_ERR_OOM;

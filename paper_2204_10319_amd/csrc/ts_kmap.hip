@@ -288,28 +288,75 @@ __global__ void k_row_masks(const int32_t *nbr, int64_t n_out, int K3, uint32_t 
 }
 
 // One block per tile of kTileRows sorted outputs: records the output row of each slot, the
-// tile's offset bitmask, and the neighbour rows of every offset present in the tile.
+// tile's offset bitmask, the neighbour rows of every offset present in the tile, and the same
+// per group of 32 rows in rank order (rank = position among the group's present offsets)
+// with a 32-byte header {count, offset of rank 0, offset of rank 1, ...}.
 __global__ void __launch_bounds__(kTileRows) k_build_tiles(const int32_t *nbr, int64_t n_out, int K3,
                                                             const uint32_t *sorted_masks,
                                                             const int32_t *sorted_rows, int32_t *perm,
-                                                            int32_t *tnbr, uint32_t *tmask) {
+                                                            int32_t *tnbr, uint32_t *tmask, uint32_t *tmask32,
+                                                            int32_t *gnbr, uint32_t *ghdr, uint32_t *work,
+                                                            uint32_t *work_count, int thr1, int thr2) {
     __shared__ uint32_t s_mask;
+    __shared__ int s_max_count;
     int64_t tile = blockIdx.x, r = tile * kTileRows + threadIdx.x;
-    if (threadIdx.x == 0) s_mask = 0;
+    if (threadIdx.x == 0) {
+        s_mask = 0;
+        s_max_count = 0;
+    }
     __syncthreads();
     int32_t k = r < n_out ? sorted_rows[r] : -1;
     uint32_t m = r < n_out ? sorted_masks[r] : 0;
     perm[r] = k;
-    for (int d = 32; d >= 1; d >>= 1) m |= __shfl_xor(m, d, 64);
-    if ((threadIdx.x & 63) == 0) atomicOr(&s_mask, m);
+    for (int d = 16; d >= 1; d >>= 1) m |= __shfl_xor(m, d, 64);
+    const uint32_t gm = m;                  // mask of this thread's group of 32 rows
+    const int64_t group = r >> 5;
+    const int lane32 = threadIdx.x & 31;
+    if (lane32 == 0) {
+        tmask32[group] = gm;
+        atomicOr(&s_mask, gm);
+        atomicMax(&s_max_count, __popc(gm));
+    }
+    // header: byte 0 = count, byte 1+rank = offset index; lanes 0..7 write one word each
+    if (lane32 < 8) {
+        uint32_t word = 0;
+        int rank = 0;
+        for (int n = 0; n < K3; ++n) {
+            if (!((gm >> n) & 1)) continue;
+            int byte = 1 + rank;
+            if ((byte >> 2) == lane32) word |= (uint32_t)n << (8 * (byte & 3));
+            ++rank;
+        }
+        if (lane32 == 0) word |= (uint32_t)rank;
+        ghdr[group * 8 + lane32] = word;
+    }
     __syncthreads();
     uint32_t tm = s_mask;
-    if (threadIdx.x == 0) tmask[tile] = tm;
+    if (threadIdx.x == 0) {
+        tmask[tile] = tm;
+        // work items of the group kernel: a tile whose largest group has many offsets is given
+        // to 2 or 4 workgroups (item = tile << 4 | part << 2 | log2(parts)); list order is
+        // arbitrary and does not affect results
+        const int c = s_max_count;
+        const int lg = c <= thr1 ? 0 : (c <= thr2 ? 1 : 2);
+        const uint32_t base = atomicAdd(work_count, 1u << lg);
+        for (uint32_t i = 0; i < (1u << lg); ++i) work[base + i] = ((uint32_t)tile << 4) | (i << 2) | (uint32_t)lg;
+    }
+    int rank = 0;
     for (int n = 0; n < K3; ++n) {
         if (!((tm >> n) & 1)) continue;
-        tnbr[(tile * K3 + n) * kTileRows + threadIdx.x] = k >= 0 ? nbr[(int64_t)n * n_out + k] : -1;
+        int32_t j = k >= 0 ? nbr[(int64_t)n * n_out + k] : -1;
+        tnbr[(tile * K3 + n) * kTileRows + threadIdx.x] = j;
+        if ((gm >> n) & 1) {
+            gnbr[(group * K3 + rank) * 32 + lane32] = j;
+            ++rank;
+        }
     }
 }
+
+// Largest per-group offset count handled by 1 (which = 1) or 2 (which = 2) workgroups per tile
+// (measured on ~150k-voxel scans: chains of more than ~6 dependent offsets per wave dominate).
+inline int split_thr(int which) { return which == 1 ? 6 : 12; }
 
 inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
@@ -353,6 +400,10 @@ void destroy(ts_kmap *m) {
     dev_free(m->d_perm);
     dev_free(m->d_tnbr);
     dev_free(m->d_tmask);
+    dev_free(m->d_tmask32);
+    dev_free(m->d_gnbr);
+    dev_free(m->d_ghdr);
+    dev_free(m->d_work);
     delete m;
 }
 
@@ -418,7 +469,12 @@ int finish_map(ts_kmap *m, Temps &tmp, int *d_status) {
     TS_TRY(alloc_n(&m->d_perm, (size_t)m->n_tiles * kTileRows));
     TS_TRY(alloc_n(&m->d_tnbr, (size_t)m->n_tiles * K3 * kTileRows));
     TS_TRY(alloc_n(&m->d_tmask, (size_t)m->n_tiles));
-    TS_LAUNCH("k_build_tiles", k_build_tiles, dim3((unsigned)m->n_tiles), dim3(kTileRows), m->d_nbr, n_out, K3, masks_sorted, rows_sorted, m->d_perm, m->d_tnbr, m->d_tmask);
+    TS_TRY(alloc_n(&m->d_tmask32, (size_t)m->n_tiles * (kTileRows / 32)));
+    TS_TRY(alloc_n(&m->d_gnbr, (size_t)m->n_tiles * K3 * kTileRows));
+    TS_TRY(alloc_n(&m->d_ghdr, (size_t)m->n_tiles * (kTileRows / 32) * 8));
+    TS_TRY(alloc_n(&m->d_work, (size_t)m->n_tiles * 4 + 1));
+    TS_HIP(hipMemsetAsync(m->d_work + m->n_tiles * 4, 0, sizeof(uint32_t), st));
+    TS_LAUNCH("k_build_tiles", k_build_tiles, dim3((unsigned)m->n_tiles), dim3(kTileRows), m->d_nbr, n_out, K3, masks_sorted, rows_sorted, m->d_perm, m->d_tnbr, m->d_tmask, m->d_tmask32, m->d_gnbr, m->d_ghdr, m->d_work, m->d_work + m->n_tiles * 4, split_thr(1), split_thr(2));
     TS_HIP(hipGetLastError());
     // temporaries go back to the pool when the caller's Temps dies; later work on the same
     // stream is ordered after the kernels above, so reuse is safe without another wait

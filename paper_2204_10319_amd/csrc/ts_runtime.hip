@@ -156,7 +156,7 @@ hipEvent_t prof_event() {
 
 ProfScope::ProfScope(const char *name) : rec_(-1) {
     if (!g_prof_on) return;
-    if (!g_prof_filter.empty() && g_prof_filter != name) return;
+    if (!g_prof_filter.empty() && strncmp(name, g_prof_filter.c_str(), g_prof_filter.size()) != 0) return;
     ProfRec r{name, prof_event(), prof_event()};
     if (!r.a || !r.b) return;
     (void)hipEventRecord(r.a, g_stream);
