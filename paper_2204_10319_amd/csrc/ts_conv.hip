@@ -153,8 +153,9 @@ __device__ __forceinline__ void store_rows(TO *out, int64_t row, int cout, int c
 // count them: rows without a neighbour read `zero_row` instead.
 template <class T, int NCB, int KC, int G>
 __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, const T *__restrict__ Wt,
-                                                    const int32_t *__restrict__ tnbr,
+                                                    const int32_t *__restrict__ gnbr,
                                                     const uint32_t *__restrict__ tmask,
+                                                    const uint32_t *__restrict__ tmask32,
                                                     const int32_t *__restrict__ perm, T *__restrict__ out,
                                                     const T *__restrict__ zero_row, int cin, int cout, int K3) {
     typedef Shape<T, NCB, KC> S;
@@ -172,24 +173,29 @@ __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, con
         for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
 
     if (mask) {
-        // Neighbour rows of the tile -> LDS.  All loads are issued before the first is used
-        // (a load-wait-store loop over the present offsets would pay one memory latency per
-        // offset); entries of absent offsets hold unspecified values and are never read back.
+        // Neighbour rows of the tile -> LDS, from the per-group rank-ordered lists (the rank of
+        // offset n in a group is the number of lower offsets present in it).  All loads are
+        // issued before the first is used (a load-wait-store loop over the offsets would pay
+        // one memory latency per offset).
         {
             constexpr int PER = (kMaxK3 + 1) / 2;
             const int half = threadIdx.x >> 7, col = threadIdx.x & 127;
+            const int64_t group = tile * 4 + (col >> 5);
+            const uint32_t gm = tmask32[group];
+            const int32_t *src = gnbr + group * K3 * 32 + (col & 31);
             int32_t v[PER];
 #pragma unroll
             for (int i = 0; i < PER; ++i) {
-                int n = 2 * i + half;
-                n = n < K3 ? n : K3 - 1;
-                v[i] = tnbr[(tile * K3 + n) * kTileRows + col];
+                const int n = 2 * i + half;
+                const bool present = n < K3 && ((gm >> n) & 1);
+                const int rank = present ? __builtin_popcount(gm & ((1u << n) - 1)) : 0;
+                v[i] = src[rank * 32];
             }
 #pragma unroll
             for (int i = 0; i < PER; ++i) {
-                int n = 2 * i + half;
-                n = n < K3 ? n : K3 - 1;
-                lds_j[n][col] = v[i];
+                const int n = 2 * i + half;
+                const bool present = n < K3 && ((gm >> n) & 1);
+                if (n < K3) lds_j[n][col] = present ? v[i] : -1;
             }
         }
         // Iterator over the tile's (offset, chunk) pairs; a stage takes the next G of them.
@@ -614,7 +620,7 @@ struct FusedLaunch {
         constexpr int G = fused_group(NCB, KSTEPS);
         dim3 grid((unsigned)kmap->n_tiles, out->cols / (NCB * 32));
         TS_LAUNCH("k_fused", (k_fused<T, NCB, KC, G>), grid, dim3(kThreads), static_cast<const T *>(pr.x),
-                  static_cast<const T *>(pr.wt), kmap->d_tnbr, kmap->d_tmask, kmap->d_perm,
+                  static_cast<const T *>(pr.wt), kmap->d_gnbr, kmap->d_tmask, kmap->d_tmask32, kmap->d_perm,
                   static_cast<T *>(out->data), zero, pr.cin_pad, out->cols, kmap->K3);
     }
 };

@@ -109,7 +109,6 @@ struct ts_kmap {
     // output-stationary tiles of the fused kernel: outputs sorted by their neighbour bitmask
     int64_t n_tiles = 0;
     int32_t *d_perm = nullptr;            // [n_tiles*kTileRows] sorted position -> output row, -1 = padding
-    int32_t *d_tnbr = nullptr;            // [n_tiles][K3][kTileRows] input row or -1
     uint32_t *d_tmask = nullptr;          // [n_tiles] OR of the rows' neighbour bitmasks
     uint32_t *d_tmask32 = nullptr;        // [n_tiles*4] the same per group of 32 rows
     int32_t *d_gnbr = nullptr;            // [n_tiles*4][K3][32] per group: input rows in rank order

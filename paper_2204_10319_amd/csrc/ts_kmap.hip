@@ -24,7 +24,7 @@ namespace {
 constexpr int kThreads = 256;
 
 // status words written by the kernels and read back once per build
-enum { ST_RANGE = 0, ST_DUP = 1, ST_WORDS = 8 };
+enum { ST_RANGE = 0, ST_DUP = 1, ST_TOTALS = 8, ST_WORDS = 8 + 32 };   // ST_TOTALS: per-offset map sizes
 
 struct Table {
     uint64_t *keys;
@@ -101,6 +101,24 @@ __global__ void k_insert(const uint64_t *keys, int64_t n, Table t, int32_t *cent
     if (key == kEmptyKey) return;
     table_insert(t, key, (int32_t)i, status);
     if (centre_row) centre_row[i] = (int32_t)i;
+}
+
+// Stride-1 front end in one pass: pack, insert (key -> i) and write the identity map of the
+// centre offset (output i is input i).
+__global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, Table t, int32_t *centre_row,
+                              int *status) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    int4 c = coords[i];
+    if (!coord_ok(c)) {
+        atomicOr(&status[ST_RANGE], 1);
+        keys[i] = kEmptyKey;
+        return;
+    }
+    uint64_t key = pack_key(c.x, c.y, c.z, c.w);
+    keys[i] = key;
+    table_insert(t, key, (int32_t)i, status);
+    centre_row[i] = (int32_t)i;
 }
 
 // Stride 1, odd K: blockIdx.y = offset index n < K^3/2.  A hit (j at p_i + delta_n) gives the
@@ -192,7 +210,7 @@ __global__ void k_unpack(const uint64_t *keys, int64_t n, int4 *coords) {
 }
 
 // ---- per-offset compaction -------------------------------------------------------------------
-constexpr int kItems = 4;                        // entries per thread
+constexpr int kItems = 1;                        // entries per thread
 constexpr int kChunk = kThreads * kItems;        // entries per block
 
 __device__ __forceinline__ int block_exclusive_scan(int v, int *total) {
@@ -216,35 +234,63 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *total) {
     return base + incl - v;
 }
 
-// blkcnt[n][b] = number of valid entries of nbr[n][b*kChunk .. +kChunk)
-__global__ void k_count(const int32_t *nbr, int64_t n_out, int nblk, int32_t *blkcnt) {
-    int n = blockIdx.y, b = blockIdx.x;
-    const int32_t *row = nbr + (int64_t)n * n_out;
-    int c = 0;
-    for (int it = 0; it < kItems; ++it) {
-        int64_t k = (int64_t)b * kChunk + it * kThreads + threadIdx.x;
-        if (k < n_out && row[k] >= 0) ++c;
+// One pass over the neighbour table: blkcnt[n][b] = number of valid entries of
+// nbr[n][b*kChunk .. +kChunk), and per output its neighbour bitmask (plus the identity row list
+// that the mask sort permutes).
+__global__ void k_count_masks(const int32_t *nbr, int64_t n_out, int nblk, int K3, int32_t *blkcnt, uint32_t *masks,
+                              int32_t *rows, int *totals) {
+    __shared__ int s_cnt[kMaxK3];
+    static_assert(kItems == 1, "one output per thread");
+    const int b = blockIdx.x;
+    if (threadIdx.x < kMaxK3) s_cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t k = (int64_t)b * kChunk + threadIdx.x;
+    const int64_t kc = k < n_out ? k : n_out - 1;
+    int32_t v[kMaxK3];
+#pragma unroll
+    for (int n = 0; n < kMaxK3; ++n) v[n] = nbr[(int64_t)(n < K3 ? n : K3 - 1) * n_out + kc];   // all loads first
+    uint32_t m = 0;
+#pragma unroll
+    for (int n = 0; n < kMaxK3; ++n)
+        if (n < K3 && k < n_out && v[n] >= 0) m |= 1u << n;
+#pragma unroll
+    for (int n = 0; n < kMaxK3; ++n) {
+        const int c = __popcll(__ballot((m >> n) & 1));
+        if ((threadIdx.x & 63) == 0 && c) atomicAdd(&s_cnt[n], c);
     }
-    int total;
-    block_exclusive_scan(c, &total);
-    if (threadIdx.x == 0) blkcnt[(int64_t)n * nblk + b] = total;
+    if (k < n_out) {
+        masks[k] = m;
+        rows[k] = (int32_t)k;
+    }
+    __syncthreads();
+    if (threadIdx.x < K3) {
+        blkcnt[(int64_t)threadIdx.x * nblk + b] = s_cnt[threadIdx.x];
+        if (s_cnt[threadIdx.x]) atomicAdd(&totals[threadIdx.x], s_cnt[threadIdx.x]);
+    }
 }
 
-// Exclusive scan of blkcnt (offset-major) in place; offs[n] = start of offset n, offs[K3] = |M|.
-__global__ void k_scan_counts(int32_t *blkcnt, int64_t entries, int nblk, int K3, int32_t *offs) {
-    int64_t per = (entries + kThreads - 1) / kThreads;
-    int64_t lo = (int64_t)threadIdx.x * per, hi = lo + per < entries ? lo + per : entries;
+// Exclusive scan of blkcnt (offset-major) in place, one block per offset: the start of offset n
+// is the sum of the totals before it.  offs[n] = start of offset n, offs[K3] = |M|.
+__global__ void k_scan_counts(int32_t *blkcnt, int nblk, int K3, const int *totals, int32_t *offs) {
+    const int n = blockIdx.x;
+    int start = 0;
+    for (int q = 0; q < n; ++q) start += totals[q];
+    int32_t *row = blkcnt + (int64_t)n * nblk;
+    const int per = (nblk + kThreads - 1) / kThreads;
+    const int lo = threadIdx.x * per, hi = lo + per < nblk ? lo + per : nblk;
     int sum = 0;
-    for (int64_t e = lo; e < hi; ++e) sum += blkcnt[e];
+    for (int e = lo; e < hi; ++e) sum += row[e];
     int total;
-    int run = block_exclusive_scan(sum, &total);
-    for (int64_t e = lo; e < hi; ++e) {
-        int c = blkcnt[e];
-        blkcnt[e] = run;
-        if (e % nblk == 0) offs[e / nblk] = run;
+    int run = start + block_exclusive_scan(sum, &total);
+    for (int e = lo; e < hi; ++e) {
+        int c = row[e];
+        row[e] = run;
         run += c;
     }
-    if (threadIdx.x == 0) offs[K3] = total;
+    if (threadIdx.x == 0) {
+        offs[n] = start;
+        if (n == K3 - 1) offs[K3] = start + total;
+    }
 }
 
 // Write pairs and positions.  Block (b, n) owns entries [b*kChunk, +kChunk) of offset n; its
@@ -276,26 +322,14 @@ __global__ void k_compact(const int32_t *nbr, int64_t n_out, int nblk, const int
     }
 }
 
-// ---- tiles for the output-stationary kernel ----------------------------------------------------
-__global__ void k_row_masks(const int32_t *nbr, int64_t n_out, int K3, uint32_t *masks, int32_t *rows) {
-    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= n_out) return;
-    uint32_t m = 0;
-    for (int n = 0; n < K3; ++n)
-        if (nbr[(int64_t)n * n_out + k] >= 0) m |= 1u << n;
-    masks[k] = m;
-    rows[k] = (int32_t)k;
-}
-
+// ---- tiles for the output-stationary kernels ---------------------------------------------------
 // One block per tile of kTileRows sorted outputs: records the output row of each slot, the
-// tile's offset bitmask, the neighbour rows of every offset present in the tile, and the same
-// per group of 32 rows in rank order (rank = position among the group's present offsets)
+// tile's offset bitmask, and per group of 32 rows the neighbour rows in rank order (rank = position among the group's present offsets)
 // with a 32-byte header {count, offset of rank 0, offset of rank 1, ...}.
 __global__ void __launch_bounds__(kTileRows) k_build_tiles(const int32_t *nbr, int64_t n_out, int K3,
                                                             const uint32_t *sorted_masks,
                                                             const int32_t *sorted_rows, int32_t *perm,
-                                                            int32_t *tnbr, uint32_t *tmask, uint32_t *tmask32,
-                                                            int32_t *gnbr, uint32_t *ghdr, uint32_t *work,
+                                                            uint32_t *tmask, uint32_t *tmask32, int32_t *gnbr, uint32_t *ghdr, uint32_t *work,
                                                             uint32_t *work_count, int thr1, int thr2) {
     __shared__ uint32_t s_mask;
     __shared__ int s_max_count;
@@ -344,13 +378,9 @@ __global__ void __launch_bounds__(kTileRows) k_build_tiles(const int32_t *nbr, i
     }
     int rank = 0;
     for (int n = 0; n < K3; ++n) {
-        if (!((tm >> n) & 1)) continue;
-        int32_t j = k >= 0 ? nbr[(int64_t)n * n_out + k] : -1;
-        tnbr[(tile * K3 + n) * kTileRows + threadIdx.x] = j;
-        if ((gm >> n) & 1) {
-            gnbr[(group * K3 + rank) * 32 + lane32] = j;
-            ++rank;
-        }
+        if (!((gm >> n) & 1)) continue;
+        gnbr[(group * K3 + rank) * 32 + lane32] = k >= 0 ? nbr[(int64_t)n * n_out + k] : -1;
+        ++rank;
     }
 }
 
@@ -398,7 +428,6 @@ void destroy(ts_kmap *m) {
     dev_free(m->d_out_idx);
     dev_free(m->d_offs);
     dev_free(m->d_perm);
-    dev_free(m->d_tnbr);
     dev_free(m->d_tmask);
     dev_free(m->d_tmask32);
     dev_free(m->d_gnbr);
@@ -426,8 +455,14 @@ int finish_map(ts_kmap *m, Temps &tmp, int *d_status) {
     int32_t *blkcnt;
     TS_TRY(tmp.get(&blkcnt, (size_t)K3 * nblk));
     TS_TRY(alloc_n(&m->d_offs, K3 + 1));
-    TS_LAUNCH("k_count", k_count, dim3(nblk, K3), dim3(kThreads), m->d_nbr, n_out, nblk, blkcnt);
-    TS_LAUNCH("k_scan_counts", k_scan_counts, dim3(1), dim3(kThreads), blkcnt, (int64_t)K3 * nblk, nblk, K3, m->d_offs);
+    uint32_t *masks, *masks_sorted;
+    int32_t *rows, *rows_sorted;
+    TS_TRY(tmp.get(&masks, (size_t)n_out));
+    TS_TRY(tmp.get(&masks_sorted, (size_t)n_out));
+    TS_TRY(tmp.get(&rows, (size_t)n_out));
+    TS_TRY(tmp.get(&rows_sorted, (size_t)n_out));
+    TS_LAUNCH("k_count_masks", k_count_masks, dim3(nblk), dim3(kThreads), m->d_nbr, n_out, nblk, K3, blkcnt, masks, rows, d_status + ST_TOTALS);
+    TS_LAUNCH("k_scan_counts", k_scan_counts, dim3(K3), dim3(kThreads), blkcnt, nblk, K3, d_status + ST_TOTALS, m->d_offs);
 
     // the one host round trip: status flags and the per-offset starts
     int32_t *h = static_cast<int32_t *>(host_staging((ST_WORDS + kMaxK3 + 1) * sizeof(int32_t)));
@@ -449,13 +484,6 @@ int finish_map(ts_kmap *m, Temps &tmp, int *d_status) {
     TS_LAUNCH("k_compact", k_compact, dim3(nblk, K3), dim3(kThreads), m->d_nbr, n_out, nblk, blkcnt, m->d_in_idx, m->d_out_idx, m->d_pos);
 
     // tiles: outputs ordered by neighbour bitmask so that a tile's rows share their offsets
-    uint32_t *masks, *masks_sorted;
-    int32_t *rows, *rows_sorted;
-    TS_TRY(tmp.get(&masks, (size_t)n_out));
-    TS_TRY(tmp.get(&masks_sorted, (size_t)n_out));
-    TS_TRY(tmp.get(&rows, (size_t)n_out));
-    TS_TRY(tmp.get(&rows_sorted, (size_t)n_out));
-    TS_LAUNCH("k_row_masks", k_row_masks, dim3(blocks_for(n_out, kThreads)), dim3(kThreads), m->d_nbr, n_out, K3, masks, rows);
     size_t bytes = 0;
     TS_HIP(rocprim::radix_sort_pairs(nullptr, bytes, masks, masks_sorted, rows, rows_sorted, (size_t)n_out, 0, K3,
                                      st));
@@ -467,14 +495,13 @@ int finish_map(ts_kmap *m, Temps &tmp, int *d_status) {
     }
     m->n_tiles = (n_out + kTileRows - 1) / kTileRows;
     TS_TRY(alloc_n(&m->d_perm, (size_t)m->n_tiles * kTileRows));
-    TS_TRY(alloc_n(&m->d_tnbr, (size_t)m->n_tiles * K3 * kTileRows));
     TS_TRY(alloc_n(&m->d_tmask, (size_t)m->n_tiles));
     TS_TRY(alloc_n(&m->d_tmask32, (size_t)m->n_tiles * (kTileRows / 32)));
     TS_TRY(alloc_n(&m->d_gnbr, (size_t)m->n_tiles * K3 * kTileRows));
     TS_TRY(alloc_n(&m->d_ghdr, (size_t)m->n_tiles * (kTileRows / 32) * 8));
     TS_TRY(alloc_n(&m->d_work, (size_t)m->n_tiles * 4 + 1));
     TS_HIP(hipMemsetAsync(m->d_work + m->n_tiles * 4, 0, sizeof(uint32_t), st));
-    TS_LAUNCH("k_build_tiles", k_build_tiles, dim3((unsigned)m->n_tiles), dim3(kTileRows), m->d_nbr, n_out, K3, masks_sorted, rows_sorted, m->d_perm, m->d_tnbr, m->d_tmask, m->d_tmask32, m->d_gnbr, m->d_ghdr, m->d_work, m->d_work + m->n_tiles * 4, split_thr(1), split_thr(2));
+    TS_LAUNCH("k_build_tiles", k_build_tiles, dim3((unsigned)m->n_tiles), dim3(kTileRows), m->d_nbr, n_out, K3, masks_sorted, rows_sorted, m->d_perm, m->d_tmask, m->d_tmask32, m->d_gnbr, m->d_ghdr, m->d_work, m->d_work + m->n_tiles * 4, split_thr(1), split_thr(2));
     TS_HIP(hipGetLastError());
     // temporaries go back to the pool when the caller's Temps dies; later work on the same
     // stream is ordered after the kernels above, so reuse is safe without another wait
@@ -499,7 +526,8 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
     uint64_t *given;   // keys of the caller's coordinates
     TS_TRY(alloc_n(&given, (size_t)N));
     m->d_in_keys = given;   // provisional owner, so that an early error frees it
-    TS_LAUNCH("k_pack", k_pack, dim3(blocks_for(N, kThreads)), dim3(kThreads), reinterpret_cast<const int4 *>(coords), N, given, d_status);
+    if (s != 1)
+        TS_LAUNCH("k_pack", k_pack, dim3(blocks_for(N, kThreads)), dim3(kThreads), reinterpret_cast<const int4 *>(coords), N, given, d_status);
 
     Table table;
     if (s == 1) {
@@ -511,7 +539,7 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             TS_HIP(hipMemsetAsync(m->d_nbr, 0xFF, (size_t)K3 * N * sizeof(int32_t), st));
         }
         TS_TRY(make_table(tmp, N, &table));
-        TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, table, m->d_nbr + (int64_t)m->centre * N, d_status);
+        TS_LAUNCH("k_pack_insert", k_pack_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), reinterpret_cast<const int4 *>(coords), N, given, table, m->d_nbr + (int64_t)m->centre * N, d_status);
         if (K3 > 1)
             TS_LAUNCH("k_probe_symmetric", k_probe_symmetric, dim3(blocks_for(N, kThreads), K3 / 2), dim3(kThreads), given, N, table, K, m->d_nbr);
     } else {
