@@ -2,11 +2,14 @@
 """Benchmark of the sparse-convolution hot path on one MI355X.
 
 A "step" is one pass of the whole path over the ~150k-voxel LiDAR-like workload
-(config 3): ts_build_kmap (pack, hash build, probe, compaction, tile sort) followed by
-ts_sparse_conv (fused output-stationary kernel), C_in = C_out = 64, fp16 in / fp32
-accumulate, inputs resident in HBM.  Prints one JSON line (see README/DESIGN for fields).
+(config 3): ts_build_kmap (pack + hash build, probe, per-offset compaction, mask sort,
+tiles) followed by ts_sparse_conv (fused output-stationary kernel), C_in = C_out = 64,
+fp16 in / fp32 accumulate, inputs resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--channels C]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--channels C] [--no-cpu-baseline]
+    python bench.py --pmc-run      # short run for `rocprofv3 --pmc ...`: a few steps plus three
+                                   # 256 MiB plain copies that calibrate the byte counters
+    python bench.py --sweep        # adds the layer at 10x the voxels (batch-tiled scene)
 """
 import argparse
 import json
@@ -20,13 +23,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, vendor figure
+COPY_BYTES = 256 << 20
 
 
 def fused_conv_bytes(n_in, n_out, m, c_in, c_out, k3, b):
-    """Algorithmic HBM bytes of one fused layer: read X_in once, write X_out once, the map's
-    index pairs, the weights."""
+    """Algorithmic HBM bytes of one fused layer: X_in read once, X_out written once, the map's
+    (in, out) index pairs, the weights."""
     return n_in * c_in * b + n_out * c_out * b + 8 * m + k3 * c_in * c_out * b
 
 
@@ -44,6 +48,19 @@ def kmap_bytes(n, m, k3, table_slots):
     return 16 * n + 12 * table_slots + 12 * n + (k3 - 1) // 2 * n * 8 + 8 * m + 8 * m
 
 
+def read_traffic(kernel, workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, calibrated);
+    kept in profiles/traffic.txt as 'kernel workload fetch_bytes write_bytes'."""
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) == 4 and parts[0] == kernel and parts[1] == workload:
+            return int(float(parts[2]) + float(parts[3]))
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -51,6 +68,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--channels", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-run", action="store_true")
+    ap.add_argument("--sweep", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -59,7 +78,7 @@ def main():
 
     import torch
     from paper_2204_10319_amd import binding as ts
-    from workloads import lidar_scan_coords, features, conv_weights
+    from workloads import lidar_scan_coords, tile_batches, features, conv_weights
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -83,11 +102,25 @@ def main():
         ts.ts_sparse_conv(x, w, kmap, out)
         return kmap
 
+    if args.pmc_run:
+        src = torch.zeros(COPY_BYTES // 4, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            step().free()
+        for _ in range(3):
+            ts.ts_copy_bytes(dst, src)
+        for _ in range(5):
+            step().free()
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_run": True, "copy_bytes": COPY_BYTES, "N": int(N)}))
+        return
+
     for _ in range(args.warmup):
         step().free()
     torch.cuda.synchronize()
 
     # ---- timed region: exactly `steps` steps; the dominant kernel is bracketed by HIP events
+    # recorded by the library on its stream
     dominant = "k_fused"
     ts.ts_profile_enable(True, dominant)
     torch.cuda.synchronize()
@@ -104,7 +137,7 @@ def main():
     launches, total_ms = prof[dom_name]
     dom_us = total_ms * 1e3 / launches
 
-    # ---- untimed extras: per-kernel breakdown of a step, and the layer alone at several widths
+    # ---- untimed extras: per-kernel breakdown of a step, copy reference, the layer at several widths
     kmap = ts.ts_build_kmap(coords, K, 1)
     M = kmap.num_pairs
     sizes = kmap.sizes()
@@ -112,7 +145,14 @@ def main():
     for _ in range(20):
         step().free()
     per_kernel = {k: round(v[1] * 1e3 / 20, 2) for k, v in ts.ts_profile_read().items()}   # us per step
+    src = torch.zeros(COPY_BYTES // 4, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(13):
+        ts.ts_copy_bytes(dst, src)
+    cp = ts.ts_profile_read()["k_copy_bytes"]
+    copy_gbs = 2 * COPY_BYTES / (cp[1] / cp[0] * 1e-3) * 1e-9
     ts.ts_profile_enable(False)
+    del src, dst
 
     def time_calls(fn, iters=50):
         for _ in range(5):
@@ -125,42 +165,54 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) * 1e3 / iters   # us
 
-    kmap_us = time_calls(lambda: ts.ts_build_kmap(coords, K, 1).free(), 30)
-    layers = {}
-    for c in (32, 64, 128):
-        xc = torch.from_numpy(features(300 + c, N, c, np.float16)).cuda()
+    def layer_report(km, n, m, c):
+        xc = torch.from_numpy(features(300 + c, n, c, np.float16)).cuda()
         wc = torch.from_numpy(conv_weights(301 + c, K3, c, c, np.float16)).cuda()
-        oc = torch.empty((N, c), dtype=torch.float16, device="cuda")
-        fused_us = time_calls(lambda: ts.ts_sparse_conv(xc, wc, kmap, oc, ts.TS_DATAFLOW_FUSED))
-        expl_us = time_calls(lambda: ts.ts_sparse_conv(xc, wc, kmap, oc, ts.TS_DATAFLOW_EXPLICIT))
+        oc = torch.empty((n, c), dtype=torch.float16, device="cuda")
+        fused_us = time_calls(lambda: ts.ts_sparse_conv(xc, wc, km, oc, ts.TS_DATAFLOW_FUSED), 30)
+        expl_us = time_calls(lambda: ts.ts_sparse_conv(xc, wc, km, oc, ts.TS_DATAFLOW_EXPLICIT), 30)
         ts.ts_profile_enable(True)
         for _ in range(20):
-            ts.ts_sparse_conv(xc, wc, kmap, oc, ts.TS_DATAFLOW_EXPLICIT)
-            ts.ts_sparse_conv(xc, wc, kmap, oc, ts.TS_DATAFLOW_FUSED)
+            ts.ts_sparse_conv(xc, wc, km, oc, ts.TS_DATAFLOW_EXPLICIT)
+            ts.ts_sparse_conv(xc, wc, km, oc, ts.TS_DATAFLOW_FUSED)
         pk = {k: v[1] * 1e3 / v[0] for k, v in ts.ts_profile_read().items()}
-        fused_name = [k for k in pk if k.startswith("k_fused")][0]
-        pk["k_fused"] = pk[fused_name]
         ts.ts_profile_enable(False)
-        m_moved = M - N   # the centre offset is not gathered
-        gb, mb, sb = explicit_stage_bytes(N, N, M, m_moved, c, c, K3, 2)
-        fb = fused_conv_bytes(N, N, M, c, c, K3, 2)
-        flops = 2.0 * M * c * c
-        layers[f"C{c}"] = {
-            "fused_layer_us": round(fused_us, 2), "explicit_layer_us": round(expl_us, 2), "fused_kernel": fused_name,
-            "k_fused_us": round(pk["k_fused"], 2),
-            "k_fused_GBs": round(fb / pk["k_fused"] * 1e-3, 1),
-            "k_fused_frac_hbm": round(fb / pk["k_fused"] * 1e-3 / HBM_PEAK_GBS, 4),
-            "k_fused_TFLOPs": round(flops / pk["k_fused"] * 1e-6, 1),
-            "k_fused_frac_mfma": round(flops / pk["k_fused"] * 1e-6 / MFMA_F16_PEAK_TFLOPS, 4),
+        fused_name = [k for k in pk if k.startswith("k_fused")][0]
+        fu = pk[fused_name]
+        gb, mb, sb = explicit_stage_bytes(n, n, m, m - n, c, c, K3, 2)   # the centre offset is not gathered
+        fb = fused_conv_bytes(n, n, m, c, c, K3, 2)
+        flops = 2.0 * m * c * c
+        return {
+            "fused_layer_us": round(fused_us, 2), "explicit_layer_us": round(expl_us, 2),
+            "fused_kernel": fused_name, "k_fused_us": round(fu, 2),
+            "k_fused_GBs": round(fb / fu * 1e-3, 1), "k_fused_frac_hbm": round(fb / fu * 1e-3 / HBM_PEAK_GBS, 4),
+            "k_fused_TFLOPs": round(flops / fu * 1e-6, 1),
+            "k_fused_frac_mfma": round(flops / fu * 1e-6 / MFMA_F16_PEAK_TFLOPS, 4),
             "k_gather_us": round(pk["k_gather"], 2), "k_gather_GBs": round(gb / pk["k_gather"] * 1e-3, 1),
             "k_grouped_mm_us": round(pk["k_grouped_mm"], 2),
             "k_grouped_mm_GBs": round(mb / pk["k_grouped_mm"] * 1e-3, 1),
             "k_grouped_mm_TFLOPs": round(flops / pk["k_grouped_mm"] * 1e-6, 1),
+            "k_grouped_mm_frac_mfma": round(flops / pk["k_grouped_mm"] * 1e-6 / MFMA_F16_PEAK_TFLOPS, 4),
             "k_scatter_reduce_us": round(pk["k_scatter_reduce"], 2),
             "k_scatter_reduce_GBs": round(sb / pk["k_scatter_reduce"] * 1e-3, 1),
         }
+
+    kmap_us = time_calls(lambda: ts.ts_build_kmap(coords, K, 1).free(), 30)
+    layers = {f"C{c}": layer_report(kmap, N, M, c) for c in (32, 64, 128)}
     table_slots = 1 << int(np.ceil(np.log2(2 * N)))
     kb = kmap_bytes(N, M, K3, table_slots)
+    breakdown = {"kmap_build_us": round(kmap_us, 1), "kmap_algorithmic_bytes": int(kb),
+                 "kmap_GBs": round(kb / kmap_us * 1e-3, 1), "copy_kernel_GBs": round(copy_gbs, 1),
+                 "per_kernel_us_per_step": per_kernel, "layers": layers}
+
+    if args.sweep:
+        big_h = tile_batches(coords_h, 10)
+        big = torch.from_numpy(big_h).cuda()
+        kbig = ts.ts_build_kmap(big, K, 1)
+        breakdown["sweep_10x"] = {"N": int(big_h.shape[0]), "M": int(kbig.num_pairs),
+                                  "kmap_build_us": round(time_calls(lambda: ts.ts_build_kmap(big, K, 1).free(), 10), 1),
+                                  "C64": layer_report(kbig, big_h.shape[0], kbig.num_pairs, 64)}
+        kbig.free()
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores (whole config-3 layer)
     cpu = None
@@ -179,6 +231,7 @@ def main():
 
     fb = fused_conv_bytes(N, N, M, C, C, K3, 2)
     achieved = fb / dom_us * 1e-3   # GB/s
+    workload = f"config3_C{C}"
     result = {
         "metric": "sparse_conv_layer_latency_ms (kernel-map build + one 3x3x3 submanifold layer, ~150k voxels)",
         "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -188,14 +241,13 @@ def main():
                    "M": int(M), "C_in": C, "C_out": C, "kernel": 3, "stride": 1,
                    "map_sizes": [int(s) for s in sizes]},
         "roofline": {"kernel": dom_name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": read_traffic(dom_name, workload),
                      "avg_us": round(dom_us, 2), "algorithmic_bytes": int(fb),
                      "mfma_tflops": round(2.0 * M * C * C / dom_us * 1e-6, 1),
                      "mfma_frac": round(2.0 * M * C * C / dom_us * 1e-6 / MFMA_F16_PEAK_TFLOPS, 4)},
         "cpu_baseline": cpu,
-        "breakdown": {"kmap_build_us": round(kmap_us, 1), "kmap_algorithmic_bytes": int(kb),
-                      "kmap_GBs": round(kb / kmap_us * 1e-3, 1), "per_kernel_us_per_step": per_kernel,
-                      "layers": layers},
+        "breakdown": breakdown,
     }
     print(json.dumps(result))
 

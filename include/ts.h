@@ -169,6 +169,13 @@ int ts_set_stream(void *hip_stream);
 /* Free the library's cached scratch and pooled device memory (synchronises the device). */
 int ts_release_cache(void);
 /*
+ * Plain device-to-device streaming copy kernel (dst, src: device, 16-byte aligned; bytes a
+ * multiple of 16; buffers must not overlap).  Not part of the layer: benchmarks use it as the
+ * achievable-bandwidth reference and to calibrate hardware byte counters against a known size.
+ */
+int ts_copy_bytes(void *dst, const void *src, size_t bytes);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, the library brackets each kernel launch
  * (or library sort) with a hipEvent pair on its stream; `only`, when not NULL/empty, restricts
  * this to the kernels whose name starts with it.  ts_profile_read synchronises the stream, writes one

@@ -28,7 +28,7 @@ EXPORTS = [
     "ts_build_kmap", "ts_free", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
-    "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read",
+    "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes",
 ]
 
 
@@ -79,6 +79,8 @@ def load_library(path: str | None = None):
                  "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_set_stream",
                  "ts_release_cache"):
         getattr(lib, name).restype = ci
+    lib.ts_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t]
+    lib.ts_copy_bytes.restype = ci
     lib.ts_profile_enable.argtypes = [ci, ctypes.c_char_p]
     lib.ts_profile_enable.restype = ci
     lib.ts_profile_read.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
@@ -127,6 +129,15 @@ def ts_release_cache():
 
 def ts_version() -> str:
     return load_library().ts_version().decode()
+
+
+def ts_copy_bytes(dst: torch.Tensor, src: torch.Tensor):
+    """Plain streaming copy of src into dst (same byte size), for bandwidth reference/calibration."""
+    _use_current_stream()
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("size mismatch")
+    _check(load_library().ts_copy_bytes(dst.data_ptr(), src.data_ptr(), nbytes))
 
 
 def ts_profile_enable(on: bool, only: str | None = None):

@@ -170,7 +170,31 @@ ProfScope::~ProfScope() {
 
 }  // namespace ts
 
+// Plain streaming copy, 16 bytes per thread per step (grid-stride).
+__global__ void k_copy_bytes(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n_vec) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n_vec; i += stride) dst[i] = src[i];
+}
+
 extern "C" {
+
+int ts_copy_bytes(void *dst, const void *src, size_t bytes) {
+    if (!dst || !src) return ts::fail(TS_ERR_INVALID_ARG, "NULL pointer");
+    if ((bytes & 15) || (reinterpret_cast<uintptr_t>(dst) & 15) || (reinterpret_cast<uintptr_t>(src) & 15))
+        return ts::fail(TS_ERR_INVALID_ARG, "pointers and size must be multiples of 16 bytes");
+    if (bytes == 0) return TS_OK;
+    const size_t n_vec = bytes / 16;
+    size_t blocks = (n_vec + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;   // 32 workgroups per CU, grid-stride beyond that
+    {
+        ts::ProfScope ps("k_copy_bytes");
+        hipLaunchKernelGGL(k_copy_bytes, dim3((unsigned)blocks), dim3(256), 0, ts::g_stream,
+                           static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n_vec);
+    }
+    TS_HIP(hipGetLastError());
+    return TS_OK;
+}
 
 int ts_profile_enable(int on, const char *only) {
     ts::g_prof_on = on != 0;
