@@ -205,6 +205,20 @@ def main():
                  "kmap_GBs": round(kb / kmap_us * 1e-3, 1), "copy_kernel_GBs": round(copy_gbs, 1),
                  "per_kernel_us_per_step": per_kernel, "layers": layers}
 
+    # ---- config 5: MinkUNet-style forward pass on the same scene (maps built once, then the 45 convs)
+    from paper_2204_10319_amd.network import SparseNet
+    from workloads.minkunet import build_plan, make_params
+    ops, net_out = build_plan(4)
+    params = {k: (torch.from_numpy(wt).cuda(), torch.from_numpy(bs).cuda()) for k, (wt, bs) in make_params(50, ops).items()}
+    net = SparseNet(ops, net_out, params)
+    x4 = torch.from_numpy(features(51, N, 4, np.float16)).cuda()
+    maps_us = time_calls(lambda: SparseNet.free_maps(net.build_maps(coords)[0]), 5)
+    maps, _ = net.build_maps(coords)
+    fwd_us = time_calls(lambda: net.forward(maps, x4), 10)
+    SparseNet.free_maps(maps)
+    breakdown["config5_network"] = {"maps_build_ms": round(maps_us * 1e-3, 3), "forward_ms": round(fwd_us * 1e-3, 3),
+                                    "convs": sum(1 for k, _ in ops if k == "conv"), "maps": 17}
+
     if args.sweep:
         big_h = tile_batches(coords_h, 10)
         big = torch.from_numpy(big_h).cuda()

@@ -162,6 +162,17 @@ int ts_grouped_matmul(const ts_tensor *F, const ts_tensor *feats, const ts_tenso
                       const ts_kmap *kmap, ts_tensor *G);
 int ts_scatter_reduce(const ts_tensor *G, const ts_kmap *kmap, ts_tensor *out);
 
+/* ---- elementwise steps between layers (not in the paper; needed to chain layers into a network) ---- */
+
+/*
+ * out[r][c] = act(x[r][c] + bias[c] + residual[r][c]): bias (device, [cols], dtype of x) and
+ * residual (same shape and dtype as x) may be NULL; relu != 0 clamps at zero.  fp32
+ * arithmetic, one rounding at the store.  out may alias x or residual.
+ */
+int ts_bias_act(const ts_tensor *x, const void *bias, const ts_tensor *residual, int relu, ts_tensor *out);
+/* out[r] = [a[r], b[r]]: channel concatenation of two tensors with equal rows and dtype. */
+int ts_concat_cols(const ts_tensor *a, const ts_tensor *b, ts_tensor *out);
+
 /* ---- runtime ---------------------------------------------------------------------------------- */
 
 /* Stream (hipStream_t) all later calls enqueue on; NULL = the null stream. */

@@ -28,7 +28,7 @@ EXPORTS = [
     "ts_build_kmap", "ts_free", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
-    "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes",
+    "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_bias_act", "ts_concat_cols",
 ]
 
 
@@ -79,6 +79,10 @@ def load_library(path: str | None = None):
                  "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_set_stream",
                  "ts_release_cache"):
         getattr(lib, name).restype = ci
+    lib.ts_bias_act.argtypes = [tp, vp, tp, ci, tp]
+    lib.ts_bias_act.restype = ci
+    lib.ts_concat_cols.argtypes = [tp, tp, tp]
+    lib.ts_concat_cols.restype = ci
     lib.ts_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t]
     lib.ts_copy_bytes.restype = ci
     lib.ts_profile_enable.argtypes = [ci, ctypes.c_char_p]
@@ -129,6 +133,30 @@ def ts_release_cache():
 
 def ts_version() -> str:
     return load_library().ts_version().decode()
+
+
+def ts_bias_act(x: torch.Tensor, bias: torch.Tensor | None = None, residual: torch.Tensor | None = None,
+                relu: bool = True, out: torch.Tensor | None = None) -> torch.Tensor:
+    """out = act(x + bias + residual) with per-channel bias; fp32 arithmetic, dtype of x."""
+    _use_current_stream()
+    if out is None:
+        out = torch.empty_like(x)
+    if bias is not None and (bias.dtype != x.dtype or bias.numel() != x.shape[1] or not bias.is_cuda):
+        raise ValueError("bias must be a device vector [cols] of the dtype of x")
+    xs, os_ = _as_ts(x), _as_ts(out)
+    rs = ctypes.byref(_as_ts(residual)) if residual is not None else None
+    _check(load_library().ts_bias_act(ctypes.byref(xs), bias.data_ptr() if bias is not None else None, rs,
+                                      int(bool(relu)), ctypes.byref(os_)))
+    return out
+
+
+def ts_concat_cols(a: torch.Tensor, b: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    _use_current_stream()
+    if out is None:
+        out = torch.empty((a.shape[0], a.shape[1] + b.shape[1]), dtype=a.dtype, device=a.device)
+    at, bt, ot = _as_ts(a), _as_ts(b), _as_ts(out)
+    _check(load_library().ts_concat_cols(ctypes.byref(at), ctypes.byref(bt), ctypes.byref(ot)))
+    return out
 
 
 def ts_copy_bytes(dst: torch.Tensor, src: torch.Tensor):

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libts.so")
-SOURCES = ["ts_runtime.hip", "ts_kmap.hip", "ts_conv.hip"]
+SOURCES = ["ts_runtime.hip", "ts_kmap.hip", "ts_conv.hip", "ts_elementwise.hip"]
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-result",
     # packed fp32 math is kept off for all device code

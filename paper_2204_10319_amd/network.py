@@ -1,0 +1,61 @@
+"""Runs a layer plan (see ``workloads/minkunet.py``) on the GPU through the C-ABI binding.
+
+Only sequencing lives here: kernel maps per resolution level, one ``ts_sparse_conv`` per conv op,
+``ts_bias_act`` for bias / residual / ReLU, ``ts_concat_cols`` for skip connections.  Maps are
+built once per (kind, level) and reused by every layer that needs them (the paper builds maps
+per downsampling block, Sec. 2.3).
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as ts
+
+
+class SparseNet:
+    def __init__(self, ops, output, params):
+        """ops/output from the plan; params: {name: (weights, bias)} as device tensors."""
+        self.ops, self.output, self.params = ops, output, params
+
+    def build_maps(self, coords: torch.Tensor):
+        """Kernel maps for every (kind, level) of the plan, plus the coordinates of each level."""
+        kinds = []
+        for k, op in self.ops:
+            if k == "conv" and op["map"] not in kinds:
+                kinds.append(op["map"])
+        levels = {0: coords}
+        maps = {}
+        top = max(level for _, level in kinds)
+        for level in range(top + 1):
+            if ("down", level) in kinds or ("up", level) in kinds:
+                down = ts.ts_build_kmap(levels[level], 2, 2, False)
+                maps[("down", level)] = down
+                levels[level + 1] = down.out_coords()
+        for kind, level in kinds:
+            if kind == "sub":
+                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 3, 1, False)
+            elif kind == "id":
+                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 1, 1, False)
+            elif kind == "up":
+                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 2, 2, True)
+        return maps, levels
+
+    def forward(self, maps, feats: torch.Tensor, hook=None):
+        """Executes the plan; ``hook(name, tensor)`` (optional) sees every tensor written."""
+        t = {"input": feats}
+        for kind, op in self.ops:
+            if kind == "concat":
+                t[op["dst"]] = ts.ts_concat_cols(t[op["a"]], t[op["b"]])
+            else:
+                w, b = self.params[op["name"]]
+                y = ts.ts_sparse_conv(t[op["src"]], w, maps[op["map"]])
+                res = t[op["residual"]] if op["residual"] else None
+                t[op["dst"]] = ts.ts_bias_act(y, b, res, op["relu"], out=y)
+            if hook:
+                hook(op["dst"], t[op["dst"]])
+        return t[self.output]
+
+    @staticmethod
+    def free_maps(maps):
+        for m in maps.values():
+            m.free()

@@ -1,0 +1,62 @@
+"""Config 5: the MinkUNet-style forward pass, GPU library vs. CPU oracle, tensor by tensor.
+
+The oracle runs the whole network on its own (no value of the GPU run enters it); every
+intermediate tensor and the output are compared.  The end-to-end value has no closed form:
+it is pinned only through the per-layer pins of the oracle ("parity unpinned" beyond that).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2204_10319_amd import binding as ts
+from paper_2204_10319_amd.network import SparseNet
+from workloads import lidar_scan_coords, features
+from workloads.minkunet import build_plan, make_params
+from _net_oracle import run_plan
+from _util import to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_both(coords, seed):
+    ops, output = build_plan(4)
+    params = make_params(seed, ops)
+    x = features(seed + 1, coords.shape[0], 4, np.float16)
+    ref = {}
+    y_ref, levels = run_plan(ops, output, params, coords, x, hook=lambda n, v: ref.__setitem__(n, v))
+    net = SparseNet(ops, output, {k: (to_dev(w), to_dev(b)) for k, (w, b) in params.items()})
+    maps, dev_levels = net.build_maps(to_dev(coords))
+    for level, c in levels.items():
+        assert np.array_equal(dev_levels[level].cpu().numpy(), c), f"level {level} coordinates"
+    got = {}
+    y = net.forward(maps, to_dev(x), hook=lambda n, v: got.__setitem__(n, v.cpu().numpy()))
+    torch.cuda.synchronize()
+    SparseNet.free_maps(maps)
+    worst = 0.0
+    for name, r in ref.items():
+        g = got[name]
+        assert g.shape == r.shape, name
+        assert np.isfinite(g.astype(np.float64)).all(), name
+        rms = float(np.sqrt(np.mean(r.astype(np.float64) ** 2)))
+        assert 2.0 ** -6 < rms < 2.0 ** 6, f"{name}: activation RMS {rms} out of the fp16 comfort range"
+        err = oracle.rel_l2(g, r)
+        worst = max(worst, err)
+        assert err <= 2e-3, f"{name}: relative L2 error {err:.3e}"
+    assert oracle.rel_l2(y.cpu().numpy(), y_ref) <= 2e-3
+    return worst, len(ref)
+
+
+def test_network_small_scene():
+    """One sweep (~58k voxels): all 45 convs, 4 concats, every intermediate tensor checked."""
+    coords = lidar_scan_coords(4, n_sweeps=1)
+    worst, n = _run_both(coords, seed=40)
+    print(f"config 5 (1 sweep): {n} tensors, worst rel L2 {worst:.2e}")
+
+
+@pytest.mark.timeout(600)
+def test_config5_full_scene():
+    """Config 3's input (5 sweeps, ~150k voxels), 4 input channels."""
+    coords = lidar_scan_coords(2, n_sweeps=5)
+    worst, n = _run_both(coords, seed=50)
+    print(f"config 5 (full): {n} tensors, worst rel L2 {worst:.2e}")
