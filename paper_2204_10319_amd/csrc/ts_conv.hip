@@ -153,51 +153,61 @@ __device__ __forceinline__ void store_rows(TO *out, int64_t row, int cout, int c
 // count them: rows without a neighbour read `zero_row` instead.
 template <class T, int NCB, int KC, int G>
 __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, const T *__restrict__ Wt,
-                                                    const int32_t *__restrict__ gnbr,
-                                                    const uint32_t *__restrict__ tmask,
-                                                    const uint32_t *__restrict__ tmask32,
+                                                    const int32_t *__restrict__ nbr, int stride,
                                                     const int32_t *__restrict__ perm, T *__restrict__ out,
                                                     const T *__restrict__ zero_row, int cin, int cout, int K3) {
     typedef Shape<T, NCB, KC> S;
     typedef typename S::vec vec;
     __shared__ __attribute__((aligned(16))) T lds_w[2][G][S::SLAB];
     __shared__ int32_t lds_j[kMaxK3][kTileRows];
+    __shared__ uint32_t s_mask;
     const int64_t tile = blockIdx.x;
     const int co0 = blockIdx.y * NCB * 32;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
     const int slot = wave * kWaveRows + m;
-    const uint32_t mask = tmask[tile];
     floatx16 acc[NCB];
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb)
         for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
 
-    if (mask) {
-        // Neighbour rows of the tile -> LDS, from the per-group rank-ordered lists (the rank of
-        // offset n in a group is the number of lower offsets present in it).  All loads are
-        // issued before the first is used (a load-wait-store loop over the offsets would pay
-        // one memory latency per offset).
-        {
-            constexpr int PER = (kMaxK3 + 1) / 2;
-            const int half = threadIdx.x >> 7, col = threadIdx.x & 127;
-            const int64_t group = tile * 4 + (col >> 5);
-            const uint32_t gm = tmask32[group];
-            const int32_t *src = gnbr + group * K3 * 32 + (col & 31);
-            int32_t v[PER];
+    // Neighbour rows of the tile's outputs -> LDS (offset-major), and the OR of their offset
+    // bitmasks.  Two threads share an output row and read half of its table row each, all
+    // loads issued before the first is used.
+    if (threadIdx.x == 0) s_mask = 0;
+    __syncthreads();
+    {
+        const int half = threadIdx.x >> 7, col = threadIdx.x & 127;
+        const int32_t k = perm[tile * kTileRows + col];
+        const int chunks = stride / 4, cph = chunks >= 2 ? chunks / 2 : 1;
+        const int4 *src = reinterpret_cast<const int4 *>(nbr + (int64_t)(k >= 0 ? k : 0) * stride);
+        int4 v[4];
 #pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int n = 2 * i + half;
-                const bool present = n < K3 && ((gm >> n) & 1);
-                const int rank = present ? __builtin_popcount(gm & ((1u << n) - 1)) : 0;
-                v[i] = src[rank * 32];
-            }
+        for (int i = 0; i < 4; ++i) {
+            const int ch = half * cph + i;
+            v[i] = make_int4(-1, -1, -1, -1);
+            if (k >= 0 && i < cph && ch < chunks) v[i] = src[ch];
+        }
+        uint32_t mm = 0;
 #pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int n = 2 * i + half;
-                const bool present = n < K3 && ((gm >> n) & 1);
-                if (n < K3) lds_j[n][col] = present ? v[i] : -1;
+        for (int i = 0; i < 4; ++i) {
+            const int ch = half * cph + i;
+            if (i < cph && ch < chunks) {
+                const int32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = ch * 4 + q;
+                    if (idx < K3) lds_j[idx][col] = e[q];
+                    if (idx == K3 && k >= 0) mm = (uint32_t)e[q];
+                }
             }
         }
+        for (int d = 32; d >= 1; d >>= 1) mm |= (uint32_t)__shfl_xor((int)mm, d, 64);
+        if (lane == 0 && mm) atomicOr(&s_mask, mm);
+    }
+    __syncthreads();   // lds_j and s_mask complete
+    const uint32_t mask = s_mask;
+
+    if (mask) {
         // Iterator over the tile's (offset, chunk) pairs; a stage takes the next G of them.
         // Past the end it keeps returning the last pair with live = false (loads stay
         // unconditional and in bounds, the MFMAs are skipped).
@@ -232,7 +242,6 @@ __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, con
                 load_x_regs<S, T>(b[g], (j[g] >= 0 ? X + (int64_t)j[g] * cin + k0 : zero_row) + h * S::VEC);
             }
         };
-        __syncthreads();   // lds_j complete
         issue_loads(bx_a, j_a, live_a);
 #pragma unroll
         for (int g = 0; g < G; ++g) store_w_regs<S, T>(wreg[g], lds_w[0][g]);
@@ -258,135 +267,6 @@ __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, con
         }
     }
     store_rows<T, NCB>(out, perm[tile * kTileRows + slot], cout, co0, acc);
-}
-
-// ---- fused kernel over 32-row groups with an adaptive split of the offsets -----------------------
-// The time of a wave is its chain of dependent memory round trips, one per offset of its
-// group, so a group with many offsets is shared by 2 or 4 waves (each takes every 2nd / 4th
-// rank) whose partial sums meet in LDS and are added in wave order.  Per 128-row tile the
-// split factor sf follows the largest group: sf = 1 -> one workgroup, a wave per group, direct
-// store; sf = 2 / 4 -> two / four workgroups.  grid.x = 4 * tiles; surplus workgroups exit.
-// Weights are read from global memory in MFMA fragment order (k_pack_weights_frag).
-template <class T, int NCB, int KC>
-__global__ void __launch_bounds__(kThreads) k_fused_group(const T *__restrict__ X, const T *__restrict__ Wf,
-                                                          const int32_t *__restrict__ gnbr,
-                                                          const uint32_t *__restrict__ ghdr,
-                                                          const int32_t *__restrict__ perm, T *__restrict__ out,
-                                                          const T *__restrict__ zero_row,
-                                                          const uint32_t *__restrict__ work,
-                                                          const uint32_t *__restrict__ work_count, int cin, int cout,
-                                                          int K3) {
-    typedef Shape<T, NCB, KC> S;
-    typedef typename S::vec vec;
-    constexpr int NKB = S::NKB, COLS = NCB * 32, RSTRIDE = COLS + 4, QUADS = COLS / 4;
-    __shared__ __attribute__((aligned(16))) float red[kWaves][32][RSTRIDE];
-    static_assert(sizeof(float) * 32 * RSTRIDE >= sizeof(T) * 32 * S::STRIDE, "transposition tile must fit in a wave's slice of red");
-    if (blockIdx.x >= *work_count) return;   // the grid is sized for the worst case
-    const uint32_t item = work[blockIdx.x];
-    const int64_t tile = item >> 4;
-    const int b = (item >> 2) & 3;
-    const int sf = 1 << (item & 3);
-    const int co0 = blockIdx.y * COLS;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
-    const int grp = b * (kWaves / sf) + wave / sf;     // group of this wave within the tile
-    const int part = wave % sf;                        // which ranks it takes
-    const int64_t group = tile * 4 + grp;
-    const uint32_t hv = ghdr[group * 8 + (lane & 7)];  // header words, one per lane
-    const int cnt = __builtin_amdgcn_readlane(hv, 0) & 0xff;
-    const int32_t row_out = perm[group * 32 + m];
-    const int32_t *jbase = gnbr + group * K3 * 32 + m;
-    const int nkb_total = cin / S::KSTEP;
-    floatx16 acc[NCB];
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
-        for (int r = 0; r < 16; ++r) acc[cb][r] = 0.f;
-
-    // Feature rows are fetched with consecutive lanes on consecutive 16-byte pieces of a row
-    // (few cache lines per load instruction: the texture unit serves about one line per two
-    // cycles) and turned into the MFMA operand layout, one row per lane, through a
-    // wave-private LDS tile with padded rows.
-    constexpr int CPR = KC / S::VEC;          // 16-byte pieces per row chunk
-    constexpr int RPI = 64 / CPR;             // rows per load instruction
-    constexpr int RI = 32 / RPI;              // load instructions per chunk
-    T *xt = reinterpret_cast<T *>(&red[0][0][0]) + wave * (32 * S::STRIDE);   // red is not in use yet
-    const int piece = lane % CPR, rsub = lane / CPR;
-
-    int r = part;
-    int32_t j = jbase[(r < cnt ? r : 0) * 32];
-    while (r < cnt) {
-        const int byte = 1 + r;
-        const int n = (__builtin_amdgcn_readlane(hv, byte >> 2) >> (8 * (byte & 3))) & 0xff;
-        const int r_next = r + sf;
-        const int32_t j_next = jbase[(r_next < cnt ? r_next : r) * 32];
-        const T *wsrc = Wf + (((int64_t)n * (cout / 32) + co0 / 32) * nkb_total) * (64 * S::VEC) + lane * S::VEC;
-        const T *xsrc[RI];
-        int xstep[RI];
-#pragma unroll
-        for (int i = 0; i < RI; ++i) {
-            const int32_t jr = __shfl(j, i * RPI + rsub, 64);
-            xsrc[i] = (jr >= 0 ? X + (int64_t)jr * cin : zero_row) + piece * S::VEC;
-            xstep[i] = jr >= 0 ? KC : 0;   // the zero row is one chunk long
-        }
-        for (int k0 = 0, kc = 0; k0 < cin; k0 += KC, ++kc) {
-            vec wa[NCB][NKB], xv[RI], bx[NKB];
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-                for (int kb = 0; kb < NKB; ++kb)
-                    wa[cb][kb] = *reinterpret_cast<const vec *>(wsrc + ((int64_t)cb * nkb_total + kc * NKB + kb) * (64 * S::VEC));
-#pragma unroll
-            for (int i = 0; i < RI; ++i) xv[i] = *reinterpret_cast<const vec *>(xsrc[i] + kc * xstep[i]);
-            // keep every load of the stage ahead of its use: the scheduler would otherwise
-            // interleave them to save registers and pay the memory latency several times
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < RI; ++i)
-                *reinterpret_cast<vec *>(xt + (i * RPI + rsub) * S::STRIDE + piece * S::VEC) = xv[i];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) bx[kb] = *reinterpret_cast<const vec *>(xt + m * S::STRIDE + kb * S::KSTEP + h * S::VEC);
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                for (int cb = 0; cb < NCB; ++cb) mma_step(wa[cb][kb], bx[kb], acc[cb]);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
-        r = r_next;
-        j = j_next;
-    }
-    if (sf > 1) __syncthreads();   // every wave is done with its transposition tile before red is written
-    if (sf == 1) {
-        store_rows<T, NCB>(out, row_out, cout, co0, acc);
-        return;
-    }
-    // partial sums -> LDS, added in part order by the sf waves of the group
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            floatx4 v = {acc[cb][g * 4 + 0], acc[cb][g * 4 + 1], acc[cb][g * 4 + 2], acc[cb][g * 4 + 3]};
-            *reinterpret_cast<floatx4 *>(&red[wave][m][cb * 32 + g * 8 + h * 4]) = v;
-        }
-    __syncthreads();
-    const int w0 = wave - part;   // first wave of this group
-    for (int e = part * 64 + lane; e < 32 * QUADS; e += sf * 64) {
-        const int rr = e / QUADS, q = e % QUADS;
-        const int32_t ro = perm[group * 32 + rr];
-        if (ro < 0) continue;
-        floatx4 sum = *reinterpret_cast<const floatx4 *>(&red[w0][rr][q * 4]);
-        for (int w = 1; w < sf; ++w) sum += *reinterpret_cast<const floatx4 *>(&red[w0 + w][rr][q * 4]);
-        T *dst = out + (int64_t)ro * cout + co0 + q * 4;
-        if constexpr (sizeof(T) == 2) {
-            half4 v = {(_Float16)sum[0], (_Float16)sum[1], (_Float16)sum[2], (_Float16)sum[3]};
-            *reinterpret_cast<half4 *>(dst) = v;
-        } else {
-            *reinterpret_cast<floatx4 *>(dst) = sum;
-        }
-    }
 }
 
 // ---- explicit dataflow ------------------------------------------------------------------------
@@ -443,19 +323,28 @@ __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F
 }
 
 // Scatter-accumulate, output-stationary: thread = (output row, 4 channels); partial sums are
-// added in offset order in fp32 registers and the row is written once.
+// added in offset order in fp32 registers and the row is written once.  The row of G that holds
+// the pair (k, n) follows from the offset's start, the base of k's 64-row block and the block's
+// presence bitmap.
 template <class T>
-__global__ void k_scatter_reduce(const float *__restrict__ G, const int32_t *__restrict__ pos, T *__restrict__ out,
+__global__ void k_scatter_reduce(const float *__restrict__ G, const int32_t *__restrict__ nbr, int stride,
+                                 const uint64_t *__restrict__ colbits, const int32_t *__restrict__ colbase,
+                                 const int32_t *__restrict__ offs, int64_t n_blocks, T *__restrict__ out,
                                  int64_t n_out, int cout, int K3) {
     const int quads = cout / 4;
     int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t k = g / quads;
     int q = (int)(g - k * quads);
     if (k >= n_out) return;
+    uint32_t mask = (uint32_t)nbr[k * stride + K3];
+    const int64_t b = k >> 6;
+    const uint64_t before = (1ull << (k & 63)) - 1ull;
     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int n = 0; n < K3; ++n) {
-        int32_t p = pos[(int64_t)n * n_out + k];
-        if (p >= 0) acc += *reinterpret_cast<const floatx4 *>(G + (int64_t)p * cout + q * 4);
+    while (mask) {
+        const int n = __builtin_ctz(mask);
+        mask &= mask - 1;
+        const int64_t p = offs[n] + colbase[n * n_blocks + b] + __popcll(colbits[n * n_blocks + b] & before);
+        acc += *reinterpret_cast<const floatx4 *>(G + p * cout + q * 4);
     }
     if constexpr (sizeof(T) == 2) {
         half4 v = {(_Float16)acc[0], (_Float16)acc[1], (_Float16)acc[2], (_Float16)acc[3]};
@@ -620,48 +509,14 @@ struct FusedLaunch {
         constexpr int G = fused_group(NCB, KSTEPS);
         dim3 grid((unsigned)kmap->n_tiles, out->cols / (NCB * 32));
         TS_LAUNCH("k_fused", (k_fused<T, NCB, KC, G>), grid, dim3(kThreads), static_cast<const T *>(pr.x),
-                  static_cast<const T *>(pr.wt), kmap->d_gnbr, kmap->d_tmask, kmap->d_tmask32, kmap->d_perm,
+                  static_cast<const T *>(pr.wt), kmap->d_nbr, kmap->stride, kmap->d_perm,
                   static_cast<T *>(out->data), zero, pr.cin_pad, out->cols, kmap->K3);
     }
 };
 
 template <class T>
-struct GroupLaunch {
-    const Prepared &pr;
-    const ts_kmap *kmap;
-    ts_tensor *out;
-    const T *zero;
-    template <int NCB, int KSTEPS>
-    void operator()() const {
-        constexpr int KC = KSTEPS * Elem<T>::KSTEP;
-        dim3 grid((unsigned)kmap->n_tiles * 4, out->cols / (NCB * 32));   // worst case: every tile split 4 ways
-        TS_LAUNCH("k_fused_group", (k_fused_group<T, NCB, KC>), grid, dim3(kThreads), static_cast<const T *>(pr.x),
-                  static_cast<const T *>(pr.wt), kmap->d_gnbr, kmap->d_ghdr, kmap->d_perm,
-                  static_cast<T *>(out->data), zero, kmap->d_work, kmap->d_work + kmap->n_tiles * 4, pr.cin_pad,
-                  out->cols, kmap->K3);
-    }
-};
-
-// Narrow layers (C_in of at most 4 operand steps, C_out <= 64) run the group
-// kernel: little MFMA work per offset, so short per-wave chains and many resident waves win.
-// Wider layers run k_fused, which shares each weight slab among four waves through LDS.
-template <class T>
-bool group_applies(int cin_pad, int cout) {
-    return cin_pad <= 4 * Elem<T>::KSTEP && cout <= 64;
-}
-
-template <class T>
 int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
     Prepared pr;
-    const int cin_pad_guess = (feats->cols + Elem<T>::KSTEP - 1) / Elem<T>::KSTEP * Elem<T>::KSTEP;
-    if (group_applies<T>(cin_pad_guess, out->cols)) {
-        TS_TRY(prepare<T>(feats, weights, kmap, &pr, true));
-        const T *zero = static_cast<const T *>(zero_row());
-        if (!zero) return TS_ERR_OOM;
-        dispatch_shape(pick_ncb(out->cols), pick_ksteps(pr.cin_pad, Elem<T>::KSTEP), GroupLaunch<T>{pr, kmap, out, zero});
-        TS_HIP(hipGetLastError());
-        return TS_OK;
-    }
     TS_TRY(prepare<T>(feats, weights, kmap, &pr));
     const T *zero = static_cast<const T *>(zero_row());
     if (!zero) return TS_ERR_OOM;
@@ -722,7 +577,7 @@ template <class T>
 int reduce_impl(const float *G, const ts_kmap *kmap, ts_tensor *out) {
     if (kmap->n_out == 0) return TS_OK;
     int64_t threads = kmap->n_out * (out->cols / 4);
-    TS_LAUNCH("k_scatter_reduce", k_scatter_reduce<T>, dim3(blocks_for(threads, kThreads)), dim3(kThreads), G, kmap->d_pos, static_cast<T *>(out->data), kmap->n_out, out->cols, kmap->K3);
+    TS_LAUNCH("k_scatter_reduce", k_scatter_reduce<T>, dim3(blocks_for(threads, kThreads)), dim3(kThreads), G, kmap->d_nbr, kmap->stride, kmap->d_colbits, kmap->d_colbase, kmap->d_offs, kmap->n_blocks, static_cast<T *>(out->data), kmap->n_out, out->cols, kmap->K3);
     TS_HIP(hipGetLastError());
     return TS_OK;
 }

@@ -90,28 +90,35 @@ __host__ __device__ inline int64_t key_delta(int dx, int dy, int dz) {
 constexpr int kMaxK3 = 27;      // kernel volumes up to 3^3 (one bit per offset in a 32-bit mask)
 constexpr int kTileRows = 128;  // output rows per workgroup tile of the fused kernel
 
+// Row stride (in int32) of the neighbour table for a kernel volume: K3 neighbour entries, then
+// the row's offset bitmask at index K3, padded to a power of two (16-byte multiples).
+__host__ __device__ constexpr int nbr_stride(int K3) { return K3 > 8 ? 32 : (K3 > 1 ? 16 : 4); }
+
 }  // namespace ts
 
 // The kernel map.  Everything with a d_ prefix is device memory owned by the map.
 struct ts_kmap {
     int K = 0, s = 0, transposed = 0, K3 = 0;
     int centre = -1;            // index of the identity offset (odd K, stride 1), else -1
+    int stride = 0;             // nbr_stride(K3)
     int64_t n_in = 0, n_out = 0, M = 0;
+    int64_t n_blocks = 0;       // ceil(n_out / 64): 64-row blocks of the rank structure
     int64_t sizes[ts::kMaxK3] = {0};      // |M[W_n]|
     int64_t offs[ts::kMaxK3 + 1] = {0};   // exclusive prefix of sizes
     uint64_t *d_in_keys = nullptr;        // [n_in]  packed input coordinates, row order of X_in
     uint64_t *d_out_keys = nullptr;       // [n_out] packed output coordinates (may alias d_in_keys)
-    int32_t *d_nbr = nullptr;             // [K3][n_out] input row feeding output k through offset n, or -1
-    int32_t *d_pos = nullptr;             // [K3][n_out] row of that pair in the offset-major buffers, or -1
-    int32_t *d_in_idx = nullptr;          // [M] offset-major, ordered by output index inside an offset
+    // Out-major view (what Alg. 1 yields per output): row k holds, for every offset n, the input
+    // row feeding output k through W_n (or -1), then the bitmask of the offsets present.
+    int32_t *d_nbr = nullptr;             // [n_out][stride]
+    // Offset-major view M[W_n] (Sec. 2.1): pair lists ordered by output index inside an offset ...
+    int32_t *d_in_idx = nullptr;          // [M]
     int32_t *d_out_idx = nullptr;         // [M]
     int32_t *d_offs = nullptr;            // [K3+1] device copy of offs
-    // output-stationary tiles of the fused kernel: outputs sorted by their neighbour bitmask
+    // ... and the link between the two views: the pair (k, n) sits at
+    // offs[n] + colbase[n][k/64] + popcount(colbits[n][k/64] & ((1 << k%64) - 1)).
+    uint64_t *d_colbits = nullptr;        // [K3][n_blocks] bit r: output 64*b + r has offset n
+    int32_t *d_colbase = nullptr;         // [K3][n_blocks] pairs of offset n in the blocks before b
+    // Output rows ordered by offset bitmask, so that the rows of a tile share their offsets.
     int64_t n_tiles = 0;
     int32_t *d_perm = nullptr;            // [n_tiles*kTileRows] sorted position -> output row, -1 = padding
-    uint32_t *d_tmask = nullptr;          // [n_tiles] OR of the rows' neighbour bitmasks
-    uint32_t *d_tmask32 = nullptr;        // [n_tiles*4] the same per group of 32 rows
-    int32_t *d_gnbr = nullptr;            // [n_tiles*4][K3][32] per group: input rows in rank order
-    uint32_t *d_ghdr = nullptr;           // [n_tiles*4][8] per group: byte 0 count, byte 1+rank offset index
-    uint32_t *d_work = nullptr;           // [n_tiles*4 + 1] work items of the group kernel, then their count
 };

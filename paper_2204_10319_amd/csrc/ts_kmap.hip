@@ -1,14 +1,22 @@
 // Kernel-map construction (paper Sec. 2.1: output coordinates, Alg. 3; map search, Alg. 1).
 //
 // Pipeline on the device, one stream:
-//   pack (b,x,y,z) -> 64-bit keys                      ("flattening the coordinate", Sec. 2.1.2)
-//   stride>1: candidate keys (p - delta)/s, radix sort, unique -> P_out      (Alg. 3, fused 1-4)
-//   insert the searched point set into an open-addressing hash table (64-bit CAS, linear probing)
-//   probe s*q_k + delta_n for every output and offset -> neighbour table nbr[n][k]   (Alg. 1)
-//       odd K, stride 1: only the first half of the offsets is probed, the mirrored entry
-//       (k, j, K^3-1-n) is written alongside (Sec. 4.2.1), the centre map is the identity
-//   per-offset compaction (count, scan, write) -> pair lists M[W_n], ordered by output index
-//   outputs sorted by neighbour bitmask -> tiles for the output-stationary fused kernel
+//   fill     one launch clears the hash tables, counters and the tile permutation
+//   pack     (b,x,y,z) -> order-preserving 64-bit keys       ("flattening the coordinate", Sec. 2.1.2)
+//   stride>1: candidate keys (p - delta)/s, radix sort, unique -> P_out           (Alg. 3, stages 1-4)
+//   insert   the searched point set into an open-addressing table (64-bit CAS); the 8 cells of a
+//            2x2x2 block share one 128-byte bucket, so the 27 probes of a point touch ~8 lines
+//   probe    one thread per OUTPUT point looks up s*q_k + delta_n for every offset n (Alg. 1) with
+//            all loads in flight at once, and leaves per output: the row of neighbour indices and
+//            its offset bitmask; per 64 outputs and offset: a presence bitmap and its count; per
+//            distinct bitmask: the number of rows holding it (a small hash table)
+//   scan     per-offset exclusive scan of the block counts -> where each pair sits in the
+//            offset-major lists
+//   rank     first position of each distinct bitmask = rows whose mask sorts lower (by counting)
+//   place    rows go to (first position of their bitmask) + (arrival rank): rows with equal masks
+//            are adjacent, which lets the output-stationary kernel skip absent offsets per tile
+//   compact  pair lists M[W_n] (in, out), ordered by output index inside an offset
+// The host waits once, for the map sizes and error flags, while `rank` and `place` are running.
 #include "ts_internal.h"
 
 #include <cstring>
@@ -24,44 +32,68 @@ namespace {
 constexpr int kThreads = 256;
 
 // status words written by the kernels and read back once per build
-enum { ST_RANGE = 0, ST_DUP = 1, ST_TOTALS = 8, ST_WORDS = 8 + 32 };   // ST_TOTALS: per-offset map sizes
-
-struct Table {
-    uint64_t *keys;
-    int32_t *vals;
-    uint32_t mask;   // capacity - 1 (capacity is a power of two >= 2 * entries)
-    int shift;       // 64 - log2(capacity)
+enum {
+    ST_RANGE = 0,       // a coordinate was outside the packable range
+    ST_DUP = 1,         // two input rows held the same coordinate
+    ST_DCOUNT = 2,      // distinct offset bitmasks seen
+    ST_OVERFLOW = 3,    // the bitmask table could not hold them all
+    ST_TOTALS = 8,      // [32] per-offset map sizes
+    ST_WORDS = 40
 };
 
-__device__ __forceinline__ uint32_t hash_slot(uint64_t key, int shift) {
-    return (uint32_t)((key * 0x9E3779B97F4A7C15ull) >> shift);   // multiplicative (Fibonacci) hashing
+// ---- coordinate hash table ------------------------------------------------------------------------
+// 16-byte slots {key, value}; 8 slots form a 128-byte bucket addressed by the hash of the point's
+// 2x2x2 block, the home slot inside the bucket by the three parity bits.
+struct Slot {
+    uint64_t key;
+    int32_t val;
+    int32_t pad;
+};
+static_assert(sizeof(Slot) == 16, "one slot is one 128-bit load");
+
+struct Table {
+    Slot *slots;
+    uint32_t mask;   // capacity - 1 (capacity: power of two >= 2 * entries, >= 1024)
+    int shift;       // 64 - log2(capacity / 8)
+};
+
+constexpr uint64_t kParityBits = 1ull | (1ull << kFieldBits) | (1ull << (2 * kFieldBits));
+
+__device__ __forceinline__ uint32_t home_sub(uint64_t key) {
+    return (uint32_t)(key & 1) | (((uint32_t)(key >> kFieldBits) & 1) << 1) | (((uint32_t)(key >> (2 * kFieldBits)) & 1) << 2);
+}
+__device__ __forceinline__ uint32_t home_slot(uint64_t key, int shift) {
+    const uint64_t cell = key & ~kParityBits;
+    return (uint32_t)((cell * 0x9E3779B97F4A7C15ull) >> shift) * 8 + home_sub(key);   // multiplicative (Fibonacci) hashing
+}
+// Slot after `slot` in a probe sequence: 9 further (next bucket, next position; odd, so the sequence
+// visits every slot of the power-of-two table).  A miss therefore ends at the first empty slot it
+// meets, which for a point's absent neighbour is almost always the home slot itself.
+__device__ __forceinline__ uint32_t next_slot(uint32_t slot, uint32_t mask) { return (slot + 9u) & mask; }
+
+// Loads by 32-bit byte offset from the table base (capacity is at most 2^27 slots), which keeps
+// one register per lookup for the address instead of two.
+__device__ __forceinline__ uint64_t slot_key(const Table &t, uint32_t slot) {
+    return *reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(t.slots) + (slot << 4));
+}
+__device__ __forceinline__ int32_t slot_val(const Table &t, uint32_t slot) {
+    return *reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(t.slots) + ((slot << 4) + 8u));
 }
 
 __device__ __forceinline__ void table_insert(const Table &t, uint64_t key, int32_t value, int *status) {
-    uint32_t slot = hash_slot(key, t.shift);
+    uint32_t slot = home_slot(key, t.shift);
     for (;;) {
-        unsigned long long prev =
-            atomicCAS(reinterpret_cast<unsigned long long *>(&t.keys[slot]), (unsigned long long)kEmptyKey,
-                      (unsigned long long)key);
+        unsigned long long prev = atomicCAS(reinterpret_cast<unsigned long long *>(&t.slots[slot].key),
+                                            (unsigned long long)kEmptyKey, (unsigned long long)key);
         if (prev == kEmptyKey) {
-            t.vals[slot] = value;
+            t.slots[slot].val = value;
             return;
         }
         if (prev == key) {
             atomicOr(&status[ST_DUP], 1);
             return;
         }
-        slot = (slot + 1) & t.mask;   // the table is at most half full, so an empty slot exists
-    }
-}
-
-__device__ __forceinline__ int32_t table_find(const Table &t, uint64_t key) {
-    uint32_t slot = hash_slot(key, t.shift);
-    for (;;) {
-        uint64_t k = t.keys[slot];
-        if (k == key) return t.vals[slot];
-        if (k == kEmptyKey) return -1;
-        slot = (slot + 1) & t.mask;
+        slot = next_slot(slot, t.mask);   // the table is at most half full, so an empty slot exists
     }
 }
 
@@ -70,14 +102,40 @@ __device__ __forceinline__ bool coord_ok(int4 c) {
            c.z >= TS_COORD_MIN && c.z <= TS_COORD_MAX && c.w >= TS_COORD_MIN && c.w <= TS_COORD_MAX;
 }
 
-__device__ __forceinline__ void offset_of(int K, int n, int &dx, int &dy, int &dz) {
-    int r = (K - 1) / 2;
-    dx = n / (K * K) - r;
-    dy = (n / K) % K - r;
-    dz = n % K - r;
+__host__ __device__ constexpr int offset_component(int K, int n, int axis) {
+    const int r = (K - 1) / 2;
+    return axis == 0 ? n / (K * K) - r : (axis == 1 ? (n / K) % K - r : n % K - r);
 }
 
 __device__ __forceinline__ int floor_div(int a, int s) { return a >= 0 ? a / s : -((-a + s - 1) / s); }
+
+// ---- one launch for every buffer that must start at a known value -----------------------------------
+struct FillSeg {
+    uint4 *p;
+    uint64_t n_vec;     // 16-byte vectors
+    uint32_t value;     // replicated into every 32-bit word
+};
+struct FillArgs {
+    FillSeg seg[8];
+    int n = 0;
+    void add(void *p, size_t bytes, uint32_t value) {
+        if (bytes == 0) return;
+        seg[n].p = static_cast<uint4 *>(p);
+        seg[n].n_vec = (bytes + 15) / 16;
+        seg[n].value = value;
+        ++n;
+    }
+};
+
+__global__ void k_fill(FillArgs a) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (int s = 0; s < a.n; ++s) {
+        const uint32_t v = a.seg[s].value;
+        const uint4 vv = make_uint4(v, v, v, v);
+        for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < a.seg[s].n_vec; i += stride)
+            a.seg[s].p[i] = vv;
+    }
+}
 
 // keys[i] = pack(coords[i]); out-of-range rows get the empty key and raise ST_RANGE.
 __global__ void k_pack(const int4 *coords, int64_t n, uint64_t *keys, int *status) {
@@ -92,21 +150,17 @@ __global__ void k_pack(const int4 *coords, int64_t n, uint64_t *keys, int *statu
     keys[i] = pack_key(c.x, c.y, c.z, c.w);
 }
 
-// Insert (keys[i] -> i).  With centre_row != nullptr also writes the identity map of the
-// centre offset (stride 1: output i is input i).
-__global__ void k_insert(const uint64_t *keys, int64_t n, Table t, int32_t *centre_row, int *status) {
+// Insert (keys[i] -> i).
+__global__ void k_insert(const uint64_t *keys, int64_t n, Table t, int *status) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     uint64_t key = keys[i];
     if (key == kEmptyKey) return;
     table_insert(t, key, (int32_t)i, status);
-    if (centre_row) centre_row[i] = (int32_t)i;
 }
 
-// Stride-1 front end in one pass: pack, insert (key -> i) and write the identity map of the
-// centre offset (output i is input i).
-__global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, Table t, int32_t *centre_row,
-                              int *status) {
+// Stride-1 front end in one pass: pack and insert (key -> i).
+__global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, Table t, int *status) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     int4 c = coords[i];
@@ -118,23 +172,6 @@ __global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, Tab
     uint64_t key = pack_key(c.x, c.y, c.z, c.w);
     keys[i] = key;
     table_insert(t, key, (int32_t)i, status);
-    centre_row[i] = (int32_t)i;
-}
-
-// Stride 1, odd K: blockIdx.y = offset index n < K^3/2.  A hit (j at p_i + delta_n) gives the
-// entry (j, i, n) and its mirror (i, j, K^3-1-n).
-__global__ void k_probe_symmetric(const uint64_t *keys, int64_t n_pts, Table t, int K, int32_t *nbr) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_pts) return;
-    int n = blockIdx.y, dx, dy, dz;
-    offset_of(K, n, dx, dy, dz);
-    uint64_t key = keys[i];
-    if (key == kEmptyKey) return;
-    int32_t j = table_find(t, (uint64_t)((int64_t)key + key_delta(dx, dy, dz)));
-    if (j >= 0) {
-        nbr[(int64_t)n * n_pts + i] = j;
-        nbr[(int64_t)(K * K * K - 1 - n) * n_pts + j] = (int32_t)i;
-    }
 }
 
 // Alg. 3 stages 1-4 in registers: candidate u = p - delta_n, modular check, key of u/s.
@@ -142,8 +179,8 @@ __global__ void k_probe_symmetric(const uint64_t *keys, int64_t n_pts, Table t, 
 __global__ void k_candidates(const uint64_t *keys, int64_t n, int K, int s, uint64_t *cand) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    int nn = blockIdx.y, K3 = K * K * K, dx, dy, dz;
-    offset_of(K, nn, dx, dy, dz);
+    const int nn = blockIdx.y, K3 = K * K * K;
+    const int dx = offset_component(K, nn, 0), dy = offset_component(K, nn, 1), dz = offset_component(K, nn, 2);
     uint64_t key = keys[i], out = kEmptyKey;
     if (key != kEmptyKey) {
         int32_t c[4];
@@ -167,36 +204,6 @@ __global__ void k_candidates_k2s2(const uint64_t *keys, int64_t n, uint64_t *can
     cand[i] = out;
 }
 
-// Alg. 1, forward strided map: thread per (output k, offset n): look up s*q_k + delta_n among the inputs.
-__global__ void k_probe_forward(const uint64_t *out_keys, int64_t n_out, Table t, int K, int s, int32_t *nbr) {
-    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= n_out) return;
-    int n = blockIdx.y, dx, dy, dz;
-    offset_of(K, n, dx, dy, dz);
-    int32_t c[4];
-    unpack_key(out_keys[k], c);
-    nbr[(int64_t)n * n_out + k] = table_find(t, pack_key(c[0], s * c[1] + dx, s * c[2] + dy, s * c[3] + dz));
-}
-
-// Transposed map: thread per (fine point j, offset n): the coarse point (p_j - delta_n)/s, if any.
-__global__ void k_probe_transposed(const uint64_t *fine_keys, int64_t n_fine, Table coarse, int K, int s,
-                                   int32_t *nbr) {
-    int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= n_fine) return;
-    int n = blockIdx.y, dx, dy, dz;
-    offset_of(K, n, dx, dy, dz);
-    int32_t found = -1;
-    uint64_t key = fine_keys[j];
-    if (key != kEmptyKey) {
-        int32_t c[4];
-        unpack_key(key, c);
-        int ux = c[1] - dx, uy = c[2] - dy, uz = c[3] - dz;
-        if (ux % s == 0 && uy % s == 0 && uz % s == 0)
-            found = table_find(coarse, pack_key(c[0], ux / s, uy / s, uz / s));
-    }
-    nbr[(int64_t)n * n_fine + j] = found;
-}
-
 __global__ void k_drop_empty_key(const uint64_t *uniq, int64_t *count) {
     if (*count > 0 && uniq[*count - 1] == kEmptyKey) --*count;
 }
@@ -209,12 +216,224 @@ __global__ void k_unpack(const uint64_t *keys, int64_t n, int4 *coords) {
     coords[i] = make_int4(c[0], c[1], c[2], c[3]);
 }
 
-// ---- per-offset compaction -------------------------------------------------------------------
-constexpr int kItems = 1;                        // entries per thread
-constexpr int kChunk = kThreads * kItems;        // entries per block
+// ---- distinct offset bitmasks ------------------------------------------------------------------------
+// A small open-addressing table bitmask -> number of rows.  Rows take an arrival rank from the
+// counter; the distinct masks are ranked afterwards, so rows with equal masks end up adjacent.
+// Which of those rows comes first depends on arrival order, which no result depends on: the
+// compute kernels add a row's terms in offset order whatever tile the row sits in.
+struct MaskHash {
+    uint32_t *key;      // [cap]  0xFFFFFFFF = empty
+    int32_t *cnt;       // [cap]  rows holding the mask
+    int32_t *start;     // [cap]  first sorted position of the mask (filled by the rank step)
+    int32_t *dlist;     // [dmax] slots in use, in arrival order
+    uint32_t cap_mask;  // cap - 1
+    int shift;          // 32 - log2(cap)
+    int dmax;           // most distinct masks the fast path ranks
+};
+constexpr int kMaskHashCap = 1 << 15;
+constexpr int kMaskHashMaxDistinct = 1 << 14;
+constexpr int kMaskHashMaxSteps = 128;
 
+__device__ __forceinline__ int mask_hash_insert(const MaskHash &mh, uint32_t mask, int *status) {
+    uint32_t sl = (mask * 0x9E3779B1u) >> mh.shift;
+    for (int step = 0; step < kMaskHashMaxSteps; ++step) {
+        uint32_t prev = __atomic_load_n(&mh.key[sl], __ATOMIC_RELAXED);   // most masks are in the table already
+        if (prev == 0xFFFFFFFFu) prev = atomicCAS(&mh.key[sl], 0xFFFFFFFFu, mask);
+        if (prev == 0xFFFFFFFFu) {
+            const int id = atomicAdd(&status[ST_DCOUNT], 1);
+            if (id < mh.dmax)
+                mh.dlist[id] = (int32_t)sl;
+            else
+                atomicOr(&status[ST_OVERFLOW], 1);
+            return (int)sl;
+        }
+        if (prev == mask) return (int)sl;
+        sl = (sl + 1) & mh.cap_mask;
+    }
+    atomicOr(&status[ST_OVERFLOW], 1);   // too crowded: the build falls back to a radix sort of the masks
+    return -1;
+}
+
+// Order in which distinct masks are laid out.  For K = 3 the bits of rarely present offsets
+// (corners, then edges, then faces, then the centre) are made the most significant, so that
+// neighbouring masks in the order differ in few offsets where rows of several masks share a tile.
+struct BitPos27 {
+    uint8_t p[27];
+};
+constexpr BitPos27 make_bitpos27() {
+    BitPos27 b{};
+    int next = 0;
+    for (int cls = 0; cls <= 3; ++cls)
+        for (int n = 0; n < 27; ++n) {
+            const int nz = (n / 9 != 1) + ((n / 3) % 3 != 1) + (n % 3 != 1);
+            if (nz == cls) b.p[n] = (uint8_t)next++;
+        }
+    return b;
+}
+__host__ __device__ __forceinline__ uint32_t mask_sort_key(uint32_t mask, int K3) {
+    if (K3 != 27) return mask;
+    constexpr BitPos27 bp = make_bitpos27();
+    uint32_t key = 0;
+#pragma unroll
+    for (int n = 0; n < 27; ++n) key |= ((mask >> n) & 1u) << bp.p[n];
+    return key;
+}
+
+// ---- map search (Alg. 1) -------------------------------------------------------------------------------
+enum { MODE_SUB = 0, MODE_FWD = 1, MODE_TR = 2 };
+
+// One thread per output point k.
+//   MODE_SUB  stride 1, odd K: neighbour key = key_k + key_delta(delta_n); the centre is k itself
+//   MODE_FWD  stride s: input at s*q_k + delta_n
+//   MODE_TR   transposed: coarse point (p_k - delta_n)/s when s divides the difference
+// Writes nbr[k][0..K3) (input row or -1) and nbr[k][K3] = bitmask of the offsets present; per wave
+// (64 consecutive outputs) and offset the presence bitmap and its popcount; registers the row's
+// bitmask in the mask table.  (No global counters here: atomics from every wave on one cache
+// line are served one after the other and would take longer than everything else.)
+template <int MODE, int K>
+__global__ void __launch_bounds__(kThreads, 3) k_probe(const uint64_t *__restrict__ out_keys, int64_t n_out, Table t, int s,
+                                                    int32_t *__restrict__ nbr, uint64_t *__restrict__ colbits,
+                                                    int32_t *__restrict__ colcnt, int64_t n_blocks, int *__restrict__ status,
+                                                    MaskHash mh, int2 *__restrict__ slot_rank) {
+    constexpr int K3 = K * K * K, STRIDE = nbr_stride(K3), CENTRE = (K3 - 1) / 2;
+    const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int64_t block64 = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);   // wave-uniform
+    const uint64_t key = k < n_out ? out_keys[k] : kEmptyKey;
+    const bool ok = key != kEmptyKey;
+    int32_t c[4] = {0, 0, 0, 0};
+    if (MODE != MODE_SUB && ok) unpack_key(key, c);
+
+    // Key searched for offset n.  Stride 1 and forward maps: a base key plus the constant
+    // key_delta(delta_n), so a loaded key is tested as (loaded - base == constant) and nothing per
+    // offset stays in registers but the slot; transposed maps keep the searched keys.
+    uint64_t base = key;
+    if (MODE == MODE_FWD) base = pack_key(c[0], s * c[1], s * c[2], s * c[3]);
+    auto delta_of = [](int n) -> int64_t {
+        constexpr int r = (K - 1) / 2;
+        return key_delta(n / (K * K) - r, (n / K) % K - r, n % K - r);
+    };
+    uint64_t want_tr[MODE == MODE_TR ? K3 : 1];
+    auto is_wanted = [&](int n, uint64_t loaded) -> bool {
+        if (MODE == MODE_TR) return loaded == want_tr[MODE == MODE_TR ? n : 0];
+        return (int64_t)(loaded - base) == delta_of(n);
+    };
+    // All lookups advance together.  The first load of each (its key only) is issued before any
+    // is examined; then rounds: lookups whose slot held another key move on together, so a wave
+    // pays one memory access time per round, not per collision.  A finished lookup leaves the
+    // slot it hit (or none); the values are fetched in one last batch.
+    constexpr uint32_t kNone = 0xFFFFFFFFu;
+    uint32_t slot[K3];
+    uint64_t got[K3];
+    uint32_t pending = 0;   // bit n: lookup n has not ended yet
+#pragma unroll
+    for (int n = 0; n < K3; ++n) {
+        bool probe = ok && !(MODE == MODE_SUB && n == CENTRE);
+        uint64_t want = base + (uint64_t)delta_of(n);
+        if (MODE == MODE_TR) {
+            constexpr int r = (K - 1) / 2;
+            const int ux = c[1] - (n / (K * K) - r), uy = c[2] - ((n / K) % K - r), uz = c[3] - (n % K - r);
+            probe = ok && ux % s == 0 && uy % s == 0 && uz % s == 0;
+            want = pack_key(c[0], ux / s, uy / s, uz / s);
+            want_tr[MODE == MODE_TR ? n : 0] = want;
+        }
+        slot[n] = kNone;
+        if (probe) {
+            pending |= 1u << n;
+            slot[n] = home_slot(want, t.shift);
+            got[n] = slot_key(t, slot[n]);
+        }
+    }
+    for (;;) {
+#pragma unroll
+        for (int n = 0; n < K3; ++n) {
+            if ((pending >> n) & 1u) {
+                if (is_wanted(n, got[n])) {
+                    pending &= ~(1u << n);
+                } else if (got[n] == kEmptyKey) {
+                    pending &= ~(1u << n);
+                    slot[n] = kNone;
+                }
+            }
+        }
+        if (__ballot(pending != 0) == 0) break;
+#pragma unroll
+        for (int n = 0; n < K3; ++n) {
+            if ((pending >> n) & 1u) {
+                slot[n] = next_slot(slot[n], t.mask);
+                got[n] = slot_key(t, slot[n]);
+            }
+        }
+    }
+    int32_t j[K3];
+#pragma unroll
+    for (int n = 0; n < K3; ++n) {
+        j[n] = (MODE == MODE_SUB && n == CENTRE && ok) ? (int32_t)k : -1;
+        if (slot[n] != kNone) j[n] = slot_val(t, slot[n]);
+    }
+    uint32_t mask = 0;
+#pragma unroll
+    for (int n = 0; n < K3; ++n)
+        if (j[n] >= 0) mask |= 1u << n;
+
+    // the row of the out-major table
+    if (k < n_out) {
+        constexpr int CHUNKS = (K3 + 1 + 3) / 4;
+        int4 *dst = reinterpret_cast<int4 *>(nbr + k * STRIDE);
+#pragma unroll
+        for (int ch = 0; ch < CHUNKS; ++ch) {
+            int32_t v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int idx = ch * 4 + q;
+                v[q] = idx < K3 ? j[idx < K3 ? idx : 0] : (idx == K3 ? (int32_t)mask : 0);
+            }
+            dst[ch] = make_int4(v[0], v[1], v[2], v[3]);
+        }
+    }
+
+    // presence bitmaps of this wave's 64 outputs, one per offset, and their counts
+    uint64_t mine = 0;
+#pragma unroll
+    for (int n = 0; n < K3; ++n) {
+        const uint64_t b = __ballot((mask >> n) & 1u);
+        if (lane == n) mine = b;
+    }
+    if (lane < K3 && block64 < n_blocks) {
+        const int cnt = __popcll(mine);
+        colbits[(int64_t)lane * n_blocks + block64] = mine;
+        colcnt[(int64_t)lane * n_blocks + block64] = cnt;
+    }
+
+    // register the bitmask; lanes of a wave holding the same mask share one counter update.
+    // First the wave's classes of equal masks (registers only), then every class leader talks to
+    // the table at once, so a wave pays two memory round trips however many masks it holds.
+    int my_leader = lane;
+    uint64_t my_class = 0;
+    uint64_t todo = __ballot(ok);
+    while (todo) {
+        const int leader = __ffsll((unsigned long long)todo) - 1;
+        const uint32_t lm = (uint32_t)__shfl((int)mask, leader, 64);
+        const uint64_t same = __ballot(ok && mask == lm);
+        if ((same >> lane) & 1ull) {
+            my_leader = leader;
+            my_class = same;
+        }
+        todo &= ~same;
+    }
+    int sl = -1, first = 0;
+    if (ok && lane == my_leader) {
+        sl = mask_hash_insert(mh, mask, status);
+        if (sl >= 0) first = atomicAdd(&mh.cnt[sl], __popcll(my_class));
+    }
+    const int my_slot = __shfl(sl, my_leader, 64);
+    const int my_rank = __shfl(first, my_leader, 64) + __popcll(my_class & ((1ull << lane) - 1ull));
+    if (k < n_out) slot_rank[k] = make_int2(my_slot, my_rank);
+}
+
+template <int THREADS = kThreads>
 __device__ __forceinline__ int block_exclusive_scan(int v, int *total) {
-    __shared__ int wave_sums[kThreads / 64];
+    __shared__ int wave_sums[THREADS / 64];
     int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int incl = v;
     for (int d = 1; d < 64; d <<= 1) {
@@ -224,7 +443,7 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *total) {
     if (lane == 63) wave_sums[wave] = incl;
     __syncthreads();
     int base = 0, all = 0;
-    for (int w = 0; w < kThreads / 64; ++w) {
+    for (int w = 0; w < THREADS / 64; ++w) {
         int sw = wave_sums[w];
         if (w < wave) base += sw;
         all += sw;
@@ -234,165 +453,172 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *total) {
     return base + incl - v;
 }
 
-// One pass over the neighbour table: blkcnt[n][b] = number of valid entries of
-// nbr[n][b*kChunk .. +kChunk), and per output its neighbour bitmask (plus the identity row list
-// that the mask sort permutes).
-__global__ void k_count_masks(const int32_t *nbr, int64_t n_out, int nblk, int K3, int32_t *blkcnt, uint32_t *masks,
-                              int32_t *rows, int *totals) {
-    __shared__ int s_cnt[kMaxK3];
-    static_assert(kItems == 1, "one output per thread");
-    const int b = blockIdx.x;
-    if (threadIdx.x < kMaxK3) s_cnt[threadIdx.x] = 0;
-    __syncthreads();
-    const int64_t k = (int64_t)b * kChunk + threadIdx.x;
-    const int64_t kc = k < n_out ? k : n_out - 1;
-    int32_t v[kMaxK3];
-#pragma unroll
-    for (int n = 0; n < kMaxK3; ++n) v[n] = nbr[(int64_t)(n < K3 ? n : K3 - 1) * n_out + kc];   // all loads first
-    uint32_t m = 0;
-#pragma unroll
-    for (int n = 0; n < kMaxK3; ++n)
-        if (n < K3 && k < n_out && v[n] >= 0) m |= 1u << n;
-#pragma unroll
-    for (int n = 0; n < kMaxK3; ++n) {
-        const int c = __popcll(__ballot((m >> n) & 1));
-        if ((threadIdx.x & 63) == 0 && c) atomicAdd(&s_cnt[n], c);
+// Block n: exclusive scan of colcnt[n][*] -> colbase[n][b] = pairs of offset n in the 64-row
+// blocks before b (relative to the start of the offset's list), and the offset's total.
+// Extra blocks: the distinct bitmasks as a dense list of (sort key, rows) for the rank step.
+constexpr int kScanThreads = 1024, kScanItems = 4;
+constexpr int kRankSlices = 32, kRankPer = 4, kRankUnroll = 16;
+constexpr int kDensePad = kRankSlices * kRankUnroll;   // sentinel entries behind the list
+__global__ void __launch_bounds__(kScanThreads) k_scan(const int32_t *__restrict__ colcnt, int32_t *__restrict__ colbase,
+                                                       int64_t n_blocks, int K3, int *__restrict__ status, MaskHash mh,
+                                                       int2 *__restrict__ dense) {
+    if ((int)blockIdx.x >= K3) {
+        int D = status[ST_DCOUNT];
+        D = D < mh.dmax ? D : mh.dmax;
+        const int d = ((int)blockIdx.x - K3) * kScanThreads + threadIdx.x;
+        if (d < D) {
+            const int sl = mh.dlist[d];
+            dense[d] = make_int2((int)mask_sort_key(mh.key[sl], K3), mh.cnt[sl]);
+        } else if (d < mh.dmax + kDensePad) {
+            dense[d] = make_int2(-1, 0);   // sorts after every mask, holds no rows
+        }
+        return;
     }
-    if (k < n_out) {
-        masks[k] = m;
-        rows[k] = (int32_t)k;
-    }
-    __syncthreads();
-    if (threadIdx.x < K3) {
-        blkcnt[(int64_t)threadIdx.x * nblk + b] = s_cnt[threadIdx.x];
-        if (s_cnt[threadIdx.x]) atomicAdd(&totals[threadIdx.x], s_cnt[threadIdx.x]);
-    }
-}
-
-// Exclusive scan of blkcnt (offset-major) in place, one block per offset: the start of offset n
-// is the sum of the totals before it.  offs[n] = start of offset n, offs[K3] = |M|.
-__global__ void k_scan_counts(int32_t *blkcnt, int nblk, int K3, const int *totals, int32_t *offs) {
     const int n = blockIdx.x;
-    int start = 0;
-    for (int q = 0; q < n; ++q) start += totals[q];
-    int32_t *row = blkcnt + (int64_t)n * nblk;
-    const int per = (nblk + kThreads - 1) / kThreads;
-    const int lo = threadIdx.x * per, hi = lo + per < nblk ? lo + per : nblk;
+    const int32_t *src = colcnt + (int64_t)n * n_blocks;
+    int32_t *dst = colbase + (int64_t)n * n_blocks;
+    int run = 0;
+    for (int64_t base = 0; base < n_blocks; base += kScanThreads * kScanItems) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * kScanItems;
+        int v[kScanItems], sum = 0;
+#pragma unroll
+        for (int e = 0; e < kScanItems; ++e) {
+            v[e] = i0 + e < n_blocks ? src[i0 + e] : 0;
+            sum += v[e];
+        }
+        int total;
+        int at = run + block_exclusive_scan<kScanThreads>(sum, &total);
+#pragma unroll
+        for (int e = 0; e < kScanItems; ++e) {
+            if (i0 + e < n_blocks) dst[i0 + e] = at;
+            at += v[e];
+        }
+        run += total;
+    }
+    if (threadIdx.x == 0) status[ST_TOTALS + n] = run;
+}
+
+// Rank step for the distinct bitmasks: start of mask d = rows whose mask sorts lower.  Block
+// (d-block, slice) adds up, for 1024 masks (4 per thread), the rows of the lower masks found in
+// one slice of the list; k_rank_sum adds the slices.  The list is read with wave-uniform
+// addresses (scalar loads), so the inner loop is compare / select / add only.
+// Block 0 of k_rank_partial instead turns the per-offset totals into the prefix offs[].
+__global__ void __launch_bounds__(kThreads) k_rank_partial(const int2 *__restrict__ dense, int K3, int *__restrict__ status,
+                                                           int32_t *__restrict__ offs, int dmax,
+                                                           int32_t *__restrict__ partial) {
+    if (blockIdx.x == 0) {
+        if (threadIdx.x == 0) {
+            int run = 0;
+            for (int n = 0; n < K3; ++n) {
+                offs[n] = run;
+                run += status[ST_TOTALS + n];
+            }
+            offs[K3] = run;
+        }
+        return;
+    }
+    const int rb = blockIdx.x - 1, dblk = rb / kRankSlices, slice = rb % kRankSlices;
+    int D = status[ST_DCOUNT];
+    D = D < dmax ? D : dmax;
+    if (dblk * kThreads * kRankPer >= D) return;
+    // slices are whole groups of kRankUnroll entries; what lies behind the list are sentinels
+    const int per = ((D + kRankSlices - 1) / kRankSlices + kRankUnroll - 1) / kRankUnroll * kRankUnroll;
+    const int lo = slice * per, hi = lo + per;
+    uint32_t my_key[kRankPer];
+    int sum[kRankPer];
+#pragma unroll
+    for (int e = 0; e < kRankPer; ++e) {
+        const int d = (dblk * kRankPer + e) * kThreads + threadIdx.x;
+        my_key[e] = d < D ? (uint32_t)dense[d].x : 0u;
+        sum[e] = 0;
+    }
+    for (int q = lo; q < hi; q += kRankUnroll) {
+        int2 kc[kRankUnroll];   // same addresses in every lane; all loaded before the first use
+#pragma unroll
+        for (int u = 0; u < kRankUnroll; ++u) kc[u] = dense[q + u];
+#pragma unroll
+        for (int u = 0; u < kRankUnroll; ++u)
+#pragma unroll
+            for (int e = 0; e < kRankPer; ++e) sum[e] += (uint32_t)kc[u].x < my_key[e] ? kc[u].y : 0;
+    }
+#pragma unroll
+    for (int e = 0; e < kRankPer; ++e) {
+        const int d = (dblk * kRankPer + e) * kThreads + threadIdx.x;
+        if (d < D) partial[(int64_t)slice * dmax + d] = sum[e];
+    }
+}
+
+__global__ void k_rank_sum(const int32_t *__restrict__ partial, const int *__restrict__ status, MaskHash mh) {
+    int D = status[ST_DCOUNT];
+    D = D < mh.dmax ? D : mh.dmax;
+    const int d = blockIdx.x * blockDim.x + threadIdx.x;
+    if (d >= D) return;
     int sum = 0;
-    for (int e = lo; e < hi; ++e) sum += row[e];
-    int total;
-    int run = start + block_exclusive_scan(sum, &total);
-    for (int e = lo; e < hi; ++e) {
-        int c = row[e];
-        row[e] = run;
-        run += c;
-    }
-    if (threadIdx.x == 0) {
-        offs[n] = start;
-        if (n == K3 - 1) offs[K3] = start + total;
-    }
+#pragma unroll
+    for (int sl = 0; sl < kRankSlices; ++sl) sum += partial[(int64_t)sl * mh.dmax + d];
+    mh.start[mh.dlist[d]] = sum;
 }
 
-// Write pairs and positions.  Block (b, n) owns entries [b*kChunk, +kChunk) of offset n; its
-// first output slot is blkbase[n][b]; inside the block entries keep ascending output order.
-__global__ void k_compact(const int32_t *nbr, int64_t n_out, int nblk, const int32_t *blkbase, int32_t *in_idx,
-                          int32_t *out_idx, int32_t *pos) {
-    int n = blockIdx.y, b = blockIdx.x;
-    const int32_t *row = nbr + (int64_t)n * n_out;
-    int64_t k0 = (int64_t)b * kChunk + (int64_t)threadIdx.x * kItems;   // thread owns kItems consecutive outputs
-    int32_t j[kItems];
-    int c = 0;
-    for (int it = 0; it < kItems; ++it) {
-        int64_t k = k0 + it;
-        j[it] = k < n_out ? row[k] : -1;
-        if (j[it] >= 0) ++c;
-    }
-    int total;
-    int p = blkbase[(int64_t)n * nblk + b] + block_exclusive_scan(c, &total);
-    for (int it = 0; it < kItems; ++it) {
-        int64_t k = k0 + it;
-        if (k >= n_out) break;
-        if (j[it] >= 0) {
-            in_idx[p] = j[it];
-            out_idx[p] = (int32_t)k;
-            pos[(int64_t)n * n_out + k] = p++;
-        } else {
-            pos[(int64_t)n * n_out + k] = -1;
-        }
-    }
+// perm[start of the row's mask + arrival rank] = row.
+__global__ void k_place(const int2 *__restrict__ slot_rank, int64_t n_out, MaskHash mh, int32_t *__restrict__ perm) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_out) return;
+    const int2 sr = slot_rank[k];
+    if (sr.x < 0) return;
+    const int64_t pos = (int64_t)mh.start[sr.x] + sr.y;
+    if (pos < n_out) perm[pos] = (int32_t)k;
 }
 
-// ---- tiles for the output-stationary kernels ---------------------------------------------------
-// One block per tile of kTileRows sorted outputs: records the output row of each slot, the
-// tile's offset bitmask, and per group of 32 rows the neighbour rows in rank order (rank = position among the group's present offsets)
-// with a 32-byte header {count, offset of rank 0, offset of rank 1, ...}.
-__global__ void __launch_bounds__(kTileRows) k_build_tiles(const int32_t *nbr, int64_t n_out, int K3,
-                                                            const uint32_t *sorted_masks,
-                                                            const int32_t *sorted_rows, int32_t *perm,
-                                                            uint32_t *tmask, uint32_t *tmask32, int32_t *gnbr, uint32_t *ghdr, uint32_t *work,
-                                                            uint32_t *work_count, int thr1, int thr2) {
-    __shared__ uint32_t s_mask;
-    __shared__ int s_max_count;
-    int64_t tile = blockIdx.x, r = tile * kTileRows + threadIdx.x;
-    if (threadIdx.x == 0) {
-        s_mask = 0;
-        s_max_count = 0;
+// Pair lists: thread per output row; the pair (k, n) goes to offs[n] + colbase[n][k/64] + (outputs of the
+// same 64-block with offset n before k), which keeps ascending output order inside an offset.
+template <int K3>
+__global__ void __launch_bounds__(kThreads) k_compact(const int32_t *__restrict__ nbr, int64_t n_out,
+                                                      const int32_t *__restrict__ colbase, int64_t n_blocks,
+                                                      const int32_t *__restrict__ offs, int32_t *__restrict__ in_idx,
+                                                      int32_t *__restrict__ out_idx) {
+    constexpr int STRIDE = nbr_stride(K3), CHUNKS = (K3 + 3) / 4;
+    const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int64_t block64 = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    int base_mine = 0;
+    if (lane < K3 && block64 < n_blocks) base_mine = offs[lane] + colbase[(int64_t)lane * n_blocks + block64];
+    int32_t j[CHUNKS * 4];
+#pragma unroll
+    for (int ch = 0; ch < CHUNKS; ++ch) {
+        int4 v = make_int4(-1, -1, -1, -1);
+        if (k < n_out) v = reinterpret_cast<const int4 *>(nbr + k * STRIDE)[ch];
+        j[ch * 4 + 0] = v.x;
+        j[ch * 4 + 1] = v.y;
+        j[ch * 4 + 2] = v.z;
+        j[ch * 4 + 3] = v.w;
     }
-    __syncthreads();
-    int32_t k = r < n_out ? sorted_rows[r] : -1;
-    uint32_t m = r < n_out ? sorted_masks[r] : 0;
-    perm[r] = k;
-    for (int d = 16; d >= 1; d >>= 1) m |= __shfl_xor(m, d, 64);
-    const uint32_t gm = m;                  // mask of this thread's group of 32 rows
-    const int64_t group = r >> 5;
-    const int lane32 = threadIdx.x & 31;
-    if (lane32 == 0) {
-        tmask32[group] = gm;
-        atomicOr(&s_mask, gm);
-        atomicMax(&s_max_count, __popc(gm));
-    }
-    // header: byte 0 = count, byte 1+rank = offset index; lanes 0..7 write one word each
-    if (lane32 < 8) {
-        uint32_t word = 0;
-        int rank = 0;
-        for (int n = 0; n < K3; ++n) {
-            if (!((gm >> n) & 1)) continue;
-            int byte = 1 + rank;
-            if ((byte >> 2) == lane32) word |= (uint32_t)n << (8 * (byte & 3));
-            ++rank;
-        }
-        if (lane32 == 0) word |= (uint32_t)rank;
-        ghdr[group * 8 + lane32] = word;
-    }
-    __syncthreads();
-    uint32_t tm = s_mask;
-    if (threadIdx.x == 0) {
-        tmask[tile] = tm;
-        // work items of the group kernel: a tile whose largest group has many offsets is given
-        // to 2 or 4 workgroups (item = tile << 4 | part << 2 | log2(parts)); list order is
-        // arbitrary and does not affect results
-        const int c = s_max_count;
-        const int lg = c <= thr1 ? 0 : (c <= thr2 ? 1 : 2);
-        const uint32_t base = atomicAdd(work_count, 1u << lg);
-        for (uint32_t i = 0; i < (1u << lg); ++i) work[base + i] = ((uint32_t)tile << 4) | (i << 2) | (uint32_t)lg;
-    }
-    int rank = 0;
+#pragma unroll
     for (int n = 0; n < K3; ++n) {
-        if (!((gm >> n) & 1)) continue;
-        gnbr[(group * K3 + rank) * 32 + lane32] = k >= 0 ? nbr[(int64_t)n * n_out + k] : -1;
-        ++rank;
+        const bool has = j[n] >= 0;
+        const uint64_t bal = __ballot(has);
+        const int base = __shfl(base_mine, n, 64);
+        if (has) {
+            const int p = base + __popcll(bal & ((1ull << lane) - 1ull));
+            in_idx[p] = j[n];
+            out_idx[p] = (int32_t)k;
+        }
     }
 }
 
-// Largest per-group offset count handled by 1 (which = 1) or 2 (which = 2) workgroups per tile
-// (measured on ~150k-voxel scans: chains of more than ~6 dependent offsets per wave dominate).
-inline int split_thr(int which) { return which == 1 ? 6 : 12; }
+// Fallback ordering input: the sort key of each row's bitmask and the identity row list.
+__global__ void k_extract_masks(const int32_t *__restrict__ nbr, int64_t n_out, int stride, int K3,
+                                uint32_t *__restrict__ keys, int32_t *__restrict__ rows) {
+    int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_out) return;
+    keys[k] = mask_sort_key((uint32_t)nbr[k * stride + K3], K3);
+    rows[k] = (int32_t)k;
+}
 
 inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
 // Owns the temporaries of one build; everything goes back to the pool on scope exit.
 struct Temps {
-    void *p[40];
+    void *p[48];
     int n = 0;
     template <class T>
     int get(T **out, size_t count) {
@@ -405,16 +631,40 @@ struct Temps {
     }
 };
 
-int make_table(Temps &tmp, int64_t entries, Table *t) {
+int launch_fill(const FillArgs &f) {
+    if (f.n == 0) return TS_OK;
+    uint64_t most = 0;
+    for (int i = 0; i < f.n; ++i) most = f.seg[i].n_vec > most ? f.seg[i].n_vec : most;
+    unsigned blocks = blocks_for((int64_t)most, kThreads);
+    if (blocks > 4096) blocks = 4096;
+    TS_LAUNCH("k_fill", k_fill, dim3(blocks), dim3(kThreads), f);
+    return TS_OK;
+}
+
+// Allocates the table; its clearing is added to `fill`.
+int make_table(Temps &tmp, int64_t entries, Table *t, FillArgs *fill) {
     uint64_t cap = 1024;
     while (cap < (uint64_t)(2 * entries)) cap <<= 1;
-    if (cap > (1ull << 31)) return fail(TS_ERR_UNSUPPORTED, "too many points for the hash table");
-    TS_TRY(tmp.get(&t->keys, cap));
-    TS_TRY(tmp.get(&t->vals, cap));
+    if (cap > (1ull << 27)) return fail(TS_ERR_UNSUPPORTED, "too many points for the hash table");
+    TS_TRY(tmp.get(&t->slots, cap));
     t->mask = (uint32_t)(cap - 1);
-    t->shift = 64 - __builtin_ctzll(cap);
-    ProfScope ps("memset_table");
-    TS_HIP(hipMemsetAsync(t->keys, 0xFF, cap * sizeof(uint64_t), stream()));
+    t->shift = 64 - __builtin_ctzll(cap / 8);
+    fill->add(t->slots, cap * sizeof(Slot), 0xFFFFFFFFu);
+    return TS_OK;
+}
+
+int make_mask_hash(Temps &tmp, MaskHash *mh, FillArgs *fill) {
+    int32_t *cnt_start;
+    TS_TRY(tmp.get(&mh->key, (size_t)kMaskHashCap));
+    TS_TRY(tmp.get(&cnt_start, (size_t)2 * kMaskHashCap));
+    TS_TRY(tmp.get(&mh->dlist, (size_t)kMaskHashMaxDistinct));
+    mh->cnt = cnt_start;
+    mh->start = cnt_start + kMaskHashCap;
+    mh->cap_mask = kMaskHashCap - 1;
+    mh->shift = 32 - __builtin_ctz(kMaskHashCap);
+    mh->dmax = kMaskHashMaxDistinct;
+    fill->add(mh->key, (size_t)kMaskHashCap * sizeof(uint32_t), 0xFFFFFFFFu);
+    fill->add(mh->cnt, (size_t)kMaskHashCap * sizeof(int32_t), 0u);
     return TS_OK;
 }
 
@@ -423,16 +673,12 @@ void destroy(ts_kmap *m) {
     if (m->d_out_keys != m->d_in_keys) dev_free(m->d_out_keys);
     dev_free(m->d_in_keys);
     dev_free(m->d_nbr);
-    dev_free(m->d_pos);
     dev_free(m->d_in_idx);
     dev_free(m->d_out_idx);
     dev_free(m->d_offs);
+    dev_free(m->d_colbits);
+    dev_free(m->d_colbase);
     dev_free(m->d_perm);
-    dev_free(m->d_tmask);
-    dev_free(m->d_tmask32);
-    dev_free(m->d_gnbr);
-    dev_free(m->d_ghdr);
-    dev_free(m->d_work);
     delete m;
 }
 
@@ -446,65 +692,115 @@ int sort_keys(Temps &tmp, uint64_t *in, uint64_t *out, size_t n) {
     return TS_OK;
 }
 
-// From the neighbour table to pair lists, positions and fused-kernel tiles.
-int finish_map(ts_kmap *m, Temps &tmp, int *d_status) {
-    hipStream_t st = stream();
-    const int K3 = m->K3;
-    const int64_t n_out = m->n_out;
-    const int nblk = (int)blocks_for(n_out, kChunk);
-    int32_t *blkcnt;
-    TS_TRY(tmp.get(&blkcnt, (size_t)K3 * nblk));
-    TS_TRY(alloc_n(&m->d_offs, K3 + 1));
-    uint32_t *masks, *masks_sorted;
-    int32_t *rows, *rows_sorted;
-    TS_TRY(tmp.get(&masks, (size_t)n_out));
-    TS_TRY(tmp.get(&masks_sorted, (size_t)n_out));
-    TS_TRY(tmp.get(&rows, (size_t)n_out));
-    TS_TRY(tmp.get(&rows_sorted, (size_t)n_out));
-    TS_LAUNCH("k_count_masks", k_count_masks, dim3(nblk), dim3(kThreads), m->d_nbr, n_out, nblk, K3, blkcnt, masks, rows, d_status + ST_TOTALS);
-    TS_LAUNCH("k_scan_counts", k_scan_counts, dim3(K3), dim3(kThreads), blkcnt, nblk, K3, d_status + ST_TOTALS, m->d_offs);
+hipEvent_t sizes_event() {
+    static hipEvent_t ev = nullptr;
+    if (!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+        (void)hipGetLastError();
+        ev = nullptr;
+    }
+    return ev;
+}
 
-    // the one host round trip: status flags and the per-offset starts
-    int32_t *h = static_cast<int32_t *>(host_staging((ST_WORDS + kMaxK3 + 1) * sizeof(int32_t)));
-    if (!h) return TS_ERR_OOM;
+template <int MODE, int K>
+void launch_probe(const ts_kmap *m, const Table &t, int32_t *colcnt, int *d_status, const MaskHash &mh, int2 *slot_rank) {
+    TS_LAUNCH("k_probe", (k_probe<MODE, K>), dim3(blocks_for(m->n_out, kThreads)), dim3(kThreads), m->d_out_keys, m->n_out,
+              t, m->s, m->d_nbr, m->d_colbits, colcnt, m->n_blocks, d_status, mh, slot_rank);
+}
+
+// Map search and everything after it.  `table` holds the searched point set; m->d_out_keys the
+// outputs; the clearing of status words, mask table and permutation has been enqueued.
+int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, const MaskHash &mh, int *d_status) {
+    hipStream_t st = stream();
+    const int K3 = m->K3, K = m->K;
+    const int64_t n_out = m->n_out;
+    int32_t *colcnt;
+    int2 *slot_rank;
+    TS_TRY(tmp.get(&colcnt, (size_t)K3 * m->n_blocks));
+    TS_TRY(tmp.get(&slot_rank, (size_t)n_out));
+    const int mode = m->s == 1 ? MODE_SUB : (m->transposed ? MODE_TR : MODE_FWD);
+    if (mode == MODE_SUB && K == 1) launch_probe<MODE_SUB, 1>(m, table, colcnt, d_status, mh, slot_rank);
+    else if (mode == MODE_SUB && K == 3) launch_probe<MODE_SUB, 3>(m, table, colcnt, d_status, mh, slot_rank);
+    else if (mode == MODE_FWD && K == 1) launch_probe<MODE_FWD, 1>(m, table, colcnt, d_status, mh, slot_rank);
+    else if (mode == MODE_TR && K == 1) launch_probe<MODE_TR, 1>(m, table, colcnt, d_status, mh, slot_rank);
+    else if (mode == MODE_FWD && K == 2) launch_probe<MODE_FWD, 2>(m, table, colcnt, d_status, mh, slot_rank);
+    else if (mode == MODE_FWD && K == 3) launch_probe<MODE_FWD, 3>(m, table, colcnt, d_status, mh, slot_rank);
+    else if (mode == MODE_TR && K == 2) launch_probe<MODE_TR, 2>(m, table, colcnt, d_status, mh, slot_rank);
+    else if (mode == MODE_TR && K == 3) launch_probe<MODE_TR, 3>(m, table, colcnt, d_status, mh, slot_rank);
+    else return fail(TS_ERR_UNSUPPORTED, "no map search for kernel_size %d, stride %d", K, m->s);
+
+    int2 *dense;
+    int32_t *partial;
+    TS_TRY(tmp.get(&dense, (size_t)mh.dmax + kDensePad));
+    TS_TRY(tmp.get(&partial, (size_t)kRankSlices * mh.dmax));
+    TS_LAUNCH("k_scan", k_scan, dim3(K3 + (mh.dmax + kDensePad + kScanThreads - 1) / kScanThreads), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, K3,
+              d_status, mh, dense);
+
+    // the one host round trip: error flags, map sizes, whether the mask table sufficed; ranking
+    // and placement are enqueued behind the copy so the device keeps working meanwhile
+    int32_t *h = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
+    hipEvent_t ev = sizes_event();
+    if (!h || !ev) return fail(TS_ERR_OOM, "host staging area or event unavailable");
     TS_HIP(hipMemcpyAsync(h, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    TS_HIP(hipMemcpyAsync(h + ST_WORDS, m->d_offs, (K3 + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    TS_HIP(hipStreamSynchronize(st));
+    TS_HIP(hipEventRecord(ev, st));
+    {
+        const unsigned rank_blocks = (unsigned)(mh.dmax / (kThreads * kRankPer)) * kRankSlices;
+        ProfScope ps("k_rank");
+        hipLaunchKernelGGL(k_rank_partial, dim3(1 + rank_blocks), dim3(kThreads), 0, st, dense, K3, d_status, m->d_offs,
+                           mh.dmax, partial);
+        hipLaunchKernelGGL(k_rank_sum, dim3(mh.dmax / kThreads), dim3(kThreads), 0, st, partial, d_status, mh);
+    }
+    TS_LAUNCH("k_place", k_place, dim3(blocks_for(n_out, kThreads)), dim3(kThreads), slot_rank, n_out, mh, m->d_perm);
+    TS_HIP(hipEventSynchronize(ev));
     if (h[ST_RANGE])
         return fail(TS_ERR_COORD_RANGE, "coordinate outside batch [0,%d] / xyz [%d,%d]", TS_BATCH_MAX,
                     TS_COORD_MIN, TS_COORD_MAX);
     if (h[ST_DUP]) return fail(TS_ERR_DUPLICATE_COORD, "input coordinates are not distinct");
-    for (int n = 0; n <= K3; ++n) m->offs[n] = h[ST_WORDS + n];
+    m->offs[0] = 0;
+    for (int n = 0; n < K3; ++n) m->offs[n + 1] = m->offs[n] + h[ST_TOTALS + n];
     for (int n = 0; n < K3; ++n) m->sizes[n] = m->offs[n + 1] - m->offs[n];
     m->M = m->offs[K3];
+    const bool overflow = h[ST_OVERFLOW] != 0;
 
     TS_TRY(alloc_n(&m->d_in_idx, (size_t)m->M));
     TS_TRY(alloc_n(&m->d_out_idx, (size_t)m->M));
-    TS_TRY(alloc_n(&m->d_pos, (size_t)K3 * n_out));
-    TS_LAUNCH("k_compact", k_compact, dim3(nblk, K3), dim3(kThreads), m->d_nbr, n_out, nblk, blkcnt, m->d_in_idx, m->d_out_idx, m->d_pos);
+    const dim3 grid(blocks_for(n_out, kThreads)), block(kThreads);
+    if (K3 == 27) TS_LAUNCH("k_compact", k_compact<27>, grid, block, m->d_nbr, n_out, m->d_colbase, m->n_blocks, m->d_offs, m->d_in_idx, m->d_out_idx);
+    else if (K3 == 8) TS_LAUNCH("k_compact", k_compact<8>, grid, block, m->d_nbr, n_out, m->d_colbase, m->n_blocks, m->d_offs, m->d_in_idx, m->d_out_idx);
+    else TS_LAUNCH("k_compact", k_compact<1>, grid, block, m->d_nbr, n_out, m->d_colbase, m->n_blocks, m->d_offs, m->d_in_idx, m->d_out_idx);
 
-    // tiles: outputs ordered by neighbour bitmask so that a tile's rows share their offsets
-    size_t bytes = 0;
-    TS_HIP(rocprim::radix_sort_pairs(nullptr, bytes, masks, masks_sorted, rows, rows_sorted, (size_t)n_out, 0, K3,
-                                     st));
-    void *ws;
-    TS_TRY(tmp.get((char **)&ws, bytes));
-    {
+    if (overflow) {
+        // more distinct bitmasks than the table ranks: order the rows with a radix sort instead
+        uint32_t *keys, *keys_sorted;
+        int32_t *rows;
+        TS_TRY(tmp.get(&keys, (size_t)n_out));
+        TS_TRY(tmp.get(&keys_sorted, (size_t)n_out));
+        TS_TRY(tmp.get(&rows, (size_t)n_out));
+        TS_LAUNCH("k_extract_masks", k_extract_masks, grid, block, m->d_nbr, n_out, m->stride, K3, keys, rows);
+        size_t bytes = 0;
+        TS_HIP(rocprim::radix_sort_pairs(nullptr, bytes, keys, keys_sorted, rows, m->d_perm, (size_t)n_out, 0, K3, st));
+        void *ws;
+        TS_TRY(tmp.get((char **)&ws, bytes));
         ProfScope ps("sort_masks");
-        TS_HIP(rocprim::radix_sort_pairs(ws, bytes, masks, masks_sorted, rows, rows_sorted, (size_t)n_out, 0, K3, st));
+        TS_HIP(rocprim::radix_sort_pairs(ws, bytes, keys, keys_sorted, rows, m->d_perm, (size_t)n_out, 0, K3, st));
     }
-    m->n_tiles = (n_out + kTileRows - 1) / kTileRows;
-    TS_TRY(alloc_n(&m->d_perm, (size_t)m->n_tiles * kTileRows));
-    TS_TRY(alloc_n(&m->d_tmask, (size_t)m->n_tiles));
-    TS_TRY(alloc_n(&m->d_tmask32, (size_t)m->n_tiles * (kTileRows / 32)));
-    TS_TRY(alloc_n(&m->d_gnbr, (size_t)m->n_tiles * K3 * kTileRows));
-    TS_TRY(alloc_n(&m->d_ghdr, (size_t)m->n_tiles * (kTileRows / 32) * 8));
-    TS_TRY(alloc_n(&m->d_work, (size_t)m->n_tiles * 4 + 1));
-    TS_HIP(hipMemsetAsync(m->d_work + m->n_tiles * 4, 0, sizeof(uint32_t), st));
-    TS_LAUNCH("k_build_tiles", k_build_tiles, dim3((unsigned)m->n_tiles), dim3(kTileRows), m->d_nbr, n_out, K3, masks_sorted, rows_sorted, m->d_perm, m->d_tmask, m->d_tmask32, m->d_gnbr, m->d_ghdr, m->d_work, m->d_work + m->n_tiles * 4, split_thr(1), split_thr(2));
     TS_HIP(hipGetLastError());
     // temporaries go back to the pool when the caller's Temps dies; later work on the same
     // stream is ordered after the kernels above, so reuse is safe without another wait
+    return TS_OK;
+}
+
+// Allocations of the map that depend on n_out only; adds the permutation's clearing to `fill`.
+int alloc_outputs(ts_kmap *m, FillArgs *fill) {
+    const int K3 = m->K3;
+    m->stride = nbr_stride(K3);
+    m->n_blocks = (m->n_out + 63) / 64;
+    m->n_tiles = (m->n_out + kTileRows - 1) / kTileRows;
+    TS_TRY(alloc_n(&m->d_nbr, (size_t)m->n_out * m->stride));
+    TS_TRY(alloc_n(&m->d_colbits, (size_t)K3 * m->n_blocks));
+    TS_TRY(alloc_n(&m->d_colbase, (size_t)K3 * m->n_blocks));
+    TS_TRY(alloc_n(&m->d_offs, (size_t)K3 + 1));
+    TS_TRY(alloc_n(&m->d_perm, (size_t)m->n_tiles * kTileRows));
+    fill->add(m->d_perm, (size_t)m->n_tiles * kTileRows * sizeof(int32_t), 0xFFFFFFFFu);
     return TS_OK;
 }
 
@@ -516,33 +812,33 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
     m->s = s;
     m->transposed = transposed;
     m->K3 = K3;
+    m->stride = nbr_stride(K3);
     m->centre = (s == 1) ? (K3 - 1) / 2 : -1;
     if (N == 0) return TS_OK;
 
     int *d_status;
     TS_TRY(tmp.get(&d_status, ST_WORDS));
-    TS_HIP(hipMemsetAsync(d_status, 0, ST_WORDS * sizeof(int), st));
+    MaskHash mh;
+    FillArgs fill;
+    fill.add(d_status, ST_WORDS * sizeof(int), 0u);
+    TS_TRY(make_mask_hash(tmp, &mh, &fill));
 
     uint64_t *given;   // keys of the caller's coordinates
     TS_TRY(alloc_n(&given, (size_t)N));
     m->d_in_keys = given;   // provisional owner, so that an early error frees it
-    if (s != 1)
-        TS_LAUNCH("k_pack", k_pack, dim3(blocks_for(N, kThreads)), dim3(kThreads), reinterpret_cast<const int4 *>(coords), N, given, d_status);
 
     Table table;
     if (s == 1) {
         m->n_in = m->n_out = N;
         m->d_out_keys = given;
-        TS_TRY(alloc_n(&m->d_nbr, (size_t)K3 * N));
-        {
-            ProfScope ps("memset_nbr");
-            TS_HIP(hipMemsetAsync(m->d_nbr, 0xFF, (size_t)K3 * N * sizeof(int32_t), st));
-        }
-        TS_TRY(make_table(tmp, N, &table));
-        TS_LAUNCH("k_pack_insert", k_pack_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), reinterpret_cast<const int4 *>(coords), N, given, table, m->d_nbr + (int64_t)m->centre * N, d_status);
-        if (K3 > 1)
-            TS_LAUNCH("k_probe_symmetric", k_probe_symmetric, dim3(blocks_for(N, kThreads), K3 / 2), dim3(kThreads), given, N, table, K, m->d_nbr);
+        TS_TRY(alloc_outputs(m, &fill));
+        TS_TRY(make_table(tmp, N, &table, &fill));
+        TS_TRY(launch_fill(fill));
+        TS_LAUNCH("k_pack_insert", k_pack_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), reinterpret_cast<const int4 *>(coords), N, given, table, d_status);
     } else {
+        TS_TRY(launch_fill(fill));
+        fill = FillArgs();
+        TS_LAUNCH("k_pack", k_pack, dim3(blocks_for(N, kThreads)), dim3(kThreads), reinterpret_cast<const int4 *>(coords), N, given, d_status);
         // coarse set: candidates -> sort -> unique (the empty key, if present, sorts last)
         const bool one_each = (K == 2 && s == 2);
         const size_t n_cand = one_each ? (size_t)N : (size_t)N * K3;
@@ -572,6 +868,9 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
         TS_HIP(hipMemcpyAsync(h, d_count, sizeof(int64_t), hipMemcpyDeviceToHost, st));
         TS_HIP(hipStreamSynchronize(st));
         const int64_t n_coarse = h[0];
+        if (n_coarse == 0) {   // only possible when every coordinate was rejected
+            return fail(TS_ERR_COORD_RANGE, "no valid input coordinate");
+        }
         uint64_t *coarse;
         TS_TRY(alloc_n(&coarse, (size_t)n_coarse));
         TS_HIP(hipMemcpyAsync(coarse, uniq, (size_t)n_coarse * sizeof(uint64_t), hipMemcpyDeviceToDevice, st));
@@ -579,31 +878,27 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             m->n_in = N;
             m->n_out = n_coarse;
             m->d_out_keys = coarse;
-            if (n_coarse == 0) {   // only possible when every coordinate was rejected
-                return fail(TS_ERR_COORD_RANGE, "no valid input coordinate");
-            }
-            TS_TRY(alloc_n(&m->d_nbr, (size_t)K3 * n_coarse));
-            TS_TRY(make_table(tmp, N, &table));
-            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, table, (int32_t *)nullptr, d_status);
-            TS_LAUNCH("k_probe_forward", k_probe_forward, dim3(blocks_for(n_coarse, kThreads), K3), dim3(kThreads), coarse, n_coarse, table, K, s, m->d_nbr);
+            TS_TRY(alloc_outputs(m, &fill));
+            TS_TRY(make_table(tmp, N, &table, &fill));
+            TS_TRY(launch_fill(fill));
+            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, table, d_status);
         } else {
             m->n_in = n_coarse;
             m->n_out = N;
             m->d_in_keys = coarse;
             m->d_out_keys = given;
-            if (n_coarse == 0) return fail(TS_ERR_COORD_RANGE, "no valid input coordinate");
-            TS_TRY(alloc_n(&m->d_nbr, (size_t)K3 * N));
+            TS_TRY(alloc_outputs(m, &fill));
             // duplicates among the fine points are found by inserting them as well
             Table fine_table;
-            TS_TRY(make_table(tmp, N, &fine_table));
-            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, fine_table, (int32_t *)nullptr, d_status);
-            TS_TRY(make_table(tmp, n_coarse, &table));
-            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(n_coarse, kThreads)), dim3(kThreads), coarse, n_coarse, table, (int32_t *)nullptr, d_status);
-            TS_LAUNCH("k_probe_transposed", k_probe_transposed, dim3(blocks_for(N, kThreads), K3), dim3(kThreads), given, N, table, K, s, m->d_nbr);
+            TS_TRY(make_table(tmp, N, &fine_table, &fill));
+            TS_TRY(make_table(tmp, n_coarse, &table, &fill));
+            TS_TRY(launch_fill(fill));
+            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, fine_table, d_status);
+            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(n_coarse, kThreads)), dim3(kThreads), coarse, n_coarse, table, d_status);
         }
     }
     TS_HIP(hipGetLastError());
-    return finish_map(m, tmp, d_status);
+    return search_and_finish(m, tmp, table, mh, d_status);
 }
 
 }  // namespace
@@ -622,7 +917,7 @@ int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride,
     if (stride == 1 && kernel_size % 2 == 0) return fail(TS_ERR_INVALID_ARG, "stride 1 needs an odd kernel_size");
     if (transposed != 0 && transposed != 1) return fail(TS_ERR_INVALID_ARG, "transposed must be 0 or 1");
     if (transposed && stride == 1) return fail(TS_ERR_INVALID_ARG, "a transposed map needs stride > 1");
-    if (N > (int64_t)((1u << 31) - 1) / (ts::kMaxK3 + 1)) return fail(TS_ERR_UNSUPPORTED, "N too large for 32-bit pair indices");
+    if (N > (int64_t)((1u << 31) - 1) / (ts::kMaxK3 + 5)) return fail(TS_ERR_UNSUPPORTED, "N too large for 32-bit pair indices");
     ts_kmap *m = new (std::nothrow) ts_kmap();
     if (!m) return fail(TS_ERR_OOM, "host allocation failed");
     int rc = build(coords, N, kernel_size, stride, transposed, m);
