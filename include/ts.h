@@ -102,6 +102,15 @@ typedef struct ts_kmap ts_kmap;
 int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
                   ts_kmap **out_kmap);
 
+/*
+ * Optional.  Orders the output rows of a map by their offset bitmask (which offsets meet an input),
+ * so that the 128 rows a workgroup of the output-stationary kernel handles share their offsets and
+ * absent ones are skipped per tile (Sec. 4.2 argues the same way for grouping by map size).  It
+ * costs about as much as the search itself, so it pays for maps that serve several layers; results
+ * of ts_sparse_conv do not depend on it bit for bit.  Idempotent.  Synchronises the stream.
+ */
+int ts_kmap_sort_rows(ts_kmap *kmap);
+
 /* Release a map and everything it owns.  NULL is allowed. */
 void ts_free(ts_kmap *kmap);
 

@@ -154,8 +154,9 @@ __device__ __forceinline__ void store_rows(TO *out, int64_t row, int cout, int c
 template <class T, int NCB, int KC, int G>
 __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, const T *__restrict__ Wt,
                                                     const int32_t *__restrict__ nbr, int stride,
-                                                    const int32_t *__restrict__ perm, T *__restrict__ out,
-                                                    const T *__restrict__ zero_row, int cin, int cout, int K3) {
+                                                    const int32_t *__restrict__ perm, int64_t n_out,
+                                                    T *__restrict__ out, const T *__restrict__ zero_row, int cin,
+                                                    int cout, int K3) {
     typedef Shape<T, NCB, KC> S;
     typedef typename S::vec vec;
     __shared__ __attribute__((aligned(16))) T lds_w[2][G][S::SLAB];
@@ -177,7 +178,8 @@ __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, con
     __syncthreads();
     {
         const int half = threadIdx.x >> 7, col = threadIdx.x & 127;
-        const int32_t k = perm[tile * kTileRows + col];
+        const int64_t pos = tile * kTileRows + col;
+        const int32_t k = perm ? perm[pos] : (pos < n_out ? (int32_t)pos : -1);
         const int chunks = stride / 4, cph = chunks >= 2 ? chunks / 2 : 1;
         const int4 *src = reinterpret_cast<const int4 *>(nbr + (int64_t)(k >= 0 ? k : 0) * stride);
         int4 v[4];
@@ -266,7 +268,10 @@ __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, con
             if (!stage(bx_b, j_b, live_b, bx_a, j_a, live_a)) break;
         }
     }
-    store_rows<T, NCB>(out, perm[tile * kTileRows + slot], cout, co0, acc);
+    {
+        const int64_t pos = tile * kTileRows + slot;
+        store_rows<T, NCB>(out, perm ? perm[pos] : (pos < n_out ? pos : -1), cout, co0, acc);
+    }
 }
 
 // ---- explicit dataflow ------------------------------------------------------------------------
@@ -509,7 +514,7 @@ struct FusedLaunch {
         constexpr int G = fused_group(NCB, KSTEPS);
         dim3 grid((unsigned)kmap->n_tiles, out->cols / (NCB * 32));
         TS_LAUNCH("k_fused", (k_fused<T, NCB, KC, G>), grid, dim3(kThreads), static_cast<const T *>(pr.x),
-                  static_cast<const T *>(pr.wt), kmap->d_nbr, kmap->stride, kmap->d_perm,
+                  static_cast<const T *>(pr.wt), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->n_out,
                   static_cast<T *>(out->data), zero, pr.cin_pad, out->cols, kmap->K3);
     }
 };

@@ -118,7 +118,8 @@ struct ts_kmap {
     // offs[n] + colbase[n][k/64] + popcount(colbits[n][k/64] & ((1 << k%64) - 1)).
     uint64_t *d_colbits = nullptr;        // [K3][n_blocks] bit r: output 64*b + r has offset n
     int32_t *d_colbase = nullptr;         // [K3][n_blocks] pairs of offset n in the blocks before b
-    // Output rows ordered by offset bitmask, so that the rows of a tile share their offsets.
-    int64_t n_tiles = 0;
+    // Optional (ts_kmap_sort_rows): output rows ordered by offset bitmask, so that the rows of a
+    // tile of the output-stationary kernel share their offsets.  NULL = natural row order.
+    int64_t n_tiles = 0;                  // ceil(n_out / kTileRows)
     int32_t *d_perm = nullptr;            // [n_tiles*kTileRows] sorted position -> output row, -1 = padding
 };

@@ -1,22 +1,23 @@
 // Kernel-map construction (paper Sec. 2.1: output coordinates, Alg. 3; map search, Alg. 1).
 //
 // Pipeline on the device, one stream:
-//   fill     one launch clears the hash tables, counters and the tile permutation
+//   fill     one launch clears the hash table, the counters and (stride 1) the neighbour table
 //   pack     (b,x,y,z) -> order-preserving 64-bit keys       ("flattening the coordinate", Sec. 2.1.2)
 //   stride>1: candidate keys (p - delta)/s, radix sort, unique -> P_out           (Alg. 3, stages 1-4)
-//   insert   the searched point set into an open-addressing table (64-bit CAS); the 8 cells of a
-//            2x2x2 block share one 128-byte bucket, so the 27 probes of a point touch ~8 lines
-//   probe    one thread per OUTPUT point looks up s*q_k + delta_n for every offset n (Alg. 1) with
-//            all loads in flight at once, and leaves per output: the row of neighbour indices and
-//            its offset bitmask; per 64 outputs and offset: a presence bitmap and its count; per
-//            distinct bitmask: the number of rows holding it (a small hash table)
+//   insert   the searched point set into an open-addressing table (64-bit CAS)
+//   search   s*q_k + delta_n for every output k and offset n (Alg. 1).  Stride 1, K = 3: one thread
+//            per (point, offset below the centre), the mirrored entry written alongside
+//            (Sec. 4.2.1), then a pass over the rows; otherwise one thread per output.  Leaves per
+//            output the row of neighbour indices and its offset bitmask, and per 64 outputs and
+//            offset a presence bitmap with its count
 //   scan     per-offset exclusive scan of the block counts -> where each pair sits in the
-//            offset-major lists
-//   rank     first position of each distinct bitmask = rows whose mask sorts lower (by counting)
-//   place    rows go to (first position of their bitmask) + (arrival rank): rows with equal masks
-//            are adjacent, which lets the output-stationary kernel skip absent offsets per tile
+//            offset-major lists; the last block to finish turns the totals into offs[]
 //   compact  pair lists M[W_n] (in, out), ordered by output index inside an offset
-// The host waits once, for the map sizes and error flags, while `rank` and `place` are running.
+// The host waits once, after `scan`, for the map sizes and error flags.
+//
+// ts_kmap_sort_rows (optional, for maps that serve several layers) orders the output rows by
+// offset bitmask: distinct bitmasks are counted in a small hash table, ranked, and every row
+// goes to (first position of its bitmask) + (arrival rank).
 #include "ts_internal.h"
 
 #include <cstring>
@@ -35,24 +36,22 @@ constexpr int kThreads = 256;
 enum {
     ST_RANGE = 0,       // a coordinate was outside the packable range
     ST_DUP = 1,         // two input rows held the same coordinate
-    ST_DCOUNT = 2,      // distinct offset bitmasks seen
+    ST_DCOUNT = 2,      // distinct offset bitmasks seen (ts_kmap_sort_rows)
     ST_OVERFLOW = 3,    // the bitmask table could not hold them all
+    ST_TICKET = 4,      // scan blocks that have finished
     ST_TOTALS = 8,      // [32] per-offset map sizes
     ST_WORDS = 40
 };
 
 // ---- coordinate hash table ------------------------------------------------------------------------
-// 16-byte slots {key, value}; 8 slots form a 128-byte bucket addressed by the hash of the point's
-// 2x2x2 block, the home slot inside the bucket by the three parity bits.
-struct Slot {
-    uint64_t key;
-    int32_t val;
-    int32_t pad;
-};
-static_assert(sizeof(Slot) == 16, "one slot is one 128-bit load");
-
+// Open addressing over two arrays: 64-bit keys (what lookups read) and 32-bit values (read on a
+// hit only).  Random lookups cost about twice as much once the array they walk no longer fits a
+// 4 MiB L2 slice, so the probed array is kept as small as the key allows.  8 keys form a 64-byte
+// bucket addressed by the hash of the point's 2x2x2 block, the home slot inside the bucket by the
+// three parity bits: the cells around a point share a few buckets.
 struct Table {
-    Slot *slots;
+    uint64_t *keys;
+    int32_t *vals;
     uint32_t mask;   // capacity - 1 (capacity: power of two >= 2 * entries, >= 1024)
     int shift;       // 64 - log2(capacity / 8)
 };
@@ -67,26 +66,26 @@ __device__ __forceinline__ uint32_t home_slot(uint64_t key, int shift) {
     return (uint32_t)((cell * 0x9E3779B97F4A7C15ull) >> shift) * 8 + home_sub(key);   // multiplicative (Fibonacci) hashing
 }
 // Slot after `slot` in a probe sequence: 9 further (next bucket, next position; odd, so the sequence
-// visits every slot of the power-of-two table).  A miss therefore ends at the first empty slot it
-// meets, which for a point's absent neighbour is almost always the home slot itself.
+// visits every slot of the power-of-two table).  A miss ends at the first empty slot it meets, which
+// for a point's absent neighbour is usually the home slot itself.
 __device__ __forceinline__ uint32_t next_slot(uint32_t slot, uint32_t mask) { return (slot + 9u) & mask; }
 
-// Loads by 32-bit byte offset from the table base (capacity is at most 2^27 slots), which keeps
+// Loads by 32-bit byte offset from the array base (capacity is at most 2^27 slots), which keeps
 // one register per lookup for the address instead of two.
 __device__ __forceinline__ uint64_t slot_key(const Table &t, uint32_t slot) {
-    return *reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(t.slots) + (slot << 4));
+    return *reinterpret_cast<const uint64_t *>(reinterpret_cast<const char *>(t.keys) + (slot << 3));
 }
 __device__ __forceinline__ int32_t slot_val(const Table &t, uint32_t slot) {
-    return *reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(t.slots) + ((slot << 4) + 8u));
+    return *reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(t.vals) + (slot << 2));
 }
 
 __device__ __forceinline__ void table_insert(const Table &t, uint64_t key, int32_t value, int *status) {
     uint32_t slot = home_slot(key, t.shift);
     for (;;) {
-        unsigned long long prev = atomicCAS(reinterpret_cast<unsigned long long *>(&t.slots[slot].key),
+        unsigned long long prev = atomicCAS(reinterpret_cast<unsigned long long *>(&t.keys[slot]),
                                             (unsigned long long)kEmptyKey, (unsigned long long)key);
         if (prev == kEmptyKey) {
-            t.slots[slot].val = value;
+            t.vals[slot] = value;
             return;
         }
         if (prev == key) {
@@ -230,14 +229,24 @@ struct MaskHash {
     int shift;          // 32 - log2(cap)
     int dmax;           // most distinct masks the fast path ranks
 };
-constexpr int kMaskHashCap = 1 << 15;
+constexpr int kMaskHashCap = 1 << 16;
 constexpr int kMaskHashMaxDistinct = 1 << 14;
 constexpr int kMaskHashMaxSteps = 128;
 
 __device__ __forceinline__ int mask_hash_insert(const MaskHash &mh, uint32_t mask, int *status) {
-    uint32_t sl = (mask * 0x9E3779B1u) >> mh.shift;
+    // bitmasks are structured keys: mix all bits before taking the top ones
+    uint32_t h = mask;
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    uint32_t sl = h >> mh.shift;
     for (int step = 0; step < kMaskHashMaxSteps; ++step) {
-        uint32_t prev = __atomic_load_n(&mh.key[sl], __ATOMIC_RELAXED);   // most masks are in the table already
+        // An ordinary (cached) load first: most masks are in the table already, and a key never
+        // changes once set.  A stale "empty" only means the compare-and-swap below decides.
+        uint32_t prev = mh.key[sl];
+        if (prev == 0xFFFFFFFFu) prev = __hip_atomic_load(&mh.key[sl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (prev == 0xFFFFFFFFu) prev = atomicCAS(&mh.key[sl], 0xFFFFFFFFu, mask);
         if (prev == 0xFFFFFFFFu) {
             const int id = atomicAdd(&status[ST_DCOUNT], 1);
@@ -279,6 +288,58 @@ __host__ __device__ __forceinline__ uint32_t mask_sort_key(uint32_t mask, int K3
     return key;
 }
 
+// What every search kernel does once a thread knows the offset bitmask of its output row:
+// presence bitmaps of the wave's 64 outputs, one per offset, and their counts.
+template <int K3>
+__device__ __forceinline__ void finish_rows(uint32_t mask, uint64_t *__restrict__ colbits, int32_t *__restrict__ colcnt,
+                                            int64_t n_blocks) {
+    const int lane = threadIdx.x & 63;
+    const int64_t block64 = (int64_t)blockIdx.x * (blockDim.x / 64) + (threadIdx.x >> 6);   // wave-uniform
+    uint64_t mine = 0;
+#pragma unroll
+    for (int n = 0; n < K3; ++n) {
+        const uint64_t b = __ballot((mask >> n) & 1u);
+        if (lane == n) mine = b;
+    }
+    if (lane < K3 && block64 < n_blocks) {
+        colbits[(int64_t)lane * n_blocks + block64] = mine;
+        colcnt[(int64_t)lane * n_blocks + block64] = __popcll(mine);
+    }
+}
+
+// ts_kmap_sort_rows, step 1: register every row's bitmask in the mask table; slot_rank[k] = (table
+// slot, arrival rank among the rows of that mask).  Lanes of a wave holding the same mask share
+// one counter update: first the wave's classes of equal masks (registers only), then every class
+// leader talks to the table at once.
+__global__ void __launch_bounds__(kThreads) k_register(const int32_t *__restrict__ nbr, int64_t n_out, int stride, int K3,
+                                                       int *__restrict__ status, MaskHash mh, int2 *__restrict__ slot_rank) {
+    const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const bool ok = k < n_out;
+    const uint32_t mask = ok ? (uint32_t)nbr[k * stride + K3] : 0u;
+    int my_leader = lane;
+    uint64_t my_class = 0;
+    uint64_t todo = __ballot(ok);
+    while (todo) {
+        const int leader = __ffsll((unsigned long long)todo) - 1;
+        const uint32_t lm = (uint32_t)__shfl((int)mask, leader, 64);
+        const uint64_t same = __ballot(ok && mask == lm);
+        if ((same >> lane) & 1ull) {
+            my_leader = leader;
+            my_class = same;
+        }
+        todo &= ~same;
+    }
+    int sl = -1, first = 0;
+    if (ok && lane == my_leader) {
+        sl = mask_hash_insert(mh, mask, status);
+        if (sl >= 0) first = atomicAdd(&mh.cnt[sl], __popcll(my_class));
+    }
+    const int my_slot = __shfl(sl, my_leader, 64);
+    const int my_rank = __shfl(first, my_leader, 64) + __popcll(my_class & ((1ull << lane) - 1ull));
+    if (ok) slot_rank[k] = make_int2(my_slot, my_rank);
+}
+
 // ---- map search (Alg. 1) -------------------------------------------------------------------------------
 enum { MODE_SUB = 0, MODE_FWD = 1, MODE_TR = 2 };
 
@@ -287,18 +348,14 @@ enum { MODE_SUB = 0, MODE_FWD = 1, MODE_TR = 2 };
 //   MODE_FWD  stride s: input at s*q_k + delta_n
 //   MODE_TR   transposed: coarse point (p_k - delta_n)/s when s divides the difference
 // Writes nbr[k][0..K3) (input row or -1) and nbr[k][K3] = bitmask of the offsets present; per wave
-// (64 consecutive outputs) and offset the presence bitmap and its popcount; registers the row's
-// bitmask in the mask table.  (No global counters here: atomics from every wave on one cache
-// line are served one after the other and would take longer than everything else.)
+// (64 consecutive outputs) and offset the presence bitmap and its popcount.  (No global counters
+// here: atomics from every wave on one cache line are served one after the other.)
 template <int MODE, int K>
 __global__ void __launch_bounds__(kThreads, 3) k_probe(const uint64_t *__restrict__ out_keys, int64_t n_out, Table t, int s,
                                                     int32_t *__restrict__ nbr, uint64_t *__restrict__ colbits,
-                                                    int32_t *__restrict__ colcnt, int64_t n_blocks, int *__restrict__ status,
-                                                    MaskHash mh, int2 *__restrict__ slot_rank) {
+                                                    int32_t *__restrict__ colcnt, int64_t n_blocks) {
     constexpr int K3 = K * K * K, STRIDE = nbr_stride(K3), CENTRE = (K3 - 1) / 2;
     const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int lane = threadIdx.x & 63;
-    const int64_t block64 = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);   // wave-uniform
     const uint64_t key = k < n_out ? out_keys[k] : kEmptyKey;
     const bool ok = key != kEmptyKey;
     int32_t c[4] = {0, 0, 0, 0};
@@ -392,43 +449,64 @@ __global__ void __launch_bounds__(kThreads, 3) k_probe(const uint64_t *__restric
         }
     }
 
-    // presence bitmaps of this wave's 64 outputs, one per offset, and their counts
-    uint64_t mine = 0;
-#pragma unroll
-    for (int n = 0; n < K3; ++n) {
-        const uint64_t b = __ballot((mask >> n) & 1u);
-        if (lane == n) mine = b;
-    }
-    if (lane < K3 && block64 < n_blocks) {
-        const int cnt = __popcll(mine);
-        colbits[(int64_t)lane * n_blocks + block64] = mine;
-        colcnt[(int64_t)lane * n_blocks + block64] = cnt;
-    }
+    finish_rows<K3>(mask, colbits, colcnt, n_blocks);
+}
 
-    // register the bitmask; lanes of a wave holding the same mask share one counter update.
-    // First the wave's classes of equal masks (registers only), then every class leader talks to
-    // the table at once, so a wave pays two memory round trips however many masks it holds.
-    int my_leader = lane;
-    uint64_t my_class = 0;
-    uint64_t todo = __ballot(ok);
-    while (todo) {
-        const int leader = __ffsll((unsigned long long)todo) - 1;
-        const uint32_t lm = (uint32_t)__shfl((int)mask, leader, 64);
-        const uint64_t same = __ballot(ok && mask == lm);
-        if ((same >> lane) & 1ull) {
-            my_leader = leader;
-            my_class = same;
+// Map search for stride 1, odd K, one thread per (point i, offset n) with n below the centre.
+// A hit (j at p_i + delta_n) gives two entries: (j, i, n) in row i and, by symmetry (Sec. 4.2.1),
+// (i, j, K^3-1-n) in row j; rows start out all -1.  One lookup per thread: a long probe chain
+// delays one wave of 64 lookups, not a wave holding all 26 lookups of 64 points, and the many
+// waves in flight hide the memory round trips.
+__global__ void k_probe_symmetric(const uint64_t *__restrict__ keys, int64_t n_pts, Table t, int K, int32_t *__restrict__ nbr,
+                                  int stride) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_pts) return;
+    const int n = blockIdx.y, K3 = K * K * K;
+    const uint64_t key = keys[i];
+    if (key == kEmptyKey) return;
+    const uint64_t want = (uint64_t)((int64_t)key + key_delta(offset_component(K, n, 0), offset_component(K, n, 1), offset_component(K, n, 2)));
+    uint32_t slot = home_slot(want, t.shift);
+    for (;;) {
+        const uint64_t found = slot_key(t, slot);
+        if (found == want) {
+            const int32_t j = slot_val(t, slot);
+            nbr[i * stride + n] = j;
+            nbr[(int64_t)j * stride + (K3 - 1 - n)] = (int32_t)i;
+            return;
         }
-        todo &= ~same;
+        if (found == kEmptyKey) return;
+        slot = next_slot(slot, t.mask);
     }
-    int sl = -1, first = 0;
-    if (ok && lane == my_leader) {
-        sl = mask_hash_insert(mh, mask, status);
-        if (sl >= 0) first = atomicAdd(&mh.cnt[sl], __popcll(my_class));
+}
+
+// Second half of the stride-1 search: a thread per output row reads the row the symmetric probe
+// left, sets the centre entry (output k is input k) and the row's offset bitmask, and does what
+// every probe kernel does once the bitmask is known.
+template <int K3>
+__global__ void __launch_bounds__(kThreads) k_rows(int32_t *__restrict__ nbr, const uint64_t *__restrict__ keys, int64_t n_out,
+                                                   uint64_t *__restrict__ colbits, int32_t *__restrict__ colcnt,
+                                                   int64_t n_blocks) {
+    constexpr int STRIDE = nbr_stride(K3), CHUNKS = (K3 + 3) / 4, CENTRE = (K3 - 1) / 2;
+    const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const bool ok = k < n_out && keys[k] != kEmptyKey;
+    uint32_t mask = 0;
+    if (ok) {
+        int32_t j[CHUNKS * 4];
+#pragma unroll
+        for (int ch = 0; ch < CHUNKS; ++ch) {
+            const int4 v = reinterpret_cast<const int4 *>(nbr + k * STRIDE)[ch];
+            j[ch * 4 + 0] = v.x;
+            j[ch * 4 + 1] = v.y;
+            j[ch * 4 + 2] = v.z;
+            j[ch * 4 + 3] = v.w;
+        }
+#pragma unroll
+        for (int n = 0; n < K3; ++n)
+            if (n == CENTRE || j[n] >= 0) mask |= 1u << n;
+        nbr[k * STRIDE + CENTRE] = (int32_t)k;
+        nbr[k * STRIDE + K3] = (int32_t)mask;
     }
-    const int my_slot = __shfl(sl, my_leader, 64);
-    const int my_rank = __shfl(first, my_leader, 64) + __popcll(my_class & ((1ull << lane) - 1ull));
-    if (k < n_out) slot_rank[k] = make_int2(my_slot, my_rank);
+    finish_rows<K3>(mask, colbits, colcnt, n_blocks);
 }
 
 template <int THREADS = kThreads>
@@ -454,26 +532,12 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *total) {
 }
 
 // Block n: exclusive scan of colcnt[n][*] -> colbase[n][b] = pairs of offset n in the 64-row
-// blocks before b (relative to the start of the offset's list), and the offset's total.
-// Extra blocks: the distinct bitmasks as a dense list of (sort key, rows) for the rank step.
+// blocks before b (relative to the start of the offset's list), and the offset's total.  The
+// block that finishes last turns the totals into offs[] (start of each offset's list).
 constexpr int kScanThreads = 1024, kScanItems = 4;
-constexpr int kRankSlices = 32, kRankPer = 4, kRankUnroll = 16;
-constexpr int kDensePad = kRankSlices * kRankUnroll;   // sentinel entries behind the list
 __global__ void __launch_bounds__(kScanThreads) k_scan(const int32_t *__restrict__ colcnt, int32_t *__restrict__ colbase,
-                                                       int64_t n_blocks, int K3, int *__restrict__ status, MaskHash mh,
-                                                       int2 *__restrict__ dense) {
-    if ((int)blockIdx.x >= K3) {
-        int D = status[ST_DCOUNT];
-        D = D < mh.dmax ? D : mh.dmax;
-        const int d = ((int)blockIdx.x - K3) * kScanThreads + threadIdx.x;
-        if (d < D) {
-            const int sl = mh.dlist[d];
-            dense[d] = make_int2((int)mask_sort_key(mh.key[sl], K3), mh.cnt[sl]);
-        } else if (d < mh.dmax + kDensePad) {
-            dense[d] = make_int2(-1, 0);   // sorts after every mask, holds no rows
-        }
-        return;
-    }
+                                                       int64_t n_blocks, int K3, int *__restrict__ status,
+                                                       int32_t *__restrict__ offs) {
     const int n = blockIdx.x;
     const int32_t *src = colcnt + (int64_t)n * n_blocks;
     int32_t *dst = colbase + (int64_t)n * n_blocks;
@@ -495,29 +559,44 @@ __global__ void __launch_bounds__(kScanThreads) k_scan(const int32_t *__restrict
         }
         run += total;
     }
-    if (threadIdx.x == 0) status[ST_TOTALS + n] = run;
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(&status[ST_TOTALS + n], run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        if (atomicAdd(&status[ST_TICKET], 1) == K3 - 1) {   // every total is visible now
+            __threadfence();
+            int at = 0;
+            for (int q = 0; q < K3; ++q) {
+                offs[q] = at;
+                at += __hip_atomic_load(&status[ST_TOTALS + q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            offs[K3] = at;
+        }
+    }
 }
 
-// Rank step for the distinct bitmasks: start of mask d = rows whose mask sorts lower.  Block
-// (d-block, slice) adds up, for 1024 masks (4 per thread), the rows of the lower masks found in
-// one slice of the list; k_rank_sum adds the slices.  The list is read with wave-uniform
-// addresses (scalar loads), so the inner loop is compare / select / add only.
-// Block 0 of k_rank_partial instead turns the per-offset totals into the prefix offs[].
-__global__ void __launch_bounds__(kThreads) k_rank_partial(const int2 *__restrict__ dense, int K3, int *__restrict__ status,
-                                                           int32_t *__restrict__ offs, int dmax,
-                                                           int32_t *__restrict__ partial) {
-    if (blockIdx.x == 0) {
-        if (threadIdx.x == 0) {
-            int run = 0;
-            for (int n = 0; n < K3; ++n) {
-                offs[n] = run;
-                run += status[ST_TOTALS + n];
-            }
-            offs[K3] = run;
-        }
-        return;
+// ts_kmap_sort_rows, step 2: the distinct bitmasks as a dense list of (sort key, rows), followed
+// by sentinel entries that sort last and hold no rows.
+constexpr int kRankSlices = 32, kRankPer = 4, kRankUnroll = 16;
+constexpr int kDensePad = kRankSlices * kRankUnroll;
+__global__ void k_dense(const int *__restrict__ status, MaskHash mh, int K3, int2 *__restrict__ dense) {
+    int D = status[ST_DCOUNT];
+    D = D < mh.dmax ? D : mh.dmax;
+    const int d = blockIdx.x * blockDim.x + threadIdx.x;
+    if (d < D) {
+        const int sl = mh.dlist[d];
+        dense[d] = make_int2((int)mask_sort_key(mh.key[sl], K3), mh.cnt[sl]);
+    } else if (d < mh.dmax + kDensePad) {
+        dense[d] = make_int2(-1, 0);
     }
-    const int rb = blockIdx.x - 1, dblk = rb / kRankSlices, slice = rb % kRankSlices;
+}
+
+// ts_kmap_sort_rows, step 3: start of mask d = rows whose mask sorts lower.  Block (d-block, slice)
+// adds up, for 1024 masks (4 per thread), the rows of the lower masks found in one slice of the
+// list; k_rank_sum adds the slices.  The list is read with wave-uniform addresses (scalar loads),
+// so the inner loop is compare / select / add only.
+__global__ void __launch_bounds__(kThreads) k_rank_partial(const int2 *__restrict__ dense, const int *__restrict__ status,
+                                                           int dmax, int32_t *__restrict__ partial) {
+    const int rb = blockIdx.x, dblk = rb / kRankSlices, slice = rb % kRankSlices;
     int D = status[ST_DCOUNT];
     D = D < dmax ? D : dmax;
     if (dblk * kThreads * kRankPer >= D) return;
@@ -559,7 +638,7 @@ __global__ void k_rank_sum(const int32_t *__restrict__ partial, const int *__res
     mh.start[mh.dlist[d]] = sum;
 }
 
-// perm[start of the row's mask + arrival rank] = row.
+// ts_kmap_sort_rows, step 4: perm[start of the row's mask + arrival rank] = row.
 __global__ void k_place(const int2 *__restrict__ slot_rank, int64_t n_out, MaskHash mh, int32_t *__restrict__ perm) {
     int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= n_out) return;
@@ -646,10 +725,11 @@ int make_table(Temps &tmp, int64_t entries, Table *t, FillArgs *fill) {
     uint64_t cap = 1024;
     while (cap < (uint64_t)(2 * entries)) cap <<= 1;
     if (cap > (1ull << 27)) return fail(TS_ERR_UNSUPPORTED, "too many points for the hash table");
-    TS_TRY(tmp.get(&t->slots, cap));
+    TS_TRY(tmp.get(&t->keys, cap));
+    TS_TRY(tmp.get(&t->vals, cap));
     t->mask = (uint32_t)(cap - 1);
     t->shift = 64 - __builtin_ctzll(cap / 8);
-    fill->add(t->slots, cap * sizeof(Slot), 0xFFFFFFFFu);
+    fill->add(t->keys, cap * sizeof(uint64_t), 0xFFFFFFFFu);
     return TS_OK;
 }
 
@@ -692,65 +772,44 @@ int sort_keys(Temps &tmp, uint64_t *in, uint64_t *out, size_t n) {
     return TS_OK;
 }
 
-hipEvent_t sizes_event() {
-    static hipEvent_t ev = nullptr;
-    if (!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
-        (void)hipGetLastError();
-        ev = nullptr;
-    }
-    return ev;
-}
-
 template <int MODE, int K>
-void launch_probe(const ts_kmap *m, const Table &t, int32_t *colcnt, int *d_status, const MaskHash &mh, int2 *slot_rank) {
+void launch_probe(const ts_kmap *m, const Table &t, int32_t *colcnt) {
     TS_LAUNCH("k_probe", (k_probe<MODE, K>), dim3(blocks_for(m->n_out, kThreads)), dim3(kThreads), m->d_out_keys, m->n_out,
-              t, m->s, m->d_nbr, m->d_colbits, colcnt, m->n_blocks, d_status, mh, slot_rank);
+              t, m->s, m->d_nbr, m->d_colbits, colcnt, m->n_blocks);
 }
 
 // Map search and everything after it.  `table` holds the searched point set; m->d_out_keys the
-// outputs; the clearing of status words, mask table and permutation has been enqueued.
-int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, const MaskHash &mh, int *d_status) {
+// outputs; the clearing of the status words (and of the neighbour table where the search
+// writes hits only) has been enqueued.
+int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status) {
     hipStream_t st = stream();
     const int K3 = m->K3, K = m->K;
     const int64_t n_out = m->n_out;
     int32_t *colcnt;
-    int2 *slot_rank;
     TS_TRY(tmp.get(&colcnt, (size_t)K3 * m->n_blocks));
-    TS_TRY(tmp.get(&slot_rank, (size_t)n_out));
     const int mode = m->s == 1 ? MODE_SUB : (m->transposed ? MODE_TR : MODE_FWD);
-    if (mode == MODE_SUB && K == 1) launch_probe<MODE_SUB, 1>(m, table, colcnt, d_status, mh, slot_rank);
-    else if (mode == MODE_SUB && K == 3) launch_probe<MODE_SUB, 3>(m, table, colcnt, d_status, mh, slot_rank);
-    else if (mode == MODE_FWD && K == 1) launch_probe<MODE_FWD, 1>(m, table, colcnt, d_status, mh, slot_rank);
-    else if (mode == MODE_TR && K == 1) launch_probe<MODE_TR, 1>(m, table, colcnt, d_status, mh, slot_rank);
-    else if (mode == MODE_FWD && K == 2) launch_probe<MODE_FWD, 2>(m, table, colcnt, d_status, mh, slot_rank);
-    else if (mode == MODE_FWD && K == 3) launch_probe<MODE_FWD, 3>(m, table, colcnt, d_status, mh, slot_rank);
-    else if (mode == MODE_TR && K == 2) launch_probe<MODE_TR, 2>(m, table, colcnt, d_status, mh, slot_rank);
-    else if (mode == MODE_TR && K == 3) launch_probe<MODE_TR, 3>(m, table, colcnt, d_status, mh, slot_rank);
+    if (mode == MODE_SUB && K == 1) launch_probe<MODE_SUB, 1>(m, table, colcnt);
+    else if (mode == MODE_SUB && K == 3) {
+        TS_LAUNCH("k_probe_symmetric", k_probe_symmetric, dim3(blocks_for(n_out, kThreads), K3 / 2), dim3(kThreads), m->d_out_keys,
+                  n_out, table, K, m->d_nbr, m->stride);
+        TS_LAUNCH("k_rows", k_rows<27>, dim3(blocks_for(n_out, kThreads)), dim3(kThreads), m->d_nbr, m->d_out_keys, n_out,
+                  m->d_colbits, colcnt, m->n_blocks);
+    }
+    else if (mode == MODE_FWD && K == 1) launch_probe<MODE_FWD, 1>(m, table, colcnt);
+    else if (mode == MODE_TR && K == 1) launch_probe<MODE_TR, 1>(m, table, colcnt);
+    else if (mode == MODE_FWD && K == 2) launch_probe<MODE_FWD, 2>(m, table, colcnt);
+    else if (mode == MODE_FWD && K == 3) launch_probe<MODE_FWD, 3>(m, table, colcnt);
+    else if (mode == MODE_TR && K == 2) launch_probe<MODE_TR, 2>(m, table, colcnt);
+    else if (mode == MODE_TR && K == 3) launch_probe<MODE_TR, 3>(m, table, colcnt);
     else return fail(TS_ERR_UNSUPPORTED, "no map search for kernel_size %d, stride %d", K, m->s);
 
-    int2 *dense;
-    int32_t *partial;
-    TS_TRY(tmp.get(&dense, (size_t)mh.dmax + kDensePad));
-    TS_TRY(tmp.get(&partial, (size_t)kRankSlices * mh.dmax));
-    TS_LAUNCH("k_scan", k_scan, dim3(K3 + (mh.dmax + kDensePad + kScanThreads - 1) / kScanThreads), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, K3,
-              d_status, mh, dense);
+    TS_LAUNCH("k_scan", k_scan, dim3(K3), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, K3, d_status, m->d_offs);
 
-    // the one host round trip: error flags, map sizes, whether the mask table sufficed; ranking
-    // and placement are enqueued behind the copy so the device keeps working meanwhile
+    // the one host round trip: error flags and map sizes
     int32_t *h = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
-    hipEvent_t ev = sizes_event();
-    if (!h || !ev) return fail(TS_ERR_OOM, "host staging area or event unavailable");
+    if (!h) return TS_ERR_OOM;
     TS_HIP(hipMemcpyAsync(h, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    TS_HIP(hipEventRecord(ev, st));
-    {
-        const unsigned rank_blocks = (unsigned)(mh.dmax / (kThreads * kRankPer)) * kRankSlices;
-        ProfScope ps("k_rank");
-        hipLaunchKernelGGL(k_rank_partial, dim3(1 + rank_blocks), dim3(kThreads), 0, st, dense, K3, d_status, m->d_offs,
-                           mh.dmax, partial);
-        hipLaunchKernelGGL(k_rank_sum, dim3(mh.dmax / kThreads), dim3(kThreads), 0, st, partial, d_status, mh);
-    }
-    TS_LAUNCH("k_place", k_place, dim3(blocks_for(n_out, kThreads)), dim3(kThreads), slot_rank, n_out, mh, m->d_perm);
-    TS_HIP(hipEventSynchronize(ev));
+    TS_HIP(hipStreamSynchronize(st));
     if (h[ST_RANGE])
         return fail(TS_ERR_COORD_RANGE, "coordinate outside batch [0,%d] / xyz [%d,%d]", TS_BATCH_MAX,
                     TS_COORD_MIN, TS_COORD_MAX);
@@ -759,7 +818,6 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, const MaskHash
     for (int n = 0; n < K3; ++n) m->offs[n + 1] = m->offs[n] + h[ST_TOTALS + n];
     for (int n = 0; n < K3; ++n) m->sizes[n] = m->offs[n + 1] - m->offs[n];
     m->M = m->offs[K3];
-    const bool overflow = h[ST_OVERFLOW] != 0;
 
     TS_TRY(alloc_n(&m->d_in_idx, (size_t)m->M));
     TS_TRY(alloc_n(&m->d_out_idx, (size_t)m->M));
@@ -767,29 +825,81 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, const MaskHash
     if (K3 == 27) TS_LAUNCH("k_compact", k_compact<27>, grid, block, m->d_nbr, n_out, m->d_colbase, m->n_blocks, m->d_offs, m->d_in_idx, m->d_out_idx);
     else if (K3 == 8) TS_LAUNCH("k_compact", k_compact<8>, grid, block, m->d_nbr, n_out, m->d_colbase, m->n_blocks, m->d_offs, m->d_in_idx, m->d_out_idx);
     else TS_LAUNCH("k_compact", k_compact<1>, grid, block, m->d_nbr, n_out, m->d_colbase, m->n_blocks, m->d_offs, m->d_in_idx, m->d_out_idx);
-
-    if (overflow) {
-        // more distinct bitmasks than the table ranks: order the rows with a radix sort instead
-        uint32_t *keys, *keys_sorted;
-        int32_t *rows;
-        TS_TRY(tmp.get(&keys, (size_t)n_out));
-        TS_TRY(tmp.get(&keys_sorted, (size_t)n_out));
-        TS_TRY(tmp.get(&rows, (size_t)n_out));
-        TS_LAUNCH("k_extract_masks", k_extract_masks, grid, block, m->d_nbr, n_out, m->stride, K3, keys, rows);
-        size_t bytes = 0;
-        TS_HIP(rocprim::radix_sort_pairs(nullptr, bytes, keys, keys_sorted, rows, m->d_perm, (size_t)n_out, 0, K3, st));
-        void *ws;
-        TS_TRY(tmp.get((char **)&ws, bytes));
-        ProfScope ps("sort_masks");
-        TS_HIP(rocprim::radix_sort_pairs(ws, bytes, keys, keys_sorted, rows, m->d_perm, (size_t)n_out, 0, K3, st));
-    }
     TS_HIP(hipGetLastError());
     // temporaries go back to the pool when the caller's Temps dies; later work on the same
     // stream is ordered after the kernels above, so reuse is safe without another wait
     return TS_OK;
 }
 
-// Allocations of the map that depend on n_out only; adds the permutation's clearing to `fill`.
+// Orders the output rows by offset bitmask (see the head of this file).
+int sort_rows(ts_kmap *m) {
+    hipStream_t st = stream();
+    Temps tmp;
+    const int K3 = m->K3;
+    const int64_t n_out = m->n_out;
+    int *d_status;
+    int2 *slot_rank, *dense;
+    int32_t *partial, *perm;
+    MaskHash mh;
+    FillArgs fill;
+    const int64_t n_tiles = (n_out + kTileRows - 1) / kTileRows;
+    TS_TRY(tmp.get(&d_status, ST_WORDS));
+    TS_TRY(tmp.get(&slot_rank, (size_t)n_out));
+    TS_TRY(alloc_n(&perm, (size_t)n_tiles * kTileRows));
+    fill.add(d_status, ST_WORDS * sizeof(int), 0u);
+    fill.add(perm, (size_t)n_tiles * kTileRows * sizeof(int32_t), 0xFFFFFFFFu);
+    int rc = make_mask_hash(tmp, &mh, &fill);
+    if (rc == TS_OK) rc = tmp.get(&dense, (size_t)mh.dmax + kDensePad);
+    if (rc == TS_OK) rc = tmp.get(&partial, (size_t)kRankSlices * mh.dmax);
+    int32_t *h = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
+    if (rc == TS_OK && !h) rc = TS_ERR_OOM;
+    if (rc != TS_OK) {
+        dev_free(perm);
+        return rc;
+    }
+    auto body = [&]() -> int {
+        TS_TRY(launch_fill(fill));
+        const dim3 grid(blocks_for(n_out, kThreads)), block(kThreads);
+        TS_LAUNCH("k_register", k_register, grid, block, m->d_nbr, n_out, m->stride, K3, d_status, mh, slot_rank);
+        TS_LAUNCH("k_dense", k_dense, dim3(blocks_for(mh.dmax + kDensePad, kThreads)), block, d_status, mh, K3, dense);
+        {
+            const unsigned rank_blocks = (unsigned)(mh.dmax / (kThreads * kRankPer)) * kRankSlices;
+            ProfScope ps("k_rank");
+            hipLaunchKernelGGL(k_rank_partial, dim3(rank_blocks), block, 0, st, dense, d_status, mh.dmax, partial);
+            hipLaunchKernelGGL(k_rank_sum, dim3(mh.dmax / kThreads), block, 0, st, partial, d_status, mh);
+        }
+        TS_LAUNCH("k_place", k_place, grid, block, slot_rank, n_out, mh, perm);
+        TS_HIP(hipMemcpyAsync(h, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        TS_HIP(hipStreamSynchronize(st));
+        if (h[ST_OVERFLOW]) {
+            // more distinct bitmasks than the table ranks: order the rows with a radix sort instead
+            uint32_t *keys, *keys_sorted;
+            int32_t *rows;
+            TS_TRY(tmp.get(&keys, (size_t)n_out));
+            TS_TRY(tmp.get(&keys_sorted, (size_t)n_out));
+            TS_TRY(tmp.get(&rows, (size_t)n_out));
+            TS_LAUNCH("k_extract_masks", k_extract_masks, grid, block, m->d_nbr, n_out, m->stride, K3, keys, rows);
+            size_t bytes = 0;
+            TS_HIP(rocprim::radix_sort_pairs(nullptr, bytes, keys, keys_sorted, rows, perm, (size_t)n_out, 0, K3, st));
+            void *ws;
+            TS_TRY(tmp.get((char **)&ws, bytes));
+            ProfScope ps("sort_masks");
+            TS_HIP(rocprim::radix_sort_pairs(ws, bytes, keys, keys_sorted, rows, perm, (size_t)n_out, 0, K3, st));
+        }
+        TS_HIP(hipGetLastError());
+        return TS_OK;
+    };
+    rc = body();
+    if (rc != TS_OK) {
+        (void)hipStreamSynchronize(st);
+        dev_free(perm);
+        return rc;
+    }
+    m->d_perm = perm;
+    return TS_OK;
+}
+
+// Allocations of the map that depend on n_out only.
 int alloc_outputs(ts_kmap *m, FillArgs *fill) {
     const int K3 = m->K3;
     m->stride = nbr_stride(K3);
@@ -799,8 +909,7 @@ int alloc_outputs(ts_kmap *m, FillArgs *fill) {
     TS_TRY(alloc_n(&m->d_colbits, (size_t)K3 * m->n_blocks));
     TS_TRY(alloc_n(&m->d_colbase, (size_t)K3 * m->n_blocks));
     TS_TRY(alloc_n(&m->d_offs, (size_t)K3 + 1));
-    TS_TRY(alloc_n(&m->d_perm, (size_t)m->n_tiles * kTileRows));
-    fill->add(m->d_perm, (size_t)m->n_tiles * kTileRows * sizeof(int32_t), 0xFFFFFFFFu);
+    if (m->s == 1 && K3 == 27) fill->add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);   // the symmetric probe writes hits only
     return TS_OK;
 }
 
@@ -818,10 +927,8 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
 
     int *d_status;
     TS_TRY(tmp.get(&d_status, ST_WORDS));
-    MaskHash mh;
     FillArgs fill;
     fill.add(d_status, ST_WORDS * sizeof(int), 0u);
-    TS_TRY(make_mask_hash(tmp, &mh, &fill));
 
     uint64_t *given;   // keys of the caller's coordinates
     TS_TRY(alloc_n(&given, (size_t)N));
@@ -898,7 +1005,7 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
         }
     }
     TS_HIP(hipGetLastError());
-    return search_and_finish(m, tmp, table, mh, d_status);
+    return search_and_finish(m, tmp, table, d_status);
 }
 
 }  // namespace
@@ -931,6 +1038,12 @@ int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride,
 }
 
 void ts_free(ts_kmap *kmap) { destroy(kmap); }
+
+int ts_kmap_sort_rows(ts_kmap *kmap) {
+    if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    if (kmap->d_perm || kmap->n_out == 0) return TS_OK;
+    return sort_rows(kmap);
+}
 
 int64_t ts_kmap_num_in(const ts_kmap *kmap) { return kmap ? kmap->n_in : -1; }
 int64_t ts_kmap_num_out(const ts_kmap *kmap) { return kmap ? kmap->n_out : -1; }

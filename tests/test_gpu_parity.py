@@ -253,3 +253,38 @@ def test_row_order_independence():
     kmap_p = ts.ts_build_kmap(to_dev(coords[perm]), 3, 1)
     yp = ts.ts_sparse_conv(to_dev(x[perm]), to_dev(w), kmap_p).cpu().numpy()
     assert oracle.rel_l2(yp, y[perm]) < 1e-3
+
+
+@pytest.mark.parametrize("K,s,transposed", [(3, 1, False), (2, 2, False), (2, 2, True)])
+def test_sorted_rows_give_the_same_result(lidar_coords, K, s, transposed):
+    """ts_kmap_sort_rows only regroups the output rows: every row's sum keeps its order, so the
+    outputs are equal bit for bit; pairs and sizes are untouched; a second call is a no-op."""
+    coords = lidar_coords[:60000]
+    plain = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
+    grouped = ts.ts_build_kmap(to_dev(coords), K, s, transposed).sort_rows().sort_rows()
+    assert np.array_equal(gpu_triples(plain), gpu_triples(grouped))
+    for c_in, c_out in ((32, 64), (128, 128)):
+        x = to_dev(features(800 + c_in, plain.num_in, c_in, np.float16))
+        w = to_dev(conv_weights(801 + c_in, K ** 3, c_in, c_out, np.float16))
+        y1 = ts.ts_sparse_conv(x, w, plain, dataflow=ts.TS_DATAFLOW_FUSED)
+        y2 = ts.ts_sparse_conv(x, w, grouped, dataflow=ts.TS_DATAFLOW_FUSED)
+        assert torch.equal(y1, y2)
+    ref = oracle_conv(coords, features(832, plain.num_in, 32, np.float16), conv_weights(833, K ** 3, 32, 64, np.float16),
+                      K, s, transposed)
+    check_features(ts.ts_sparse_conv(to_dev(features(832, plain.num_in, 32, np.float16)),
+                                     to_dev(conv_weights(833, K ** 3, 32, 64, np.float16)), grouped), ref, torch.float16,
+                   "sorted rows")
+
+
+def test_sorted_rows_many_distinct_masks():
+    """Uniform random occupancy gives more distinct bitmasks than the mask table ranks (the radix-sort path)."""
+    coords = _rand_coords(91, 120000, 0, 64)
+    kmap = ts.ts_build_kmap(to_dev(coords), 3, 1)
+    x = to_dev(features(900, kmap.num_in, 32, np.float16))
+    w = to_dev(conv_weights(901, 27, 32, 32, np.float16))
+    y1 = ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_FUSED)
+    kmap.sort_rows()
+    y2 = ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_FUSED)
+    assert torch.equal(y1, y2)
+    y3 = ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_EXPLICIT)
+    assert oracle.rel_l2(y3.cpu().numpy(), y1.cpu().numpy()) < 1e-3
