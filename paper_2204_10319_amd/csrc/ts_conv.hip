@@ -18,6 +18,9 @@
 // one row per accumulator quad, which makes the stores 8-16 bytes wide.
 #include "ts_internal.h"
 
+#include <type_traits>
+#include <utility>
+
 using namespace ts;
 
 namespace {
@@ -274,6 +277,224 @@ __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, con
     }
 }
 
+// ---- fused output-stationary kernel, fp16, deep software pipeline ---------------------------------
+// D[co][m] += Wt[co][ci] * X[m][ci] with v_mfma_f32_16x16x32_f16: lane l of a wave holds, of the
+// "B" operand, 8 consecutive input channels (8 * (l / 16) + 0..7 of a 32-channel step) of
+// output row l % 16, i.e. 16 contiguous bytes of the neighbour's feature row, so gathered rows
+// go from memory straight into the operand registers, 4 lanes per 64 bytes of a row.  A wave owns
+// 32 output rows (two 16-column blocks), a workgroup 128; the accumulators hold NCO blocks of 16
+// output channels.  A stage is one (offset, KC-channel chunk) of the tile: its weight slab, kept
+// in global memory in operand order, goes global -> registers -> LDS once for the four waves.
+// What a wave pays for is dependent memory round trips, so the loads of a stage are issued DEPTH
+// stages before their use and rotate through DEPTH register sets; one barrier per stage.
+// Rows of an output are added in offset order whatever the tile holds, so results do not depend
+// on how rows are grouped.
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: arrays of it stay in registers
+
+// Calls fn(std::integral_constant<int, 0>{}) ... fn(std::integral_constant<int, N-1>{}): the index
+// is a constant expression inside fn, so arrays indexed with it stay in registers.
+template <class Fn, int... I>
+__device__ __forceinline__ void static_for_impl(Fn &&fn, std::integer_sequence<int, I...>) {
+    (fn(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class Fn>
+__device__ __forceinline__ void static_for(Fn &&fn) {
+    static_for_impl(fn, std::make_integer_sequence<int, N>{});
+}
+
+template <int NCO, int KSTEPS, int DEPTH>
+__global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restrict__ X, const u32x4 *__restrict__ Wf,
+                                                        const int32_t *__restrict__ nbr, int stride,
+                                                        const int32_t *__restrict__ perm, int64_t n_out,
+                                                        _Float16 *__restrict__ out, int *__restrict__ sched,
+                                                        int cin, int cout, int K3) {
+    constexpr int KC = KSTEPS * 32, FRAGS = NCO * KSTEPS, SLAB = FRAGS * 64;   // slab in 16-byte vectors
+    constexpr int WV = (SLAB + kThreads - 1) / kThreads;
+    __shared__ u32x4 lds_w[2][SLAB];
+    __shared__ int32_t lds_j[kMaxK3][kTileRows];
+    __shared__ uint32_t s_mask;
+    __shared__ int s_nlist[32];
+    __shared__ int s_tile;
+    // The launch holds as many workgroups as stay resident at once.  Workgroup b starts with tile b;
+    // the tiles beyond the grid are handed out through counters, so nobody waits for a second
+    // round of workgroups.  One counter per XCD (blockIdx % 8), on cache lines of their own:
+    // atomics on one address are served one after the other.
+    const int64_t n_tiles = (n_out + kTileRows - 1) / kTileRows;
+    sched += kSchedWords * blockIdx.y;
+    const int xcd = blockIdx.x & 7;
+    const int cb0 = blockIdx.y * NCO;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m16 = lane & 15, g = lane >> 4;
+    const int r0 = wave * kWaveRows + m16, r1 = r0 + 16;   // the lane's two output rows (tile slots)
+    // Rows sorted by bitmask put the tiles with the most offsets last: take tiles from the end
+    // then, so that the longest ones do not start when everything else is done.
+    int64_t turn = blockIdx.x;
+    while (turn < n_tiles) {
+    const int64_t tile = perm ? n_tiles - 1 - turn : turn;
+    // ask for the next tile now; the answer is needed when this one is done
+    int ticket = 0;
+    if (threadIdx.x == 0) ticket = atomicAdd(&sched[xcd * 32], 1);
+
+    // Neighbour rows of the tile's outputs -> LDS (offset-major), and the OR of their offset
+    // bitmasks.  Two threads share an output row and read half of its table row each.
+    if (threadIdx.x == 0) s_mask = 0;
+    __syncthreads();
+    {
+        const int half = threadIdx.x >> 7, col = threadIdx.x & 127;
+        const int64_t pos = tile * kTileRows + col;
+        const int32_t k = perm ? perm[pos] : (pos < n_out ? (int32_t)pos : -1);
+        const int chunks = stride / 4, cph = chunks >= 2 ? chunks / 2 : 1;
+        const int4 *src = reinterpret_cast<const int4 *>(nbr + (int64_t)(k >= 0 ? k : 0) * stride);
+        int4 v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ch = half * cph + i;
+            v[i] = make_int4(-1, -1, -1, -1);
+            if (k >= 0 && i < cph && ch < chunks) v[i] = src[ch];
+        }
+        uint32_t mm = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ch = half * cph + i;
+            if (i < cph && ch < chunks) {
+                const int32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = ch * 4 + q;
+                    if (idx < K3) lds_j[idx][col] = e[q];
+                    if (idx == K3 && k >= 0) mm = (uint32_t)e[q];
+                }
+            }
+        }
+        for (int d = 32; d >= 1; d >>= 1) mm |= (uint32_t)__shfl_xor((int)mm, d, 64);
+        if (lane == 0 && mm) atomicOr(&s_mask, mm);
+    }
+    __syncthreads();
+    const uint32_t mask = s_mask;
+    if (threadIdx.x < 32) {
+        // offsets present in the tile, ascending: s_nlist[r] = r-th set bit of the mask
+        const uint32_t below = mask & ((1u << threadIdx.x) - 1u);
+        if ((mask >> threadIdx.x) & 1u) s_nlist[__builtin_popcount(below)] = threadIdx.x;
+    }
+    __syncthreads();
+    const int nchunks = cin / KC;
+    const int nstage = __builtin_popcount(mask) * nchunks;
+    const int cblocks = cout / 16;
+
+    floatx4 acc[NCO][2];
+#pragma unroll
+    for (int cb = 0; cb < NCO; ++cb)
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2) acc[cb][c2] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 wreg[DEPTH][WV];
+    half8v xreg[DEPTH][2][KSTEPS];
+    bool xlive[DEPTH];
+    // Issue the loads of stage s into register set d (d is a compile-time constant at every call).
+    // Every call issues the same number of loads, unconditionally (past the last stage it repeats
+    // that stage; rows without the offset read the zero row): the compiler counts outstanding
+    // loads to place its waits, and a load it cannot count would make every wait a full drain.
+    auto issue = [&](int s, auto dc) __attribute__((always_inline)) {
+        constexpr int d = decltype(dc)::value;
+        const bool real = s < nstage;
+        s = real ? s : nstage - 1;
+        const int r = s / nchunks, ch = s - r * nchunks, n = s_nlist[r];
+        const u32x4 *wsrc = Wf + ((((int64_t)n * nchunks + ch) * cblocks + cb0) * KSTEPS) * 64;
+#pragma unroll
+        for (int v = 0; v < WV; ++v) {
+            int idx = threadIdx.x + v * kThreads;
+            if (SLAB % kThreads != 0) idx = idx < SLAB ? idx : SLAB - 1;
+            wreg[d][v] = wsrc[idx];
+        }
+        const int32_t j0 = lds_j[n][r0], j1 = lds_j[n][r1];
+        xlive[d] = real && __ballot(j0 >= 0 || j1 >= 0) != 0;   // false: none of the wave's rows has this offset
+        // rows without this offset contribute zeros and load nothing (the load path is what
+        // this kernel saturates, and most row slots of an unsorted tile are such rows)
+        const _Float16 *p0 = X + (int64_t)(j0 >= 0 ? j0 : 0) * cin + ch * KC + g * 8;
+        const _Float16 *p1 = X + (int64_t)(j1 >= 0 ? j1 : 0) * cin + ch * KC + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            half8v v0 = {0, 0, 0, 0, 0, 0, 0, 0}, v1 = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (j0 >= 0) v0 = *reinterpret_cast<const half8v *>(p0 + ks * 32);
+            if (j1 >= 0) v1 = *reinterpret_cast<const half8v *>(p1 + ks * 32);
+            xreg[d][0][ks] = v0;
+            xreg[d][1][ks] = v1;
+        }
+    };
+    auto run = [&](int s, auto dc) __attribute__((always_inline)) {
+        constexpr int d = decltype(dc)::value;
+        u32x4 *slab = lds_w[s & 1];
+#pragma unroll
+        for (int v = 0; v < WV; ++v) {
+            int idx = threadIdx.x + v * kThreads;
+            if (SLAB % kThreads != 0) idx = idx < SLAB ? idx : SLAB - 1;   // surplus threads repeat the last vector
+            slab[idx] = wreg[d][v];
+        }
+        __syncthreads();   // slab complete; everybody is done with the other slab
+        if (xlive[d]) {
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+                for (int cb = 0; cb < NCO; ++cb) {
+                    const u32x4 raw = slab[(cb * KSTEPS + ks) * 64 + lane];
+                    half8v a;
+                    __builtin_memcpy(&a, &raw, 16);
+                    acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xreg[d][0][ks], acc[cb][0], 0, 0, 0);
+                    acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xreg[d][1][ks], acc[cb][1], 0, 0, 0);
+                }
+        }
+        issue(s + DEPTH, dc);
+    };
+    if (nstage > 0) {
+        static_for<DEPTH>([&](auto dc) __attribute__((always_inline)) { issue(decltype(dc)::value, dc); });
+        // whole rounds of DEPTH stages; stages past the end only repeat loads and skip the MFMAs
+        for (int s0 = 0; s0 < nstage; s0 += DEPTH) static_for<DEPTH>([&](auto dc) __attribute__((always_inline)) { run(s0 + decltype(dc)::value, dc); });
+    }
+
+    // lane l holds, per block, output channels 4 * (l / 16) + 0..3 of rows r0 (c2 = 0) and r1 (c2 = 1)
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2) {
+        const int64_t pos = tile * kTileRows + (c2 ? r1 : r0);
+        const int64_t row = perm ? perm[pos] : (pos < n_out ? pos : -1);
+        if (row < 0) continue;
+        _Float16 *dst = out + row * cout + cb0 * 16 + g * 4;
+#pragma unroll
+        for (int cb = 0; cb < NCO; ++cb) {
+            half4 v = {(_Float16)acc[cb][c2][0], (_Float16)acc[cb][c2][1], (_Float16)acc[cb][c2][2], (_Float16)acc[cb][c2][3]};
+            *reinterpret_cast<half4 *>(dst + cb * 16) = v;
+        }
+    }
+    if (threadIdx.x == 0) s_tile = ticket;
+    __syncthreads();   // the tile's LDS is free; s_tile is set
+    turn = (int64_t)gridDim.x + xcd + 8 * (int64_t)s_tile;
+    }
+    // the last workgroup to leave rearms the counters for the next launch on this map
+    if (threadIdx.x == 0 && atomicAdd(&sched[8 * 32], 1) == (int)gridDim.x - 1) {
+        for (int i = 0; i <= 8; ++i) sched[i * 32] = 0;
+    }
+}
+
+// Weights in the operand order of k_conv_tile:
+// Wf[n][chunk][cb][ks][lane][e] = W[n][ci][co], co = cb*16 + lane%16, ci = chunk*KC + ks*32 + 8*(lane/16) + e
+// (0 for ci >= cin).  One (n, chunk, cb, ks) fragment is 64 lanes x 16 bytes, contiguous.
+__global__ void k_pack_weights_tile(const _Float16 *__restrict__ W, _Float16 *__restrict__ Wf, int K3, int cin,
+                                    int cin_pad, int cout, int ksteps) {
+    const int64_t gidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)K3 * cout * cin_pad;
+    if (gidx >= total) return;
+    const int kc = ksteps * 32, nchunks = cin_pad / kc, cblocks = cout / 16;
+    int64_t r = gidx;
+    const int e = (int)(r % 8); r /= 8;
+    const int lane = (int)(r % 64); r /= 64;
+    const int ks = (int)(r % ksteps); r /= ksteps;
+    const int cb = (int)(r % cblocks); r /= cblocks;
+    const int chunk = (int)(r % nchunks); r /= nchunks;
+    const int n = (int)r;
+    const int co = cb * 16 + (lane & 15);
+    const int ci = chunk * kc + ks * 32 + 8 * (lane >> 4) + e;
+    Wf[gidx] = ci < cin ? W[((int64_t)n * cin + ci) * cout + co] : (_Float16)0;
+}
+
 // ---- explicit dataflow ------------------------------------------------------------------------
 // Gather (Alg. 2, "F[m] <- X_in[j]") for all offsets: one thread per 16-byte vector of F.
 __global__ void k_gather(const uint4 *__restrict__ X, const int32_t *__restrict__ in_idx, uint4 *__restrict__ F,
@@ -520,7 +741,7 @@ struct FusedLaunch {
 };
 
 template <class T>
-int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
+int run_fused_staged(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
     Prepared pr;
     TS_TRY(prepare<T>(feats, weights, kmap, &pr));
     const T *zero = static_cast<const T *>(zero_row());
@@ -528,6 +749,73 @@ int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *k
     dispatch_shape(pick_ncb(out->cols), pick_ksteps(pr.cin_pad, Elem<T>::KSTEP), FusedLaunch<T>{pr, kmap, out, zero});
     TS_HIP(hipGetLastError());
     return TS_OK;
+}
+
+constexpr int kTileDepth = 3;
+
+inline int compute_units() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
+
+template <int NCO, int KSTEPS>
+void launch_conv_tile(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap, ts_tensor *out, int cin_pad) {
+    // as many workgroups as stay resident at once (register-limited), fewer for small maps
+    const int64_t resident = (int64_t)compute_units() * (NCO <= 4 ? 4 : 3);
+    dim3 grid((unsigned)(kmap->n_tiles < resident ? kmap->n_tiles : resident), out->cols / (NCO * 16));
+    TS_LAUNCH("k_conv_tile", (k_conv_tile<NCO, KSTEPS, kTileDepth>), grid, dim3(kThreads), x,
+              reinterpret_cast<const u32x4 *>(wf), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->n_out,
+              static_cast<_Float16 *>(out->data), kmap->d_sched, cin_pad, out->cols, kmap->K3);
+}
+
+// fp16: input channels padded to a multiple of 32 (one MFMA step), chunks of 64 where possible.
+int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
+    typedef _Float16 T;
+    const int cin = feats->cols, cout = out->cols;
+    const int cin_pad = (cin + 31) / 32 * 32;
+    const int ksteps = cin_pad % 64 == 0 ? 2 : 1;
+    const size_t wn = (size_t)kmap->K3 * cout * cin_pad;
+    T *wf = static_cast<T *>(scratch(2, wn * sizeof(T)));
+    if (!wf) return TS_ERR_OOM;
+    TS_LAUNCH("k_pack_weights", k_pack_weights_tile, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads),
+              static_cast<const T *>(weights->data), wf, kmap->K3, cin, cin_pad, cout, ksteps);
+    const T *x = static_cast<const T *>(feats->data);
+    if (cin_pad != cin) {
+        const size_t xn = (size_t)feats->rows * cin_pad;
+        T *xp = static_cast<T *>(scratch(3, xn * sizeof(T)));
+        if (!xp) return TS_ERR_OOM;
+        TS_LAUNCH("k_pad_rows", k_pad_rows<T>, dim3(blocks_for((int64_t)xn, kThreads)), dim3(kThreads), x, xp, feats->rows, cin, cin_pad);
+        x = xp;
+    }
+    const int cblocks = cout / 16;
+    int nco = 2;
+    for (int c : {8, 6, 4, 2})
+        if (cblocks % c == 0) {
+            nco = c;
+            break;
+        }
+#define TS_TILE_CASE(N)                                                                    \
+    if (nco == N) {                                                                        \
+        if (ksteps == 2) launch_conv_tile<N, 2>(x, wf, kmap, out, cin_pad);          \
+        else launch_conv_tile<N, 1>(x, wf, kmap, out, cin_pad);                      \
+    }
+    TS_TILE_CASE(8) TS_TILE_CASE(6) TS_TILE_CASE(4) TS_TILE_CASE(2)
+#undef TS_TILE_CASE
+    static_assert(1024 / 32 <= kMaxSchedSlices, "C_out <= 1024 in slices of at least 32 channels");
+    TS_HIP(hipGetLastError());
+    return TS_OK;
+}
+
+template <class T>
+int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
+    if constexpr (sizeof(T) == 2) return run_fused_f16(feats, weights, kmap, out);
+    return run_fused_staged<T>(feats, weights, kmap, out);
 }
 
 int64_t total_mm_tiles(const ts_kmap *kmap) {

@@ -89,6 +89,8 @@ __host__ __device__ inline int64_t key_delta(int dx, int dy, int dz) {
 
 constexpr int kMaxK3 = 27;      // kernel volumes up to 3^3 (one bit per offset in a 32-bit mask)
 constexpr int kTileRows = 128;  // output rows per workgroup tile of the fused kernel
+constexpr int kMaxSchedSlices = 32;   // output-channel slices of a layer that take tiles from counters of their own
+constexpr int kSchedWords = 9 * 32;   // per slice: 8 tile counters (one per XCD) and a done count, 128 bytes apart
 
 // Row stride (in int32) of the neighbour table for a kernel volume: K3 neighbour entries, then
 // the row's offset bitmask at index K3, padded to a power of two (16-byte multiples).
@@ -122,4 +124,7 @@ struct ts_kmap {
     // tile of the output-stationary kernel share their offsets.  NULL = natural row order.
     int64_t n_tiles = 0;                  // ceil(n_out / kTileRows)
     int32_t *d_perm = nullptr;            // [n_tiles*kTileRows] sorted position -> output row, -1 = padding
+    // Tile counters of the fused kernel, per output-channel slice; all zero between launches (the
+    // last workgroup of a launch rearms them).
+    int32_t *d_sched = nullptr;           // [kMaxSchedSlices][kSchedWords]
 };

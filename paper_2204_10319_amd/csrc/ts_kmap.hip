@@ -759,6 +759,7 @@ void destroy(ts_kmap *m) {
     dev_free(m->d_colbits);
     dev_free(m->d_colbase);
     dev_free(m->d_perm);
+    dev_free(m->d_sched);
     delete m;
 }
 
@@ -909,6 +910,8 @@ int alloc_outputs(ts_kmap *m, FillArgs *fill) {
     TS_TRY(alloc_n(&m->d_colbits, (size_t)K3 * m->n_blocks));
     TS_TRY(alloc_n(&m->d_colbase, (size_t)K3 * m->n_blocks));
     TS_TRY(alloc_n(&m->d_offs, (size_t)K3 + 1));
+    TS_TRY(alloc_n(&m->d_sched, (size_t)kMaxSchedSlices * kSchedWords));
+    fill->add(m->d_sched, (size_t)kMaxSchedSlices * kSchedWords * sizeof(int32_t), 0u);
     if (m->s == 1 && K3 == 27) fill->add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);   // the symmetric probe writes hits only
     return TS_OK;
 }
