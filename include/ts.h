@@ -147,7 +147,18 @@ int ts_kmap_pairs(const ts_kmap *kmap, int32_t *in_idx, int32_t *out_idx);
 int ts_sparse_conv(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
                    ts_tensor *out);
 
-/* Same, with the dataflow chosen by the caller (TS_DATAFLOW_*). */
+/*
+ * out = act(sparse convolution + bias + residual): ts_sparse_conv followed by ts_bias_act (below)
+ * in one call.  bias (device, [C_out], dtype of out) and residual ([num_out][C_out], dtype of out,
+ * must not alias out) may be NULL; relu != 0 clamps at zero.  The result equals, bit for bit, that
+ * of the two calls made one after the other (the layer's sum is rounded to the I/O dtype first);
+ * for TS_F16 it is computed in the layer kernel's epilogue, so the activation tensor is written
+ * once and not read back (the paper's Principle II: data movement is what to cut, Sec. 3).
+ */
+int ts_sparse_conv_act(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
+                       const void *bias, const ts_tensor *residual, int relu, ts_tensor *out);
+
+/* Same as ts_sparse_conv, with the dataflow chosen by the caller (TS_DATAFLOW_*). */
 int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
                       ts_tensor *out, int dataflow);
 

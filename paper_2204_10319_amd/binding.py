@@ -27,7 +27,7 @@ _lib = None
 EXPORTS = [
     "ts_build_kmap", "ts_free", "ts_kmap_sort_rows", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
-    "ts_sparse_conv", "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
+    "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
     "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_bias_act", "ts_concat_cols",
 ]
 
@@ -72,6 +72,8 @@ def load_library(path: str | None = None):
     lib.ts_kmap_pairs.argtypes = [vp, vp, vp]
     lib.ts_sparse_conv.argtypes = [tp, tp, vp, tp]
     lib.ts_sparse_conv_ex.argtypes = [tp, tp, vp, tp, ci]
+    lib.ts_sparse_conv_act.argtypes = [tp, tp, vp, vp, tp, ci, tp]
+    lib.ts_sparse_conv_act.restype = ci
     lib.ts_gather.argtypes = [tp, vp, tp]
     lib.ts_grouped_matmul.argtypes = [tp, tp, tp, vp, tp]
     lib.ts_scatter_reduce.argtypes = [tp, vp, tp]
@@ -304,6 +306,23 @@ def ts_sparse_conv(feats: torch.Tensor, weights: torch.Tensor, kmap: KMap, out: 
     else:
         rc = lib.ts_sparse_conv_ex(ctypes.byref(f), ctypes.byref(w), kmap.handle, ctypes.byref(o), int(dataflow))
     _check(rc)
+    return out
+
+
+def ts_sparse_conv_act(feats: torch.Tensor, weights: torch.Tensor, kmap: KMap, bias: torch.Tensor | None = None,
+                       residual: torch.Tensor | None = None, relu: bool = True,
+                       out: torch.Tensor | None = None) -> torch.Tensor:
+    """out = act(conv(feats) + bias + residual) in one call (fused epilogue for fp16)."""
+    _use_current_stream()
+    c_out = weights.shape[-1]
+    if out is None:
+        out = torch.empty((kmap.num_out, c_out), dtype=feats.dtype, device=feats.device)
+    f, w, o = _as_ts(feats), _weights_ts(weights), _as_ts(out)
+    r = _as_ts(residual) if residual is not None else None
+    _check(load_library().ts_sparse_conv_act(ctypes.byref(f), ctypes.byref(w), kmap.handle,
+                                             bias.data_ptr() if bias is not None else None,
+                                             ctypes.byref(r) if r is not None else None, int(bool(relu)),
+                                             ctypes.byref(o)))
     return out
 
 

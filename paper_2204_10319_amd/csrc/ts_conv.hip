@@ -308,7 +308,8 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
                                                         const int32_t *__restrict__ nbr, int stride,
                                                         const int32_t *__restrict__ perm, int64_t n_out,
                                                         _Float16 *__restrict__ out, int *__restrict__ sched,
-                                                        int cin, int cout, int K3) {
+                                                        int cin, int cout, int K3, const _Float16 *__restrict__ bias,
+                                                        const _Float16 *__restrict__ residual, int relu) {
     constexpr int KC = KSTEPS * 32, FRAGS = NCO * KSTEPS, SLAB = FRAGS * 64;   // slab in 16-byte vectors
     constexpr int WV = (SLAB + kThreads - 1) / kThreads;
     __shared__ u32x4 lds_w[2][SLAB];
@@ -457,11 +458,28 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
         const int64_t pos = tile * kTileRows + (c2 ? r1 : r0);
         const int64_t row = perm ? perm[pos] : (pos < n_out ? pos : -1);
         if (row < 0) continue;
-        _Float16 *dst = out + row * cout + cb0 * 16 + g * 4;
+        const int64_t at = row * cout + cb0 * 16 + g * 4;
 #pragma unroll
         for (int cb = 0; cb < NCO; ++cb) {
+            // the layer's own result, rounded once to fp16 ...
             half4 v = {(_Float16)acc[cb][c2][0], (_Float16)acc[cb][c2][1], (_Float16)acc[cb][c2][2], (_Float16)acc[cb][c2][3]};
-            *reinterpret_cast<half4 *>(dst + cb * 16) = v;
+            // ... then, if asked for, what ts_bias_act would do with it: fp32 sum, ReLU, one rounding
+            if (bias || residual || relu) {
+                float f[4] = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+                if (bias) {
+                    const half4 b = *reinterpret_cast<const half4 *>(bias + cb0 * 16 + cb * 16 + g * 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) f[e] += (float)b[e];
+                }
+                if (residual) {
+                    const half4 r = *reinterpret_cast<const half4 *>(residual + at + cb * 16);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) f[e] += (float)r[e];
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = (_Float16)(relu && f[e] < 0.f ? 0.f : f[e]);
+            }
+            *reinterpret_cast<half4 *>(out + at + cb * 16) = v;
         }
     }
     if (threadIdx.x == 0) s_tile = ticket;
@@ -753,6 +771,14 @@ int run_fused_staged(const ts_tensor *feats, const ts_tensor *weights, const ts_
 
 constexpr int kTileDepth = 3;
 
+// What follows the layer's sum, if anything: y = act(conv + bias + residual) (see ts_sparse_conv_act).
+struct Epilogue {
+    const void *bias = nullptr;
+    const void *residual = nullptr;
+    int relu = 0;
+    bool any() const { return bias || residual || relu; }
+};
+
 inline int compute_units() {
     static int n = 0;
     if (n == 0) {
@@ -765,17 +791,20 @@ inline int compute_units() {
 }
 
 template <int NCO, int KSTEPS>
-void launch_conv_tile(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap, ts_tensor *out, int cin_pad) {
+void launch_conv_tile(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap, ts_tensor *out, int cin_pad,
+                      const Epilogue &ep) {
     // as many workgroups as stay resident at once (register-limited), fewer for small maps
     const int64_t resident = (int64_t)compute_units() * (NCO <= 4 ? 4 : 3);
     dim3 grid((unsigned)(kmap->n_tiles < resident ? kmap->n_tiles : resident), out->cols / (NCO * 16));
     TS_LAUNCH("k_conv_tile", (k_conv_tile<NCO, KSTEPS, kTileDepth>), grid, dim3(kThreads), x,
               reinterpret_cast<const u32x4 *>(wf), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->n_out,
-              static_cast<_Float16 *>(out->data), kmap->d_sched, cin_pad, out->cols, kmap->K3);
+              static_cast<_Float16 *>(out->data), kmap->d_sched, cin_pad, out->cols, kmap->K3,
+              static_cast<const _Float16 *>(ep.bias), static_cast<const _Float16 *>(ep.residual), ep.relu);
 }
 
 // fp16: input channels padded to a multiple of 32 (one MFMA step), chunks of 64 where possible.
-int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
+int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
+                  const Epilogue &ep) {
     typedef _Float16 T;
     const int cin = feats->cols, cout = out->cols;
     const int cin_pad = (cin + 31) / 32 * 32;
@@ -802,8 +831,8 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
         }
 #define TS_TILE_CASE(N)                                                                    \
     if (nco == N) {                                                                        \
-        if (ksteps == 2) launch_conv_tile<N, 2>(x, wf, kmap, out, cin_pad);          \
-        else launch_conv_tile<N, 1>(x, wf, kmap, out, cin_pad);                      \
+        if (ksteps == 2) launch_conv_tile<N, 2>(x, wf, kmap, out, cin_pad, ep);          \
+        else launch_conv_tile<N, 1>(x, wf, kmap, out, cin_pad, ep);                      \
     }
     TS_TILE_CASE(8) TS_TILE_CASE(6) TS_TILE_CASE(4) TS_TILE_CASE(2)
 #undef TS_TILE_CASE
@@ -814,7 +843,7 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
 
 template <class T>
 int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
-    if constexpr (sizeof(T) == 2) return run_fused_f16(feats, weights, kmap, out);
+    if constexpr (sizeof(T) == 2) return run_fused_f16(feats, weights, kmap, out, Epilogue());
     return run_fused_staged<T>(feats, weights, kmap, out);
 }
 
@@ -906,6 +935,30 @@ int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts
 
 int ts_sparse_conv(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
     return ts_sparse_conv_ex(feats, weights, kmap, out, TS_DATAFLOW_AUTO);
+}
+
+int ts_sparse_conv_act(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, const void *bias,
+                       const ts_tensor *residual, int relu, ts_tensor *out) {
+    TS_TRY(check_layer(feats, weights, kmap, out));
+    if (residual) {
+        TS_TRY(check_tensor(residual, "residual"));
+        if (residual->rows != out->rows || residual->cols != out->cols || residual->dtype != out->dtype)
+            return fail(TS_ERR_SHAPE, "residual must have the shape and dtype of out");
+        if (residual->data == out->data) return fail(TS_ERR_INVALID_ARG, "residual must not alias out");
+    }
+    if (bias && (reinterpret_cast<uintptr_t>(bias) & 15)) return fail(TS_ERR_INVALID_ARG, "bias must be 16-byte aligned");
+    if (kmap->n_out == 0) return TS_OK;
+    if (feats->dtype == TS_F16) {
+        Epilogue ep;
+        ep.bias = bias;
+        ep.residual = residual ? residual->data : nullptr;
+        ep.relu = relu != 0;
+        return run_fused_f16(feats, weights, kmap, out, ep);
+    }
+    // fp32: the layer, then the elementwise step on its output
+    TS_TRY(run_fused<float>(feats, weights, kmap, out));
+    if (!bias && !residual && !relu) return TS_OK;
+    return ts_bias_act(out, bias, residual, relu, out);
 }
 
 int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F) {

@@ -1,7 +1,8 @@
 """Runs a layer plan (see ``workloads/minkunet.py``) on the GPU through the C-ABI binding.
 
-Only sequencing lives here: kernel maps per resolution level, one ``ts_sparse_conv`` per conv op,
-``ts_bias_act`` for bias / residual / ReLU, ``ts_concat_cols`` for skip connections.  Maps are
+Only sequencing lives here: kernel maps per resolution level, one ``ts_sparse_conv_act`` per conv op,
+bias / residual / ReLU in the layer kernel's epilogue (``ts_sparse_conv_act``), ``ts_concat_cols`` for
+skip connections.  Maps are
 built once per (kind, level) and reused by every layer that needs them (the paper builds maps
 per downsampling block, Sec. 2.3).
 """
@@ -48,9 +49,8 @@ class SparseNet:
                 t[op["dst"]] = ts.ts_concat_cols(t[op["a"]], t[op["b"]])
             else:
                 w, b = self.params[op["name"]]
-                y = ts.ts_sparse_conv(t[op["src"]], w, maps[op["map"]])
                 res = t[op["residual"]] if op["residual"] else None
-                t[op["dst"]] = ts.ts_bias_act(y, b, res, op["relu"], out=y)
+                t[op["dst"]] = ts.ts_sparse_conv_act(t[op["src"]], w, maps[op["map"]], b, res, op["relu"])
             if hook:
                 hook(op["dst"], t[op["dst"]])
         return t[self.output]

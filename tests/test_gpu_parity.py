@@ -288,3 +288,25 @@ def test_sorted_rows_many_distinct_masks():
     assert torch.equal(y1, y2)
     y3 = ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_EXPLICIT)
     assert oracle.rel_l2(y3.cpu().numpy(), y1.cpu().numpy()) < 1e-3
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("K,s,transposed,c_in,c_out", [(3, 1, False, 32, 64), (2, 2, False, 64, 96), (2, 2, True, 128, 32)])
+def test_fused_epilogue_equals_two_calls(dtype, K, s, transposed, c_in, c_out):
+    """ts_sparse_conv_act = ts_sparse_conv then ts_bias_act, bit for bit, with every subset of the extras."""
+    coords = _rand_coords(55 + K, 3000, -9, 9, batches=2)
+    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
+    nd = np_dtype(dtype)
+    x = to_dev(features(1000, kmap.num_in, c_in, nd))
+    w = to_dev(conv_weights(1001, K ** 3, c_in, c_out, nd))
+    bias = to_dev(features(1002, 1, c_out, nd).reshape(-1))
+    res = to_dev(features(1003, kmap.num_out, c_out, nd))
+    plain = ts.ts_sparse_conv(x, w, kmap)
+    for b, r, relu in [(None, None, False), (bias, None, True), (None, res, False), (bias, res, True), (None, None, True)]:
+        want = ts.ts_bias_act(plain.clone(), b, r, relu)
+        got = ts.ts_sparse_conv_act(x, w, kmap, b, r, relu)
+        assert torch.equal(got, want), (b is not None, r is not None, relu)
+    ref = oracle_conv(coords, x.cpu().numpy(), w.cpu().numpy(), K, s, transposed)
+    y = oracle.round_to(ref, nd).astype(np.float64) + bias.cpu().numpy().astype(np.float64)[None, :] + res.cpu().numpy().astype(np.float64)
+    y = np.maximum(y, 0.0)
+    check_features(ts.ts_sparse_conv_act(x, w, kmap, bias, res, True), y, dtype, "fused epilogue vs oracle")
