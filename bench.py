@@ -2,8 +2,8 @@
 """Benchmark of the sparse-convolution hot path on one MI355X.
 
 A "step" is one pass of the whole path over the ~150k-voxel LiDAR-like workload
-(config 3): ts_build_kmap (pack + hash build, probe, per-offset compaction, mask sort,
-tiles) followed by ts_sparse_conv (fused output-stationary kernel), C_in = C_out = 64,
+(config 3): ts_build_kmap (pack + hash build, map search, rank bitmaps, per-offset
+compaction) followed by ts_sparse_conv (fused output-stationary kernel), C_in = C_out = 64,
 fp16 in / fp32 accumulate, inputs resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--channels C] [--no-cpu-baseline]
@@ -199,11 +199,21 @@ def main():
 
     kmap_us = time_calls(lambda: ts.ts_build_kmap(coords, K, 1).free(), 30)
     layers = {f"C{c}": layer_report(kmap, N, M, c) for c in (32, 64, 128)}
+    # optional ordering of the output rows by offset bitmask (for maps that serve several layers)
+    sort_us = time_calls(lambda: ts.ts_build_kmap(coords, K, 1).sort_rows().free(), 20) - kmap_us
+    ksorted = ts.ts_build_kmap(coords, K, 1).sort_rows()
+    sorted_rows = {"sort_rows_us": round(sort_us, 1)}
+    for c in (32, 64, 128):
+        xc = torch.from_numpy(features(300 + c, N, c, np.float16)).cuda()
+        wc = torch.from_numpy(conv_weights(301 + c, K3, c, c, np.float16)).cuda()
+        oc = torch.empty((N, c), dtype=torch.float16, device="cuda")
+        sorted_rows[f"C{c}_fused_layer_us"] = round(time_calls(lambda: ts.ts_sparse_conv(xc, wc, ksorted, oc), 30), 2)
+    ksorted.free()
     table_slots = 1 << int(np.ceil(np.log2(2 * N)))
     kb = kmap_bytes(N, M, K3, table_slots)
     breakdown = {"kmap_build_us": round(kmap_us, 1), "kmap_algorithmic_bytes": int(kb),
                  "kmap_GBs": round(kb / kmap_us * 1e-3, 1), "copy_kernel_GBs": round(copy_gbs, 1),
-                 "per_kernel_us_per_step": per_kernel, "layers": layers}
+                 "per_kernel_us_per_step": per_kernel, "layers": layers, "sorted_rows": sorted_rows}
 
     # ---- config 5: MinkUNet-style forward pass on the same scene (maps built once, then the 45 convs)
     from paper_2204_10319_amd.network import SparseNet
@@ -212,12 +222,19 @@ def main():
     params = {k: (torch.from_numpy(wt).cuda(), torch.from_numpy(bs).cuda()) for k, (wt, bs) in make_params(50, ops).items()}
     net = SparseNet(ops, net_out, params)
     x4 = torch.from_numpy(features(51, N, 4, np.float16)).cuda()
-    maps_us = time_calls(lambda: SparseNet.free_maps(net.build_maps(coords)[0]), 5)
-    maps, _ = net.build_maps(coords)
-    fwd_us = time_calls(lambda: net.forward(maps, x4), 10)
-    SparseNet.free_maps(maps)
-    breakdown["config5_network"] = {"maps_build_ms": round(maps_us * 1e-3, 3), "forward_ms": round(fwd_us * 1e-3, 3),
-                                    "convs": sum(1 for k, _ in ops if k == "conv"), "maps": 17}
+    net_report = {"convs": sum(1 for k, _ in ops if k == "conv"), "maps": 17}
+    for tag, srt in (("", False), ("_sorted_rows", True)):
+        maps_us = time_calls(lambda: SparseNet.free_maps(net.build_maps(coords, srt)[0]), 5)
+        maps, _ = net.build_maps(coords, srt)
+        fwd_us = time_calls(lambda: net.forward(maps, x4), 10)
+        graph, _, _ = net.capture(maps, x4)
+        graph_us = time_calls(graph.replay, 20)
+        del graph
+        SparseNet.free_maps(maps)
+        net_report["maps_build_ms" + tag] = round(maps_us * 1e-3, 3)
+        net_report["forward_ms" + tag] = round(fwd_us * 1e-3, 3)
+        net_report["forward_graph_ms" + tag] = round(graph_us * 1e-3, 3)
+    breakdown["config5_network"] = net_report
 
     if args.sweep:
         big_h = tile_batches(coords_h, 10)

@@ -919,6 +919,20 @@ int run_explicit(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap
 
 }  // namespace
 
+// TS_DATAFLOW_AUTO.  The fused kernel re-reads a layer's weights for every tile of 128 outputs
+// (about 20 of the 27 offsets meet an input somewhere in a tile); the explicit dataflow reads
+// them once but moves every pair's rows through the buffers F and G.  Wide layers on point sets too
+// small to fill the machine with tiles (the coarse levels of a U-Net) are cheaper explicit,
+// everything else fused; the factor and the size limit come from timing both on the layers of
+// the MinkUNet-style benchmark network.
+bool prefer_explicit(const ts_kmap *kmap, int cin, int cout, size_t elem) {
+    if (kmap->n_tiles > compute_units()) return false;
+    const double tile_offsets = kmap->K3 < 20 ? kmap->K3 : 20;
+    const double fused_weight_bytes = (double)kmap->n_tiles * tile_offsets * cin * cout * elem;
+    const double explicit_bytes = (double)kmap->M * (2.0 * cin * elem + 2.0 * cout * sizeof(float));
+    return fused_weight_bytes > 0.45 * explicit_bytes;
+}
+
 extern "C" {
 
 int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
@@ -928,6 +942,7 @@ int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts
         return fail(TS_ERR_INVALID_ARG, "unknown dataflow %d", dataflow);
     if (kmap->n_out == 0) return TS_OK;
     const bool f16 = feats->dtype == TS_F16;
+    if (dataflow == TS_DATAFLOW_AUTO && prefer_explicit(kmap, feats->cols, out->cols, f16 ? 2 : 4)) dataflow = TS_DATAFLOW_EXPLICIT;
     if (dataflow == TS_DATAFLOW_EXPLICIT)
         return f16 ? run_explicit<_Float16>(feats, weights, kmap, out) : run_explicit<float>(feats, weights, kmap, out);
     return f16 ? run_fused<_Float16>(feats, weights, kmap, out) : run_fused<float>(feats, weights, kmap, out);
@@ -948,15 +963,15 @@ int ts_sparse_conv_act(const ts_tensor *feats, const ts_tensor *weights, const t
     }
     if (bias && (reinterpret_cast<uintptr_t>(bias) & 15)) return fail(TS_ERR_INVALID_ARG, "bias must be 16-byte aligned");
     if (kmap->n_out == 0) return TS_OK;
-    if (feats->dtype == TS_F16) {
+    if (feats->dtype == TS_F16 && !prefer_explicit(kmap, feats->cols, out->cols, 2)) {
         Epilogue ep;
         ep.bias = bias;
         ep.residual = residual ? residual->data : nullptr;
         ep.relu = relu != 0;
         return run_fused_f16(feats, weights, kmap, out, ep);
     }
-    // fp32: the layer, then the elementwise step on its output
-    TS_TRY(run_fused<float>(feats, weights, kmap, out));
+    // otherwise: the layer, then the elementwise step on its output
+    TS_TRY(ts_sparse_conv_ex(feats, weights, kmap, out, TS_DATAFLOW_AUTO));
     if (!bias && !residual && !relu) return TS_OK;
     return ts_bias_act(out, bias, residual, relu, out);
 }

@@ -18,8 +18,10 @@ class SparseNet:
         """ops/output from the plan; params: {name: (weights, bias)} as device tensors."""
         self.ops, self.output, self.params = ops, output, params
 
-    def build_maps(self, coords: torch.Tensor):
-        """Kernel maps for every (kind, level) of the plan, plus the coordinates of each level."""
+    def build_maps(self, coords: torch.Tensor, sort_rows: bool = False):
+        """Kernel maps for every (kind, level) of the plan, plus the coordinates of each level.
+        With ``sort_rows`` the 3x3x3 maps, which serve 4 to 9 layers each, get their output rows
+        ordered by offset bitmask (``ts_kmap_sort_rows``)."""
         kinds = []
         for k, op in self.ops:
             if k == "conv" and op["map"] not in kinds:
@@ -35,6 +37,8 @@ class SparseNet:
         for kind, level in kinds:
             if kind == "sub":
                 maps[(kind, level)] = ts.ts_build_kmap(levels[level], 3, 1, False)
+                if sort_rows:
+                    maps[(kind, level)].sort_rows()
             elif kind == "id":
                 maps[(kind, level)] = ts.ts_build_kmap(levels[level], 1, 1, False)
             elif kind == "up":
@@ -54,6 +58,27 @@ class SparseNet:
             if hook:
                 hook(op["dst"], t[op["dst"]])
         return t[self.output]
+
+    def capture(self, maps, feats: torch.Tensor):
+        """Records one forward pass into a HIP graph and returns (graph, input buffer, output).
+
+        The forward pass is a fixed sequence of launches with no host synchronisation, so the
+        host cost of ~50 library calls per pass (it exceeds the device time on the coarse
+        levels) is paid once.  One eager pass runs first so that every scratch area of the
+        library has its final size: nothing may allocate while the stream is being captured.
+        Replay with ``graph.replay()`` after copying new features into the input buffer.
+        """
+        static_in = feats.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.forward(maps, static_in)          # sizes the library's scratch areas
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            static_out = self.forward(maps, static_in)
+        return graph, static_in, static_out
 
     @staticmethod
     def free_maps(maps):

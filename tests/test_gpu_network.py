@@ -60,3 +60,29 @@ def test_config5_full_scene():
     coords = lidar_scan_coords(2, n_sweeps=5)
     worst, n = _run_both(coords, seed=50)
     print(f"config 5 (full): {n} tensors, worst rel L2 {worst:.2e}")
+
+
+def test_graph_replay_equals_eager():
+    """The forward pass captured in a HIP graph gives the eager result on every replay, with other
+    work of the library (a map build, a layer) and synchronisations between the replays."""
+    coords = lidar_scan_coords(4, n_sweeps=1)
+    ops, output = build_plan(4)
+    params = make_params(60, ops)
+    net = SparseNet(ops, output, {k: (to_dev(w), to_dev(b)) for k, (w, b) in params.items()})
+    maps, _ = net.build_maps(to_dev(coords))
+    xs = [to_dev(features(61 + i, coords.shape[0], 4, np.float16)) for i in range(3)]
+    eager = [net.forward(maps, x).clone() for x in xs]
+    torch.cuda.synchronize()
+    graph, static_in, static_out = net.capture(maps, xs[0])
+    for rep in range(2):
+        for x, want in zip(xs, eager):
+            static_in.copy_(x)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(static_out, want)
+            other = ts.ts_build_kmap(to_dev(coords[:5000]), 3, 1)      # eager library work in between
+            ts.ts_sparse_conv(to_dev(features(70, 5000, 32, np.float16)), to_dev(np.zeros((27, 32, 32), np.float16)), other)
+            torch.cuda.synchronize()
+            other.free()
+    del graph
+    SparseNet.free_maps(maps)
