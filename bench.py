@@ -10,6 +10,7 @@ fp16 in / fp32 accumulate, inputs resident in HBM.  Prints ONE JSON line.
     python bench.py --pmc-run      # short run for `rocprofv3 --pmc ...`: a few steps plus three
                                    # 256 MiB plain copies that calibrate the byte counters
     python bench.py --sweep        # adds the layer at 10x the voxels (batch-tiled scene)
+    python bench.py --step-only    # the timed steps and nothing else (what the kernel-trace profile runs)
 """
 import argparse
 import json
@@ -70,6 +71,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-run", action="store_true")
     ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--step-only", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -137,10 +139,16 @@ def main():
     launches, total_ms = prof[dom_name]
     dom_us = total_ms * 1e3 / launches
 
-    # ---- untimed extras: per-kernel breakdown of a step, copy reference, the layer at several widths
     kmap = ts.ts_build_kmap(coords, K, 1)
     M = kmap.num_pairs
     sizes = kmap.sizes()
+    if args.step_only:
+        fb = fused_conv_bytes(N, N, M, C, C, K3, 2)
+        print(json.dumps({"step_only": True, "ms_per_step": round(ms_per_step, 4), "kernel": dom_name,
+                          "avg_us": round(dom_us, 2), "GBs": round(fb / dom_us * 1e-3, 1), "N": int(N), "M": int(M)}))
+        return
+
+    # ---- untimed extras: per-kernel breakdown of a step, copy reference, the layer at several widths
     ts.ts_profile_enable(True)
     for _ in range(20):
         step().free()
