@@ -514,14 +514,28 @@ __global__ void k_pack_weights_tile(const _Float16 *__restrict__ W, _Float16 *__
 }
 
 // ---- explicit dataflow ------------------------------------------------------------------------
-// Gather (Alg. 2, "F[m] <- X_in[j]") for all offsets: one thread per 16-byte vector of F.
-__global__ void k_gather(const uint4 *__restrict__ X, const int32_t *__restrict__ in_idx, uint4 *__restrict__ F,
-                         int64_t M, int vec_per_row, int64_t skip_lo, int64_t skip_hi) {
-    int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t p = g / vec_per_row;
-    int v = (int)(g - p * vec_per_row);
-    if (p >= M || (p >= skip_lo && p < skip_hi)) return;
-    F[p * vec_per_row + v] = X[(int64_t)in_idx[p] * vec_per_row + v];
+// Gather (Alg. 2, "F[m] <- X_in[j]") for all offsets: a thread moves kGatherPer 16-byte vectors,
+// one each of rows a workgroup-stride apart, all loaded before the first store.  F is written
+// once and read once by the matmul, so its stores bypass the caches and leave them to X, every row
+// of which is gathered several times.
+constexpr int kGatherPer = 2;
+__global__ void __launch_bounds__(kThreads) k_gather(const u32x4 *__restrict__ X, const int32_t *__restrict__ in_idx,
+                                                     u32x4 *__restrict__ F, int64_t M, int vec_per_row, int64_t skip_lo,
+                                                     int64_t skip_hi) {
+    const int64_t base = (int64_t)blockIdx.x * (kThreads * kGatherPer) + threadIdx.x;
+    u32x4 v[kGatherPer];
+    int64_t at[kGatherPer];
+#pragma unroll
+    for (int u = 0; u < kGatherPer; ++u) {
+        const int64_t g = base + (int64_t)u * kThreads;
+        const int64_t p = g / vec_per_row;
+        const int c = (int)(g - p * vec_per_row);
+        at[u] = (p < M && !(p >= skip_lo && p < skip_hi)) ? g : -1;
+        if (at[u] >= 0) v[u] = X[(int64_t)in_idx[p] * vec_per_row + c];
+    }
+#pragma unroll
+    for (int u = 0; u < kGatherPer; ++u)
+        if (at[u] >= 0) __builtin_nontemporal_store(v[u], &F[at[u]]);
 }
 
 // Grouped matmul: block -> (offset n, 128-row block) by walking the per-offset tile counts.
@@ -571,10 +585,11 @@ __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F
 // the pair (k, n) follows from the offset's start, the base of k's 64-row block and the block's
 // presence bitmap.
 template <class T>
-__global__ void k_scatter_reduce(const float *__restrict__ G, const int32_t *__restrict__ nbr, int stride,
-                                 const uint64_t *__restrict__ colbits, const int32_t *__restrict__ colbase,
-                                 const int32_t *__restrict__ offs, int64_t n_blocks, T *__restrict__ out,
-                                 int64_t n_out, int cout, int K3) {
+__global__ void __launch_bounds__(kThreads) k_scatter_reduce(const float *__restrict__ G, const int32_t *__restrict__ nbr,
+                                                             int stride, const uint64_t *__restrict__ colbits,
+                                                             const int32_t *__restrict__ colbase,
+                                                             const int32_t *__restrict__ offs, int64_t n_blocks,
+                                                             T *__restrict__ out, int64_t n_out, int cout, int K3) {
     const int quads = cout / 4;
     int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t k = g / quads;
@@ -584,11 +599,26 @@ __global__ void k_scatter_reduce(const float *__restrict__ G, const int32_t *__r
     const int64_t b = k >> 6;
     const uint64_t before = (1ull << (k & 63)) - 1ull;
     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    // four offsets at a time: their positions first, then their rows of G (read once: streamed
+    // past the caches), then the adds in offset order
     while (mask) {
-        const int n = __builtin_ctz(mask);
-        mask &= mask - 1;
-        const int64_t p = offs[n] + colbase[n * n_blocks + b] + __popcll(colbits[n * n_blocks + b] & before);
-        acc += *reinterpret_cast<const floatx4 *>(G + p * cout + q * 4);
+        int64_t p[4];
+        floatx4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            p[u] = -1;
+            if (mask) {
+                const int n = __builtin_ctz(mask);
+                mask &= mask - 1;
+                p[u] = offs[n] + colbase[n * n_blocks + b] + __popcll(colbits[n * n_blocks + b] & before);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (p[u] >= 0) v[u] = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(G + p[u] * cout + q * 4));
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (p[u] >= 0) acc += v[u];
     }
     if constexpr (sizeof(T) == 2) {
         half4 v = {(_Float16)acc[0], (_Float16)acc[1], (_Float16)acc[2], (_Float16)acc[3]};
@@ -877,7 +907,7 @@ int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const t
         lo = kmap->offs[kmap->centre];
         hi = kmap->offs[kmap->centre + 1];
     }
-    TS_LAUNCH("k_gather", k_gather, dim3(blocks_for(kmap->M * vec_per_row, kThreads)), dim3(kThreads), static_cast<const uint4 *>(x), kmap->d_in_idx, static_cast<uint4 *>(F), kmap->M, vec_per_row, lo, hi);
+    TS_LAUNCH("k_gather", k_gather, dim3(blocks_for(kmap->M * vec_per_row, kThreads * kGatherPer)), dim3(kThreads), static_cast<const u32x4 *>(x), kmap->d_in_idx, static_cast<u32x4 *>(F), kmap->M, vec_per_row, lo, hi);
     TS_HIP(hipGetLastError());
     return TS_OK;
 }
