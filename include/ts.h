@@ -95,9 +95,10 @@ typedef struct ts_kmap ts_kmap;
  *   out_kmap     receives the new map; *out_kmap = NULL on error.
  * Internally: pack coordinates to 64-bit keys, (stride>1: candidate keys, sort, unique),
  * insert inputs into an open-addressing hash table, probe s*q_k + delta_n for every
- * output and offset, then compact into per-offset pair lists.  Synchronises the stream
- * (it must learn N_out and the map sizes to allocate).  The map may be reused by any
- * number of ts_sparse_conv calls.
+ * output and offset (one row of neighbour indices per output), count per offset.  The
+ * per-offset pair lists are derived from that when first asked for (ts_kmap_pairs, the
+ * explicit dataflow).  Synchronises the stream (it must learn N_out and the map sizes and
+ * report bad input).  The map may be reused by any number of ts_sparse_conv calls.
  */
 int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
                   ts_kmap **out_kmap);

@@ -901,6 +901,7 @@ struct GroupedLaunch {
 
 int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const ts_kmap *kmap, void *F) {
     if (kmap->M == 0) return TS_OK;
+    TS_TRY(ensure_pairs(kmap));
     const int vec_per_row = (int)(cin_pad * elem_size(dtype) / 16);
     int64_t lo = 0, hi = 0;
     if (kmap->centre >= 0) {

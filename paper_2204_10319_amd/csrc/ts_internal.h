@@ -63,6 +63,9 @@ inline int alloc_n(T **p, size_t n) {
     return *p ? TS_OK : TS_ERR_OOM;
 }
 
+// Makes sure the offset-major pair lists of a map exist (they are derived on first use).
+int ensure_pairs(const struct ::ts_kmap *kmap);
+
 // ---- 64-bit coordinate keys ----------------------------------------------------------------
 // key = batch<<51 | (x+B)<<34 | (y+B)<<17 | (z+B), B = 2^16: order-preserving in (b,x,y,z)
 // ("flattening the coordinate of each dimension into an integer", paper Sec. 2.1.2).
@@ -112,7 +115,8 @@ struct ts_kmap {
     // Out-major view (what Alg. 1 yields per output): row k holds, for every offset n, the input
     // row feeding output k through W_n (or -1), then the bitmask of the offsets present.
     int32_t *d_nbr = nullptr;             // [n_out][stride]
-    // Offset-major view M[W_n] (Sec. 2.1): pair lists ordered by output index inside an offset ...
+    // Offset-major view M[W_n] (Sec. 2.1): pair lists ordered by output index inside an offset,
+    // derived from the out-major table on first use (ts::ensure_pairs); NULL until then ...
     int32_t *d_in_idx = nullptr;          // [M]
     int32_t *d_out_idx = nullptr;         // [M]
     int32_t *d_offs = nullptr;            // [K3+1] device copy of offs

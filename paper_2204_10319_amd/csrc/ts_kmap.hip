@@ -12,8 +12,9 @@
 //            offset a presence bitmap with its count
 //   scan     per-offset exclusive scan of the block counts -> where each pair sits in the
 //            offset-major lists; the last block to finish turns the totals into offs[]
-//   compact  pair lists M[W_n] (in, out), ordered by output index inside an offset
 // The host waits once, after `scan`, for the map sizes and error flags.
+//   compact  pair lists M[W_n] (in, out), ordered by output index inside an offset: derived from
+//            the above when first asked for (ts_kmap_pairs, the explicit dataflow's gather)
 //
 // ts_kmap_sort_rows (optional, for maps that serve several layers) orders the output rows by
 // offset bitmask: distinct bitmasks are counted in a small hash table, ranked, and every row
@@ -820,12 +821,6 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status)
     for (int n = 0; n < K3; ++n) m->sizes[n] = m->offs[n + 1] - m->offs[n];
     m->M = m->offs[K3];
 
-    TS_TRY(alloc_n(&m->d_in_idx, (size_t)m->M));
-    TS_TRY(alloc_n(&m->d_out_idx, (size_t)m->M));
-    const dim3 grid(blocks_for(n_out, kThreads)), block(kThreads);
-    if (K3 == 27) TS_LAUNCH("k_compact", k_compact<27>, grid, block, m->d_nbr, n_out, m->d_colbase, m->n_blocks, m->d_offs, m->d_in_idx, m->d_out_idx);
-    else if (K3 == 8) TS_LAUNCH("k_compact", k_compact<8>, grid, block, m->d_nbr, n_out, m->d_colbase, m->n_blocks, m->d_offs, m->d_in_idx, m->d_out_idx);
-    else TS_LAUNCH("k_compact", k_compact<1>, grid, block, m->d_nbr, n_out, m->d_colbase, m->n_blocks, m->d_offs, m->d_in_idx, m->d_out_idx);
     TS_HIP(hipGetLastError());
     // temporaries go back to the pool when the caller's Temps dies; later work on the same
     // stream is ordered after the kernels above, so reuse is safe without another wait
@@ -1013,6 +1008,31 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
 
 }  // namespace
 
+namespace ts {
+
+// The offset-major pair lists are derived from the out-major table when something first asks for
+// them (ts_kmap_pairs, the gather of the explicit dataflow); the fused kernel never does.
+int ensure_pairs(const ts_kmap *kmap) {
+    ts_kmap *m = const_cast<ts_kmap *>(kmap);
+    if (m->d_in_idx || m->M == 0) return TS_OK;
+    int32_t *in_idx, *out_idx;
+    TS_TRY(alloc_n(&in_idx, (size_t)m->M));
+    if (alloc_n(&out_idx, (size_t)m->M) != TS_OK) {
+        dev_free(in_idx);
+        return TS_ERR_OOM;
+    }
+    const dim3 grid(blocks_for(m->n_out, kThreads)), block(kThreads);
+    if (m->K3 == 27) TS_LAUNCH("k_compact", k_compact<27>, grid, block, m->d_nbr, m->n_out, m->d_colbase, m->n_blocks, m->d_offs, in_idx, out_idx);
+    else if (m->K3 == 8) TS_LAUNCH("k_compact", k_compact<8>, grid, block, m->d_nbr, m->n_out, m->d_colbase, m->n_blocks, m->d_offs, in_idx, out_idx);
+    else TS_LAUNCH("k_compact", k_compact<1>, grid, block, m->d_nbr, m->n_out, m->d_colbase, m->n_blocks, m->d_offs, in_idx, out_idx);
+    m->d_in_idx = in_idx;
+    m->d_out_idx = out_idx;
+    TS_HIP(hipGetLastError());
+    return TS_OK;
+}
+
+}  // namespace ts
+
 extern "C" {
 
 int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
@@ -1080,6 +1100,7 @@ int ts_kmap_sizes(const ts_kmap *kmap, int64_t *dst) {
 int ts_kmap_pairs(const ts_kmap *kmap, int32_t *in_idx, int32_t *out_idx) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
     if (kmap->M == 0) return TS_OK;
+    TS_TRY(ts::ensure_pairs(kmap));
     size_t bytes = (size_t)kmap->M * sizeof(int32_t);
     if (in_idx) TS_HIP(hipMemcpyAsync(in_idx, kmap->d_in_idx, bytes, hipMemcpyDeviceToDevice, ts::stream()));
     if (out_idx) TS_HIP(hipMemcpyAsync(out_idx, kmap->d_out_idx, bytes, hipMemcpyDeviceToDevice, ts::stream()));
