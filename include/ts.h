@@ -104,6 +104,15 @@ int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride,
                   ts_kmap **out_kmap);
 
 /*
+ * The transposed map of `forward` (built with stride > 1, transposed = 0): the same map that
+ * ts_build_kmap(fine coords, kernel_size, stride, 1) yields for the coordinates `forward` was built
+ * from, derived from `forward` without another search.  A network's upsampling layer takes this
+ * instead of building its map from coordinates (maps are shared between layers, Sec. 2.3).
+ * `forward` is not modified and need not outlive the result.  Does not synchronise.
+ */
+int ts_kmap_transpose(const ts_kmap *forward, ts_kmap **out_kmap);
+
+/*
  * Optional.  Orders the output rows of a map by their offset bitmask (which offsets meet an input),
  * so that the 128 rows a workgroup of the output-stationary kernel handles share their offsets and
  * absent ones are skipped per tile (Sec. 4.2 argues the same way for grouping by map size).  It

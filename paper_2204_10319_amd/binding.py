@@ -25,7 +25,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libts.so")
 _lib = None
 
 EXPORTS = [
-    "ts_build_kmap", "ts_free", "ts_kmap_sort_rows", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
+    "ts_build_kmap", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
     "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_bias_act", "ts_concat_cols",
@@ -61,6 +61,8 @@ def load_library(path: str | None = None):
     lib.ts_free.restype = None
     lib.ts_kmap_sort_rows.argtypes = [vp]
     lib.ts_kmap_sort_rows.restype = ci
+    lib.ts_kmap_transpose.argtypes = [vp, ctypes.POINTER(vp)]
+    lib.ts_kmap_transpose.restype = ci
     for name in ("ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs"):
         getattr(lib, name).argtypes = [vp]
         getattr(lib, name).restype = i64
@@ -217,6 +219,9 @@ class KMap:
     def pairs(self):
         return ts_kmap_pairs(self)
 
+    def transpose(self) -> "KMap":
+        return ts_kmap_transpose(self)
+
     def sort_rows(self):
         ts_kmap_sort_rows(self)
         return self
@@ -245,6 +250,14 @@ def ts_build_kmap(coords: torch.Tensor, kernel_size: int, stride: int = 1, trans
                                       int(kernel_size), int(stride), int(bool(transposed)), ctypes.byref(h))
     _check(rc)
     return KMap(h.value)
+
+
+def ts_kmap_transpose(forward: KMap) -> KMap:
+    """The transposed map of a forward strided map, derived without another search."""
+    _use_current_stream()
+    handle = ctypes.c_void_p()
+    _check(load_library().ts_kmap_transpose(forward.handle, ctypes.byref(handle)))
+    return KMap(handle.value)
 
 
 def ts_kmap_sort_rows(kmap: KMap):

@@ -29,6 +29,8 @@
 
 using namespace ts;
 
+int rows_and_scan(ts_kmap *m, int32_t *colcnt, int *d_status);   // row pass + scan, defined below the build
+
 namespace {
 
 constexpr int kThreads = 256;
@@ -480,10 +482,11 @@ __global__ void k_probe_symmetric(const uint64_t *__restrict__ keys, int64_t n_p
     }
 }
 
-// Second half of the stride-1 search: a thread per output row reads the row the symmetric probe
-// left, sets the centre entry (output k is input k) and the row's offset bitmask, and does what
-// every probe kernel does once the bitmask is known.
-template <int K3>
+// Row pass over a neighbour table whose hits have been written into rows that started out as -1
+// (the symmetric probe; the transposition of a forward map): a thread per output row reads its
+// row, sets the centre entry where the map has one (stride 1: output k is input k) and the row's
+// offset bitmask, and does what every search kernel does once the bitmask is known.
+template <int K3, bool HAS_CENTRE>
 __global__ void __launch_bounds__(kThreads) k_rows(int32_t *__restrict__ nbr, const uint64_t *__restrict__ keys, int64_t n_out,
                                                    uint64_t *__restrict__ colbits, int32_t *__restrict__ colcnt,
                                                    int64_t n_blocks) {
@@ -503,11 +506,33 @@ __global__ void __launch_bounds__(kThreads) k_rows(int32_t *__restrict__ nbr, co
         }
 #pragma unroll
         for (int n = 0; n < K3; ++n)
-            if (n == CENTRE || j[n] >= 0) mask |= 1u << n;
-        nbr[k * STRIDE + CENTRE] = (int32_t)k;
+            if ((HAS_CENTRE && n == CENTRE) || j[n] >= 0) mask |= 1u << n;
+        if (HAS_CENTRE) nbr[k * STRIDE + CENTRE] = (int32_t)k;
         nbr[k * STRIDE + K3] = (int32_t)mask;
     }
     finish_rows<K3>(mask, colbits, colcnt, n_blocks);
+}
+
+// Transposition of a forward map: entry (input j, output k, offset n) of the forward table becomes
+// entry (input k, output j, offset n).  A thread per forward output row.
+template <int K3>
+__global__ void __launch_bounds__(kThreads) k_transpose(const int32_t *__restrict__ fwd, int64_t n_fwd_out,
+                                                        int32_t *__restrict__ tnbr) {
+    constexpr int STRIDE = nbr_stride(K3), CHUNKS = (K3 + 3) / 4;
+    const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (k >= n_fwd_out) return;
+    int32_t j[CHUNKS * 4];
+#pragma unroll
+    for (int ch = 0; ch < CHUNKS; ++ch) {
+        const int4 v = reinterpret_cast<const int4 *>(fwd + k * STRIDE)[ch];
+        j[ch * 4 + 0] = v.x;
+        j[ch * 4 + 1] = v.y;
+        j[ch * 4 + 2] = v.z;
+        j[ch * 4 + 3] = v.w;
+    }
+#pragma unroll
+    for (int n = 0; n < K3; ++n)
+        if (j[n] >= 0) tnbr[(int64_t)j[n] * STRIDE + n] = (int32_t)k;
 }
 
 template <int THREADS = kThreads>
@@ -646,7 +671,7 @@ __global__ void k_place(const int2 *__restrict__ slot_rank, int64_t n_out, MaskH
     const int2 sr = slot_rank[k];
     if (sr.x < 0) return;
     const int64_t pos = (int64_t)mh.start[sr.x] + sr.y;
-    if (pos < n_out) perm[pos] = (int32_t)k;
+    if (pos >= 0 && pos < n_out) perm[pos] = (int32_t)k;   // (out of range only when the table overflowed)
 }
 
 // Pair lists: thread per output row; the pair (k, n) goes to offs[n] + colbase[n][k/64] + (outputs of the
@@ -745,7 +770,9 @@ int make_mask_hash(Temps &tmp, MaskHash *mh, FillArgs *fill) {
     mh->shift = 32 - __builtin_ctz(kMaskHashCap);
     mh->dmax = kMaskHashMaxDistinct;
     fill->add(mh->key, (size_t)kMaskHashCap * sizeof(uint32_t), 0xFFFFFFFFu);
-    fill->add(mh->cnt, (size_t)kMaskHashCap * sizeof(int32_t), 0u);
+    // counts and first positions: a mask that entered the table after the list of distinct masks
+    // was full is never ranked, and its rows must not be placed through a stale position
+    fill->add(cnt_start, (size_t)2 * kMaskHashCap * sizeof(int32_t), 0u);
     return TS_OK;
 }
 
@@ -794,7 +821,7 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status)
     else if (mode == MODE_SUB && K == 3) {
         TS_LAUNCH("k_probe_symmetric", k_probe_symmetric, dim3(blocks_for(n_out, kThreads), K3 / 2), dim3(kThreads), m->d_out_keys,
                   n_out, table, K, m->d_nbr, m->stride);
-        TS_LAUNCH("k_rows", k_rows<27>, dim3(blocks_for(n_out, kThreads)), dim3(kThreads), m->d_nbr, m->d_out_keys, n_out,
+        TS_LAUNCH("k_rows", (k_rows<27, true>), dim3(blocks_for(n_out, kThreads)), dim3(kThreads), m->d_nbr, m->d_out_keys, n_out,
                   m->d_colbits, colcnt, m->n_blocks);
     }
     else if (mode == MODE_FWD && K == 1) launch_probe<MODE_FWD, 1>(m, table, colcnt);
@@ -973,8 +1000,36 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
         TS_HIP(hipMemcpyAsync(h, d_count, sizeof(int64_t), hipMemcpyDeviceToHost, st));
         TS_HIP(hipStreamSynchronize(st));
         const int64_t n_coarse = h[0];
-        if (n_coarse == 0) {   // only possible when every coordinate was rejected
-            return fail(TS_ERR_COORD_RANGE, "no valid input coordinate");
+        if (n_coarse == 0) {
+            // No candidate passed the modular check (or every coordinate was out of range): a map
+            // without pairs.  The inputs are still checked for duplicates and range.
+            Table t0;
+            int32_t *colcnt = nullptr;
+            TS_TRY(make_table(tmp, N, &t0, &fill));
+            if (!transposed) {
+                m->n_in = N;
+                m->n_out = 0;
+            } else {
+                m->n_in = 0;
+                m->n_out = N;
+                m->d_in_keys = nullptr;
+                m->d_out_keys = given;
+                TS_TRY(alloc_outputs(m, &fill));
+                fill.add(m->d_nbr, (size_t)N * m->stride * sizeof(int32_t), 0xFFFFFFFFu);
+                TS_TRY(tmp.get(&colcnt, (size_t)K3 * m->n_blocks));
+            }
+            TS_TRY(launch_fill(fill));
+            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, t0, d_status);
+            if (transposed) TS_TRY(rows_and_scan(m, colcnt, d_status));
+            int32_t *hs = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
+            if (!hs) return TS_ERR_OOM;
+            TS_HIP(hipMemcpyAsync(hs, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+            TS_HIP(hipStreamSynchronize(st));
+            if (hs[ST_RANGE])
+                return fail(TS_ERR_COORD_RANGE, "coordinate outside batch [0,%d] / xyz [%d,%d]", TS_BATCH_MAX, TS_COORD_MIN,
+                            TS_COORD_MAX);
+            if (hs[ST_DUP]) return fail(TS_ERR_DUPLICATE_COORD, "input coordinates are not distinct");
+            return TS_OK;
         }
         uint64_t *coarse;
         TS_TRY(alloc_n(&coarse, (size_t)n_coarse));
@@ -1007,6 +1062,56 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
 }
 
 }  // namespace
+
+// Row pass (bitmasks, presence bitmaps) and scan over a neighbour table that is already filled in.
+int rows_and_scan(ts_kmap *m, int32_t *colcnt, int *d_status) {
+    const dim3 grid(blocks_for(m->n_out, kThreads)), block(kThreads);
+    if (m->K3 == 27) TS_LAUNCH("k_rows", (k_rows<27, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, m->n_blocks);
+    else if (m->K3 == 8) TS_LAUNCH("k_rows", (k_rows<8, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, m->n_blocks);
+    else TS_LAUNCH("k_rows", (k_rows<1, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, m->n_blocks);
+    TS_LAUNCH("k_scan", k_scan, dim3(m->K3), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, m->K3, d_status, m->d_offs);
+    TS_HIP(hipGetLastError());
+    return TS_OK;
+}
+
+// The transposed map of a forward strided map, derived from its neighbour table: no search, and no
+// host round trip either, because the sizes are those of the forward map.
+int transpose(const ts_kmap *f, ts_kmap *m) {
+    hipStream_t st = stream();
+    Temps tmp;
+    const int K3 = f->K3;
+    m->K = f->K;
+    m->s = f->s;
+    m->transposed = 1;
+    m->K3 = K3;
+    m->centre = -1;
+    m->n_in = f->n_out;
+    m->n_out = f->n_in;
+    m->M = f->M;
+    for (int n = 0; n < K3; ++n) m->sizes[n] = f->sizes[n];
+    for (int n = 0; n <= K3; ++n) m->offs[n] = f->offs[n];
+    if (m->n_out == 0) return TS_OK;
+    TS_TRY(alloc_n(&m->d_in_keys, (size_t)m->n_in));
+    TS_TRY(alloc_n(&m->d_out_keys, (size_t)m->n_out));
+    if (m->n_in > 0) TS_HIP(hipMemcpyAsync(m->d_in_keys, f->d_out_keys, (size_t)m->n_in * sizeof(uint64_t), hipMemcpyDeviceToDevice, st));
+    TS_HIP(hipMemcpyAsync(m->d_out_keys, f->d_in_keys, (size_t)m->n_out * sizeof(uint64_t), hipMemcpyDeviceToDevice, st));
+    FillArgs fill;
+    int *d_status;
+    int32_t *colcnt;
+    TS_TRY(tmp.get(&d_status, ST_WORDS));
+    fill.add(d_status, ST_WORDS * sizeof(int), 0u);
+    TS_TRY(alloc_outputs(m, &fill));
+    fill.add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);
+    TS_TRY(tmp.get(&colcnt, (size_t)K3 * m->n_blocks));
+    TS_TRY(launch_fill(fill));
+    if (f->n_out > 0) {
+        const dim3 gf(blocks_for(f->n_out, kThreads)), block(kThreads);
+        if (K3 == 27) TS_LAUNCH("k_transpose", k_transpose<27>, gf, block, f->d_nbr, f->n_out, m->d_nbr);
+        else if (K3 == 8) TS_LAUNCH("k_transpose", k_transpose<8>, gf, block, f->d_nbr, f->n_out, m->d_nbr);
+        else TS_LAUNCH("k_transpose", k_transpose<1>, gf, block, f->d_nbr, f->n_out, m->d_nbr);
+    }
+    return rows_and_scan(m, colcnt, d_status);
+}
 
 namespace ts {
 
@@ -1061,6 +1166,23 @@ int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride,
 }
 
 void ts_free(ts_kmap *kmap) { destroy(kmap); }
+
+int ts_kmap_transpose(const ts_kmap *forward, ts_kmap **out_kmap) {
+    if (!out_kmap) return fail(TS_ERR_INVALID_ARG, "out_kmap is NULL");
+    *out_kmap = nullptr;
+    if (!forward) return fail(TS_ERR_INVALID_ARG, "forward is NULL");
+    if (forward->s == 1 || forward->transposed) return fail(TS_ERR_INVALID_ARG, "a forward map with stride > 1 is needed");
+    ts_kmap *m = new (std::nothrow) ts_kmap();
+    if (!m) return fail(TS_ERR_OOM, "host allocation failed");
+    int rc = transpose(forward, m);
+    if (rc != TS_OK) {
+        (void)hipStreamSynchronize(ts::stream());
+        destroy(m);
+        return rc;
+    }
+    *out_kmap = m;
+    return TS_OK;
+}
 
 int ts_kmap_sort_rows(ts_kmap *kmap) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");

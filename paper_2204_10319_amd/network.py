@@ -42,7 +42,7 @@ class SparseNet:
             elif kind == "id":
                 maps[(kind, level)] = ts.ts_build_kmap(levels[level], 1, 1, False)
             elif kind == "up":
-                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 2, 2, True)
+                maps[(kind, level)] = maps[("down", level)].transpose()
         return maps, levels
 
     def forward(self, maps, feats: torch.Tensor, hook=None):

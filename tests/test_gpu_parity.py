@@ -310,3 +310,49 @@ def test_fused_epilogue_equals_two_calls(dtype, K, s, transposed, c_in, c_out):
     y = oracle.round_to(ref, nd).astype(np.float64) + bias.cpu().numpy().astype(np.float64)[None, :] + res.cpu().numpy().astype(np.float64)
     y = np.maximum(y, 0.0)
     check_features(ts.ts_sparse_conv_act(x, w, kmap, bias, res, True), y, dtype, "fused epilogue vs oracle")
+
+
+@pytest.mark.parametrize("K", [1, 2, 3])
+@pytest.mark.parametrize("n", [1, 700, 20000])
+def test_transposed_map_derived_from_forward_map(K, n):
+    """ts_kmap_transpose(forward map) is the map ts_build_kmap(..., transposed=1) searches for."""
+    coords = _rand_coords(300 + n + K, n, -20, 20, batches=2)
+    fwd = ts.ts_build_kmap(to_dev(coords), K, 2, False)
+    built = ts.ts_build_kmap(to_dev(coords), K, 2, True)
+    derived = fwd.transpose()
+    _, _, tri = oracle_map(coords, K, 2, True)
+    assert derived.num_in == built.num_in and derived.num_out == built.num_out and derived.num_pairs == built.num_pairs
+    assert torch.equal(derived.in_coords(), built.in_coords()) and torch.equal(derived.out_coords(), built.out_coords())
+    assert np.array_equal(derived.sizes(), built.sizes())
+    assert np.array_equal(gpu_triples(derived), tri)
+    pa, pb = derived.pairs(), built.pairs()
+    assert torch.equal(pa[0], pb[0]) and torch.equal(pa[1], pb[1])
+    x = to_dev(features(310, built.num_in, 64, np.float16))
+    w = to_dev(conv_weights(311, K ** 3, 64, 32, np.float16))
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+        assert torch.equal(ts.ts_sparse_conv(x, w, derived, dataflow=df), ts.ts_sparse_conv(x, w, built, dataflow=df))
+    fwd.free()   # the derived map does not depend on the forward map's memory
+    assert torch.equal(ts.ts_sparse_conv(x, w, derived), ts.ts_sparse_conv(x, w, built))
+
+
+def test_transpose_rejects_other_maps():
+    ok = to_dev(_rand_coords(5, 100, 0, 6))
+    for K, s, tr in [(3, 1, False), (2, 2, True)]:
+        with pytest.raises(ts.TsError) as e:
+            ts.ts_build_kmap(ok, K, s, tr).transpose()
+        assert e.value.code == ts.TS_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("transposed", [False, True])
+def test_strided_map_without_outputs(transposed):
+    """K = 1, s = 2 on odd coordinates: no candidate passes the modular check of Alg. 3, the map has no pairs."""
+    coords = np.array([[0, 1, 3, 5], [0, 7, 1, 1], [1, 3, 3, 3]], dtype=np.int32)
+    kmap = _check_map(coords, 1, 2, transposed)
+    assert kmap.num_pairs == 0
+    x = to_dev(features(5, kmap.num_in, 32, np.float16))
+    y = ts.ts_sparse_conv(x, to_dev(conv_weights(6, 1, 32, 32, np.float16)), kmap)
+    assert y.shape == (kmap.num_out, 32) and not y.any()
+    dup = np.array([[0, 1, 3, 5], [0, 1, 3, 5]], dtype=np.int32)
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(dup), 1, 2, transposed)
+    assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
