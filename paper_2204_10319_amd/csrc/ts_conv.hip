@@ -309,7 +309,8 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
                                                         const int32_t *__restrict__ perm, int64_t n_out,
                                                         _Float16 *__restrict__ out, int *__restrict__ sched,
                                                         int cin, int cout, int K3, const _Float16 *__restrict__ bias,
-                                                        const _Float16 *__restrict__ residual, int relu) {
+                                                        const _Float16 *__restrict__ residual, int relu, int x_bytes,
+                                                        int w_bytes) {
     constexpr int KC = KSTEPS * 32, FRAGS = NCO * KSTEPS, SLAB = FRAGS * 64;   // slab in 16-byte vectors
     constexpr int WV = (SLAB + kThreads - 1) / kThreads;
     __shared__ u32x4 lds_w[2][SLAB];
@@ -395,54 +396,75 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
     // Every call issues the same number of loads, unconditionally (past the last stage it repeats
     // that stage; rows without the offset read the zero row): the compiler counts outstanding
     // loads to place its waits, and a load it cannot count would make every wait a full drain.
+    // Loads go through buffer descriptors: a 32-bit byte offset per lane plus a wave-uniform one, no
+    // 64-bit address arithmetic in the loop, and an offset beyond the buffer reads as zero without
+    // touching memory, which is what a row without the offset must contribute.  The loop body is
+    // short on purpose: with ~200 vector instructions per stage around 16 MFMAs this kernel was
+    // bound by instruction issue.
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16 *>(X), 0, x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4 *>(Wf), 0, w_bytes, 0x00020000);
+    constexpr int kNoRow = (int)0x80000000u;   // beyond any buffer this kernel is launched with
+    const int row_bytes = cin * 2, xlane = g * 16;
+    int wlane[WV];
+#pragma unroll
+    for (int v = 0; v < WV; ++v) {
+        int idx = threadIdx.x + v * kThreads;
+        if (SLAB % kThreads != 0) idx = idx < SLAB ? idx : SLAB - 1;   // surplus threads repeat the last vector
+        wlane[v] = idx * 16;
+    }
+    int it_r = 0, it_ch = 0;   // (offset rank, chunk) of the next stage to issue
+    // Issue the loads of stage s into register set d (a compile-time constant at every call).
+    // Every call issues the same loads, unconditionally (past the last stage it repeats that
+    // stage): the compiler counts outstanding loads to place its waits, and a load it cannot count
+    // makes every wait a full drain.
     auto issue = [&](int s, auto dc) __attribute__((always_inline)) {
         constexpr int d = decltype(dc)::value;
         const bool real = s < nstage;
-        s = real ? s : nstage - 1;
-        const int r = s / nchunks, ch = s - r * nchunks, n = s_nlist[r];
-        const u32x4 *wsrc = Wf + ((((int64_t)n * nchunks + ch) * cblocks + cb0) * KSTEPS) * 64;
-#pragma unroll
-        for (int v = 0; v < WV; ++v) {
-            int idx = threadIdx.x + v * kThreads;
-            if (SLAB % kThreads != 0) idx = idx < SLAB ? idx : SLAB - 1;
-            wreg[d][v] = wsrc[idx];
+        const int r = it_r, ch = it_ch, n = s_nlist[r];
+        if (s + 1 < nstage) {   // stages are issued in order: step the pair, stay on the last one past the end
+            if (++it_ch == nchunks) {
+                it_ch = 0;
+                ++it_r;
+            }
         }
+        const int wsoff = (((n * nchunks + ch) * cblocks + cb0) * KSTEPS) * 1024;
+#pragma unroll
+        for (int v = 0; v < WV; ++v) wreg[d][v] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane[v], wsoff, 0);
         const int32_t j0 = lds_j[n][r0], j1 = lds_j[n][r1];
         xlive[d] = real && __ballot(j0 >= 0 || j1 >= 0) != 0;   // false: none of the wave's rows has this offset
-        // rows without this offset contribute zeros and load nothing (the load path is what
-        // this kernel saturates, and most row slots of an unsorted tile are such rows)
-        const _Float16 *p0 = X + (int64_t)(j0 >= 0 ? j0 : 0) * cin + ch * KC + g * 8;
-        const _Float16 *p1 = X + (int64_t)(j1 >= 0 ? j1 : 0) * cin + ch * KC + g * 8;
+        const int off0 = j0 >= 0 ? j0 * row_bytes + xlane : kNoRow;
+        const int off1 = j1 >= 0 ? j1 * row_bytes + xlane : kNoRow;
+        const int xsoff = ch * (KC * 2);
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
-            half8v v0 = {0, 0, 0, 0, 0, 0, 0, 0}, v1 = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (j0 >= 0) v0 = *reinterpret_cast<const half8v *>(p0 + ks * 32);
-            if (j1 >= 0) v1 = *reinterpret_cast<const half8v *>(p1 + ks * 32);
-            xreg[d][0][ks] = v0;
-            xreg[d][1][ks] = v1;
+            const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off0, xsoff + ks * 64, 0);
+            const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off1, xsoff + ks * 64, 0);
+            __builtin_memcpy(&xreg[d][0][ks], &v0, 16);
+            __builtin_memcpy(&xreg[d][1][ks], &v1, 16);
         }
     };
     auto run = [&](int s, auto dc) __attribute__((always_inline)) {
         constexpr int d = decltype(dc)::value;
         u32x4 *slab = lds_w[s & 1];
 #pragma unroll
-        for (int v = 0; v < WV; ++v) {
-            int idx = threadIdx.x + v * kThreads;
-            if (SLAB % kThreads != 0) idx = idx < SLAB ? idx : SLAB - 1;   // surplus threads repeat the last vector
-            slab[idx] = wreg[d][v];
-        }
+        for (int v = 0; v < WV; ++v) slab[wlane[v] >> 4] = wreg[d][v];
         __syncthreads();   // slab complete; everybody is done with the other slab
         if (xlive[d]) {
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks)
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                // all weight fragments of the step out of LDS first, then the MFMAs: a read placed
+                // right before its MFMA costs one LDS latency per fragment
+                u32x4 raw[NCO];
+#pragma unroll
+                for (int cb = 0; cb < NCO; ++cb) raw[cb] = slab[(cb * KSTEPS + ks) * 64 + lane];
 #pragma unroll
                 for (int cb = 0; cb < NCO; ++cb) {
-                    const u32x4 raw = slab[(cb * KSTEPS + ks) * 64 + lane];
                     half8v a;
-                    __builtin_memcpy(&a, &raw, 16);
+                    __builtin_memcpy(&a, &raw[cb], 16);
                     acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xreg[d][0][ks], acc[cb][0], 0, 0, 0);
                     acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xreg[d][1][ks], acc[cb][1], 0, 0, 0);
                 }
+            }
         }
         issue(s + DEPTH, dc);
     };
@@ -823,13 +845,23 @@ inline int compute_units() {
 template <int NCO, int KSTEPS>
 void launch_conv_tile(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap, ts_tensor *out, int cin_pad,
                       const Epilogue &ep) {
-    // as many workgroups as stay resident at once (register-limited), fewer for small maps
-    const int64_t resident = (int64_t)compute_units() * (NCO <= 4 ? 4 : 3);
+    // as many workgroups as stay resident at once, fewer for small maps
+    static int per_cu = 0;   // per instantiation
+    if (per_cu == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_conv_tile<NCO, KSTEPS, kTileDepth>, kThreads, 0) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            n = 2;
+        }
+        per_cu = n;
+    }
+    const int64_t resident = (int64_t)compute_units() * per_cu;
     dim3 grid((unsigned)(kmap->n_tiles < resident ? kmap->n_tiles : resident), out->cols / (NCO * 16));
     TS_LAUNCH("k_conv_tile", (k_conv_tile<NCO, KSTEPS, kTileDepth>), grid, dim3(kThreads), x,
               reinterpret_cast<const u32x4 *>(wf), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->n_out,
               static_cast<_Float16 *>(out->data), kmap->d_sched, cin_pad, out->cols, kmap->K3,
-              static_cast<const _Float16 *>(ep.bias), static_cast<const _Float16 *>(ep.residual), ep.relu);
+              static_cast<const _Float16 *>(ep.bias), static_cast<const _Float16 *>(ep.residual), ep.relu,
+              (int)((size_t)kmap->n_in * cin_pad * 2), (int)((size_t)kmap->K3 * cin_pad * out->cols * 2));
 }
 
 // fp16: input channels padded to a multiple of 32 (one MFMA step), chunks of 64 where possible.
@@ -839,6 +871,11 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
     const int cin = feats->cols, cout = out->cols;
     const int cin_pad = (cin + 31) / 32 * 32;
     const int ksteps = cin_pad % 64 == 0 ? 2 : 1;
+    // the kernel addresses features and weights with 31-bit byte offsets
+    if ((size_t)kmap->n_in * cin_pad * 2 >= (1ull << 31) || (size_t)kmap->K3 * cin_pad * cout * 2 >= (1ull << 31)) {
+        if (ep.any()) return fail(TS_ERR_UNSUPPORTED, "feature matrix of 2 GiB or more: call ts_sparse_conv and ts_bias_act");
+        return run_fused_staged<_Float16>(feats, weights, kmap, out);
+    }
     const size_t wn = (size_t)kmap->K3 * cout * cin_pad;
     T *wf = static_cast<T *>(scratch(2, wn * sizeof(T)));
     if (!wf) return TS_ERR_OOM;
