@@ -168,6 +168,21 @@ int ts_sparse_conv(const ts_tensor *feats, const ts_tensor *weights, const ts_km
 int ts_sparse_conv_act(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
                        const void *bias, const ts_tensor *residual, int relu, ts_tensor *out);
 
+/*
+ * Weights of a layer, repacked once into the layouts the kernels read (the layer calls above do this
+ * on every call; a network whose weights do not change between calls prepares them once).
+ *   weights        [K^3 * C_in][C_out] as for ts_sparse_conv; not needed after the call returns
+ *                  (the copy is made on the stream).
+ *   kernel_volume  K^3 of the maps the weights will be used with: 1, 8 or 27.
+ * ts_sparse_conv_prepared is ts_sparse_conv_act with such weights; results are bit-identical.
+ * ts_weights_free releases them (NULL allowed; not before the stream has passed their last use).
+ */
+typedef struct ts_weights ts_weights;
+int  ts_weights_prepare(const ts_tensor *weights, int kernel_volume, ts_weights **out_weights);
+void ts_weights_free(ts_weights *weights);
+int  ts_sparse_conv_prepared(const ts_tensor *feats, const ts_weights *weights, const ts_kmap *kmap,
+                             const void *bias, const ts_tensor *residual, int relu, ts_tensor *out);
+
 /* Same as ts_sparse_conv, with the dataflow chosen by the caller (TS_DATAFLOW_*). */
 int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
                       ts_tensor *out, int dataflow);

@@ -27,7 +27,8 @@ _lib = None
 EXPORTS = [
     "ts_build_kmap", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
-    "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
+    "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
+    "ts_sparse_conv_prepared", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
     "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_bias_act", "ts_concat_cols",
 ]
 
@@ -76,6 +77,12 @@ def load_library(path: str | None = None):
     lib.ts_sparse_conv_ex.argtypes = [tp, tp, vp, tp, ci]
     lib.ts_sparse_conv_act.argtypes = [tp, tp, vp, vp, tp, ci, tp]
     lib.ts_sparse_conv_act.restype = ci
+    lib.ts_weights_prepare.argtypes = [tp, ci, ctypes.POINTER(vp)]
+    lib.ts_weights_prepare.restype = ci
+    lib.ts_weights_free.argtypes = [vp]
+    lib.ts_weights_free.restype = None
+    lib.ts_sparse_conv_prepared.argtypes = [tp, vp, vp, vp, tp, ci, tp]
+    lib.ts_sparse_conv_prepared.restype = ci
     lib.ts_gather.argtypes = [tp, vp, tp]
     lib.ts_grouped_matmul.argtypes = [tp, tp, tp, vp, tp]
     lib.ts_scatter_reduce.argtypes = [tp, vp, tp]
@@ -336,6 +343,55 @@ def ts_sparse_conv_act(feats: torch.Tensor, weights: torch.Tensor, kmap: KMap, b
                                              bias.data_ptr() if bias is not None else None,
                                              ctypes.byref(r) if r is not None else None, int(bool(relu)),
                                              ctypes.byref(o)))
+    return out
+
+
+class Weights:
+    """Prepared weights of one layer (owned by the library until ``free`` / garbage collection)."""
+
+    def __init__(self, handle: int, c_in: int, c_out: int, dtype: torch.dtype, device):
+        self._h, self.c_in, self.c_out, self.dtype, self.device = handle, c_in, c_out, dtype, device
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("weights already freed")
+        return self._h
+
+    def free(self):
+        if self._h is not None:
+            load_library().ts_weights_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def ts_weights_prepare(weights: torch.Tensor) -> Weights:
+    """weights [K^3, C_in, C_out] -> the same, repacked once for the layer kernels."""
+    _use_current_stream()
+    w = _weights_ts(weights)
+    handle = ctypes.c_void_p()
+    _check(load_library().ts_weights_prepare(ctypes.byref(w), int(weights.shape[0]), ctypes.byref(handle)))
+    return Weights(handle.value, weights.shape[1], weights.shape[2], weights.dtype, weights.device)
+
+
+def ts_sparse_conv_prepared(feats: torch.Tensor, weights: Weights, kmap: KMap, bias: torch.Tensor | None = None,
+                            residual: torch.Tensor | None = None, relu: bool = False,
+                            out: torch.Tensor | None = None) -> torch.Tensor:
+    """ts_sparse_conv_act with weights from ts_weights_prepare."""
+    _use_current_stream()
+    if out is None:
+        out = torch.empty((kmap.num_out, weights.c_out), dtype=feats.dtype, device=feats.device)
+    f, o = _as_ts(feats), _as_ts(out)
+    r = _as_ts(residual) if residual is not None else None
+    _check(load_library().ts_sparse_conv_prepared(ctypes.byref(f), weights.handle, kmap.handle,
+                                                  bias.data_ptr() if bias is not None else None,
+                                                  ctypes.byref(r) if r is not None else None, int(bool(relu)),
+                                                  ctypes.byref(o)))
     return out
 
 

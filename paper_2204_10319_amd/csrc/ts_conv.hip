@@ -18,6 +18,7 @@
 // one row per accumulator quad, which makes the stores 8-16 bytes wide.
 #include "ts_internal.h"
 
+#include <new>
 #include <type_traits>
 #include <utility>
 
@@ -663,27 +664,6 @@ __global__ void k_pack_weights(const T *__restrict__ W, T *__restrict__ Wt, int 
     Wt[g] = ci < cin ? W[((int64_t)n * cin + ci) * cout + co] : (T)0;
 }
 
-// Weights in MFMA fragment order for the split-offset kernel:
-// Wf[n][cb][kb][lane][e] = W[n][ci][co] with co = cb*32 + lane%32, ci = kb*KSTEP + (lane/32)*VEC + e
-// (0 for ci >= cin).  One (n, cb, kb) fragment is 64 lanes x 16 bytes, contiguous.
-template <class T>
-__global__ void k_pack_weights_frag(const T *__restrict__ W, T *__restrict__ Wf, int K3, int cin, int cin_pad,
-                                    int cout) {
-    constexpr int VEC = Elem<T>::VEC, KSTEP = Elem<T>::KSTEP;
-    int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t total = (int64_t)K3 * cout * cin_pad;
-    if (g >= total) return;
-    const int nkb = cin_pad / KSTEP;
-    int e = (int)(g % VEC);
-    int lane = (int)((g / VEC) % 64);
-    int kb = (int)((g / (VEC * 64)) % nkb);
-    int cb = (int)((g / ((int64_t)VEC * 64 * nkb)) % (cout / 32));
-    int n = (int)(g / ((int64_t)VEC * 64 * nkb * (cout / 32)));
-    int co = cb * 32 + (lane & 31);
-    int ci = kb * KSTEP + (lane >> 5) * VEC + e;
-    Wf[g] = ci < cin ? W[((int64_t)n * cin + ci) * cout + co] : (T)0;
-}
-
 // Xp[row][c] = X[row][c] for c < cin, 0 up to cin_pad.
 template <class T>
 __global__ void k_pad_rows(const T *__restrict__ X, T *__restrict__ Xp, int64_t rows, int cin, int cin_pad) {
@@ -705,6 +685,18 @@ inline int pick_ncb(int cout) {
         if (blocks % ncb == 0) return ncb;
     return 1;
 }
+
+}  // namespace
+
+// Weights of one layer in the layouts the kernels read (ts_weights_prepare); device memory owned
+// by the object.
+struct ts_weights {
+    int K3 = 0, cin = 0, cout = 0, dtype = 0;
+    void *wt = nullptr;     // [K3][cout][cin rounded up to the operand step], for k_fused / k_grouped_mm
+    void *tile = nullptr;   // fp16: operand order of k_conv_tile (see k_pack_weights_tile)
+};
+
+namespace {
 
 struct Prepared {
     const void *x;    // features, rows padded to cin_pad channels
@@ -742,19 +734,19 @@ int check_layer(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap 
 // the operand step.
 template <class T>
 int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, Prepared *pr,
-            bool fragment_order = false) {
+            const ts_weights *pw = nullptr) {
     const int cin = feats->cols, cout = weights->cols, ks = Elem<T>::KSTEP;
     const int cin_pad = (cin + ks - 1) / ks * ks;
     pr->cin_pad = cin_pad;
-    size_t wn = (size_t)kmap->K3 * cout * cin_pad;
-    T *wt = static_cast<T *>(scratch(2, wn * sizeof(T)));
-    if (!wt) return TS_ERR_OOM;
-    if (fragment_order)
-        TS_LAUNCH("k_pack_weights", k_pack_weights_frag<T>, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads),
-                  static_cast<const T *>(weights->data), wt, kmap->K3, cin, cin_pad, cout);
-    else
-    TS_LAUNCH("k_pack_weights", k_pack_weights<T>, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads), static_cast<const T *>(weights->data), wt, kmap->K3, cin, cin_pad, cout);
-    pr->wt = wt;
+    if (pw) {
+        pr->wt = pw->wt;
+    } else {
+        size_t wn = (size_t)kmap->K3 * cout * cin_pad;
+        T *wt = static_cast<T *>(scratch(2, wn * sizeof(T)));
+        if (!wt) return TS_ERR_OOM;
+        TS_LAUNCH("k_pack_weights", k_pack_weights<T>, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads), static_cast<const T *>(weights->data), wt, kmap->K3, cin, cin_pad, cout);
+        pr->wt = wt;
+    }
     pr->x = feats->data;
     if (cin_pad != cin && feats->rows > 0) {
         size_t xn = (size_t)feats->rows * cin_pad;
@@ -811,9 +803,10 @@ struct FusedLaunch {
 };
 
 template <class T>
-int run_fused_staged(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
+int run_fused_staged(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
+                     const ts_weights *pw = nullptr) {
     Prepared pr;
-    TS_TRY(prepare<T>(feats, weights, kmap, &pr));
+    TS_TRY(prepare<T>(feats, weights, kmap, &pr, pw));
     const T *zero = static_cast<const T *>(zero_row());
     if (!zero) return TS_ERR_OOM;
     dispatch_shape(pick_ncb(out->cols), pick_ksteps(pr.cin_pad, Elem<T>::KSTEP), FusedLaunch<T>{pr, kmap, out, zero});
@@ -866,7 +859,7 @@ void launch_conv_tile(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap
 
 // fp16: input channels padded to a multiple of 32 (one MFMA step), chunks of 64 where possible.
 int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
-                  const Epilogue &ep) {
+                  const Epilogue &ep, const ts_weights *pw = nullptr) {
     typedef _Float16 T;
     const int cin = feats->cols, cout = out->cols;
     const int cin_pad = (cin + 31) / 32 * 32;
@@ -874,13 +867,17 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
     // the kernel addresses features and weights with 31-bit byte offsets
     if ((size_t)kmap->n_in * cin_pad * 2 >= (1ull << 31) || (size_t)kmap->K3 * cin_pad * cout * 2 >= (1ull << 31)) {
         if (ep.any()) return fail(TS_ERR_UNSUPPORTED, "feature matrix of 2 GiB or more: call ts_sparse_conv and ts_bias_act");
-        return run_fused_staged<_Float16>(feats, weights, kmap, out);
+        return run_fused_staged<_Float16>(feats, weights, kmap, out, pw);
     }
-    const size_t wn = (size_t)kmap->K3 * cout * cin_pad;
-    T *wf = static_cast<T *>(scratch(2, wn * sizeof(T)));
-    if (!wf) return TS_ERR_OOM;
-    TS_LAUNCH("k_pack_weights", k_pack_weights_tile, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads),
-              static_cast<const T *>(weights->data), wf, kmap->K3, cin, cin_pad, cout, ksteps);
+    const T *wf = pw ? static_cast<const T *>(pw->tile) : nullptr;
+    if (!wf) {
+        const size_t wn = (size_t)kmap->K3 * cout * cin_pad;
+        T *buf = static_cast<T *>(scratch(2, wn * sizeof(T)));
+        if (!buf) return TS_ERR_OOM;
+        TS_LAUNCH("k_pack_weights", k_pack_weights_tile, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads),
+                  static_cast<const T *>(weights->data), buf, kmap->K3, cin, cin_pad, cout, ksteps);
+        wf = buf;
+    }
     const T *x = static_cast<const T *>(feats->data);
     if (cin_pad != cin) {
         const size_t xn = (size_t)feats->rows * cin_pad;
@@ -909,9 +906,10 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
 }
 
 template <class T>
-int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
-    if constexpr (sizeof(T) == 2) return run_fused_f16(feats, weights, kmap, out, Epilogue());
-    return run_fused_staged<T>(feats, weights, kmap, out);
+int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
+              const ts_weights *pw = nullptr) {
+    if constexpr (sizeof(T) == 2) return run_fused_f16(feats, weights, kmap, out, Epilogue(), pw);
+    return run_fused_staged<T>(feats, weights, kmap, out, pw);
 }
 
 int64_t total_mm_tiles(const ts_kmap *kmap) {
@@ -973,9 +971,10 @@ int reduce_impl(const float *G, const ts_kmap *kmap, ts_tensor *out) {
 }
 
 template <class T>
-int run_explicit(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
+int run_explicit(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
+                 const ts_weights *pw = nullptr) {
     Prepared pr;
-    TS_TRY(prepare<T>(feats, weights, kmap, &pr));
+    TS_TRY(prepare<T>(feats, weights, kmap, &pr, pw));
     const int64_t M = kmap->M;
     void *F = scratch(0, (size_t)(M ? M : 1) * pr.cin_pad * sizeof(T));
     float *G = static_cast<float *>(scratch(1, (size_t)(M ? M : 1) * out->cols * sizeof(float)));
@@ -1020,8 +1019,9 @@ int ts_sparse_conv(const ts_tensor *feats, const ts_tensor *weights, const ts_km
     return ts_sparse_conv_ex(feats, weights, kmap, out, TS_DATAFLOW_AUTO);
 }
 
-int ts_sparse_conv_act(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, const void *bias,
-                       const ts_tensor *residual, int relu, ts_tensor *out) {
+// The layer with its optional elementwise tail; pw, when given, holds the weights already packed.
+static int conv_act(const ts_tensor *feats, const ts_tensor *weights, const ts_weights *pw, const ts_kmap *kmap,
+                    const void *bias, const ts_tensor *residual, int relu, ts_tensor *out) {
     TS_TRY(check_layer(feats, weights, kmap, out));
     if (residual) {
         TS_TRY(check_tensor(residual, "residual"));
@@ -1031,17 +1031,85 @@ int ts_sparse_conv_act(const ts_tensor *feats, const ts_tensor *weights, const t
     }
     if (bias && (reinterpret_cast<uintptr_t>(bias) & 15)) return fail(TS_ERR_INVALID_ARG, "bias must be 16-byte aligned");
     if (kmap->n_out == 0) return TS_OK;
-    if (feats->dtype == TS_F16 && !prefer_explicit(kmap, feats->cols, out->cols, 2)) {
+    const bool f16 = feats->dtype == TS_F16;
+    const bool go_explicit = prefer_explicit(kmap, feats->cols, out->cols, f16 ? 2 : 4);
+    if (f16 && !go_explicit) {
         Epilogue ep;
         ep.bias = bias;
         ep.residual = residual ? residual->data : nullptr;
         ep.relu = relu != 0;
-        return run_fused_f16(feats, weights, kmap, out, ep);
+        return run_fused_f16(feats, weights, kmap, out, ep, pw);
     }
     // otherwise: the layer, then the elementwise step on its output
-    TS_TRY(ts_sparse_conv_ex(feats, weights, kmap, out, TS_DATAFLOW_AUTO));
+    if (go_explicit)
+        TS_TRY(f16 ? run_explicit<_Float16>(feats, weights, kmap, out, pw) : run_explicit<float>(feats, weights, kmap, out, pw));
+    else
+        TS_TRY(run_fused<float>(feats, weights, kmap, out, pw));
     if (!bias && !residual && !relu) return TS_OK;
     return ts_bias_act(out, bias, residual, relu, out);
+}
+
+int ts_sparse_conv_act(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, const void *bias,
+                       const ts_tensor *residual, int relu, ts_tensor *out) {
+    return conv_act(feats, weights, nullptr, kmap, bias, residual, relu, out);
+}
+
+int ts_weights_prepare(const ts_tensor *weights, int kernel_volume, ts_weights **out_weights) {
+    if (!out_weights) return fail(TS_ERR_INVALID_ARG, "out_weights is NULL");
+    *out_weights = nullptr;
+    TS_TRY(check_tensor(weights, "weights"));
+    if (kernel_volume != 1 && kernel_volume != 8 && kernel_volume != 27) return fail(TS_ERR_INVALID_ARG, "kernel_volume must be 1, 8 or 27");
+    if (weights->rows <= 0 || weights->rows % kernel_volume != 0) return fail(TS_ERR_SHAPE, "weights must be [K^3*C_in, C_out]");
+    const int cin = (int)(weights->rows / kernel_volume), cout = weights->cols;
+    if (cout % 32 != 0 || cout > 1024 || cin > 1024) return fail(TS_ERR_UNSUPPORTED, "C_out must be a multiple of 32, C_in and C_out at most 1024");
+    ts_weights *w = new (std::nothrow) ts_weights();
+    if (!w) return fail(TS_ERR_OOM, "host allocation failed");
+    w->K3 = kernel_volume;
+    w->cin = cin;
+    w->cout = cout;
+    w->dtype = weights->dtype;
+    const bool f16 = weights->dtype == TS_F16;
+    const int ks = f16 ? Elem<_Float16>::KSTEP : Elem<float>::KSTEP;
+    const int cin_wt = (cin + ks - 1) / ks * ks;
+    const size_t n_wt = (size_t)kernel_volume * cout * cin_wt;
+    w->wt = dev_alloc(n_wt * elem_size(weights->dtype));
+    if (!w->wt) {
+        delete w;
+        return TS_ERR_OOM;
+    }
+    if (f16)
+        TS_LAUNCH("k_pack_weights", k_pack_weights<_Float16>, dim3(blocks_for((int64_t)n_wt, kThreads)), dim3(kThreads), static_cast<const _Float16 *>(weights->data), static_cast<_Float16 *>(w->wt), kernel_volume, cin, cin_wt, cout);
+    else
+        TS_LAUNCH("k_pack_weights", k_pack_weights<float>, dim3(blocks_for((int64_t)n_wt, kThreads)), dim3(kThreads), static_cast<const float *>(weights->data), static_cast<float *>(w->wt), kernel_volume, cin, cin_wt, cout);
+    if (f16) {
+        const int cin_tile = (cin + 31) / 32 * 32, ksteps = cin_tile % 64 == 0 ? 2 : 1;
+        const size_t n_tile = (size_t)kernel_volume * cout * cin_tile;
+        w->tile = dev_alloc(n_tile * 2);
+        if (!w->tile) {
+            dev_free(w->wt);
+            delete w;
+            return TS_ERR_OOM;
+        }
+        TS_LAUNCH("k_pack_weights", k_pack_weights_tile, dim3(blocks_for((int64_t)n_tile, kThreads)), dim3(kThreads), static_cast<const _Float16 *>(weights->data), static_cast<_Float16 *>(w->tile), kernel_volume, cin, cin_tile, cout, ksteps);
+    }
+    TS_HIP(hipGetLastError());
+    *out_weights = w;
+    return TS_OK;
+}
+
+void ts_weights_free(ts_weights *w) {
+    if (!w) return;
+    dev_free(w->wt);
+    dev_free(w->tile);
+    delete w;
+}
+
+int ts_sparse_conv_prepared(const ts_tensor *feats, const ts_weights *w, const ts_kmap *kmap, const void *bias,
+                            const ts_tensor *residual, int relu, ts_tensor *out) {
+    if (!w) return fail(TS_ERR_INVALID_ARG, "weights is NULL");
+    if (kmap && w->K3 != kmap->K3) return fail(TS_ERR_SHAPE, "weights were prepared for kernel volume %d, the map has %d", w->K3, kmap->K3);
+    const ts_tensor desc = {w->wt, (int64_t)w->K3 * w->cin, w->cout, w->dtype};   // shape and dtype for the checks
+    return conv_act(feats, &desc, w, kmap, bias, residual, relu, out);
 }
 
 int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F) {

@@ -17,6 +17,8 @@ class SparseNet:
     def __init__(self, ops, output, params):
         """ops/output from the plan; params: {name: (weights, bias)} as device tensors."""
         self.ops, self.output, self.params = ops, output, params
+        # weights do not change between passes: repack them for the kernels once
+        self.prepared = {name: ts.ts_weights_prepare(w) for name, (w, _) in params.items()}
 
     def build_maps(self, coords: torch.Tensor, sort_rows: bool = False):
         """Kernel maps for every (kind, level) of the plan, plus the coordinates of each level.
@@ -54,7 +56,8 @@ class SparseNet:
             else:
                 w, b = self.params[op["name"]]
                 res = t[op["residual"]] if op["residual"] else None
-                t[op["dst"]] = ts.ts_sparse_conv_act(t[op["src"]], w, maps[op["map"]], b, res, op["relu"])
+                t[op["dst"]] = ts.ts_sparse_conv_prepared(t[op["src"]], self.prepared[op["name"]], maps[op["map"]], b, res,
+                                                          op["relu"])
             if hook:
                 hook(op["dst"], t[op["dst"]])
         return t[self.output]

@@ -356,3 +356,28 @@ def test_strided_map_without_outputs(transposed):
     with pytest.raises(ts.TsError) as e:
         ts.ts_build_kmap(to_dev(dup), 1, 2, transposed)
     assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("K,s,transposed,c_in,c_out,n", [(3, 1, False, 32, 64, 5000), (3, 1, False, 4, 32, 3000),
+                                                          (2, 2, False, 64, 96, 4000), (2, 2, True, 256, 256, 3000),
+                                                          (1, 1, False, 160, 96, 2000)])
+def test_prepared_weights_give_the_same_result(dtype, K, s, transposed, c_in, c_out, n):
+    coords = _rand_coords(66 + K + n, n, -9, 9, batches=2)
+    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
+    nd = np_dtype(dtype)
+    x = to_dev(features(1100, kmap.num_in, c_in, nd))
+    w = to_dev(conv_weights(1101, K ** 3, c_in, c_out, nd))
+    bias = to_dev(features(1102, 1, c_out, nd).reshape(-1))
+    res = to_dev(features(1103, kmap.num_out, c_out, nd))
+    pw = ts.ts_weights_prepare(w)
+    w_copy = w.clone()
+    w.zero_()                                  # the prepared copy does not depend on the caller's tensor
+    torch.cuda.synchronize()
+    assert torch.equal(ts.ts_sparse_conv_prepared(x, pw, kmap), ts.ts_sparse_conv(x, w_copy, kmap))
+    assert torch.equal(ts.ts_sparse_conv_prepared(x, pw, kmap, bias, res, True), ts.ts_sparse_conv_act(x, w_copy, kmap, bias, res, True))
+    other = ts.ts_build_kmap(to_dev(coords), 1 if K != 1 else 3, 1)
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_sparse_conv_prepared(x, pw, other)
+    assert e.value.code == ts.TS_ERR_SHAPE
+    pw.free()
