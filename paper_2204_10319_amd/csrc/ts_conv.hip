@@ -566,7 +566,7 @@ __global__ void __launch_bounds__(kThreads) k_gather(const u32x4 *__restrict__ X
 // offset's list read `zero_row` and are not stored.
 template <class T, int NCB, int KC>
 __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F, const T *__restrict__ X,
-                                                         const T *__restrict__ Wt, const int32_t *__restrict__ offs,
+                                                         const T *__restrict__ Wt, Offs offs,
                                                          float *__restrict__ G, const T *__restrict__ zero_row,
                                                          int cin, int cout, int K3, int centre) {
     typedef Shape<T, NCB, KC> S;
@@ -574,8 +574,8 @@ __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F
     __shared__ __attribute__((aligned(16))) T lds_w[S::SLAB];
     int t = blockIdx.x, n = 0, lo = 0, hi = 0;
     for (; n < K3; ++n) {
-        lo = offs[n];
-        hi = offs[n + 1];
+        lo = offs.v[n];
+        hi = offs.v[n + 1];
         int tiles = (hi - lo + kTileRows - 1) / kTileRows;
         if (t < tiles) break;
         t -= tiles;
@@ -610,8 +610,8 @@ __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F
 template <class T>
 __global__ void __launch_bounds__(kThreads) k_scatter_reduce(const float *__restrict__ G, const int32_t *__restrict__ nbr,
                                                              int stride, const uint64_t *__restrict__ colbits,
-                                                             const int32_t *__restrict__ colbase,
-                                                             const int32_t *__restrict__ offs, int64_t n_blocks,
+                                                             const int32_t *__restrict__ colbase, Offs offs,
+                                                             int64_t n_blocks,
                                                              T *__restrict__ out, int64_t n_out, int cout, int K3) {
     const int quads = cout / 4;
     int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -633,7 +633,7 @@ __global__ void __launch_bounds__(kThreads) k_scatter_reduce(const float *__rest
             if (mask) {
                 const int n = __builtin_ctz(mask);
                 mask &= mask - 1;
-                p[u] = offs[n] + colbase[n * n_blocks + b] + __popcll(colbits[n * n_blocks + b] & before);
+                p[u] = offs.v[n] + colbase[n * n_blocks + b] + __popcll(colbits[n * n_blocks + b] & before);
             }
         }
 #pragma unroll
@@ -929,7 +929,7 @@ struct GroupedLaunch {
     void operator()() const {
         constexpr int KC = KSTEPS * Elem<T>::KSTEP;
         dim3 grid((unsigned)total_mm_tiles(kmap), cout / (NCB * 32));
-        TS_LAUNCH("k_grouped_mm", (k_grouped_mm<T, NCB, KC>), grid, dim3(kThreads), F, X, wt, kmap->d_offs, G, zero,
+        TS_LAUNCH("k_grouped_mm", (k_grouped_mm<T, NCB, KC>), grid, dim3(kThreads), F, X, wt, offs_of(kmap), G, zero,
                   cin_pad, cout, kmap->K3, kmap->centre);
     }
 };
@@ -965,7 +965,7 @@ template <class T>
 int reduce_impl(const float *G, const ts_kmap *kmap, ts_tensor *out) {
     if (kmap->n_out == 0) return TS_OK;
     int64_t threads = kmap->n_out * (out->cols / 4);
-    TS_LAUNCH("k_scatter_reduce", k_scatter_reduce<T>, dim3(blocks_for(threads, kThreads)), dim3(kThreads), G, kmap->d_nbr, kmap->stride, kmap->d_colbits, kmap->d_colbase, kmap->d_offs, kmap->n_blocks, static_cast<T *>(out->data), kmap->n_out, out->cols, kmap->K3);
+    TS_LAUNCH("k_scatter_reduce", k_scatter_reduce<T>, dim3(blocks_for(threads, kThreads)), dim3(kThreads), G, kmap->d_nbr, kmap->stride, kmap->d_colbits, kmap->d_colbase, offs_of(kmap), kmap->n_blocks, static_cast<T *>(out->data), kmap->n_out, out->cols, kmap->K3);
     TS_HIP(hipGetLastError());
     return TS_OK;
 }

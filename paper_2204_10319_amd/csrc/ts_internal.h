@@ -91,6 +91,11 @@ __host__ __device__ inline int64_t key_delta(int dx, int dy, int dz) {
 }
 
 constexpr int kMaxK3 = 27;      // kernel volumes up to 3^3 (one bit per offset in a 32-bit mask)
+
+// Start of every offset's pair list (exclusive prefix of the map sizes), passed to kernels by value.
+struct Offs {
+    int32_t v[kMaxK3 + 1];
+};
 constexpr int kTileRows = 128;  // output rows per workgroup tile of the fused kernel
 constexpr int kMaxSchedSlices = 32;   // output-channel slices of a layer that take tiles from counters of their own
 constexpr int kSchedWords = 9 * 32;   // per slice: 8 tile counters (one per XCD) and a done count, 128 bytes apart
@@ -100,6 +105,11 @@ constexpr int kSchedWords = 9 * 32;   // per slice: 8 tile counters (one per XCD
 __host__ __device__ constexpr int nbr_stride(int K3) { return K3 > 8 ? 32 : (K3 > 1 ? 16 : 4); }
 
 }  // namespace ts
+
+struct ts_kmap;
+namespace ts {
+Offs offs_of(const ::ts_kmap *kmap);   // the map's offs[] as a kernel argument
+}
 
 // The kernel map.  Everything with a d_ prefix is device memory owned by the map.
 struct ts_kmap {
@@ -119,7 +129,6 @@ struct ts_kmap {
     // derived from the out-major table on first use (ts::ensure_pairs); NULL until then ...
     int32_t *d_in_idx = nullptr;          // [M]
     int32_t *d_out_idx = nullptr;         // [M]
-    int32_t *d_offs = nullptr;            // [K3+1] device copy of offs
     // ... and the link between the two views: the pair (k, n) sits at
     // offs[n] + colbase[n][k/64] + popcount(colbits[n][k/64] & ((1 << k%64) - 1)).
     uint64_t *d_colbits = nullptr;        // [K3][n_blocks] bit r: output 64*b + r has offset n

@@ -11,7 +11,7 @@
 //            output the row of neighbour indices and its offset bitmask, and per 64 outputs and
 //            offset a presence bitmap with its count
 //   scan     per-offset exclusive scan of the block counts -> where each pair sits in the
-//            offset-major lists; the last block to finish turns the totals into offs[]
+//            offset-major lists, and the per-offset totals
 // The host waits once, after `scan`, for the map sizes and error flags.
 //   compact  pair lists M[W_n] (in, out), ordered by output index inside an offset: derived from
 //            the above when first asked for (ts_kmap_pairs, the explicit dataflow's gather)
@@ -41,7 +41,6 @@ enum {
     ST_DUP = 1,         // two input rows held the same coordinate
     ST_DCOUNT = 2,      // distinct offset bitmasks seen (ts_kmap_sort_rows)
     ST_OVERFLOW = 3,    // the bitmask table could not hold them all
-    ST_TICKET = 4,      // scan blocks that have finished
     ST_TOTALS = 8,      // [32] per-offset map sizes
     ST_WORDS = 40
 };
@@ -558,12 +557,12 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *total) {
 }
 
 // Block n: exclusive scan of colcnt[n][*] -> colbase[n][b] = pairs of offset n in the 64-row
-// blocks before b (relative to the start of the offset's list), and the offset's total.  The
-// block that finishes last turns the totals into offs[] (start of each offset's list).
+// blocks before b (relative to the start of the offset's list), and the offset's total (the host
+// turns the totals into offs[], the start of each offset's list, and hands them to later kernels
+// by value).
 constexpr int kScanThreads = 1024, kScanItems = 4;
 __global__ void __launch_bounds__(kScanThreads) k_scan(const int32_t *__restrict__ colcnt, int32_t *__restrict__ colbase,
-                                                       int64_t n_blocks, int K3, int *__restrict__ status,
-                                                       int32_t *__restrict__ offs) {
+                                                       int64_t n_blocks, int *__restrict__ status) {
     const int n = blockIdx.x;
     const int32_t *src = colcnt + (int64_t)n * n_blocks;
     int32_t *dst = colbase + (int64_t)n * n_blocks;
@@ -585,19 +584,7 @@ __global__ void __launch_bounds__(kScanThreads) k_scan(const int32_t *__restrict
         }
         run += total;
     }
-    if (threadIdx.x == 0) {
-        __hip_atomic_store(&status[ST_TOTALS + n], run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();
-        if (atomicAdd(&status[ST_TICKET], 1) == K3 - 1) {   // every total is visible now
-            __threadfence();
-            int at = 0;
-            for (int q = 0; q < K3; ++q) {
-                offs[q] = at;
-                at += __hip_atomic_load(&status[ST_TOTALS + q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            offs[K3] = at;
-        }
-    }
+    if (threadIdx.x == 0) status[ST_TOTALS + n] = run;
 }
 
 // ts_kmap_sort_rows, step 2: the distinct bitmasks as a dense list of (sort key, rows), followed
@@ -679,14 +666,14 @@ __global__ void k_place(const int2 *__restrict__ slot_rank, int64_t n_out, MaskH
 template <int K3>
 __global__ void __launch_bounds__(kThreads) k_compact(const int32_t *__restrict__ nbr, int64_t n_out,
                                                       const int32_t *__restrict__ colbase, int64_t n_blocks,
-                                                      const int32_t *__restrict__ offs, int32_t *__restrict__ in_idx,
+                                                      Offs offs, int32_t *__restrict__ in_idx,
                                                       int32_t *__restrict__ out_idx) {
     constexpr int STRIDE = nbr_stride(K3), CHUNKS = (K3 + 3) / 4;
     const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int lane = threadIdx.x & 63;
     const int64_t block64 = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
     int base_mine = 0;
-    if (lane < K3 && block64 < n_blocks) base_mine = offs[lane] + colbase[(int64_t)lane * n_blocks + block64];
+    if (lane < K3 && block64 < n_blocks) base_mine = offs.v[lane] + colbase[(int64_t)lane * n_blocks + block64];
     int32_t j[CHUNKS * 4];
 #pragma unroll
     for (int ch = 0; ch < CHUNKS; ++ch) {
@@ -783,7 +770,6 @@ void destroy(ts_kmap *m) {
     dev_free(m->d_nbr);
     dev_free(m->d_in_idx);
     dev_free(m->d_out_idx);
-    dev_free(m->d_offs);
     dev_free(m->d_colbits);
     dev_free(m->d_colbase);
     dev_free(m->d_perm);
@@ -832,7 +818,7 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status)
     else if (mode == MODE_TR && K == 3) launch_probe<MODE_TR, 3>(m, table, colcnt);
     else return fail(TS_ERR_UNSUPPORTED, "no map search for kernel_size %d, stride %d", K, m->s);
 
-    TS_LAUNCH("k_scan", k_scan, dim3(K3), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, K3, d_status, m->d_offs);
+    TS_LAUNCH("k_scan", k_scan, dim3(K3), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status);
 
     // the one host round trip: error flags and map sizes
     int32_t *h = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
@@ -931,7 +917,6 @@ int alloc_outputs(ts_kmap *m, FillArgs *fill) {
     TS_TRY(alloc_n(&m->d_nbr, (size_t)m->n_out * m->stride));
     TS_TRY(alloc_n(&m->d_colbits, (size_t)K3 * m->n_blocks));
     TS_TRY(alloc_n(&m->d_colbase, (size_t)K3 * m->n_blocks));
-    TS_TRY(alloc_n(&m->d_offs, (size_t)K3 + 1));
     TS_TRY(alloc_n(&m->d_sched, (size_t)kMaxSchedSlices * kSchedWords));
     fill->add(m->d_sched, (size_t)kMaxSchedSlices * kSchedWords * sizeof(int32_t), 0u);
     if (m->s == 1 && K3 == 27) fill->add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);   // the symmetric probe writes hits only
@@ -1069,7 +1054,7 @@ int rows_and_scan(ts_kmap *m, int32_t *colcnt, int *d_status) {
     if (m->K3 == 27) TS_LAUNCH("k_rows", (k_rows<27, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, m->n_blocks);
     else if (m->K3 == 8) TS_LAUNCH("k_rows", (k_rows<8, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, m->n_blocks);
     else TS_LAUNCH("k_rows", (k_rows<1, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, m->n_blocks);
-    TS_LAUNCH("k_scan", k_scan, dim3(m->K3), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, m->K3, d_status, m->d_offs);
+    TS_LAUNCH("k_scan", k_scan, dim3(m->K3), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status);
     TS_HIP(hipGetLastError());
     return TS_OK;
 }
@@ -1115,6 +1100,12 @@ int transpose(const ts_kmap *f, ts_kmap *m) {
 
 namespace ts {
 
+Offs offs_of(const ts_kmap *kmap) {
+    Offs o;
+    for (int n = 0; n <= kMaxK3; ++n) o.v[n] = n <= kmap->K3 ? (int32_t)kmap->offs[n] : (int32_t)kmap->offs[kmap->K3];
+    return o;
+}
+
 // The offset-major pair lists are derived from the out-major table when something first asks for
 // them (ts_kmap_pairs, the gather of the explicit dataflow); the fused kernel never does.
 int ensure_pairs(const ts_kmap *kmap) {
@@ -1127,9 +1118,9 @@ int ensure_pairs(const ts_kmap *kmap) {
         return TS_ERR_OOM;
     }
     const dim3 grid(blocks_for(m->n_out, kThreads)), block(kThreads);
-    if (m->K3 == 27) TS_LAUNCH("k_compact", k_compact<27>, grid, block, m->d_nbr, m->n_out, m->d_colbase, m->n_blocks, m->d_offs, in_idx, out_idx);
-    else if (m->K3 == 8) TS_LAUNCH("k_compact", k_compact<8>, grid, block, m->d_nbr, m->n_out, m->d_colbase, m->n_blocks, m->d_offs, in_idx, out_idx);
-    else TS_LAUNCH("k_compact", k_compact<1>, grid, block, m->d_nbr, m->n_out, m->d_colbase, m->n_blocks, m->d_offs, in_idx, out_idx);
+    if (m->K3 == 27) TS_LAUNCH("k_compact", k_compact<27>, grid, block, m->d_nbr, m->n_out, m->d_colbase, m->n_blocks, offs_of(m), in_idx, out_idx);
+    else if (m->K3 == 8) TS_LAUNCH("k_compact", k_compact<8>, grid, block, m->d_nbr, m->n_out, m->d_colbase, m->n_blocks, offs_of(m), in_idx, out_idx);
+    else TS_LAUNCH("k_compact", k_compact<1>, grid, block, m->d_nbr, m->n_out, m->d_colbase, m->n_blocks, offs_of(m), in_idx, out_idx);
     m->d_in_idx = in_idx;
     m->d_out_idx = out_idx;
     TS_HIP(hipGetLastError());
