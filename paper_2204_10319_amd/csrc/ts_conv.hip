@@ -307,7 +307,8 @@ __device__ __forceinline__ void static_for(Fn &&fn) {
 template <int NCO, int KSTEPS, int DEPTH>
 __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restrict__ X, const u32x4 *__restrict__ Wf,
                                                         const int32_t *__restrict__ nbr, int stride,
-                                                        const int32_t *__restrict__ perm, int64_t n_out,
+                                                        const int32_t *__restrict__ perm,
+                                                        const int32_t *__restrict__ tile_order, int64_t n_out,
                                                         _Float16 *__restrict__ out, int *__restrict__ sched,
                                                         int cin, int cout, int K3, const _Float16 *__restrict__ bias,
                                                         const _Float16 *__restrict__ residual, int relu, int x_bytes,
@@ -329,11 +330,12 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
     const int cb0 = blockIdx.y * NCO;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m16 = lane & 15, g = lane >> 4;
     const int r0 = wave * kWaveRows + m16, r1 = r0 + 16;   // the lane's two output rows (tile slots)
-    // Rows sorted by bitmask put the tiles with the most offsets last: take tiles from the end
-    // then, so that the longest ones do not start when everything else is done.
+    // Longest tiles first, so that they do not start when everything else is done: by the order
+    // the map build prepared (tiles of rows in input order by descending number of offsets); rows
+    // sorted by bitmask put the tiles with the most offsets last, so those are taken from the end.
     int64_t turn = blockIdx.x;
     while (turn < n_tiles) {
-    const int64_t tile = perm ? n_tiles - 1 - turn : turn;
+    const int64_t tile = perm ? n_tiles - 1 - turn : tile_order[turn];
     // ask for the next tile now; the answer is needed when this one is done
     int ticket = 0;
     if (threadIdx.x == 0) ticket = atomicAdd(&sched[xcd * 32], 1);
@@ -851,8 +853,8 @@ void launch_conv_tile(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap
     const int64_t resident = (int64_t)compute_units() * per_cu;
     dim3 grid((unsigned)(kmap->n_tiles < resident ? kmap->n_tiles : resident), out->cols / (NCO * 16));
     TS_LAUNCH("k_conv_tile", (k_conv_tile<NCO, KSTEPS, kTileDepth>), grid, dim3(kThreads), x,
-              reinterpret_cast<const u32x4 *>(wf), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->n_out,
-              static_cast<_Float16 *>(out->data), kmap->d_sched, cin_pad, out->cols, kmap->K3,
+              reinterpret_cast<const u32x4 *>(wf), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->d_tile_order,
+              kmap->n_out, static_cast<_Float16 *>(out->data), kmap->d_sched, cin_pad, out->cols, kmap->K3,
               static_cast<const _Float16 *>(ep.bias), static_cast<const _Float16 *>(ep.residual), ep.relu,
               (int)((size_t)kmap->n_in * cin_pad * 2), (int)((size_t)kmap->K3 * cin_pad * out->cols * 2));
 }

@@ -137,6 +137,7 @@ struct ts_kmap {
     // tile of the output-stationary kernel share their offsets.  NULL = natural row order.
     int64_t n_tiles = 0;                  // ceil(n_out / kTileRows)
     int32_t *d_perm = nullptr;            // [n_tiles*kTileRows] sorted position -> output row, -1 = padding
+    int32_t *d_tile_order = nullptr;      // [n_tiles] tiles (of rows in input order) by descending number of offsets met
     // Tile counters of the fused kernel, per output-channel slice; all zero between launches (the
     // last workgroup of a launch rearms them).
     int32_t *d_sched = nullptr;           // [kMaxSchedSlices][kSchedWords]

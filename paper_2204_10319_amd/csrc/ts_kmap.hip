@@ -29,7 +29,6 @@
 
 using namespace ts;
 
-int rows_and_scan(ts_kmap *m, int32_t *colcnt, int *d_status);   // row pass + scan, defined below the build
 
 namespace {
 
@@ -291,10 +290,10 @@ __host__ __device__ __forceinline__ uint32_t mask_sort_key(uint32_t mask, int K3
 }
 
 // What every search kernel does once a thread knows the offset bitmask of its output row:
-// presence bitmaps of the wave's 64 outputs, one per offset, and their counts.
+// presence bitmaps of the wave's 64 outputs, one per offset, their counts, and the wave's OR.
 template <int K3>
 __device__ __forceinline__ void finish_rows(uint32_t mask, uint64_t *__restrict__ colbits, int32_t *__restrict__ colcnt,
-                                            int64_t n_blocks) {
+                                            uint32_t *__restrict__ wavemask, int64_t n_blocks) {
     const int lane = threadIdx.x & 63;
     const int64_t block64 = (int64_t)blockIdx.x * (blockDim.x / 64) + (threadIdx.x >> 6);   // wave-uniform
     uint64_t mine = 0;
@@ -307,6 +306,9 @@ __device__ __forceinline__ void finish_rows(uint32_t mask, uint64_t *__restrict_
         colbits[(int64_t)lane * n_blocks + block64] = mine;
         colcnt[(int64_t)lane * n_blocks + block64] = __popcll(mine);
     }
+    // offsets present anywhere in the wave's 64 rows (what a tile of the fused kernel has to visit)
+    const uint64_t any = __ballot(lane < K3 && mine != 0);
+    if (lane == 0 && block64 < n_blocks) wavemask[block64] = (uint32_t)any;
 }
 
 // ts_kmap_sort_rows, step 1: register every row's bitmask in the mask table; slot_rank[k] = (table
@@ -355,7 +357,8 @@ enum { MODE_SUB = 0, MODE_FWD = 1, MODE_TR = 2 };
 template <int MODE, int K>
 __global__ void __launch_bounds__(kThreads, 3) k_probe(const uint64_t *__restrict__ out_keys, int64_t n_out, Table t, int s,
                                                     int32_t *__restrict__ nbr, uint64_t *__restrict__ colbits,
-                                                    int32_t *__restrict__ colcnt, int64_t n_blocks) {
+                                                    int32_t *__restrict__ colcnt, uint32_t *__restrict__ wavemask,
+                                                    int64_t n_blocks) {
     constexpr int K3 = K * K * K, STRIDE = nbr_stride(K3), CENTRE = (K3 - 1) / 2;
     const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const uint64_t key = k < n_out ? out_keys[k] : kEmptyKey;
@@ -451,7 +454,7 @@ __global__ void __launch_bounds__(kThreads, 3) k_probe(const uint64_t *__restric
         }
     }
 
-    finish_rows<K3>(mask, colbits, colcnt, n_blocks);
+    finish_rows<K3>(mask, colbits, colcnt, wavemask, n_blocks);
 }
 
 // Map search for stride 1, odd K, one thread per (point i, offset n) with n below the centre.
@@ -488,7 +491,7 @@ __global__ void k_probe_symmetric(const uint64_t *__restrict__ keys, int64_t n_p
 template <int K3, bool HAS_CENTRE>
 __global__ void __launch_bounds__(kThreads) k_rows(int32_t *__restrict__ nbr, const uint64_t *__restrict__ keys, int64_t n_out,
                                                    uint64_t *__restrict__ colbits, int32_t *__restrict__ colcnt,
-                                                   int64_t n_blocks) {
+                                                   uint32_t *__restrict__ wavemask, int64_t n_blocks) {
     constexpr int STRIDE = nbr_stride(K3), CHUNKS = (K3 + 3) / 4, CENTRE = (K3 - 1) / 2;
     const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const bool ok = k < n_out && keys[k] != kEmptyKey;
@@ -509,7 +512,7 @@ __global__ void __launch_bounds__(kThreads) k_rows(int32_t *__restrict__ nbr, co
         if (HAS_CENTRE) nbr[k * STRIDE + CENTRE] = (int32_t)k;
         nbr[k * STRIDE + K3] = (int32_t)mask;
     }
-    finish_rows<K3>(mask, colbits, colcnt, n_blocks);
+    finish_rows<K3>(mask, colbits, colcnt, wavemask, n_blocks);
 }
 
 // Transposition of a forward map: entry (input j, output k, offset n) of the forward table becomes
@@ -562,7 +565,33 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *total) {
 // by value).
 constexpr int kScanThreads = 1024, kScanItems = 4;
 __global__ void __launch_bounds__(kScanThreads) k_scan(const int32_t *__restrict__ colcnt, int32_t *__restrict__ colbase,
-                                                       int64_t n_blocks, int *__restrict__ status) {
+                                                       int64_t n_blocks, int *__restrict__ status, int K3,
+                                                       const uint32_t *__restrict__ wavemask, int64_t n_tiles,
+                                                       int32_t *__restrict__ tile_order) {
+    if ((int)blockIdx.x == K3) {
+        // The extra block: tiles of 128 outputs (two waves of the search) in descending order of
+        // the number of offsets they meet, a counting sort.  The fused kernel takes tiles in this
+        // order, so that the long ones do not start when everything else is done.
+        __shared__ int hist[32], base[32];
+        if (threadIdx.x < 32) hist[threadIdx.x] = 0;
+        __syncthreads();
+        auto offsets_of = [&](int64_t t) {
+            const uint32_t a = wavemask[2 * t], b = 2 * t + 1 < n_blocks ? wavemask[2 * t + 1] : 0u;
+            return __builtin_popcount(a | b);
+        };
+        for (int64_t t = threadIdx.x; t < n_tiles; t += kScanThreads) atomicAdd(&hist[offsets_of(t)], 1);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int at = 0;
+            for (int c = 31; c >= 0; --c) {
+                base[c] = at;
+                at += hist[c];
+            }
+        }
+        __syncthreads();
+        for (int64_t t = threadIdx.x; t < n_tiles; t += kScanThreads) tile_order[atomicAdd(&base[offsets_of(t)], 1)] = (int32_t)t;
+        return;
+    }
     const int n = blockIdx.x;
     const int32_t *src = colcnt + (int64_t)n * n_blocks;
     int32_t *dst = colbase + (int64_t)n * n_blocks;
@@ -774,6 +803,7 @@ void destroy(ts_kmap *m) {
     dev_free(m->d_colbase);
     dev_free(m->d_perm);
     dev_free(m->d_sched);
+    dev_free(m->d_tile_order);
     delete m;
 }
 
@@ -788,9 +818,9 @@ int sort_keys(Temps &tmp, uint64_t *in, uint64_t *out, size_t n) {
 }
 
 template <int MODE, int K>
-void launch_probe(const ts_kmap *m, const Table &t, int32_t *colcnt) {
+void launch_probe(const ts_kmap *m, const Table &t, int32_t *colcnt, uint32_t *wavemask) {
     TS_LAUNCH("k_probe", (k_probe<MODE, K>), dim3(blocks_for(m->n_out, kThreads)), dim3(kThreads), m->d_out_keys, m->n_out,
-              t, m->s, m->d_nbr, m->d_colbits, colcnt, m->n_blocks);
+              t, m->s, m->d_nbr, m->d_colbits, colcnt, wavemask, m->n_blocks);
 }
 
 // Map search and everything after it.  `table` holds the searched point set; m->d_out_keys the
@@ -801,24 +831,27 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status)
     const int K3 = m->K3, K = m->K;
     const int64_t n_out = m->n_out;
     int32_t *colcnt;
+    uint32_t *wavemask;
     TS_TRY(tmp.get(&colcnt, (size_t)K3 * m->n_blocks));
+    TS_TRY(tmp.get(&wavemask, (size_t)m->n_blocks));
     const int mode = m->s == 1 ? MODE_SUB : (m->transposed ? MODE_TR : MODE_FWD);
-    if (mode == MODE_SUB && K == 1) launch_probe<MODE_SUB, 1>(m, table, colcnt);
+    if (mode == MODE_SUB && K == 1) launch_probe<MODE_SUB, 1>(m, table, colcnt, wavemask);
     else if (mode == MODE_SUB && K == 3) {
         TS_LAUNCH("k_probe_symmetric", k_probe_symmetric, dim3(blocks_for(n_out, kThreads), K3 / 2), dim3(kThreads), m->d_out_keys,
                   n_out, table, K, m->d_nbr, m->stride);
         TS_LAUNCH("k_rows", (k_rows<27, true>), dim3(blocks_for(n_out, kThreads)), dim3(kThreads), m->d_nbr, m->d_out_keys, n_out,
-                  m->d_colbits, colcnt, m->n_blocks);
+                  m->d_colbits, colcnt, wavemask, m->n_blocks);
     }
-    else if (mode == MODE_FWD && K == 1) launch_probe<MODE_FWD, 1>(m, table, colcnt);
-    else if (mode == MODE_TR && K == 1) launch_probe<MODE_TR, 1>(m, table, colcnt);
-    else if (mode == MODE_FWD && K == 2) launch_probe<MODE_FWD, 2>(m, table, colcnt);
-    else if (mode == MODE_FWD && K == 3) launch_probe<MODE_FWD, 3>(m, table, colcnt);
-    else if (mode == MODE_TR && K == 2) launch_probe<MODE_TR, 2>(m, table, colcnt);
-    else if (mode == MODE_TR && K == 3) launch_probe<MODE_TR, 3>(m, table, colcnt);
+    else if (mode == MODE_FWD && K == 1) launch_probe<MODE_FWD, 1>(m, table, colcnt, wavemask);
+    else if (mode == MODE_TR && K == 1) launch_probe<MODE_TR, 1>(m, table, colcnt, wavemask);
+    else if (mode == MODE_FWD && K == 2) launch_probe<MODE_FWD, 2>(m, table, colcnt, wavemask);
+    else if (mode == MODE_FWD && K == 3) launch_probe<MODE_FWD, 3>(m, table, colcnt, wavemask);
+    else if (mode == MODE_TR && K == 2) launch_probe<MODE_TR, 2>(m, table, colcnt, wavemask);
+    else if (mode == MODE_TR && K == 3) launch_probe<MODE_TR, 3>(m, table, colcnt, wavemask);
     else return fail(TS_ERR_UNSUPPORTED, "no map search for kernel_size %d, stride %d", K, m->s);
 
-    TS_LAUNCH("k_scan", k_scan, dim3(K3), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status);
+    TS_LAUNCH("k_scan", k_scan, dim3(K3 + 1), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status, K3, wavemask,
+              m->n_tiles, m->d_tile_order);
 
     // the one host round trip: error flags and map sizes
     int32_t *h = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
@@ -917,11 +950,14 @@ int alloc_outputs(ts_kmap *m, FillArgs *fill) {
     TS_TRY(alloc_n(&m->d_nbr, (size_t)m->n_out * m->stride));
     TS_TRY(alloc_n(&m->d_colbits, (size_t)K3 * m->n_blocks));
     TS_TRY(alloc_n(&m->d_colbase, (size_t)K3 * m->n_blocks));
+    TS_TRY(alloc_n(&m->d_tile_order, (size_t)m->n_tiles));
     TS_TRY(alloc_n(&m->d_sched, (size_t)kMaxSchedSlices * kSchedWords));
     fill->add(m->d_sched, (size_t)kMaxSchedSlices * kSchedWords * sizeof(int32_t), 0u);
     if (m->s == 1 && K3 == 27) fill->add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);   // the symmetric probe writes hits only
     return TS_OK;
 }
+
+int rows_and_scan(ts_kmap *m, Temps &tmp, int32_t *colcnt, int *d_status);   // defined below the build
 
 int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kmap *m) {
     hipStream_t st = stream();
@@ -1005,7 +1041,7 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             }
             TS_TRY(launch_fill(fill));
             TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, t0, d_status);
-            if (transposed) TS_TRY(rows_and_scan(m, colcnt, d_status));
+            if (transposed) TS_TRY(rows_and_scan(m, tmp, colcnt, d_status));
             int32_t *hs = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
             if (!hs) return TS_ERR_OOM;
             TS_HIP(hipMemcpyAsync(hs, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
@@ -1048,13 +1084,18 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
 
 }  // namespace
 
+namespace {
+
 // Row pass (bitmasks, presence bitmaps) and scan over a neighbour table that is already filled in.
-int rows_and_scan(ts_kmap *m, int32_t *colcnt, int *d_status) {
+int rows_and_scan(ts_kmap *m, Temps &tmp, int32_t *colcnt, int *d_status) {
+    uint32_t *wavemask;
+    TS_TRY(tmp.get(&wavemask, (size_t)m->n_blocks));
     const dim3 grid(blocks_for(m->n_out, kThreads)), block(kThreads);
-    if (m->K3 == 27) TS_LAUNCH("k_rows", (k_rows<27, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, m->n_blocks);
-    else if (m->K3 == 8) TS_LAUNCH("k_rows", (k_rows<8, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, m->n_blocks);
-    else TS_LAUNCH("k_rows", (k_rows<1, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, m->n_blocks);
-    TS_LAUNCH("k_scan", k_scan, dim3(m->K3), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status);
+    if (m->K3 == 27) TS_LAUNCH("k_rows", (k_rows<27, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, wavemask, m->n_blocks);
+    else if (m->K3 == 8) TS_LAUNCH("k_rows", (k_rows<8, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, wavemask, m->n_blocks);
+    else TS_LAUNCH("k_rows", (k_rows<1, false>), grid, block, m->d_nbr, m->d_out_keys, m->n_out, m->d_colbits, colcnt, wavemask, m->n_blocks);
+    TS_LAUNCH("k_scan", k_scan, dim3(m->K3 + 1), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status, m->K3, wavemask,
+              m->n_tiles, m->d_tile_order);
     TS_HIP(hipGetLastError());
     return TS_OK;
 }
@@ -1095,8 +1136,10 @@ int transpose(const ts_kmap *f, ts_kmap *m) {
         else if (K3 == 8) TS_LAUNCH("k_transpose", k_transpose<8>, gf, block, f->d_nbr, f->n_out, m->d_nbr);
         else TS_LAUNCH("k_transpose", k_transpose<1>, gf, block, f->d_nbr, f->n_out, m->d_nbr);
     }
-    return rows_and_scan(m, colcnt, d_status);
+    return rows_and_scan(m, tmp, colcnt, d_status);
 }
+
+}  // namespace
 
 namespace ts {
 
