@@ -70,8 +70,11 @@ enum { TS_F32 = 0, TS_F16 = 1 };
 enum {
     TS_DATAFLOW_AUTO = 0,     /* library's choice (the fused kernel where it applies)                     */
     TS_DATAFLOW_EXPLICIT = 1, /* Alg. 2 as three launches: gather -> grouped matmul -> scatter-accumulate */
-    TS_DATAFLOW_FUSED = 2     /* one output-stationary kernel: gather into the MFMA operand, accumulate
+    TS_DATAFLOW_FUSED = 2,    /* one output-stationary kernel: gather into the MFMA operand, accumulate
                                  over offsets in registers, write each output row once                    */
+    TS_DATAFLOW_FUSED_STAGED = 3 /* the same dataflow by the older kernel that stages weight slabs and
+                                 neighbour indices per tile in LDS with 32x32 MFMAs: what TS_F32 always
+                                 runs, and TS_F16 when features or weights reach 2 GiB                    */
 };
 
 /* Dense row-major matrix: rows x cols elements of dtype, device memory. */

@@ -1007,13 +1007,16 @@ extern "C" {
 int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
                       int dataflow) {
     TS_TRY(check_layer(feats, weights, kmap, out));
-    if (dataflow != TS_DATAFLOW_AUTO && dataflow != TS_DATAFLOW_EXPLICIT && dataflow != TS_DATAFLOW_FUSED)
+    if (dataflow != TS_DATAFLOW_AUTO && dataflow != TS_DATAFLOW_EXPLICIT && dataflow != TS_DATAFLOW_FUSED &&
+        dataflow != TS_DATAFLOW_FUSED_STAGED)
         return fail(TS_ERR_INVALID_ARG, "unknown dataflow %d", dataflow);
     if (kmap->n_out == 0) return TS_OK;
     const bool f16 = feats->dtype == TS_F16;
     if (dataflow == TS_DATAFLOW_AUTO && prefer_explicit(kmap, feats->cols, out->cols, f16 ? 2 : 4)) dataflow = TS_DATAFLOW_EXPLICIT;
     if (dataflow == TS_DATAFLOW_EXPLICIT)
         return f16 ? run_explicit<_Float16>(feats, weights, kmap, out) : run_explicit<float>(feats, weights, kmap, out);
+    if (dataflow == TS_DATAFLOW_FUSED_STAGED)
+        return f16 ? run_fused_staged<_Float16>(feats, weights, kmap, out) : run_fused_staged<float>(feats, weights, kmap, out);
     return f16 ? run_fused<_Float16>(feats, weights, kmap, out) : run_fused<float>(feats, weights, kmap, out);
 }
 

@@ -33,3 +33,13 @@ def test_constants_match_the_header():
         assert getattr(binding, name) == val
     for name, val in re.findall(r"(TS_ERR_[A-Z_]+) = (-?\d+)", text):
         assert getattr(binding, name) == int(val)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Everything here runs on one GPU; bench.py says so instead of starting ranks (no GPU needed for this)."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr

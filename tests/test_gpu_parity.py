@@ -89,7 +89,8 @@ def test_kmap_errors():
     _check_map(_rand_coords(5, 100, 0, 6), 3, 1)
 
 
-def _layer_case(coords, c_in, c_out, K, s, transposed, dtype, seed, dataflows=(ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT)):
+def _layer_case(coords, c_in, c_out, K, s, transposed, dtype, seed,
+                dataflows=(ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FUSED_STAGED, ts.TS_DATAFLOW_AUTO)):
     kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
     x = features(seed, kmap.num_in, c_in, np_dtype(dtype))
     w = conv_weights(seed + 1, K ** 3, c_in, c_out, np_dtype(dtype))
