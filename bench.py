@@ -102,7 +102,9 @@ def main():
     pw = ts.ts_weights_prepare(w)   # layer constants: repacked for the kernels once, outside the step
 
     def step():
-        kmap = ts.ts_build_kmap(coords, K, 1)
+        # the build does not wait for its sizes to reach the host (nothing in this step needs them): map
+        # build and layer run back to back on the device
+        kmap = ts.ts_build_kmap(coords, K, 1, wait=False)
         ts.ts_sparse_conv_prepared(x, pw, kmap, out=out)
         return kmap
 

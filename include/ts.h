@@ -107,6 +107,21 @@ int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride,
                   ts_kmap **out_kmap);
 
 /*
+ * ts_build_kmap without the wait at the end, where the build allows it: the map is returned as soon
+ * as its kernels are enqueued, and its sizes and the error flags of its input (duplicate or
+ * out-of-range coordinates) reach the host when something first needs them: ts_kmap_status,
+ * ts_kmap_num_pairs / _sizes / _pairs, the explicit dataflow, ts_kmap_sort_rows, ts_kmap_transpose.
+ * The fused layer kernel needs none of them, so a build followed by ts_sparse_conv runs on the
+ * device without a host round trip in between.  A map whose input was bad is safe to use (rows of
+ * bad points have no neighbours) but its results are meaningless: call ts_kmap_status before
+ * trusting them.  Strided maps still wait once inside (for the number of output points).
+ */
+int ts_build_kmap_async(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
+                        ts_kmap **out_kmap);
+/* Waits for an asynchronous build's verdict: TS_OK, TS_ERR_DUPLICATE_COORD or TS_ERR_COORD_RANGE. */
+int ts_kmap_status(const ts_kmap *kmap);
+
+/*
  * The transposed map of `forward` (built with stride > 1, transposed = 0): the same map that
  * ts_build_kmap(fine coords, kernel_size, stride, 1) yields for the coordinates `forward` was built
  * from, derived from `forward` without another search.  A network's upsampling layer takes this

@@ -25,7 +25,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libts.so")
 _lib = None
 
 EXPORTS = [
-    "ts_build_kmap", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
+    "ts_build_kmap", "ts_build_kmap_async", "ts_kmap_status", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
     "ts_sparse_conv_prepared", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
@@ -58,6 +58,10 @@ def load_library(path: str | None = None):
     tp = ctypes.POINTER(ts_tensor)
     lib.ts_build_kmap.argtypes = [vp, i64, ci, ci, ci, ctypes.POINTER(vp)]
     lib.ts_build_kmap.restype = ci
+    lib.ts_build_kmap_async.argtypes = [vp, i64, ci, ci, ci, ctypes.POINTER(vp)]
+    lib.ts_build_kmap_async.restype = ci
+    lib.ts_kmap_status.argtypes = [vp]
+    lib.ts_kmap_status.restype = ci
     lib.ts_free.argtypes = [vp]
     lib.ts_free.restype = None
     lib.ts_kmap_sort_rows.argtypes = [vp]
@@ -226,6 +230,11 @@ class KMap:
     def pairs(self):
         return ts_kmap_pairs(self)
 
+    def status(self):
+        """Waits for an asynchronous build's verdict; raises TsError if the input was bad."""
+        _check(load_library().ts_kmap_status(self.handle))
+        return self
+
     def transpose(self) -> "KMap":
         return ts_kmap_transpose(self)
 
@@ -245,16 +254,19 @@ class KMap:
             pass
 
 
-def ts_build_kmap(coords: torch.Tensor, kernel_size: int, stride: int = 1, transposed: bool = False) -> KMap:
-    """coords: device int32 [N,4] (batch, x, y, z)."""
+def ts_build_kmap(coords: torch.Tensor, kernel_size: int, stride: int = 1, transposed: bool = False,
+                  wait: bool = True) -> KMap:
+    """coords: device int32 [N,4] (batch, x, y, z).  wait=False: ts_build_kmap_async (errors of the input
+    surface at ``KMap.status()`` or the first accessor that needs the map's sizes)."""
     if coords.dtype != torch.int32 or coords.dim() != 2 or coords.shape[1] != 4:
         raise ValueError("coords must be int32 [N,4]")
     if not coords.is_cuda or not coords.is_contiguous():
         raise ValueError("coords must be a contiguous device tensor")
     _use_current_stream()
     h = ctypes.c_void_p()
-    rc = load_library().ts_build_kmap(coords.data_ptr() if coords.numel() else None, coords.shape[0],
-                                      int(kernel_size), int(stride), int(bool(transposed)), ctypes.byref(h))
+    fn = load_library().ts_build_kmap if wait else load_library().ts_build_kmap_async
+    rc = fn(coords.data_ptr() if coords.numel() else None, coords.shape[0], int(kernel_size), int(stride),
+            int(bool(transposed)), ctypes.byref(h))
     _check(rc)
     return KMap(h.value)
 

@@ -717,6 +717,7 @@ int check_tensor(const ts_tensor *t, const char *name) {
 
 int check_layer(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, const ts_tensor *out) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    if (kmap->pending_slot < 0 && kmap->error != TS_OK) return resolve(kmap);   // a map whose build found bad input
     TS_TRY(check_tensor(feats, "feats"));
     TS_TRY(check_tensor(weights, "weights"));
     TS_TRY(check_tensor(out, "out"));
@@ -975,6 +976,7 @@ int reduce_impl(const float *G, const ts_kmap *kmap, ts_tensor *out) {
 template <class T>
 int run_explicit(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
                  const ts_weights *pw = nullptr) {
+    TS_TRY(resolve(kmap));
     Prepared pr;
     TS_TRY(prepare<T>(feats, weights, kmap, &pr, pw));
     const int64_t M = kmap->M;
@@ -996,6 +998,7 @@ int run_explicit(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap
 // the MinkUNet-style benchmark network.
 bool prefer_explicit(const ts_kmap *kmap, int cin, int cout, size_t elem) {
     if (kmap->n_tiles > compute_units()) return false;
+    if (resolve(kmap) != TS_OK) return false;   // needs the number of pairs
     const double tile_offsets = kmap->K3 < 20 ? kmap->K3 : 20;
     const double fused_weight_bytes = (double)kmap->n_tiles * tile_offsets * cin * cout * elem;
     const double explicit_bytes = (double)kmap->M * (2.0 * cin * elem + 2.0 * cout * sizeof(float));
@@ -1119,6 +1122,7 @@ int ts_sparse_conv_prepared(const ts_tensor *feats, const ts_weights *w, const t
 
 int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    TS_TRY(resolve(kmap));
     TS_TRY(check_tensor(feats, "feats"));
     TS_TRY(check_tensor(F, "F"));
     if (feats->rows != kmap->n_in) return fail(TS_ERR_SHAPE, "feats has %lld rows, the map expects %lld", (long long)feats->rows, (long long)kmap->n_in);
@@ -1132,6 +1136,7 @@ int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F) {
 int ts_grouped_matmul(const ts_tensor *F, const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
                       ts_tensor *G) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    TS_TRY(resolve(kmap));
     TS_TRY(check_tensor(F, "F"));
     TS_TRY(check_tensor(weights, "weights"));
     TS_TRY(check_tensor(G, "G"));
@@ -1159,6 +1164,7 @@ int ts_grouped_matmul(const ts_tensor *F, const ts_tensor *feats, const ts_tenso
 
 int ts_scatter_reduce(const ts_tensor *G, const ts_kmap *kmap, ts_tensor *out) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    TS_TRY(resolve(kmap));
     TS_TRY(check_tensor(G, "G"));
     TS_TRY(check_tensor(out, "out"));
     if (G->dtype != TS_F32 || G->rows != kmap->M) return fail(TS_ERR_SHAPE, "G must be TS_F32 [num_pairs, C_out]");

@@ -63,6 +63,10 @@ inline int alloc_n(T **p, size_t n) {
     return *p ? TS_OK : TS_ERR_OOM;
 }
 
+// Waits, if it has not happened yet, for the sizes and error flags of a map built with
+// ts_build_kmap_async, and fills in M / sizes / offs.  Returns TS_OK or the build's error.
+int resolve(const struct ::ts_kmap *kmap);
+
 // Makes sure the offset-major pair lists of a map exist (they are derived on first use).
 int ensure_pairs(const struct ::ts_kmap *kmap);
 
@@ -116,7 +120,9 @@ struct ts_kmap {
     int K = 0, s = 0, transposed = 0, K3 = 0;
     int centre = -1;            // index of the identity offset (odd K, stride 1), else -1
     int stride = 0;             // nbr_stride(K3)
-    int64_t n_in = 0, n_out = 0, M = 0;
+    int64_t n_in = 0, n_out = 0, M = 0;   // M, sizes, offs: valid once ts::resolve has run
+    int pending_slot = -1;      // >= 0: sizes and error flags are still on their way to the host
+    int error = 0;              // TS_OK, or what the build found wrong with its input
     int64_t n_blocks = 0;       // ceil(n_out / 64): 64-row blocks of the rank structure
     int64_t sizes[ts::kMaxK3] = {0};      // |M[W_n]|
     int64_t offs[ts::kMaxK3 + 1] = {0};   // exclusive prefix of sizes

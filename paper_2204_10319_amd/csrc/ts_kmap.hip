@@ -511,6 +511,8 @@ __global__ void __launch_bounds__(kThreads) k_rows(int32_t *__restrict__ nbr, co
             if ((HAS_CENTRE && n == CENTRE) || j[n] >= 0) mask |= 1u << n;
         if (HAS_CENTRE) nbr[k * STRIDE + CENTRE] = (int32_t)k;
         nbr[k * STRIDE + K3] = (int32_t)mask;
+    } else if (k < n_out) {
+        nbr[k * STRIDE + K3] = 0;   // a row of an invalid coordinate (the build reports the error) has no neighbours
     }
     finish_rows<K3>(mask, colbits, colcnt, wavemask, n_blocks);
 }
@@ -792,8 +794,63 @@ int make_mask_hash(Temps &tmp, MaskHash *mh, FillArgs *fill) {
     return TS_OK;
 }
 
+// Pinned landing places for the status words of builds whose caller did not wait
+// (ts_build_kmap_async), each with the event that says the copy has arrived.
+struct StatusSlot {
+    int32_t *host = nullptr;
+    hipEvent_t ev = nullptr;
+    bool busy = false;          // a copy is in flight or has not been read yet
+    const ts_kmap *owner = nullptr;   // NULL while busy: the map was freed before anyone asked
+};
+constexpr int kStatusSlots = 64;
+StatusSlot g_slots[kStatusSlots];
+
+int slot_acquire() {
+    static int32_t *mem = nullptr;
+    if (!mem) {
+        if (hipHostMalloc(&mem, kStatusSlots * ST_WORDS * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            mem = nullptr;
+            return -1;
+        }
+        for (int i = 0; i < kStatusSlots; ++i) g_slots[i].host = mem + i * ST_WORDS;
+    }
+    for (int i = 0; i < kStatusSlots; ++i) {
+        StatusSlot &s = g_slots[i];
+        if (s.busy && !s.owner && hipEventQuery(s.ev) == hipSuccess) s.busy = false;   // orphan whose copy has landed
+        if (s.busy) continue;
+        if (!s.ev && hipEventCreateWithFlags(&s.ev, hipEventDisableTiming) != hipSuccess) {
+            (void)hipGetLastError();
+            s.ev = nullptr;
+            return -1;
+        }
+        return i;
+    }
+    (void)hipGetLastError();   // hipEventQuery leaves hipErrorNotReady behind
+    return -1;
+}
+
+// Status words on the host -> the map's sizes, or its error.
+int take_status(ts_kmap *m, const int32_t *h) {
+    if (h[ST_RANGE]) m->error = TS_ERR_COORD_RANGE;
+    else if (h[ST_DUP]) m->error = TS_ERR_DUPLICATE_COORD;
+    m->offs[0] = 0;
+    for (int n = 0; n < m->K3; ++n) m->offs[n + 1] = m->offs[n] + h[ST_TOTALS + n];
+    for (int n = 0; n < m->K3; ++n) m->sizes[n] = m->offs[n + 1] - m->offs[n];
+    m->M = m->offs[m->K3];
+    return m->error;
+}
+
+int report(const ts_kmap *m) {
+    if (m->error == TS_ERR_COORD_RANGE)
+        return fail(TS_ERR_COORD_RANGE, "coordinate outside batch [0,%d] / xyz [%d,%d]", TS_BATCH_MAX, TS_COORD_MIN, TS_COORD_MAX);
+    if (m->error == TS_ERR_DUPLICATE_COORD) return fail(TS_ERR_DUPLICATE_COORD, "input coordinates are not distinct");
+    return m->error;
+}
+
 void destroy(ts_kmap *m) {
     if (!m) return;
+    if (m->pending_slot >= 0) g_slots[m->pending_slot].owner = nullptr;   // the slot frees itself when its copy has landed
     if (m->d_out_keys != m->d_in_keys) dev_free(m->d_out_keys);
     dev_free(m->d_in_keys);
     dev_free(m->d_nbr);
@@ -826,7 +883,7 @@ void launch_probe(const ts_kmap *m, const Table &t, int32_t *colcnt, uint32_t *w
 // Map search and everything after it.  `table` holds the searched point set; m->d_out_keys the
 // outputs; the clearing of the status words (and of the neighbour table where the search
 // writes hits only) has been enqueued.
-int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status) {
+int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status, bool wait) {
     hipStream_t st = stream();
     const int K3 = m->K3, K = m->K;
     const int64_t n_out = m->n_out;
@@ -853,19 +910,23 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status)
     TS_LAUNCH("k_scan", k_scan, dim3(K3 + 1), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status, K3, wavemask,
               m->n_tiles, m->d_tile_order);
 
-    // the one host round trip: error flags and map sizes
-    int32_t *h = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
-    if (!h) return TS_ERR_OOM;
-    TS_HIP(hipMemcpyAsync(h, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    TS_HIP(hipStreamSynchronize(st));
-    if (h[ST_RANGE])
-        return fail(TS_ERR_COORD_RANGE, "coordinate outside batch [0,%d] / xyz [%d,%d]", TS_BATCH_MAX,
-                    TS_COORD_MIN, TS_COORD_MAX);
-    if (h[ST_DUP]) return fail(TS_ERR_DUPLICATE_COORD, "input coordinates are not distinct");
-    m->offs[0] = 0;
-    for (int n = 0; n < K3; ++n) m->offs[n + 1] = m->offs[n] + h[ST_TOTALS + n];
-    for (int n = 0; n < K3; ++n) m->sizes[n] = m->offs[n + 1] - m->offs[n];
-    m->M = m->offs[K3];
+    // the one host round trip: error flags and map sizes.  A caller that does not wait gets them
+    // when it first asks (ts::resolve); the copy lands in a pinned slot of its own meanwhile.
+    const int slot = wait ? -1 : slot_acquire();
+    if (slot >= 0) {
+        StatusSlot &sl = g_slots[slot];
+        TS_HIP(hipMemcpyAsync(sl.host, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        TS_HIP(hipEventRecord(sl.ev, st));
+        sl.busy = true;
+        sl.owner = m;
+        m->pending_slot = slot;
+    } else {
+        int32_t *h = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
+        if (!h) return TS_ERR_OOM;
+        TS_HIP(hipMemcpyAsync(h, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        TS_HIP(hipStreamSynchronize(st));
+        if (take_status(m, h) != TS_OK) return report(m);
+    }
 
     TS_HIP(hipGetLastError());
     // temporaries go back to the pool when the caller's Temps dies; later work on the same
@@ -959,7 +1020,7 @@ int alloc_outputs(ts_kmap *m, FillArgs *fill) {
 
 int rows_and_scan(ts_kmap *m, Temps &tmp, int32_t *colcnt, int *d_status);   // defined below the build
 
-int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kmap *m) {
+int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kmap *m, bool wait) {
     hipStream_t st = stream();
     Temps tmp;
     const int K3 = K * K * K;
@@ -1079,7 +1140,7 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
         }
     }
     TS_HIP(hipGetLastError());
-    return search_and_finish(m, tmp, table, d_status);
+    return search_and_finish(m, tmp, table, d_status, wait);
 }
 
 }  // namespace
@@ -1143,6 +1204,19 @@ int transpose(const ts_kmap *f, ts_kmap *m) {
 
 namespace ts {
 
+int resolve(const ts_kmap *kmap) {
+    ts_kmap *m = const_cast<ts_kmap *>(kmap);
+    if (m->pending_slot >= 0) {
+        StatusSlot &sl = g_slots[m->pending_slot];
+        TS_HIP(hipEventSynchronize(sl.ev));
+        take_status(m, sl.host);
+        sl.busy = false;
+        sl.owner = nullptr;
+        m->pending_slot = -1;
+    }
+    return m->error == TS_OK ? TS_OK : report(m);
+}
+
 Offs offs_of(const ts_kmap *kmap) {
     Offs o;
     for (int n = 0; n <= kMaxK3; ++n) o.v[n] = n <= kmap->K3 ? (int32_t)kmap->offs[n] : (int32_t)kmap->offs[kmap->K3];
@@ -1153,6 +1227,7 @@ Offs offs_of(const ts_kmap *kmap) {
 // them (ts_kmap_pairs, the gather of the explicit dataflow); the fused kernel never does.
 int ensure_pairs(const ts_kmap *kmap) {
     ts_kmap *m = const_cast<ts_kmap *>(kmap);
+    TS_TRY(resolve(m));
     if (m->d_in_idx || m->M == 0) return TS_OK;
     int32_t *in_idx, *out_idx;
     TS_TRY(alloc_n(&in_idx, (size_t)m->M));
@@ -1174,8 +1249,8 @@ int ensure_pairs(const ts_kmap *kmap) {
 
 extern "C" {
 
-int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
-                  ts_kmap **out_kmap) {
+static int build_checked(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed, ts_kmap **out_kmap,
+                         bool wait) {
     if (!out_kmap) return fail(TS_ERR_INVALID_ARG, "out_kmap is NULL");
     *out_kmap = nullptr;
     if (N < 0) return fail(TS_ERR_INVALID_ARG, "N is negative");
@@ -1189,7 +1264,7 @@ int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride,
     if (N > (int64_t)((1u << 31) - 1) / (ts::kMaxK3 + 5)) return fail(TS_ERR_UNSUPPORTED, "N too large for 32-bit pair indices");
     ts_kmap *m = new (std::nothrow) ts_kmap();
     if (!m) return fail(TS_ERR_OOM, "host allocation failed");
-    int rc = build(coords, N, kernel_size, stride, transposed, m);
+    int rc = build(coords, N, kernel_size, stride, transposed, m, wait);
     if (rc != TS_OK) {
         (void)hipStreamSynchronize(ts::stream());
         destroy(m);
@@ -1199,6 +1274,21 @@ int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride,
     return TS_OK;
 }
 
+int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
+                  ts_kmap **out_kmap) {
+    return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, true);
+}
+
+int ts_build_kmap_async(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
+                        ts_kmap **out_kmap) {
+    return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, false);
+}
+
+int ts_kmap_status(const ts_kmap *kmap) {
+    if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    return ts::resolve(kmap);
+}
+
 void ts_free(ts_kmap *kmap) { destroy(kmap); }
 
 int ts_kmap_transpose(const ts_kmap *forward, ts_kmap **out_kmap) {
@@ -1206,6 +1296,7 @@ int ts_kmap_transpose(const ts_kmap *forward, ts_kmap **out_kmap) {
     *out_kmap = nullptr;
     if (!forward) return fail(TS_ERR_INVALID_ARG, "forward is NULL");
     if (forward->s == 1 || forward->transposed) return fail(TS_ERR_INVALID_ARG, "a forward map with stride > 1 is needed");
+    TS_TRY(ts::resolve(forward));
     ts_kmap *m = new (std::nothrow) ts_kmap();
     if (!m) return fail(TS_ERR_OOM, "host allocation failed");
     int rc = transpose(forward, m);
@@ -1220,13 +1311,14 @@ int ts_kmap_transpose(const ts_kmap *forward, ts_kmap **out_kmap) {
 
 int ts_kmap_sort_rows(ts_kmap *kmap) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    TS_TRY(ts::resolve(kmap));
     if (kmap->d_perm || kmap->n_out == 0) return TS_OK;
     return sort_rows(kmap);
 }
 
 int64_t ts_kmap_num_in(const ts_kmap *kmap) { return kmap ? kmap->n_in : -1; }
 int64_t ts_kmap_num_out(const ts_kmap *kmap) { return kmap ? kmap->n_out : -1; }
-int64_t ts_kmap_num_pairs(const ts_kmap *kmap) { return kmap ? kmap->M : -1; }
+int64_t ts_kmap_num_pairs(const ts_kmap *kmap) { return kmap && ts::resolve(kmap) == TS_OK ? kmap->M : -1; }
 int ts_kmap_kernel_volume(const ts_kmap *kmap) { return kmap ? kmap->K3 : -1; }
 
 int ts_kmap_out_coords(const ts_kmap *kmap, int32_t *dst) {
@@ -1249,12 +1341,14 @@ int ts_kmap_in_coords(const ts_kmap *kmap, int32_t *dst) {
 
 int ts_kmap_sizes(const ts_kmap *kmap, int64_t *dst) {
     if (!kmap || !dst) return fail(TS_ERR_INVALID_ARG, "NULL argument");
+    TS_TRY(ts::resolve(kmap));
     for (int n = 0; n < kmap->K3; ++n) dst[n] = kmap->sizes[n];
     return TS_OK;
 }
 
 int ts_kmap_pairs(const ts_kmap *kmap, int32_t *in_idx, int32_t *out_idx) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    TS_TRY(ts::resolve(kmap));
     if (kmap->M == 0) return TS_OK;
     TS_TRY(ts::ensure_pairs(kmap));
     size_t bytes = (size_t)kmap->M * sizeof(int32_t);

@@ -33,18 +33,20 @@ class SparseNet:
         top = max(level for _, level in kinds)
         for level in range(top + 1):
             if ("down", level) in kinds or ("up", level) in kinds:
-                down = ts.ts_build_kmap(levels[level], 2, 2, False)
+                down = ts.ts_build_kmap(levels[level], 2, 2, False, wait=False)
                 maps[("down", level)] = down
                 levels[level + 1] = down.out_coords()
         for kind, level in kinds:
             if kind == "sub":
-                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 3, 1, False)
+                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 3, 1, False, wait=False)
                 if sort_rows:
                     maps[(kind, level)].sort_rows()
             elif kind == "id":
-                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 1, 1, False)
+                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 1, 1, False, wait=False)
             elif kind == "up":
                 maps[(kind, level)] = maps[("down", level)].transpose()
+        for m in maps.values():
+            m.status()      # builds did not wait one by one; bad coordinates are reported here
         return maps, levels
 
     def forward(self, maps, feats: torch.Tensor, hook=None):

@@ -382,3 +382,47 @@ def test_prepared_weights_give_the_same_result(dtype, K, s, transposed, c_in, c_
         ts.ts_sparse_conv_prepared(x, pw, other)
     assert e.value.code == ts.TS_ERR_SHAPE
     pw.free()
+
+
+@pytest.mark.parametrize("K,s,transposed", [(3, 1, False), (1, 1, False), (2, 2, False), (2, 2, True)])
+def test_async_build(K, s, transposed):
+    """ts_build_kmap_async: same map, same layer output; a layer can run before anybody asked for the sizes."""
+    coords = _rand_coords(400 + K, 6000, -12, 12, batches=2)
+    sync = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
+    x = to_dev(features(410, sync.num_in, 32, np.float16))
+    w = to_dev(conv_weights(411, K ** 3, 32, 64, np.float16))
+    want = ts.ts_sparse_conv(x, w, sync, dataflow=ts.TS_DATAFLOW_FUSED)
+    lazy = ts.ts_build_kmap(to_dev(coords), K, s, transposed, wait=False)
+    got = ts.ts_sparse_conv(x, w, lazy, dataflow=ts.TS_DATAFLOW_FUSED)     # before any accessor
+    assert torch.equal(got, want)
+    lazy.status()
+    assert lazy.num_pairs == sync.num_pairs and np.array_equal(lazy.sizes(), sync.sizes())
+    assert np.array_equal(gpu_triples(lazy), gpu_triples(sync))
+    assert torch.equal(ts.ts_sparse_conv(x, w, lazy, dataflow=ts.TS_DATAFLOW_EXPLICIT), ts.ts_sparse_conv(x, w, sync, dataflow=ts.TS_DATAFLOW_EXPLICIT))
+
+
+def test_async_build_reports_bad_input_late():
+    dup = np.concatenate([_rand_coords(5, 500, 0, 10), np.array([[0, 1, 2, 3], [0, 1, 2, 3]], np.int32)])
+    kmap = ts.ts_build_kmap(to_dev(dup), 3, 1, wait=False)          # no error yet
+    x = to_dev(features(1, dup.shape[0], 32, np.float16))
+    w = to_dev(conv_weights(2, 27, 32, 32, np.float16))
+    y = ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_FUSED)   # runs, result meaningless but finite
+    torch.cuda.synchronize()
+    assert torch.isfinite(y.float()).all()
+    with pytest.raises(ts.TsError) as e:
+        kmap.status()
+    assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
+    assert kmap.num_pairs == -1
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_sparse_conv(x, w, kmap)
+    assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
+    far = np.array([[0, 1, 2, 3], [0, ts.TS_COORD_MAX + 1, 0, 0]], dtype=np.int32)
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(far), 3, 1, wait=False).status()
+    assert e.value.code == ts.TS_ERR_COORD_RANGE
+    # many maps whose sizes nobody asks for: the status slots are recycled
+    ok = to_dev(_rand_coords(6, 300, 0, 8))
+    maps = [ts.ts_build_kmap(ok, 3, 1, wait=False) for _ in range(200)]
+    del maps
+    fresh = ts.ts_build_kmap(ok, 3, 1, wait=False)
+    assert fresh.num_pairs == ts.ts_build_kmap(ok, 3, 1).num_pairs
