@@ -111,8 +111,9 @@ int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride,
  * as its kernels are enqueued, and its sizes and the error flags of its input (duplicate or
  * out-of-range coordinates) reach the host when something first needs them: ts_kmap_status,
  * ts_kmap_num_pairs / _sizes / _pairs, the explicit dataflow, ts_kmap_sort_rows, ts_kmap_transpose.
- * The fused layer kernel needs none of them, so a build followed by ts_sparse_conv runs on the
- * device without a host round trip in between.  A map whose input was bad is safe to use (rows of
+ * For a 3x3x3 stride-1 map the part of the build that only those need (the pass that counts each
+ * offset's pairs) is put off until then as well.  The fused layer kernel needs none of it, so a
+ * build followed by ts_sparse_conv runs on the device without a host round trip in between.  A map whose input was bad is safe to use (rows of
  * bad points have no neighbours) but its results are meaningless: call ts_kmap_status before
  * trusting them.  Strided maps still wait once inside (for the number of output points).
  */

@@ -160,7 +160,7 @@ __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, con
                                                     const int32_t *__restrict__ nbr, int stride,
                                                     const int32_t *__restrict__ perm, int64_t n_out,
                                                     T *__restrict__ out, const T *__restrict__ zero_row, int cin,
-                                                    int cout, int K3) {
+                                                    int cout, int K3, int centre) {
     typedef Shape<T, NCB, KC> S;
     typedef typename S::vec vec;
     __shared__ __attribute__((aligned(16))) T lds_w[2][G][S::SLAB];
@@ -202,8 +202,13 @@ __global__ void __launch_bounds__(kThreads) k_fused(const T *__restrict__ X, con
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int idx = ch * 4 + q;
-                    if (idx < K3) lds_j[idx][col] = e[q];
-                    if (idx == K3 && k >= 0) mm = (uint32_t)e[q];
+                    // the row's offsets are read off its entries (the bitmask word of the table and
+                    // the centre entry may not have been written yet: a map's row pass runs on demand)
+                    if (idx < K3) {
+                        const int32_t j = idx == centre ? k : (k >= 0 ? e[q] : -1);
+                        lds_j[idx][col] = j;
+                        if (j >= 0) mm |= 1u << idx;
+                    }
                 }
             }
         }
@@ -312,7 +317,7 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
                                                         _Float16 *__restrict__ out, int *__restrict__ sched,
                                                         int cin, int cout, int K3, const _Float16 *__restrict__ bias,
                                                         const _Float16 *__restrict__ residual, int relu, int x_bytes,
-                                                        int w_bytes) {
+                                                        int w_bytes, int centre) {
     constexpr int KC = KSTEPS * 32, FRAGS = NCO * KSTEPS, SLAB = FRAGS * 64;   // slab in 16-byte vectors
     constexpr int WV = (SLAB + kThreads - 1) / kThreads;
     __shared__ u32x4 lds_w[2][SLAB];
@@ -335,7 +340,7 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
     // sorted by bitmask put the tiles with the most offsets last, so those are taken from the end.
     int64_t turn = blockIdx.x;
     while (turn < n_tiles) {
-    const int64_t tile = perm ? n_tiles - 1 - turn : tile_order[turn];
+    const int64_t tile = perm ? n_tiles - 1 - turn : (tile_order ? tile_order[turn] : turn);
     // ask for the next tile now; the answer is needed when this one is done
     int ticket = 0;
     if (threadIdx.x == 0) ticket = atomicAdd(&sched[xcd * 32], 1);
@@ -366,8 +371,13 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int idx = ch * 4 + q;
-                    if (idx < K3) lds_j[idx][col] = e[q];
-                    if (idx == K3 && k >= 0) mm = (uint32_t)e[q];
+                    // the row's offsets are read off its entries (the bitmask word of the table and
+                    // the centre entry may not have been written yet: a map's row pass runs on demand)
+                    if (idx < K3) {
+                        const int32_t j = idx == centre ? k : (k >= 0 ? e[q] : -1);
+                        lds_j[idx][col] = j;
+                        if (j >= 0) mm |= 1u << idx;
+                    }
                 }
             }
         }
@@ -801,7 +811,7 @@ struct FusedLaunch {
         dim3 grid((unsigned)kmap->n_tiles, out->cols / (NCB * 32));
         TS_LAUNCH("k_fused", (k_fused<T, NCB, KC, G>), grid, dim3(kThreads), static_cast<const T *>(pr.x),
                   static_cast<const T *>(pr.wt), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->n_out,
-                  static_cast<T *>(out->data), zero, pr.cin_pad, out->cols, kmap->K3);
+                  static_cast<T *>(out->data), zero, pr.cin_pad, out->cols, kmap->K3, kmap->centre);
     }
 };
 
@@ -854,10 +864,10 @@ void launch_conv_tile(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap
     const int64_t resident = (int64_t)compute_units() * per_cu;
     dim3 grid((unsigned)(kmap->n_tiles < resident ? kmap->n_tiles : resident), out->cols / (NCO * 16));
     TS_LAUNCH("k_conv_tile", (k_conv_tile<NCO, KSTEPS, kTileDepth>), grid, dim3(kThreads), x,
-              reinterpret_cast<const u32x4 *>(wf), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->d_tile_order,
+              reinterpret_cast<const u32x4 *>(wf), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->rows_done ? kmap->d_tile_order : nullptr,
               kmap->n_out, static_cast<_Float16 *>(out->data), kmap->d_sched, cin_pad, out->cols, kmap->K3,
               static_cast<const _Float16 *>(ep.bias), static_cast<const _Float16 *>(ep.residual), ep.relu,
-              (int)((size_t)kmap->n_in * cin_pad * 2), (int)((size_t)kmap->K3 * cin_pad * out->cols * 2));
+              (int)((size_t)kmap->n_in * cin_pad * 2), (int)((size_t)kmap->K3 * cin_pad * out->cols * 2), kmap->centre);
 }
 
 // fp16: input channels padded to a multiple of 32 (one MFMA step), chunks of 64 where possible.

@@ -121,6 +121,8 @@ struct ts_kmap {
     int centre = -1;            // index of the identity offset (odd K, stride 1), else -1
     int stride = 0;             // nbr_stride(K3)
     int64_t n_in = 0, n_out = 0, M = 0;   // M, sizes, offs: valid once ts::resolve has run
+    bool rows_done = true;      // false: the row pass (bitmask words, centre entries, rank bitmaps, tile order) and the
+                                // scan have not run yet; ts::resolve runs them (the fused kernel needs none of it)
     int pending_slot = -1;      // >= 0: sizes and error flags are still on their way to the host
     int error = 0;              // TS_OK, or what the build found wrong with its input
     int64_t n_blocks = 0;       // ceil(n_out / 64): 64-row blocks of the rank structure

@@ -896,6 +896,23 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status,
     else if (mode == MODE_SUB && K == 3) {
         TS_LAUNCH("k_probe_symmetric", k_probe_symmetric, dim3(blocks_for(n_out, kThreads), K3 / 2), dim3(kThreads), m->d_out_keys,
                   n_out, table, K, m->d_nbr, m->stride);
+        if (!wait) {
+            // A caller that does not wait gets the map with its search done: what the fused layer
+            // kernel reads.  The row pass and the scan (bitmask words, rank bitmaps, sizes, tile order)
+            // run when something first needs them (ts::resolve).  Error flags are known already.
+            const int slot = slot_acquire();
+            if (slot >= 0) {
+                StatusSlot &sl = g_slots[slot];
+                TS_HIP(hipMemcpyAsync(sl.host, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+                TS_HIP(hipEventRecord(sl.ev, st));
+                sl.busy = true;
+                sl.owner = m;
+                m->pending_slot = slot;
+                m->rows_done = false;
+                TS_HIP(hipGetLastError());
+                return TS_OK;
+            }
+        }
         TS_LAUNCH("k_rows", (k_rows<27, true>), dim3(blocks_for(n_out, kThreads)), dim3(kThreads), m->d_nbr, m->d_out_keys, n_out,
                   m->d_colbits, colcnt, wavemask, m->n_blocks);
     }
@@ -1213,6 +1230,30 @@ int resolve(const ts_kmap *kmap) {
         sl.busy = false;
         sl.owner = nullptr;
         m->pending_slot = -1;
+    }
+    if (!m->rows_done && m->error == TS_OK) {
+        // the part of a stride-1 build that was put off: row pass, scan, sizes
+        hipStream_t st = stream();
+        Temps tmp;
+        int *d_status;
+        int32_t *colcnt;
+        uint32_t *wavemask;
+        TS_TRY(tmp.get(&d_status, ST_WORDS));
+        TS_TRY(tmp.get(&colcnt, (size_t)m->K3 * m->n_blocks));
+        TS_TRY(tmp.get(&wavemask, (size_t)m->n_blocks));
+        FillArgs fill;
+        fill.add(d_status, ST_WORDS * sizeof(int), 0u);
+        TS_TRY(launch_fill(fill));
+        TS_LAUNCH("k_rows", (k_rows<27, true>), dim3(blocks_for(m->n_out, kThreads)), dim3(kThreads), m->d_nbr, m->d_out_keys,
+                  m->n_out, m->d_colbits, colcnt, wavemask, m->n_blocks);
+        TS_LAUNCH("k_scan", k_scan, dim3(m->K3 + 1), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status, m->K3, wavemask,
+                  m->n_tiles, m->d_tile_order);
+        int32_t *h = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
+        if (!h) return TS_ERR_OOM;
+        TS_HIP(hipMemcpyAsync(h, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        TS_HIP(hipStreamSynchronize(st));
+        take_status(m, h);
+        m->rows_done = true;
     }
     return m->error == TS_OK ? TS_OK : report(m);
 }
