@@ -186,6 +186,27 @@ def test_config3_lidar_fp16(lidar_coords, c):
     print(f"config 3 C={c} rel L2:", errs)
 
 
+def test_config3_in_the_launch_configuration_of_the_benchmark(lidar_coords):
+    """What bench.py times: the non-waiting build, weights prepared once, the fused layer at C = 64 on the
+    full ~150k-voxel scene, several steps back to back with the maps freed in between; then the
+    verdict of the builds and the whole output tensor against the oracle."""
+    c = 64
+    x_h, w_h = features(300 + c, lidar_coords.shape[0], c, np.float16), conv_weights(301 + c, 27, c, c, np.float16)
+    coords, x, w = to_dev(lidar_coords), to_dev(x_h), to_dev(w_h)
+    pw = ts.ts_weights_prepare(w)
+    out = torch.empty((lidar_coords.shape[0], c), dtype=torch.float16, device="cuda")
+    for _ in range(5):
+        kmap = ts.ts_build_kmap(coords, 3, 1, wait=False)
+        ts.ts_sparse_conv_prepared(x, pw, kmap, out=out)
+        kmap.free()
+    kmap = ts.ts_build_kmap(coords, 3, 1, wait=False)
+    ts.ts_sparse_conv_prepared(x, pw, kmap, out=out)
+    kmap.status()
+    check_features(out, oracle_conv(lidar_coords, x_h, w_h, 3, 1), torch.float16, "bench configuration")
+    _, _, tri = oracle_map(lidar_coords, 3, 1)
+    assert np.array_equal(gpu_triples(kmap), tri)
+
+
 def test_config4_down_up_pair(lidar_coords):
     """2x2x2 stride-2 conv 64->128 onto floor(coord/2), then the transposed conv 128->64 back."""
     dtype = torch.float16
