@@ -13,12 +13,18 @@ Paper passages each function follows:
 * :func:`kmap`          - map search, Sec. 2.1.2 / Alg. 1
 * :func:`conv`          - Eq. 1 evaluated per output row and per offset
 * :func:`conv_transposed` - same pair set with in/out roles swapped (not in the paper)
+* :func:`adaptive_groups` - partition of the weight indices by map size, first half of the
+  grouped matmul of Appendix B (Alg. 4)
 
 Pins (see ``tests/test_oracle_pins.py``): the paper's worked stride-2 example and
 printed offset sets, brute-force neighbour enumeration, dense 3-D convolution
 masked to the active sites, the 1x1x1 == matmul identity, full-occupancy ==
 zero-padded dense convolution, the submanifold symmetry of Sec. 4.2.1, and a
 closed-form expectation of the map sizes on uniformly sampled grids.
+:func:`adaptive_groups` is pinned by the special cases the paper names (tolerance 0 keeps only
+equal sizes together, tolerance 1 makes one group), by the invariants of the partition (contiguous,
+covering, every group within the tolerance, no group extensible) and by exhaustive comparison with
+a search over all contiguous partitions on small inputs.
 Parity status: every function above is pinned by at least one of these.
 """
 from __future__ import annotations
@@ -197,6 +203,37 @@ def rel_l2(y, y_ref) -> float:
     if den == 0.0:
         return 0.0 if num == 0.0 else float("inf")
     return num / den
+
+
+def adaptive_groups(sizes, eps: float) -> list[list[int]]:
+    """Groups of consecutive weight indices whose map sizes are close enough to be padded to a
+    common length (Appendix B, Alg. 4, first loop).
+
+    ``sizes[i]`` is the map size of weight index ``i`` (for an odd kernel at stride 1 the caller
+    passes the first floor(K^3/2) indices: each stands for itself and its mirror).  A group starts
+    at the first index not yet grouped and takes following indices as long as
+    ``1 - n_min / n_max <= eps`` over the sizes taken so far including the candidate (the share of
+    padded, i.e. wasted, rows in the longest member's terms).  The listing prints ``n_min <- 0`` and
+    never advances its outer index; read as ``n_min <- n_max <- len(M[W_i])`` and "continue after the
+    last index taken".  Two empty maps count as equal (ratio 0).
+    """
+    sizes = [int(v) for v in sizes]
+    groups, i = [], 0
+    while i < len(sizes):
+        n_min = n_max = sizes[i]
+        group = [i]
+        j = i + 1
+        while j < len(sizes):
+            lo, hi = min(n_min, sizes[j]), max(n_max, sizes[j])
+            waste = 0.0 if hi == 0 else 1.0 - lo / hi
+            if waste > eps:
+                break
+            n_min, n_max = lo, hi
+            group.append(j)
+            j += 1
+        groups.append(group)
+        i = j
+    return groups
 
 
 def sort_triples(tri: np.ndarray) -> np.ndarray:

@@ -394,3 +394,62 @@ def test_empty_input():
     assert oracle.kmap(coords, coords, 3, 1).shape == (0, 3)
     q, y = oracle.conv(coords, np.zeros((0, 4)), np.zeros((27, 4, 3)), 3, 1)
     assert y.shape == (0, 3)
+
+
+# ---- adaptive grouping (Appendix B, Alg. 4) ------------------------------------------------------------
+
+def _waste(sizes, group):
+    hi = max(sizes[i] for i in group)
+    return 0.0 if hi == 0 else 1.0 - min(sizes[i] for i in group) / hi
+
+
+def test_adaptive_groups_special_cases_named_by_the_paper():
+    """Sec. 4.2.3: tolerance 1 is dense computation (one group), tolerance 0 groups only equal sizes
+    (with mirrored offsets that is symmetric grouping: every index alone with its mirror)."""
+    sizes = [8705, 58030, 8790, 26968, 79418, 26855, 8771, 49826, 8594, 30917, 84057, 30973, 49787]
+    assert oracle.adaptive_groups(sizes, 1.0) == [list(range(13))]
+    assert oracle.adaptive_groups(sizes, 0.0) == [[i] for i in range(13)]
+    assert oracle.adaptive_groups([5, 5, 5, 7, 7, 0, 0], 0.0) == [[0, 1, 2], [3, 4], [5, 6]]
+    # a downsampling layer: all sizes similar -> one group at a small tolerance
+    assert oracle.adaptive_groups([19000, 19100, 18900, 19050, 19120, 18870, 19010, 18990], 0.02) == [list(range(8))]
+    # worked by hand: 100,90 (waste 0.1) | 60 would give 0.4 -> new group; 60,55 (0.083) | 10
+    assert oracle.adaptive_groups([100, 90, 60, 55, 10], 0.15) == [[0, 1], [2, 3], [4]]
+
+
+def test_adaptive_groups_invariants():
+    rng = np.random.Generator(np.random.PCG64(11))
+    for trial in range(300):
+        n = int(rng.integers(1, 14))
+        sizes = rng.integers(0, 50, size=n).tolist() if trial % 3 else (rng.integers(0, 4, size=n) * 10).tolist()
+        eps = float(rng.choice([0.0, 0.1, 0.25, 0.5, 0.9, 1.0]))
+        groups = oracle.adaptive_groups(sizes, eps)
+        assert [i for g in groups for i in g] == list(range(n))                    # contiguous and covering
+        for gi, g in enumerate(groups):
+            assert _waste(sizes, g) <= eps + 1e-12                                  # within the tolerance
+            if gi + 1 < len(groups):                                                # greedy: could not take the next index
+                assert _waste(sizes, g + [groups[gi + 1][0]]) > eps
+
+
+def test_adaptive_groups_equals_greedy_by_exhaustive_search():
+    """Among all contiguous partitions within the tolerance, the greedy one is the one whose groups are,
+    from left to right, as long as possible: found here by enumerating every partition of small inputs."""
+    from itertools import product
+    rng = np.random.Generator(np.random.PCG64(12))
+    for _ in range(60):
+        n = int(rng.integers(1, 9))
+        sizes = rng.integers(1, 30, size=n).tolist()
+        eps = float(rng.choice([0.0, 0.2, 0.5, 0.8]))
+        best = None
+        for cuts in product([0, 1], repeat=n - 1):
+            groups, cur = [], [0]
+            for i, c in enumerate(cuts, start=1):
+                if c:
+                    groups.append(cur)
+                    cur = []
+                cur.append(i)
+            groups.append(cur)
+            if all(_waste(sizes, g) <= eps + 1e-12 for g in groups):
+                key = tuple(len(g) for g in groups)
+                if best is None or key > best[0]:
+                    best = (key, groups)
+        assert oracle.adaptive_groups(sizes, eps) == best[1]
