@@ -211,6 +211,31 @@ def main():
 
     kmap_us = time_calls(lambda: ts.ts_build_kmap(coords, K, 1).free(), 30)
     layers = {f"C{c}": layer_report(kmap, N, M, c) for c in (32, 64, 128)}
+    # ---- grouping ablation (Sec. 4.2.3; Appendix B, Alg. 4): the matmul stage of the explicit dataflow in the
+    # launches adaptive grouping prescribes, next to the single tile-scheduled launch the library uses
+    def grouping_report(km, n_in, c):
+        xc = torch.from_numpy(features(300 + c, n_in, c, np.float16)).cuda()
+        wc = torch.from_numpy(conv_weights(301 + c, km.kernel_volume, c, c, np.float16)).cuda()
+        has_centre = km.kernel_volume == 27 and km.num_in == km.num_out
+        fc = ts.ts_gather(xc, km)
+        gc = torch.empty((km.num_pairs, c), dtype=torch.float32, device="cuda")
+        xarg = xc if has_centre else None
+        rows = {"single_launch": {"us": round(time_calls(lambda: ts.ts_grouped_matmul(fc, xarg, wc, km, gc), 30), 2),
+                                  "launches": 1, "padded_over_needed": 1.0}}
+        huge = 1 << 40
+        for tag, eps, thr in (("separate", -1.0, 0), ("symmetric_eps0", 0.0, 0), ("adaptive_eps0.1", 0.1, huge),
+                              ("adaptive_eps0.3", 0.3, huge), ("adaptive_eps0.5", 0.5, huge),
+                              ("adaptive_eps0.5_S30000", 0.5, 30000), ("dense_eps1", 1.0, huge)):
+            _, st = ts.ts_grouped_matmul_adaptive(fc, xarg, wc, km, eps, thr, gc)
+            us = time_calls(lambda: ts.ts_grouped_matmul_adaptive(fc, xarg, wc, km, eps, thr, gc), 30)
+            rows[tag] = {"us": round(us, 2), "launches": int(st["launches"]),
+                         "padded_over_needed": round(st["padded_rows"] / max(st["rows"], 1), 3)}
+        return rows
+
+    grouping = {"config3_C64_K3s1": grouping_report(kmap, N, 64)}
+    kdown = ts.ts_build_kmap(coords, 2, 2)
+    grouping["config3_C64_K2s2"] = grouping_report(kdown, N, 64)
+    kdown.free()
     # optional ordering of the output rows by offset bitmask (for maps that serve several layers)
     sort_us = time_calls(lambda: ts.ts_build_kmap(coords, K, 1).sort_rows().free(), 20) - kmap_us
     ksorted = ts.ts_build_kmap(coords, K, 1).sort_rows()
@@ -225,7 +250,8 @@ def main():
     kb = kmap_bytes(N, M, K3, table_slots)
     breakdown = {"kmap_build_us": round(kmap_us, 1), "kmap_algorithmic_bytes": int(kb),
                  "kmap_GBs": round(kb / kmap_us * 1e-3, 1), "copy_kernel_GBs": round(copy_gbs, 1),
-                 "per_kernel_us_per_step": per_kernel, "layers": layers, "sorted_rows": sorted_rows}
+                 "per_kernel_us_per_step": per_kernel, "layers": layers, "grouping_ablation": grouping,
+                 "sorted_rows": sorted_rows}
 
     # ---- config 5: MinkUNet-style forward pass on the same scene (maps built once, then the 45 convs)
     from paper_2204_10319_amd.network import SparseNet

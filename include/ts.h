@@ -226,6 +226,34 @@ int ts_grouped_matmul(const ts_tensor *F, const ts_tensor *feats, const ts_tenso
                       const ts_kmap *kmap, ts_tensor *G);
 int ts_scatter_reduce(const ts_tensor *G, const ts_kmap *kmap, ts_tensor *out);
 
+/*
+ * Adaptive grouping (Sec. 4.2.3; Appendix B, Alg. 4), kept for comparison with the single
+ * tile-scheduled launch of ts_grouped_matmul, which needs neither padding nor tuning.
+ *
+ * ts_adaptive_groups: host arithmetic only (no GPU call).  sizes[count] (host, count <= 27, all >= 0)
+ *   are the map sizes of consecutive weight indices; group_of[count] (host, written) receives the
+ *   number of the group each index falls in, *num_groups the number of groups.  A group starts at the
+ *   first index not yet grouped and takes the following ones while 1 - n_min / n_max <= epsilon over
+ *   its sizes (the share of padding a batched matmul of the group would carry; two empty maps count as
+ *   equal).  epsilon in [0, 1]: 0 groups equal sizes only, 1 makes one group.
+ *
+ * ts_grouped_matmul_adaptive: the same result as ts_grouped_matmul (bit for bit), computed in the
+ *   launches Alg. 4 prescribes.  For an odd-K stride-1 map the groups are formed over the first
+ *   floor(K^3/2) indices, index i always shares its launch with its mirror K^3-1-i (equal sizes:
+ *   symmetric grouping), and the centre offset is a launch of its own; otherwise over all K^3 indices.
+ *   A group whose longest map has fewer than S rows is one batched launch with every member padded to
+ *   that length (the padding rows are multiplied and thrown away: the redundant computation the
+ *   tolerance buys regularity with); any other group is one launch per member.  epsilon < 0 disables
+ *   grouping altogether: one launch per non-empty offset (the separate baseline of Sec. 4.2.3).
+ *   stats (host, 4 values, may be NULL) receives: launches made, groups formed, rows multiplied
+ *   including padding, rows needed (num_pairs).
+ */
+int ts_adaptive_groups(const int64_t *sizes, int32_t count, double epsilon, int32_t *group_of,
+                       int32_t *num_groups);
+int ts_grouped_matmul_adaptive(const ts_tensor *F, const ts_tensor *feats, const ts_tensor *weights,
+                               const ts_kmap *kmap, double epsilon, int64_t S, ts_tensor *G,
+                               int64_t *stats);
+
 /* ---- elementwise steps between layers (not in the paper; needed to chain layers into a network) ---- */
 
 /*

@@ -28,7 +28,7 @@ EXPORTS = [
     "ts_build_kmap", "ts_build_kmap_async", "ts_kmap_status", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
-    "ts_sparse_conv_prepared", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce",
+    "ts_sparse_conv_prepared", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
     "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_bias_act", "ts_concat_cols",
 ]
 
@@ -90,6 +90,12 @@ def load_library(path: str | None = None):
     lib.ts_gather.argtypes = [tp, vp, tp]
     lib.ts_grouped_matmul.argtypes = [tp, tp, tp, vp, tp]
     lib.ts_scatter_reduce.argtypes = [tp, vp, tp]
+    lib.ts_adaptive_groups.argtypes = [ctypes.POINTER(ctypes.c_int64), ctypes.c_int32, ctypes.c_double,
+                                       ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+    lib.ts_adaptive_groups.restype = ci
+    lib.ts_grouped_matmul_adaptive.argtypes = [tp, tp, tp, vp, ctypes.c_double, ctypes.c_int64, tp,
+                                               ctypes.POINTER(ctypes.c_int64)]
+    lib.ts_grouped_matmul_adaptive.restype = ci
     lib.ts_set_stream.argtypes = [vp]
     lib.ts_release_cache.argtypes = []
     for name in ("ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs", "ts_sparse_conv",
@@ -429,6 +435,31 @@ def ts_grouped_matmul(F: torch.Tensor, feats: torch.Tensor | None, weights: torc
     x = ctypes.byref(_as_ts(feats)) if feats is not None else None
     _check(load_library().ts_grouped_matmul(ctypes.byref(a), x, ctypes.byref(w), kmap.handle, ctypes.byref(g)))
     return G
+
+
+def ts_adaptive_groups(sizes, epsilon: float) -> list[int]:
+    """Group number of every weight index (Appendix B, Alg. 4, first loop); host arithmetic only."""
+    sizes = [int(v) for v in sizes]
+    n = len(sizes)
+    arr = (ctypes.c_int64 * max(n, 1))(*sizes)
+    group_of = (ctypes.c_int32 * max(n, 1))()
+    groups = ctypes.c_int32(0)
+    _check(load_library().ts_adaptive_groups(arr, n, float(epsilon), group_of, ctypes.byref(groups)))
+    return list(group_of[:n])
+
+
+def ts_grouped_matmul_adaptive(F: torch.Tensor, feats: torch.Tensor | None, weights: torch.Tensor, kmap: KMap,
+                               epsilon: float, S: int, G: torch.Tensor | None = None):
+    """Returns (G, stats) with stats = dict(launches, groups, padded_rows, rows)."""
+    _use_current_stream()
+    if G is None:
+        G = torch.empty((kmap.num_pairs, weights.shape[2]), dtype=torch.float32, device=F.device)
+    a, w, g = _as_ts(F), _weights_ts(weights), _as_ts(G)
+    x = ctypes.byref(_as_ts(feats)) if feats is not None else None
+    stats = (ctypes.c_int64 * 4)()
+    _check(load_library().ts_grouped_matmul_adaptive(ctypes.byref(a), x, ctypes.byref(w), kmap.handle,
+                                                     float(epsilon), int(S), ctypes.byref(g), stats))
+    return G, dict(launches=stats[0], groups=stats[1], padded_rows=stats[2], rows=stats[3])
 
 
 def ts_scatter_reduce(G: torch.Tensor, kmap: KMap, out: torch.Tensor | None = None,

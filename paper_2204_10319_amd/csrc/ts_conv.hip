@@ -573,26 +573,34 @@ __global__ void __launch_bounds__(kThreads) k_gather(const u32x4 *__restrict__ X
         if (at[u] >= 0) __builtin_nontemporal_store(v[u], &F[at[u]]);
 }
 
-// Grouped matmul: block -> (offset n, 128-row block) by walking the per-offset tile counts.
+// One launch of the grouped matmul: the offsets it covers and how many 128-row blocks each gets.
+// An offset given more blocks than its list fills stands for a list padded to a longer one
+// (the batched matmul of Appendix B, Alg. 4): the surplus blocks multiply zero rows and store nothing.
+struct MmPlan {
+    int32_t count;
+    int32_t n[kMaxK3];
+    int32_t tiles[kMaxK3];
+};
+
+// Grouped matmul: block -> (offset n, 128-row block) by walking the plan's block counts.
 // Rows of the centre offset of an identity map come from X itself.  Rows past the end of an
 // offset's list read `zero_row` and are not stored.
 template <class T, int NCB, int KC>
 __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F, const T *__restrict__ X,
-                                                         const T *__restrict__ Wt, Offs offs,
+                                                         const T *__restrict__ Wt, Offs offs, MmPlan plan,
                                                          float *__restrict__ G, const T *__restrict__ zero_row,
-                                                         int cin, int cout, int K3, int centre) {
+                                                         int cin, int cout, int centre) {
     typedef Shape<T, NCB, KC> S;
     typedef typename S::vec vec;
     __shared__ __attribute__((aligned(16))) T lds_w[S::SLAB];
-    int t = blockIdx.x, n = 0, lo = 0, hi = 0;
-    for (; n < K3; ++n) {
-        lo = offs.v[n];
-        hi = offs.v[n + 1];
-        int tiles = (hi - lo + kTileRows - 1) / kTileRows;
-        if (t < tiles) break;
-        t -= tiles;
+    int t = blockIdx.x, i = 0;
+    for (; i < plan.count; ++i) {
+        if (t < plan.tiles[i]) break;
+        t -= plan.tiles[i];
     }
-    if (n >= K3) return;
+    if (i >= plan.count) return;
+    const int n = plan.n[i];
+    const int lo = offs.v[n], hi = offs.v[n + 1];
     const int co0 = blockIdx.y * NCB * 32;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
     const int64_t p = (int64_t)lo + (int64_t)t * kTileRows + wave * kWaveRows + m;   // row of F and G
@@ -925,9 +933,23 @@ int run_fused(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *k
     return run_fused_staged<T>(feats, weights, kmap, out, pw);
 }
 
-int64_t total_mm_tiles(const ts_kmap *kmap) {
+int64_t mm_tiles(int64_t rows) { return (rows + kTileRows - 1) / kTileRows; }
+
+// Every offset with the blocks its own list needs: no padding, one launch.
+MmPlan whole_plan(const ts_kmap *kmap) {
+    MmPlan plan;
+    plan.count = 0;
+    for (int n = 0; n < kmap->K3; ++n) {
+        if (kmap->sizes[n] == 0) continue;
+        plan.n[plan.count] = n;
+        plan.tiles[plan.count++] = (int32_t)mm_tiles(kmap->sizes[n]);
+    }
+    return plan;
+}
+
+int64_t plan_tiles(const MmPlan &plan) {
     int64_t t = 0;
-    for (int n = 0; n < kmap->K3; ++n) t += (kmap->sizes[n] + kTileRows - 1) / kTileRows;
+    for (int i = 0; i < plan.count; ++i) t += plan.tiles[i];
     return t;
 }
 
@@ -935,15 +957,16 @@ template <class T>
 struct GroupedLaunch {
     const T *F, *X, *wt;
     const ts_kmap *kmap;
+    MmPlan plan;
     float *G;
     const T *zero;
     int cin_pad, cout;
     template <int NCB, int KSTEPS>
     void operator()() const {
         constexpr int KC = KSTEPS * Elem<T>::KSTEP;
-        dim3 grid((unsigned)total_mm_tiles(kmap), cout / (NCB * 32));
-        TS_LAUNCH("k_grouped_mm", (k_grouped_mm<T, NCB, KC>), grid, dim3(kThreads), F, X, wt, offs_of(kmap), G, zero,
-                  cin_pad, cout, kmap->K3, kmap->centre);
+        dim3 grid((unsigned)plan_tiles(plan), cout / (NCB * 32));
+        TS_LAUNCH("k_grouped_mm", (k_grouped_mm<T, NCB, KC>), grid, dim3(kThreads), F, X, wt, offs_of(kmap), plan, G, zero,
+                  cin_pad, cout, kmap->centre);
     }
 };
 
@@ -962,15 +985,104 @@ int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const t
 }
 
 template <class T>
-int grouped_mm_impl(const void *F, const void *X, const void *wt, const ts_kmap *kmap, float *G, int cin_pad,
-                    int cout) {
-    if (kmap->M == 0) return TS_OK;
+int grouped_mm_launch(const void *F, const void *X, const void *wt, const ts_kmap *kmap, const MmPlan &plan, float *G,
+                      int cin_pad, int cout) {
+    if (plan_tiles(plan) == 0) return TS_OK;
     const T *zero = static_cast<const T *>(zero_row());
     if (!zero) return TS_ERR_OOM;
     dispatch_shape(pick_ncb(cout), pick_ksteps(cin_pad, Elem<T>::KSTEP),
                    GroupedLaunch<T>{static_cast<const T *>(F), static_cast<const T *>(X), static_cast<const T *>(wt),
-                                    kmap, G, zero, cin_pad, cout});
+                                    kmap, plan, G, zero, cin_pad, cout});
     TS_HIP(hipGetLastError());
+    return TS_OK;
+}
+
+template <class T>
+int grouped_mm_impl(const void *F, const void *X, const void *wt, const ts_kmap *kmap, float *G, int cin_pad,
+                    int cout) {
+    return grouped_mm_launch<T>(F, X, wt, kmap, whole_plan(kmap), G, cin_pad, cout);
+}
+
+// Consecutive indices are grouped while the padded share of the group, 1 - n_min / n_max, stays within
+// epsilon (Appendix B, Alg. 4, first loop).  group_of[i] = number of the group index i falls in.
+int partition_by_size(const int64_t *sizes, int count, double epsilon, int32_t *group_of) {
+    int groups = 0;
+    for (int first = 0; first < count;) {
+        int64_t lo = sizes[first], hi = sizes[first];
+        int next = first + 1;
+        for (; next < count; ++next) {
+            const int64_t l = sizes[next] < lo ? sizes[next] : lo, h = sizes[next] > hi ? sizes[next] : hi;
+            const double padded = h == 0 ? 0.0 : 1.0 - (double)l / (double)h;
+            if (padded > epsilon) break;
+            lo = l;
+            hi = h;
+        }
+        for (int i = first; i < next; ++i) group_of[i] = groups;
+        ++groups;
+        first = next;
+    }
+    return groups;
+}
+
+// The grouped matmul the way Appendix B, Alg. 4 schedules it: per group one batched launch with every
+// member padded to the longest when that length is below S, else one launch per member.  With an odd
+// kernel at stride 1 index i and its mirror K^3-1-i have maps of one size and always share a launch
+// (symmetric grouping, Sec. 4.2.3), the groups are formed over the first half of the indices, and the
+// centre is a launch of its own.  epsilon < 0: no grouping at all, one launch per offset.
+template <class T>
+int grouped_mm_adaptive(const void *F, const void *X, const void *wt, const ts_kmap *kmap, float *G, int cin_pad, int cout,
+                        double epsilon, int64_t S, int64_t *stats) {
+    const int K3 = kmap->K3;
+    const bool mirrored = kmap->centre >= 0 && epsilon >= 0;
+    const int count = mirrored ? K3 / 2 : K3;
+    int32_t group_of[kMaxK3];
+    int groups;
+    if (epsilon < 0) {
+        for (int i = 0; i < count; ++i) group_of[i] = i;
+        groups = count;
+    } else {
+        groups = partition_by_size(kmap->sizes, count, epsilon, group_of);
+    }
+    int64_t launches = 0, padded_rows = 0;
+    auto launch = [&](const MmPlan &plan) -> int {
+        if (plan_tiles(plan) == 0) return TS_OK;
+        ++launches;
+        return grouped_mm_launch<T>(F, X, wt, kmap, plan, G, cin_pad, cout);
+    };
+    auto add = [&](MmPlan &plan, int n, int64_t rows) {
+        plan.n[plan.count] = n;
+        plan.tiles[plan.count++] = (int32_t)mm_tiles(rows);
+        padded_rows += rows;
+    };
+    for (int g = 0, first = 0; g < groups; ++g) {
+        int next = first;
+        int64_t n_max = 0;
+        for (; next < count && group_of[next] == g; ++next) n_max = kmap->sizes[next] > n_max ? kmap->sizes[next] : n_max;
+        const bool batched = n_max < S;
+        MmPlan plan;
+        plan.count = 0;
+        for (int i = first; i < next; ++i) {
+            if (!batched) plan.count = 0;
+            const int64_t rows = batched ? n_max : kmap->sizes[i];
+            add(plan, i, rows);
+            if (mirrored) add(plan, K3 - 1 - i, rows);
+            if (!batched) TS_TRY(launch(plan));
+        }
+        if (batched) TS_TRY(launch(plan));
+        first = next;
+    }
+    if (mirrored) {
+        MmPlan plan;
+        plan.count = 0;
+        add(plan, kmap->centre, kmap->sizes[kmap->centre]);
+        TS_TRY(launch(plan));
+    }
+    if (stats) {
+        stats[0] = launches;
+        stats[1] = groups;
+        stats[2] = padded_rows;
+        stats[3] = kmap->M;
+    }
     return TS_OK;
 }
 
@@ -1143,8 +1255,18 @@ int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F) {
     return gather_impl(feats->data, feats->rows, feats->cols, feats->dtype, kmap, F->data);
 }
 
-int ts_grouped_matmul(const ts_tensor *F, const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
-                      ts_tensor *G) {
+int ts_adaptive_groups(const int64_t *sizes, int32_t count, double epsilon, int32_t *group_of, int32_t *num_groups) {
+    if (!sizes || !group_of || !num_groups) return fail(TS_ERR_INVALID_ARG, "sizes, group_of and num_groups must not be NULL");
+    if (count < 0 || count > kMaxK3) return fail(TS_ERR_INVALID_ARG, "count must be in [0, %d]", kMaxK3);
+    if (!(epsilon >= 0.0 && epsilon <= 1.0)) return fail(TS_ERR_INVALID_ARG, "epsilon must be in [0, 1]");
+    for (int i = 0; i < count; ++i)
+        if (sizes[i] < 0) return fail(TS_ERR_INVALID_ARG, "sizes[%d] is negative", i);
+    *num_groups = partition_by_size(sizes, count, epsilon, group_of);
+    return TS_OK;
+}
+
+static int grouped_matmul_checked(const ts_tensor *F, const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
+                                  ts_tensor *G, bool adaptive, double epsilon, int64_t S, int64_t *stats) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
     TS_TRY(resolve(kmap));
     TS_TRY(check_tensor(F, "F"));
@@ -1164,12 +1286,28 @@ int ts_grouped_matmul(const ts_tensor *F, const ts_tensor *feats, const ts_tenso
     // weights only: the rows of F are already in the operand layout
     ts_tensor none = {nullptr, 0, F->cols, F->dtype};
     Prepared pr;
+    const void *X = feats ? feats->data : nullptr;
+    float *g = static_cast<float *>(G->data);
     if (F->dtype == TS_F16) {
         TS_TRY(prepare<_Float16>(&none, weights, kmap, &pr));
-        return grouped_mm_impl<_Float16>(F->data, feats ? feats->data : nullptr, pr.wt, kmap, static_cast<float *>(G->data), F->cols, G->cols);
+        return adaptive ? grouped_mm_adaptive<_Float16>(F->data, X, pr.wt, kmap, g, F->cols, G->cols, epsilon, S, stats)
+                        : grouped_mm_impl<_Float16>(F->data, X, pr.wt, kmap, g, F->cols, G->cols);
     }
     TS_TRY(prepare<float>(&none, weights, kmap, &pr));
-    return grouped_mm_impl<float>(F->data, feats ? feats->data : nullptr, pr.wt, kmap, static_cast<float *>(G->data), F->cols, G->cols);
+    return adaptive ? grouped_mm_adaptive<float>(F->data, X, pr.wt, kmap, g, F->cols, G->cols, epsilon, S, stats)
+                    : grouped_mm_impl<float>(F->data, X, pr.wt, kmap, g, F->cols, G->cols);
+}
+
+int ts_grouped_matmul(const ts_tensor *F, const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
+                      ts_tensor *G) {
+    return grouped_matmul_checked(F, feats, weights, kmap, G, false, 0.0, 0, nullptr);
+}
+
+int ts_grouped_matmul_adaptive(const ts_tensor *F, const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
+                               double epsilon, int64_t S, ts_tensor *G, int64_t *stats) {
+    if (!(epsilon <= 1.0)) return fail(TS_ERR_INVALID_ARG, "epsilon must be at most 1 (negative: no grouping)");
+    if (S < 0) return fail(TS_ERR_INVALID_ARG, "S must not be negative");
+    return grouped_matmul_checked(F, feats, weights, kmap, G, true, epsilon, S, stats);
 }
 
 int ts_scatter_reduce(const ts_tensor *G, const ts_kmap *kmap, ts_tensor *out) {

@@ -43,3 +43,26 @@ def test_bench_refuses_more_than_one_gpu():
                          timeout=120)
     assert res.returncode != 0
     assert "one GPU" in res.stderr
+
+
+def test_adaptive_groups_host_function_equals_the_oracle():
+    """ts_adaptive_groups is host arithmetic (Appendix B, Alg. 4, first loop): same partition as the oracle's."""
+    import numpy as np
+    import pytest
+    import oracle
+    rng = np.random.Generator(np.random.PCG64(21))
+    cases = [([], 0.3), ([0], 0.0), ([0, 0, 5], 0.0), ([100, 90, 60, 55, 10], 0.15)]
+    for trial in range(400):
+        n = int(rng.integers(1, 28))
+        sizes = (rng.integers(0, 5, size=n) * 7).tolist() if trial % 4 == 0 else rng.integers(0, 100000, size=n).tolist()
+        cases.append((sizes, float(rng.choice([0.0, 0.05, 0.2, 0.5, 0.75, 1.0]))))
+    for sizes, eps in cases:
+        expect = [0] * len(sizes)
+        for g, members in enumerate(oracle.adaptive_groups(sizes, eps)):
+            for i in members:
+                expect[i] = g
+        assert binding.ts_adaptive_groups(sizes, eps) == expect, (sizes, eps)
+    for bad in (([1, 2], -0.1), ([1, 2], 1.5), ([1, -2], 0.5), (list(range(28)), 0.5)):
+        with pytest.raises(binding.TsError) as e:
+            binding.ts_adaptive_groups(*bad)
+        assert e.value.code == binding.TS_ERR_INVALID_ARG

@@ -252,6 +252,47 @@ def test_stages_of_alg2(lidar_coords):
     check_features(y, oracle_conv(coords, x, w, 3, 1), torch.float16, "staged")
 
 
+def _expected_launches(sizes, centre, eps, S):
+    """Launch count of Appendix B, Alg. 4 from the oracle's partition (empty launches are not made)."""
+    K3 = len(sizes)
+    if eps < 0:
+        return int(np.count_nonzero(sizes))
+    idx = list(range(K3 // 2)) if centre >= 0 else list(range(K3))
+    launches = 0
+    for members in oracle.adaptive_groups([sizes[i] for i in idx], eps):
+        n_max = max(sizes[i] for i in members)
+        if n_max == 0:
+            continue
+        launches += 1 if n_max < S else sum(1 for i in members if sizes[i] > 0)
+    return launches + (1 if centre >= 0 and sizes[centre] > 0 else 0)
+
+
+@pytest.mark.parametrize("K,s", [(3, 1), (2, 2), (3, 2)])
+def test_adaptive_grouping_same_result_in_the_launches_of_alg4(K, s):
+    """Sec. 4.2.3 / Appendix B, Alg. 4: whatever the tolerance and the threshold, the partial sums are those of
+    the single launch, bit for bit; the launches made and the padded rows follow the oracle's partition."""
+    coords = lidar_scan_coords(31, n_beams=32, n_azimuth=1024)
+    kmap = ts.ts_build_kmap(to_dev(coords), K, s)
+    sizes = kmap.sizes()
+    centre = 13 if (K, s) == (3, 1) else -1
+    x = to_dev(features(520, coords.shape[0], 32, np.float16))
+    w = to_dev(conv_weights(521, K ** 3, 32, 64, np.float16))
+    F = ts.ts_gather(x, kmap)
+    G = ts.ts_grouped_matmul(F, x if centre >= 0 else None, w, kmap)
+    for eps, S in [(-1.0, 0), (0.0, 0), (0.0, 1 << 40), (0.3, 1 << 40), (0.5, int(np.median(sizes))), (1.0, 1 << 40), (1.0, 0)]:
+        G2 = torch.full_like(G, float("nan"))
+        G2, stats = ts.ts_grouped_matmul_adaptive(F, x if centre >= 0 else None, w, kmap, eps, S, G2)
+        assert torch.equal(G, G2), (eps, S)
+        assert stats["rows"] == kmap.num_pairs
+        assert stats["launches"] == _expected_launches(sizes, centre, eps, S), (eps, S, stats)
+        assert stats["padded_rows"] >= kmap.num_pairs
+        if eps <= 0 or S == 0:
+            assert stats["padded_rows"] == kmap.num_pairs            # equal sizes or no batching: nothing padded
+    if centre >= 0:
+        _, stats = ts.ts_grouped_matmul_adaptive(F, x, w, kmap, 1.0, 1 << 40)
+        assert stats["launches"] == 2 and stats["padded_rows"] == 26 * int(sizes[:13].max()) + int(sizes[13])
+
+
 def test_results_are_deterministic(lidar_coords):
     kmap_a = ts.ts_build_kmap(to_dev(lidar_coords), 3, 1)
     kmap_b = ts.ts_build_kmap(to_dev(lidar_coords), 3, 1)
