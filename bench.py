@@ -230,6 +230,10 @@ def main():
             us = time_calls(lambda: ts.ts_grouped_matmul_adaptive(fc, xarg, wc, km, eps, thr, gc), 30)
             rows[tag] = {"us": round(us, 2), "launches": int(st["launches"]),
                          "padded_over_needed": round(st["padded_rows"] / max(st["rows"], 1), 3)}
+        from paper_2204_10319_amd import tuner
+        eps, thr, us, _ = tuner.adaptive_group_search([(fc, xarg, wc, km, gc)])
+        rows["tuned_alg5"] = {"us": round(us, 2), "epsilon": eps, "S": int(thr),
+                              "search_space": len(tuner.DEFAULT_EPS_SPACE) * len(tuner.DEFAULT_S_SPACE)}
         return rows
 
     grouping = {"config3_C64_K3s1": grouping_report(kmap, N, 64)}

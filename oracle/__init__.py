@@ -15,6 +15,7 @@ Paper passages each function follows:
 * :func:`conv_transposed` - same pair set with in/out roles swapped (not in the paper)
 * :func:`adaptive_groups` - partition of the weight indices by map size, first half of the
   grouped matmul of Appendix B (Alg. 4)
+* :func:`adaptive_group_search` - exhaustive choice of the tolerance and threshold (Appendix B, Alg. 5)
 
 Pins (see ``tests/test_oracle_pins.py``): the paper's worked stride-2 example and
 printed offset sets, brute-force neighbour enumeration, dense 3-D convolution
@@ -24,7 +25,8 @@ closed-form expectation of the map sizes on uniformly sampled grids.
 :func:`adaptive_groups` is pinned by the special cases the paper names (tolerance 0 keeps only
 equal sizes together, tolerance 1 makes one group), by the invariants of the partition (contiguous,
 covering, every group within the tolerance, no group extensible) and by exhaustive comparison with
-a search over all contiguous partitions on small inputs.
+a search over all contiguous partitions on small inputs.  :func:`adaptive_group_search` is pinned by
+numpy's argmin over a table of costs, ties included.
 Parity status: every function above is pinned by at least one of these.
 """
 from __future__ import annotations
@@ -60,7 +62,7 @@ def _load():
     ci = ctypes.c_int
     lib.orc_offset.argtypes = [ci, ci, i32p]
     lib.orc_offset.restype = None
-    lib.orc_out_coords.argtypes = [i32p, i64, ci, ci, i32p, i64]
+    lib.orc_out_coords.argtypes = [i32p, i64, ci, ci, i32p, i32p, i64]
     lib.orc_out_coords.restype = i64
     lib.orc_kmap.argtypes = [i32p, i64, i32p, i64, ci, ci, i32p, i64]
     lib.orc_kmap.restype = i64
@@ -107,17 +109,24 @@ def offsets(K: int) -> np.ndarray:
     return out
 
 
-def out_coords(coords, K: int, s: int) -> np.ndarray:
-    """Output coordinates of a (K, s) convolution (Alg. 3); sorted when ``s > 1``."""
+def out_coords(coords, K: int, s: int, boundary=None) -> np.ndarray:
+    """Output coordinates of a (K, s) convolution (Alg. 3); sorted when ``s > 1``.
+
+    ``boundary`` = (bx, by, bz): candidates outside ``0 <= u < s*b`` are dropped (Alg. 3's boundary
+    check; ignored at stride 1, where the outputs are the inputs)."""
     lib = _load()
     c = _check_coords(coords)
     c, cp = _i32(c)
-    n_out = lib.orc_out_coords(cp, c.shape[0], K, s, None, 0)
+    bp = None
+    if boundary is not None:
+        b = np.ascontiguousarray(np.asarray(boundary, dtype=np.int32).reshape(3))
+        bp = b.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    n_out = lib.orc_out_coords(cp, c.shape[0], K, s, bp, None, 0)
     if n_out < 0:
         raise MemoryError("oracle: allocation failed")
     out = np.zeros((n_out, 4), dtype=np.int32)
     out, op = _i32(out)
-    lib.orc_out_coords(cp, c.shape[0], K, s, op, n_out)
+    lib.orc_out_coords(cp, c.shape[0], K, s, bp, op, n_out)
     return out
 
 
@@ -234,6 +243,23 @@ def adaptive_groups(sizes, eps: float) -> list[list[int]]:
         groups.append(group)
         i = j
     return groups
+
+
+def adaptive_group_search(samples, eps_space, S_space, cost):
+    """Pick the (tolerance, threshold) pair with the smallest cost summed over the samples
+    (Appendix B, Alg. 5).  ``cost(sample, eps, S)`` stands for the elapsed time of the grouped matmul;
+    pairs are tried with the tolerance in the outer loop and the first pair reaching the minimum is kept
+    (the listing's ``c_min = 0`` only marks "nothing chosen yet").  Returns ``(eps, S, total_cost)``.
+    """
+    best = None
+    for eps in eps_space:
+        for S in S_space:
+            c = 0.0
+            for sample in samples:
+                c = c + cost(sample, eps, S)
+            if best is None or c < best[2]:
+                best = (eps, S, c)
+    return best
 
 
 def sort_triples(tri: np.ndarray) -> np.ndarray:

@@ -24,7 +24,9 @@
  *     K=3 (as printed in Sec. 2), {0,1}^3 for K=2 (even K is not defined in
  *     the paper).
  *   - weight index n = ((dx+r)*K + (dy+r))*K + (dz+r), x slowest.
- *   - Alg. 3's boundary check is not applied (no boundary is given).
+ *   - Alg. 3's boundary check: with a boundary b (three positive ints) a candidate u is kept
+ *     when 0 <= u < s*b on every axis, i.e. outputs live on the grid [0, b) (the listing prints
+ *     the upper test only; its coordinates are never negative).  Without b nothing is cut.
  *   - Unique() returns the outputs in ascending lexicographic (b,x,y,z) order.
  *   - transposed convolution (not in the paper): same pair set as the forward
  *     strided convolution between the fine and the coarse set, roles swapped:
@@ -99,7 +101,8 @@ void orc_offset(int K, int n, int32_t d[3]) {
  * Writes at most cap rows to out (out may be NULL when cap == 0) and returns
  * the number of outputs, or -1 on allocation failure.
  */
-int64_t orc_out_coords(const int32_t *in, int64_t n_in, int K, int s, int32_t *out, int64_t cap) {
+int64_t orc_out_coords(const int32_t *in, int64_t n_in, int K, int s, const int32_t *boundary, int32_t *out,
+                       int64_t cap) {
     if (s == 1) {
         int64_t w = n_in < cap ? n_in : cap;
         if (w > 0) memcpy(out, in, (size_t)w * 4 * sizeof(int32_t));
@@ -118,6 +121,7 @@ int64_t orc_out_coords(const int32_t *in, int64_t n_in, int K, int s, int32_t *o
             for (int a = 0; a < 3; ++a) {
                 u[a] = p[1 + a] - d[a];
                 if (u[a] % s != 0) ok = 0;
+                if (boundary && (u[a] < 0 || (int64_t)u[a] >= (int64_t)s * boundary[a])) ok = 0;
             }
             if (!ok) continue;
             cand[nc].c[0] = p[0];

@@ -66,3 +66,19 @@ def test_adaptive_groups_host_function_equals_the_oracle():
         with pytest.raises(binding.TsError) as e:
             binding.ts_adaptive_groups(*bad)
         assert e.value.code == binding.TS_ERR_INVALID_ARG
+
+
+def test_tuner_picks_what_the_oracle_picks():
+    """The product's search (Appendix B, Alg. 5) with a host cost function against the oracle's."""
+    import numpy as np
+    import oracle
+    from paper_2204_10319_amd import tuner
+    rng = np.random.Generator(np.random.PCG64(22))
+    for trial in range(30):
+        eps_space, S_space = list(tuner.DEFAULT_EPS_SPACE[: int(rng.integers(1, 9))]), list(tuner.DEFAULT_S_SPACE[: int(rng.integers(1, 5))])
+        nd = int(rng.integers(1, 4))
+        costs = {(d, e, S): float(rng.integers(1, 5 if trial % 2 else 10 ** 6)) for d in range(nd) for e in eps_space for S in S_space}
+        f = lambda d, e, S: costs[(d, e, S)]
+        eps, S, c, table = tuner.adaptive_group_search(range(nd), eps_space, S_space, f)
+        assert (eps, S, c) == oracle.adaptive_group_search(range(nd), eps_space, S_space, f)
+        assert len(table) == len(eps_space) * len(S_space)

@@ -137,6 +137,33 @@ def test_out_coords_brute_force_with_negative_coords(K, s):
     assert got == _brute_out_coords(coords, K, s)
 
 
+@pytest.mark.parametrize("K,s", [(2, 2), (3, 2), (3, 3), (5, 2)])
+def test_out_coords_boundary(K, s):
+    """Alg. 3's boundary check, three ways: the unbounded result cut to the grid [0, b) afterwards (u < s*b
+    with s | u is q < b), a brute-force enumeration that tests u itself, and a boundary too large to cut."""
+    coords = _random_coords(31 + K + s, 80, -4, 9, batches=2)
+    b = (3, 4, 2)
+    free = oracle.out_coords(coords, K, s)
+    got = oracle.out_coords(coords, K, s, boundary=b)
+    keep = np.all((free[:, 1:] >= 0) & (free[:, 1:] < np.array(b)), axis=1)
+    assert 0 < keep.sum() < free.shape[0]
+    assert np.array_equal(got, free[keep])
+    r = (K - 1) // 2
+    brute = set()
+    for bb, x, y, z in coords.tolist():
+        for dx in range(-r, K - r):
+            for dy in range(-r, K - r):
+                for dz in range(-r, K - r):
+                    u = (x - dx, y - dy, z - dz)
+                    if all(v % s == 0 and 0 <= v < s * lim for v, lim in zip(u, b)):
+                        brute.add((bb, u[0] // s, u[1] // s, u[2] // s))
+    assert [tuple(row) for row in got.tolist()] == sorted(brute)
+    if K <= 3:      # radius 1: from non-negative inputs no candidate below zero passes the modular check
+        nonneg = coords[np.all(coords[:, 1:] >= 0, axis=1)]
+        assert np.array_equal(oracle.out_coords(nonneg, K, s, boundary=(100, 100, 100)), oracle.out_coords(nonneg, K, s))
+    assert np.array_equal(oracle.out_coords(coords, 3, 1, boundary=b), coords)      # stride 1: outputs are the inputs
+
+
 def test_out_coords_k2s2_closed_form():
     """K=2,s=2: every input has exactly one admissible offset (p mod 2) and its output is floor(p/2)."""
     coords = _random_coords(5, 500, -20, 20, batches=3)
@@ -453,3 +480,17 @@ def test_adaptive_groups_equals_greedy_by_exhaustive_search():
                 if best is None or key > best[0]:
                     best = (key, groups)
         assert oracle.adaptive_groups(sizes, eps) == best[1]
+
+
+def test_adaptive_group_search_is_the_argmin_of_the_summed_cost():
+    """Appendix B, Alg. 5 against numpy's argmin over the table of summed costs (first minimum in search order)."""
+    rng = np.random.Generator(np.random.PCG64(13))
+    for trial in range(50):
+        ne, ns, nd = int(rng.integers(1, 6)), int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        costs = rng.integers(1, 6 if trial % 2 else 1000, size=(nd, ne, ns)).astype(float)     # small range: ties
+        eps_space, S_space = [0.1 * i for i in range(ne)], [1000 * i for i in range(ns)]
+        got = oracle.adaptive_group_search(range(nd), eps_space, S_space,
+                                           lambda d, e, S: costs[d, eps_space.index(e), S_space.index(S)])
+        total = costs.sum(axis=0)
+        ie, js = np.unravel_index(np.argmin(total), total.shape)
+        assert got == (eps_space[ie], S_space[js], total[ie, js])
