@@ -123,6 +123,38 @@ int ts_build_kmap_async(const int32_t *coords, int64_t N, int kernel_size, int s
 int ts_kmap_status(const ts_kmap *kmap);
 
 /*
+ * ts_build_kmap with the choices the paper leaves to each layer (Sec. 4.4; Alg. 3).  options == NULL
+ * is ts_build_kmap.  The map built is the same whatever `search` says.
+ *   search        TS_SEARCH_HASH: the open-addressing table.  TS_SEARCH_GRID: the collision-free
+ *                 grid of Sec. 4.4, one int32 cell per coordinate of the box the caller states
+ *                 with grid_lo / grid_hi (inclusive bounds of x, y, z over the rows of `coords`) and
+ *                 grid_batches (batch indices are below it): one memory access per insertion and per
+ *                 lookup.  A coordinate outside the stated box is TS_ERR_COORD_RANGE.  The box may
+ *                 span at most 2^30 cells (TS_ERR_UNSUPPORTED beyond).  The cells are library memory
+ *                 kept between builds (4 bytes per cell of the largest box seen, until
+ *                 ts_release_cache): a build writes its points in and takes them out again, so it
+ *                 never clears the volume.  Builds on different streams must not overlap.
+ *   wait          0: do not wait at the end (ts_build_kmap_async).
+ *   has_boundary  != 0 with stride > 1: Alg. 3's boundary check.  A candidate u = p - delta becomes an
+ *                 output only if 0 <= u < stride * boundary on every axis, so the outputs lie on the
+ *                 grid [0, boundary) (x, y, z; each positive).  Ignored at stride 1, where the outputs
+ *                 are the inputs.  Inputs all of whose candidates are cut feed no output (forward) or
+ *                 get no contribution (transposed).
+ */
+enum { TS_SEARCH_HASH = 0, TS_SEARCH_GRID = 1 };
+typedef struct ts_kmap_options {
+    int32_t search;
+    int32_t wait;
+    int32_t has_boundary;
+    int32_t boundary[3];
+    int32_t grid_lo[3];
+    int32_t grid_hi[3];
+    int32_t grid_batches;
+} ts_kmap_options;
+int ts_build_kmap_ex(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
+                     const ts_kmap_options *options, ts_kmap **out_kmap);
+
+/*
  * The transposed map of `forward` (built with stride > 1, transposed = 0): the same map that
  * ts_build_kmap(fine coords, kernel_size, stride, 1) yields for the coordinates `forward` was built
  * from, derived from `forward` without another search.  A network's upsampling layer takes this

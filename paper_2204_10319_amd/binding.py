@@ -25,12 +25,22 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libts.so")
 _lib = None
 
 EXPORTS = [
-    "ts_build_kmap", "ts_build_kmap_async", "ts_kmap_status", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
+    "ts_build_kmap", "ts_build_kmap_async", "ts_build_kmap_ex", "ts_kmap_status", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
     "ts_sparse_conv_prepared", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
     "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_bias_act", "ts_concat_cols",
 ]
+
+
+TS_SEARCH_HASH, TS_SEARCH_GRID = 0, 1
+
+
+class KMapOptions(ctypes.Structure):
+    """ts_kmap_options of the header."""
+    _fields_ = [("search", ctypes.c_int32), ("wait", ctypes.c_int32), ("has_boundary", ctypes.c_int32),
+                ("boundary", ctypes.c_int32 * 3), ("grid_lo", ctypes.c_int32 * 3), ("grid_hi", ctypes.c_int32 * 3),
+                ("grid_batches", ctypes.c_int32)]
 
 
 class TsError(RuntimeError):
@@ -60,6 +70,8 @@ def load_library(path: str | None = None):
     lib.ts_build_kmap.restype = ci
     lib.ts_build_kmap_async.argtypes = [vp, i64, ci, ci, ci, ctypes.POINTER(vp)]
     lib.ts_build_kmap_async.restype = ci
+    lib.ts_build_kmap_ex.argtypes = [vp, i64, ci, ci, ci, ctypes.POINTER(KMapOptions), ctypes.POINTER(vp)]
+    lib.ts_build_kmap_ex.restype = ci
     lib.ts_kmap_status.argtypes = [vp]
     lib.ts_kmap_status.restype = ci
     lib.ts_free.argtypes = [vp]
@@ -261,15 +273,34 @@ class KMap:
 
 
 def ts_build_kmap(coords: torch.Tensor, kernel_size: int, stride: int = 1, transposed: bool = False,
-                  wait: bool = True) -> KMap:
+                  wait: bool = True, grid=None, boundary=None) -> KMap:
     """coords: device int32 [N,4] (batch, x, y, z).  wait=False: ts_build_kmap_async (errors of the input
-    surface at ``KMap.status()`` or the first accessor that needs the map's sizes)."""
+    surface at ``KMap.status()`` or the first accessor that needs the map's sizes).
+    grid=(lo[3], hi[3], batches): search through the coordinate grid over that box (ts_build_kmap_ex,
+    TS_SEARCH_GRID).  boundary=(bx, by, bz): Alg. 3's boundary check for a strided map."""
     if coords.dtype != torch.int32 or coords.dim() != 2 or coords.shape[1] != 4:
         raise ValueError("coords must be int32 [N,4]")
     if not coords.is_cuda or not coords.is_contiguous():
         raise ValueError("coords must be a contiguous device tensor")
     _use_current_stream()
     h = ctypes.c_void_p()
+    if grid is not None or boundary is not None:
+        opt = KMapOptions()
+        opt.wait = int(bool(wait))
+        if grid is not None:
+            lo, hi, batches = grid
+            opt.search = TS_SEARCH_GRID
+            opt.grid_lo = (ctypes.c_int32 * 3)(*[int(v) for v in lo])
+            opt.grid_hi = (ctypes.c_int32 * 3)(*[int(v) for v in hi])
+            opt.grid_batches = int(batches)
+        if boundary is not None:
+            opt.has_boundary = 1
+            opt.boundary = (ctypes.c_int32 * 3)(*[int(v) for v in boundary])
+        rc = load_library().ts_build_kmap_ex(coords.data_ptr() if coords.numel() else None, coords.shape[0],
+                                             int(kernel_size), int(stride), int(bool(transposed)), ctypes.byref(opt),
+                                             ctypes.byref(h))
+        _check(rc)
+        return KMap(h.value)
     fn = load_library().ts_build_kmap if wait else load_library().ts_build_kmap_async
     rc = fn(coords.data_ptr() if coords.numel() else None, coords.shape[0], int(kernel_size), int(stride),
             int(bool(transposed)), ctypes.byref(h))

@@ -70,6 +70,9 @@ int resolve(const struct ::ts_kmap *kmap);
 // Makes sure the offset-major pair lists of a map exist (they are derived on first use).
 int ensure_pairs(const struct ::ts_kmap *kmap);
 
+// Frees the cells of the coordinate grid (the device must be idle).
+void release_grid();
+
 // ---- 64-bit coordinate keys ----------------------------------------------------------------
 // key = batch<<51 | (x+B)<<34 | (y+B)<<17 | (z+B), B = 2^16: order-preserving in (b,x,y,z)
 // ("flattening the coordinate of each dimension into an integer", paper Sec. 2.1.2).

@@ -13,6 +13,9 @@
 //   scan     per-offset exclusive scan of the block counts -> where each pair sits in the
 //            offset-major lists, and the per-offset totals
 // The host waits once, after `scan`, for the map sizes and error flags.
+// The searched set can also be held in a coordinate grid (`grid` of Sec. 4.4: collision-free, one
+// memory access per insertion and per lookup) when the caller states the bounds of its coordinates;
+// Alg. 3's boundary check is applied where the candidates are formed.
 //   compact  pair lists M[W_n] (in, out), ordered by output index inside an offset: derived from
 //            the above when first asked for (ts_kmap_pairs, the explicit dataflow's gather)
 //
@@ -23,6 +26,7 @@
 
 #include <cstring>
 #include <new>
+#include <type_traits>
 
 #include <rocprim/device/device_radix_sort.hpp>
 #include <rocprim/device/device_select.hpp>
@@ -97,6 +101,75 @@ __device__ __forceinline__ void table_insert(const Table &t, uint64_t key, int32
     }
 }
 
+// First slot holding `want`'s value, or -1: a miss ends at the first empty slot.
+__device__ __forceinline__ int32_t table_find(const Table &t, uint64_t want) {
+    uint32_t slot = home_slot(want, t.shift);
+    for (;;) {
+        const uint64_t found = slot_key(t, slot);
+        if (found == want) return slot_val(t, slot);
+        if (found == kEmptyKey) return -1;
+        slot = next_slot(slot, t.mask);
+    }
+}
+
+// ---- coordinate grid ------------------------------------------------------------------------------------
+// The collision-free table of Sec. 4.4 (`grid`): one int32 cell per coordinate of a box, holding the
+// row of the point there or -1.  An insertion is one store, a lookup one load, whatever the
+// occupancy; the price is the box's volume in memory.  The cells live in a buffer the library keeps
+// between builds with every cell at -1: a build writes its points in, searches, and takes them out
+// again, so it touches 2 N cells and never clears the volume.
+struct Grid {
+    int32_t *vals;      // [batches][ext x][ext y][ext z]
+    int32_t lo[3];      // coordinate of cell 0 on each axis
+    uint32_t ext[3];    // cells per axis
+    uint32_t batches;
+};
+
+// Cell of a packed coordinate, or -1 outside the box.
+__device__ __forceinline__ int64_t grid_cell(const Grid &g, uint64_t key) {
+    int32_t c[4];
+    unpack_key(key, c);
+    const uint32_t x = (uint32_t)(c[1] - g.lo[0]), y = (uint32_t)(c[2] - g.lo[1]), z = (uint32_t)(c[3] - g.lo[2]);
+    if ((uint32_t)c[0] >= g.batches || x >= g.ext[0] || y >= g.ext[1] || z >= g.ext[2]) return -1;
+    return (((int64_t)c[0] * g.ext[0] + x) * g.ext[1] + y) * g.ext[2] + z;
+}
+
+__device__ __forceinline__ void table_insert(const Grid &g, uint64_t key, int32_t value, int *status) {
+    const int64_t cell = grid_cell(g, key);
+    if (cell < 0) {
+        atomicOr(&status[ST_RANGE], 1);
+        return;
+    }
+    if (atomicCAS(&g.vals[cell], -1, value) != -1) atomicOr(&status[ST_DUP], 1);
+}
+
+__device__ __forceinline__ int32_t table_find(const Grid &g, uint64_t want) {
+    const int64_t cell = grid_cell(g, want);
+    return cell < 0 ? -1 : g.vals[cell];
+}
+
+// Takes the points out again: the cells of `keys` go back to -1.
+__global__ void k_grid_erase(const uint64_t *keys, int64_t n, Grid g) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t key = keys[i];
+    if (key == kEmptyKey) return;
+    const int64_t cell = grid_cell(g, key);
+    if (cell >= 0) g.vals[cell] = -1;
+}
+
+// Bounds the caller states for its coordinates (grid search); on == 0: none stated.
+struct Box {
+    int on;
+    int32_t lo[3], hi[3];   // inclusive
+    int32_t batches;
+};
+// Alg. 3's boundary: a candidate u is kept when 0 <= u < hi on every axis (hi = s * b); on == 0: no boundary.
+struct Bound {
+    int on;
+    int32_t hi[3];
+};
+
 __device__ __forceinline__ bool coord_ok(int4 c) {
     return c.x >= 0 && c.x <= TS_BATCH_MAX && c.y >= TS_COORD_MIN && c.y <= TS_COORD_MAX &&
            c.z >= TS_COORD_MIN && c.z <= TS_COORD_MAX && c.w >= TS_COORD_MIN && c.w <= TS_COORD_MAX;
@@ -107,7 +180,12 @@ __host__ __device__ constexpr int offset_component(int K, int n, int axis) {
     return axis == 0 ? n / (K * K) - r : (axis == 1 ? (n / K) % K - r : n % K - r);
 }
 
-__device__ __forceinline__ int floor_div(int a, int s) { return a >= 0 ? a / s : -((-a + s - 1) / s); }
+__device__ __forceinline__ bool in_box(int4 c, const Box &b) {
+    return !b.on || (c.x < b.batches && c.y >= b.lo[0] && c.y <= b.hi[0] && c.z >= b.lo[1] && c.z <= b.hi[1] &&
+                     c.w >= b.lo[2] && c.w <= b.hi[2]);
+}
+
+__host__ __device__ __forceinline__ int floor_div(int a, int s) { return a >= 0 ? a / s : -((-a + s - 1) / s); }
 
 // ---- one launch for every buffer that must start at a known value -----------------------------------
 struct FillSeg {
@@ -138,11 +216,11 @@ __global__ void k_fill(FillArgs a) {
 }
 
 // keys[i] = pack(coords[i]); out-of-range rows get the empty key and raise ST_RANGE.
-__global__ void k_pack(const int4 *coords, int64_t n, uint64_t *keys, int *status) {
+__global__ void k_pack(const int4 *coords, int64_t n, uint64_t *keys, int *status, Box box) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     int4 c = coords[i];
-    if (!coord_ok(c)) {
+    if (!coord_ok(c) || !in_box(c, box)) {
         atomicOr(&status[ST_RANGE], 1);
         keys[i] = kEmptyKey;
         return;
@@ -151,7 +229,8 @@ __global__ void k_pack(const int4 *coords, int64_t n, uint64_t *keys, int *statu
 }
 
 // Insert (keys[i] -> i).
-__global__ void k_insert(const uint64_t *keys, int64_t n, Table t, int *status) {
+template <class TableT>
+__global__ void k_insert(const uint64_t *keys, int64_t n, TableT t, int *status) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     uint64_t key = keys[i];
@@ -160,11 +239,12 @@ __global__ void k_insert(const uint64_t *keys, int64_t n, Table t, int *status) 
 }
 
 // Stride-1 front end in one pass: pack and insert (key -> i).
-__global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, Table t, int *status) {
+template <class TableT>
+__global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, TableT t, int *status, Box box) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     int4 c = coords[i];
-    if (!coord_ok(c)) {
+    if (!coord_ok(c) || !in_box(c, box)) {
         atomicOr(&status[ST_RANGE], 1);
         keys[i] = kEmptyKey;
         return;
@@ -176,7 +256,7 @@ __global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, Tab
 
 // Alg. 3 stages 1-4 in registers: candidate u = p - delta_n, modular check, key of u/s.
 // One thread per (input, offset); rejected candidates become the empty key (sorts last).
-__global__ void k_candidates(const uint64_t *keys, int64_t n, int K, int s, uint64_t *cand) {
+__global__ void k_candidates(const uint64_t *keys, int64_t n, int K, int s, Bound bound, uint64_t *cand) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int nn = blockIdx.y, K3 = K * K * K;
@@ -186,20 +266,23 @@ __global__ void k_candidates(const uint64_t *keys, int64_t n, int K, int s, uint
         int32_t c[4];
         unpack_key(key, c);
         int ux = c[1] - dx, uy = c[2] - dy, uz = c[3] - dz;
-        if (ux % s == 0 && uy % s == 0 && uz % s == 0) out = pack_key(c[0], ux / s, uy / s, uz / s);
+        const bool inside = !bound.on || (ux >= 0 && ux < bound.hi[0] && uy >= 0 && uy < bound.hi[1] && uz >= 0 && uz < bound.hi[2]);
+        if (ux % s == 0 && uy % s == 0 && uz % s == 0 && inside) out = pack_key(c[0], ux / s, uy / s, uz / s);
     }
     cand[i * K3 + nn] = out;
 }
 
 // K = s = 2: exactly one admissible offset per input (delta = p mod 2), output floor(p/2).
-__global__ void k_candidates_k2s2(const uint64_t *keys, int64_t n, uint64_t *cand) {
+__global__ void k_candidates_k2s2(const uint64_t *keys, int64_t n, Bound bound, uint64_t *cand) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     uint64_t key = keys[i], out = kEmptyKey;
     if (key != kEmptyKey) {
         int32_t c[4];
         unpack_key(key, c);
-        out = pack_key(c[0], floor_div(c[1], 2), floor_div(c[2], 2), floor_div(c[3], 2));
+        const int qx = floor_div(c[1], 2), qy = floor_div(c[2], 2), qz = floor_div(c[3], 2);   // u = 2 q
+        const bool inside = !bound.on || (qx >= 0 && 2 * qx < bound.hi[0] && qy >= 0 && 2 * qy < bound.hi[1] && qz >= 0 && 2 * qz < bound.hi[2]);
+        if (inside) out = pack_key(c[0], qx, qy, qz);
     }
     cand[i] = out;
 }
@@ -354,8 +437,8 @@ enum { MODE_SUB = 0, MODE_FWD = 1, MODE_TR = 2 };
 // Writes nbr[k][0..K3) (input row or -1) and nbr[k][K3] = bitmask of the offsets present; per wave
 // (64 consecutive outputs) and offset the presence bitmap and its popcount.  (No global counters
 // here: atomics from every wave on one cache line are served one after the other.)
-template <int MODE, int K>
-__global__ void __launch_bounds__(kThreads, 3) k_probe(const uint64_t *__restrict__ out_keys, int64_t n_out, Table t, int s,
+template <int MODE, int K, class TableT>
+__global__ void __launch_bounds__(kThreads, 3) k_probe(const uint64_t *__restrict__ out_keys, int64_t n_out, TableT t, int s,
                                                     int32_t *__restrict__ nbr, uint64_t *__restrict__ colbits,
                                                     int32_t *__restrict__ colcnt, uint32_t *__restrict__ wavemask,
                                                     int64_t n_blocks) {
@@ -384,21 +467,38 @@ __global__ void __launch_bounds__(kThreads, 3) k_probe(const uint64_t *__restric
     // is examined; then rounds: lookups whose slot held another key move on together, so a wave
     // pays one memory access time per round, not per collision.  A finished lookup leaves the
     // slot it hit (or none); the values are fetched in one last batch.
+    // searched key of offset n, and whether there is anything to search for
+    auto wanted = [&](int n, bool *probe) -> uint64_t {
+        *probe = ok && !(MODE == MODE_SUB && n == CENTRE);
+        uint64_t want = base + (uint64_t)delta_of(n);
+        if (MODE == MODE_TR) {
+            constexpr int r = (K - 1) / 2;
+            const int ux = c[1] - (n / (K * K) - r), uy = c[2] - ((n / K) % K - r), uz = c[3] - (n % K - r);
+            *probe = ok && ux % s == 0 && uy % s == 0 && uz % s == 0;
+            want = pack_key(c[0], ux / s, uy / s, uz / s);
+        }
+        return want;
+    };
+    int32_t j[K3];
+    if constexpr (std::is_same<TableT, Grid>::value) {
+        // a grid lookup is one load and the K3 loads of a thread do not depend on each other
+#pragma unroll
+        for (int n = 0; n < K3; ++n) {
+            bool probe;
+            const uint64_t want = wanted(n, &probe);
+            j[n] = (MODE == MODE_SUB && n == CENTRE && ok) ? (int32_t)k : -1;
+            if (probe) j[n] = table_find(t, want);
+        }
+    } else {
     constexpr uint32_t kNone = 0xFFFFFFFFu;
     uint32_t slot[K3];
     uint64_t got[K3];
     uint32_t pending = 0;   // bit n: lookup n has not ended yet
 #pragma unroll
     for (int n = 0; n < K3; ++n) {
-        bool probe = ok && !(MODE == MODE_SUB && n == CENTRE);
-        uint64_t want = base + (uint64_t)delta_of(n);
-        if (MODE == MODE_TR) {
-            constexpr int r = (K - 1) / 2;
-            const int ux = c[1] - (n / (K * K) - r), uy = c[2] - ((n / K) % K - r), uz = c[3] - (n % K - r);
-            probe = ok && ux % s == 0 && uy % s == 0 && uz % s == 0;
-            want = pack_key(c[0], ux / s, uy / s, uz / s);
-            want_tr[MODE == MODE_TR ? n : 0] = want;
-        }
+        bool probe;
+        const uint64_t want = wanted(n, &probe);
+        if (MODE == MODE_TR) want_tr[MODE == MODE_TR ? n : 0] = want;
         slot[n] = kNone;
         if (probe) {
             pending |= 1u << n;
@@ -427,11 +527,11 @@ __global__ void __launch_bounds__(kThreads, 3) k_probe(const uint64_t *__restric
             }
         }
     }
-    int32_t j[K3];
 #pragma unroll
     for (int n = 0; n < K3; ++n) {
         j[n] = (MODE == MODE_SUB && n == CENTRE && ok) ? (int32_t)k : -1;
         if (slot[n] != kNone) j[n] = slot_val(t, slot[n]);
+    }
     }
     uint32_t mask = 0;
 #pragma unroll
@@ -462,7 +562,8 @@ __global__ void __launch_bounds__(kThreads, 3) k_probe(const uint64_t *__restric
 // (i, j, K^3-1-n) in row j; rows start out all -1.  One lookup per thread: a long probe chain
 // delays one wave of 64 lookups, not a wave holding all 26 lookups of 64 points, and the many
 // waves in flight hide the memory round trips.
-__global__ void k_probe_symmetric(const uint64_t *__restrict__ keys, int64_t n_pts, Table t, int K, int32_t *__restrict__ nbr,
+template <class TableT>
+__global__ void k_probe_symmetric(const uint64_t *__restrict__ keys, int64_t n_pts, TableT t, int K, int32_t *__restrict__ nbr,
                                   int stride) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_pts) return;
@@ -470,17 +571,10 @@ __global__ void k_probe_symmetric(const uint64_t *__restrict__ keys, int64_t n_p
     const uint64_t key = keys[i];
     if (key == kEmptyKey) return;
     const uint64_t want = (uint64_t)((int64_t)key + key_delta(offset_component(K, n, 0), offset_component(K, n, 1), offset_component(K, n, 2)));
-    uint32_t slot = home_slot(want, t.shift);
-    for (;;) {
-        const uint64_t found = slot_key(t, slot);
-        if (found == want) {
-            const int32_t j = slot_val(t, slot);
-            nbr[i * stride + n] = j;
-            nbr[(int64_t)j * stride + (K3 - 1 - n)] = (int32_t)i;
-            return;
-        }
-        if (found == kEmptyKey) return;
-        slot = next_slot(slot, t.mask);
+    const int32_t j = table_find(t, want);
+    if (j >= 0) {
+        nbr[i * stride + n] = j;
+        nbr[(int64_t)j * stride + (K3 - 1 - n)] = (int32_t)i;
     }
 }
 
@@ -777,6 +871,75 @@ int make_table(Temps &tmp, int64_t entries, Table *t, FillArgs *fill) {
     return TS_OK;
 }
 
+// How a build was asked to run.
+struct BuildOpts {
+    bool wait = true;
+    bool grid = false;      // hold the searched set in the coordinate grid instead of the hash table
+    Box box = {};           // bounds stated for the caller's coordinates (grid search)
+    Bound bound = {};       // Alg. 3's boundary, already multiplied by the stride
+};
+
+// The searched point set of a build: in the hash table or in the grid.
+struct Searched {
+    bool grid = false;
+    Table t = {};
+    Grid g = {};
+};
+
+// The grid's cells: kept between builds, every cell -1 whenever no build is using them.
+constexpr uint64_t kMaxGridCells = 1ull << 30;   // 4 GiB of cells
+int32_t *g_grid = nullptr;
+uint64_t g_grid_cells = 0;
+bool g_grid_dirty = false;   // a build put points in and did not get as far as taking them out
+
+// A grid over batches x [lo, hi] (inclusive).  Grows the buffer when the box needs more cells than it
+// has; clears it only when new or left dirty by a build that failed half way.
+int acquire_grid(const int32_t lo[3], const int32_t hi[3], int batches, Grid *g) {
+    uint64_t cells = (uint64_t)batches;
+    for (int a = 0; a < 3; ++a) {
+        const int64_t ext = (int64_t)hi[a] - lo[a] + 1;
+        if (ext <= 0 || batches <= 0) return fail(TS_ERR_INVALID_ARG, "empty grid bounds");
+        g->lo[a] = lo[a];
+        g->ext[a] = (uint32_t)ext;
+        cells *= (uint64_t)ext;
+        if (cells > kMaxGridCells)
+            return fail(TS_ERR_UNSUPPORTED, "the grid bounds span more than %llu cells", (unsigned long long)kMaxGridCells);
+    }
+    g->batches = (uint32_t)batches;
+    if (cells > g_grid_cells) {
+        if (g_grid) {
+            TS_HIP(hipStreamSynchronize(stream()));
+            (void)hipFree(g_grid);
+            g_grid = nullptr;
+            g_grid_cells = 0;
+        }
+        const uint64_t want = (cells + 3) & ~3ull;
+        if (hipMalloc(&g_grid, want * sizeof(int32_t)) != hipSuccess) {
+            (void)hipGetLastError();
+            g_grid = nullptr;
+            return fail(TS_ERR_OOM, "no memory for a grid of %llu cells", (unsigned long long)cells);
+        }
+        g_grid_cells = want;
+        g_grid_dirty = true;
+    }
+    if (g_grid_dirty) {
+        FillArgs f;
+        f.add(g_grid, g_grid_cells * sizeof(int32_t), 0xFFFFFFFFu);
+        TS_TRY(launch_fill(f));
+    }
+    g_grid_dirty = true;   // until this build has taken its points out again
+    g->vals = g_grid;
+    return TS_OK;
+}
+
+// Table or grid for `entries` points inside batches x [lo, hi].
+int make_searched(Temps &tmp, const BuildOpts &o, int64_t entries, const int32_t lo[3], const int32_t hi[3], Searched *sd,
+                  FillArgs *fill) {
+    sd->grid = o.grid;
+    if (o.grid) return acquire_grid(lo, hi, o.box.batches, &sd->g);
+    return make_table(tmp, entries, &sd->t, fill);
+}
+
 int make_mask_hash(Temps &tmp, MaskHash *mh, FillArgs *fill) {
     int32_t *cnt_start;
     TS_TRY(tmp.get(&mh->key, (size_t)kMaskHashCap));
@@ -843,7 +1006,7 @@ int take_status(ts_kmap *m, const int32_t *h) {
 
 int report(const ts_kmap *m) {
     if (m->error == TS_ERR_COORD_RANGE)
-        return fail(TS_ERR_COORD_RANGE, "coordinate outside batch [0,%d] / xyz [%d,%d]", TS_BATCH_MAX, TS_COORD_MIN, TS_COORD_MAX);
+        return fail(TS_ERR_COORD_RANGE, "coordinate outside batch [0,%d] / xyz [%d,%d], or outside the grid bounds given", TS_BATCH_MAX, TS_COORD_MIN, TS_COORD_MAX);
     if (m->error == TS_ERR_DUPLICATE_COORD) return fail(TS_ERR_DUPLICATE_COORD, "input coordinates are not distinct");
     return m->error;
 }
@@ -875,15 +1038,19 @@ int sort_keys(Temps &tmp, uint64_t *in, uint64_t *out, size_t n) {
 }
 
 template <int MODE, int K>
-void launch_probe(const ts_kmap *m, const Table &t, int32_t *colcnt, uint32_t *wavemask) {
-    TS_LAUNCH("k_probe", (k_probe<MODE, K>), dim3(blocks_for(m->n_out, kThreads)), dim3(kThreads), m->d_out_keys, m->n_out,
-              t, m->s, m->d_nbr, m->d_colbits, colcnt, wavemask, m->n_blocks);
+void launch_probe(const ts_kmap *m, const Searched &sd, int32_t *colcnt, uint32_t *wavemask) {
+    if (sd.grid)
+        TS_LAUNCH("k_probe_grid", (k_probe<MODE, K, Grid>), dim3(blocks_for(m->n_out, kThreads)), dim3(kThreads), m->d_out_keys,
+                  m->n_out, sd.g, m->s, m->d_nbr, m->d_colbits, colcnt, wavemask, m->n_blocks);
+    else
+        TS_LAUNCH("k_probe", (k_probe<MODE, K, Table>), dim3(blocks_for(m->n_out, kThreads)), dim3(kThreads), m->d_out_keys,
+                  m->n_out, sd.t, m->s, m->d_nbr, m->d_colbits, colcnt, wavemask, m->n_blocks);
 }
 
-// Map search and everything after it.  `table` holds the searched point set; m->d_out_keys the
-// outputs; the clearing of the status words (and of the neighbour table where the search
-// writes hits only) has been enqueued.
-int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status, bool wait) {
+// Map search and everything after it.  `table` holds the searched point set (the map's inputs);
+// m->d_out_keys the outputs; the clearing of the status words (and of the neighbour table where the
+// search writes hits only) has been enqueued.
+int search_and_finish(ts_kmap *m, Temps &tmp, const Searched &table, int *d_status, bool wait) {
     hipStream_t st = stream();
     const int K3 = m->K3, K = m->K;
     const int64_t n_out = m->n_out;
@@ -892,10 +1059,21 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status,
     TS_TRY(tmp.get(&colcnt, (size_t)K3 * m->n_blocks));
     TS_TRY(tmp.get(&wavemask, (size_t)m->n_blocks));
     const int mode = m->s == 1 ? MODE_SUB : (m->transposed ? MODE_TR : MODE_FWD);
+    // a grid gets its points taken out as soon as the search has been enqueued
+    auto after_search = [&]() {
+        if (!table.grid) return;
+        TS_LAUNCH("k_grid_erase", k_grid_erase, dim3(blocks_for(m->n_in, kThreads)), dim3(kThreads), m->d_in_keys, m->n_in, table.g);
+        g_grid_dirty = false;
+    };
     if (mode == MODE_SUB && K == 1) launch_probe<MODE_SUB, 1>(m, table, colcnt, wavemask);
     else if (mode == MODE_SUB && K == 3) {
-        TS_LAUNCH("k_probe_symmetric", k_probe_symmetric, dim3(blocks_for(n_out, kThreads), K3 / 2), dim3(kThreads), m->d_out_keys,
-                  n_out, table, K, m->d_nbr, m->stride);
+        if (table.grid)
+            TS_LAUNCH("k_probe_symmetric_grid", k_probe_symmetric<Grid>, dim3(blocks_for(n_out, kThreads), K3 / 2), dim3(kThreads),
+                      m->d_out_keys, n_out, table.g, K, m->d_nbr, m->stride);
+        else
+            TS_LAUNCH("k_probe_symmetric", k_probe_symmetric<Table>, dim3(blocks_for(n_out, kThreads), K3 / 2), dim3(kThreads),
+                      m->d_out_keys, n_out, table.t, K, m->d_nbr, m->stride);
+        after_search();
         if (!wait) {
             // A caller that does not wait gets the map with its search done: what the fused layer
             // kernel reads.  The row pass and the scan (bitmask words, rank bitmaps, sizes, tile order)
@@ -923,6 +1101,7 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Table &table, int *d_status,
     else if (mode == MODE_TR && K == 2) launch_probe<MODE_TR, 2>(m, table, colcnt, wavemask);
     else if (mode == MODE_TR && K == 3) launch_probe<MODE_TR, 3>(m, table, colcnt, wavemask);
     else return fail(TS_ERR_UNSUPPORTED, "no map search for kernel_size %d, stride %d", K, m->s);
+    if (!(mode == MODE_SUB && K == 3)) after_search();
 
     TS_LAUNCH("k_scan", k_scan, dim3(K3 + 1), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status, K3, wavemask,
               m->n_tiles, m->d_tile_order);
@@ -1037,7 +1216,8 @@ int alloc_outputs(ts_kmap *m, FillArgs *fill) {
 
 int rows_and_scan(ts_kmap *m, Temps &tmp, int32_t *colcnt, int *d_status);   // defined below the build
 
-int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kmap *m, bool wait) {
+int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kmap *m, const BuildOpts &opt) {
+    const bool wait = opt.wait;
     hipStream_t st = stream();
     Temps tmp;
     const int K3 = K * K * K;
@@ -1058,18 +1238,22 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
     TS_TRY(alloc_n(&given, (size_t)N));
     m->d_in_keys = given;   // provisional owner, so that an early error frees it
 
-    Table table;
+    Searched table;
+    const dim3 per_point(blocks_for(N, kThreads)), block(kThreads);
     if (s == 1) {
         m->n_in = m->n_out = N;
         m->d_out_keys = given;
         TS_TRY(alloc_outputs(m, &fill));
-        TS_TRY(make_table(tmp, N, &table, &fill));
+        TS_TRY(make_searched(tmp, opt, N, opt.box.lo, opt.box.hi, &table, &fill));
         TS_TRY(launch_fill(fill));
-        TS_LAUNCH("k_pack_insert", k_pack_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), reinterpret_cast<const int4 *>(coords), N, given, table, d_status);
+        if (table.grid)
+            TS_LAUNCH("k_pack_insert_grid", k_pack_insert<Grid>, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, table.g, d_status, opt.box);
+        else
+            TS_LAUNCH("k_pack_insert", k_pack_insert<Table>, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, table.t, d_status, opt.box);
     } else {
         TS_TRY(launch_fill(fill));
         fill = FillArgs();
-        TS_LAUNCH("k_pack", k_pack, dim3(blocks_for(N, kThreads)), dim3(kThreads), reinterpret_cast<const int4 *>(coords), N, given, d_status);
+        TS_LAUNCH("k_pack", k_pack, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, d_status, opt.box);
         // coarse set: candidates -> sort -> unique (the empty key, if present, sorts last)
         const bool one_each = (K == 2 && s == 2);
         const size_t n_cand = one_each ? (size_t)N : (size_t)N * K3;
@@ -1080,9 +1264,9 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
         TS_TRY(tmp.get(&uniq, n_cand));
         TS_TRY(tmp.get(&d_count, 1));
         if (one_each)
-            TS_LAUNCH("k_candidates_k2s2", k_candidates_k2s2, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, cand);
+            TS_LAUNCH("k_candidates_k2s2", k_candidates_k2s2, per_point, block, given, N, opt.bound, cand);
         else
-            TS_LAUNCH("k_candidates", k_candidates, dim3(blocks_for(N, kThreads), K3), dim3(kThreads), given, N, K, s, cand);
+            TS_LAUNCH("k_candidates", k_candidates, dim3(blocks_for(N, kThreads), K3), block, given, N, K, s, opt.bound, cand);
         TS_TRY(sort_keys(tmp, cand, sorted, n_cand));
         size_t bytes = 0;
         TS_HIP(rocprim::unique(nullptr, bytes, sorted, uniq, d_count, n_cand, rocprim::equal_to<uint64_t>(), st));
@@ -1118,17 +1302,15 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
                 TS_TRY(tmp.get(&colcnt, (size_t)K3 * m->n_blocks));
             }
             TS_TRY(launch_fill(fill));
-            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, t0, d_status);
+            TS_LAUNCH("k_insert", k_insert<Table>, per_point, block, given, N, t0, d_status);
             if (transposed) TS_TRY(rows_and_scan(m, tmp, colcnt, d_status));
             int32_t *hs = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
             if (!hs) return TS_ERR_OOM;
             TS_HIP(hipMemcpyAsync(hs, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
             TS_HIP(hipStreamSynchronize(st));
-            if (hs[ST_RANGE])
-                return fail(TS_ERR_COORD_RANGE, "coordinate outside batch [0,%d] / xyz [%d,%d]", TS_BATCH_MAX, TS_COORD_MIN,
-                            TS_COORD_MAX);
-            if (hs[ST_DUP]) return fail(TS_ERR_DUPLICATE_COORD, "input coordinates are not distinct");
-            return TS_OK;
+            if (hs[ST_RANGE]) m->error = TS_ERR_COORD_RANGE;
+            else if (hs[ST_DUP]) m->error = TS_ERR_DUPLICATE_COORD;
+            return report(m);
         }
         uint64_t *coarse;
         TS_TRY(alloc_n(&coarse, (size_t)n_coarse));
@@ -1138,9 +1320,10 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             m->n_out = n_coarse;
             m->d_out_keys = coarse;
             TS_TRY(alloc_outputs(m, &fill));
-            TS_TRY(make_table(tmp, N, &table, &fill));
+            TS_TRY(make_searched(tmp, opt, N, opt.box.lo, opt.box.hi, &table, &fill));
             TS_TRY(launch_fill(fill));
-            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, table, d_status);
+            if (table.grid) TS_LAUNCH("k_insert_grid", k_insert<Grid>, per_point, block, given, N, table.g, d_status);
+            else TS_LAUNCH("k_insert", k_insert<Table>, per_point, block, given, N, table.t, d_status);
         } else {
             m->n_in = n_coarse;
             m->n_out = N;
@@ -1150,10 +1333,18 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             // duplicates among the fine points are found by inserting them as well
             Table fine_table;
             TS_TRY(make_table(tmp, N, &fine_table, &fill));
-            TS_TRY(make_table(tmp, n_coarse, &table, &fill));
+            // the coarse points lie in the box of the fine ones, moved by less than K and divided by s
+            int32_t clo[3], chi[3];
+            for (int a = 0; a < 3; ++a) {
+                clo[a] = floor_div(opt.box.lo[a] - K, s);
+                chi[a] = floor_div(opt.box.hi[a] + K, s);
+            }
+            TS_TRY(make_searched(tmp, opt, n_coarse, clo, chi, &table, &fill));
             TS_TRY(launch_fill(fill));
-            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(N, kThreads)), dim3(kThreads), given, N, fine_table, d_status);
-            TS_LAUNCH("k_insert", k_insert, dim3(blocks_for(n_coarse, kThreads)), dim3(kThreads), coarse, n_coarse, table, d_status);
+            TS_LAUNCH("k_insert", k_insert<Table>, per_point, block, given, N, fine_table, d_status);
+            const dim3 per_coarse(blocks_for(n_coarse, kThreads));
+            if (table.grid) TS_LAUNCH("k_insert_grid", k_insert<Grid>, per_coarse, block, coarse, n_coarse, table.g, d_status);
+            else TS_LAUNCH("k_insert", k_insert<Table>, per_coarse, block, coarse, n_coarse, table.t, d_status);
         }
     }
     TS_HIP(hipGetLastError());
@@ -1258,6 +1449,13 @@ int resolve(const ts_kmap *kmap) {
     return m->error == TS_OK ? TS_OK : report(m);
 }
 
+void release_grid() {
+    if (g_grid) (void)hipFree(g_grid);
+    g_grid = nullptr;
+    g_grid_cells = 0;
+    g_grid_dirty = false;
+}
+
 Offs offs_of(const ts_kmap *kmap) {
     Offs o;
     for (int n = 0; n <= kMaxK3; ++n) o.v[n] = n <= kmap->K3 ? (int32_t)kmap->offs[n] : (int32_t)kmap->offs[kmap->K3];
@@ -1291,7 +1489,7 @@ int ensure_pairs(const ts_kmap *kmap) {
 extern "C" {
 
 static int build_checked(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed, ts_kmap **out_kmap,
-                         bool wait) {
+                         const BuildOpts &opt) {
     if (!out_kmap) return fail(TS_ERR_INVALID_ARG, "out_kmap is NULL");
     *out_kmap = nullptr;
     if (N < 0) return fail(TS_ERR_INVALID_ARG, "N is negative");
@@ -1305,7 +1503,7 @@ static int build_checked(const int32_t *coords, int64_t N, int kernel_size, int 
     if (N > (int64_t)((1u << 31) - 1) / (ts::kMaxK3 + 5)) return fail(TS_ERR_UNSUPPORTED, "N too large for 32-bit pair indices");
     ts_kmap *m = new (std::nothrow) ts_kmap();
     if (!m) return fail(TS_ERR_OOM, "host allocation failed");
-    int rc = build(coords, N, kernel_size, stride, transposed, m, wait);
+    int rc = build(coords, N, kernel_size, stride, transposed, m, opt);
     if (rc != TS_OK) {
         (void)hipStreamSynchronize(ts::stream());
         destroy(m);
@@ -1317,12 +1515,47 @@ static int build_checked(const int32_t *coords, int64_t N, int kernel_size, int 
 
 int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
                   ts_kmap **out_kmap) {
-    return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, true);
+    return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, BuildOpts());
 }
 
 int ts_build_kmap_async(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
                         ts_kmap **out_kmap) {
-    return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, false);
+    BuildOpts opt;
+    opt.wait = false;
+    return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, opt);
+}
+
+int ts_build_kmap_ex(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
+                     const ts_kmap_options *options, ts_kmap **out_kmap) {
+    BuildOpts opt;
+    if (out_kmap) *out_kmap = nullptr;
+    if (options) {
+        opt.wait = options->wait != 0;
+        if (options->search != TS_SEARCH_HASH && options->search != TS_SEARCH_GRID)
+            return fail(TS_ERR_INVALID_ARG, "search must be TS_SEARCH_HASH or TS_SEARCH_GRID");
+        if (options->search == TS_SEARCH_GRID) {
+            opt.grid = true;
+            opt.box.on = 1;
+            opt.box.batches = options->grid_batches;
+            if (options->grid_batches < 1 || options->grid_batches > TS_BATCH_MAX + 1)
+                return fail(TS_ERR_INVALID_ARG, "grid_batches must be in [1, %d]", TS_BATCH_MAX + 1);
+            for (int a = 0; a < 3; ++a) {
+                opt.box.lo[a] = options->grid_lo[a];
+                opt.box.hi[a] = options->grid_hi[a];
+                if (options->grid_lo[a] > options->grid_hi[a] || options->grid_lo[a] < TS_COORD_MIN || options->grid_hi[a] > TS_COORD_MAX)
+                    return fail(TS_ERR_INVALID_ARG, "grid bounds must satisfy %d <= lo <= hi <= %d", TS_COORD_MIN, TS_COORD_MAX);
+            }
+        }
+        if (options->has_boundary && stride > 1) {
+            opt.bound.on = 1;
+            for (int a = 0; a < 3; ++a) {
+                if (options->boundary[a] < 1 || (int64_t)options->boundary[a] * stride > (int64_t)TS_COORD_MAX + 1)
+                    return fail(TS_ERR_INVALID_ARG, "boundary must be positive and stride * boundary at most %d", TS_COORD_MAX + 1);
+                opt.bound.hi[a] = options->boundary[a] * stride;
+            }
+        }
+    }
+    return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, opt);
 }
 
 int ts_kmap_status(const ts_kmap *kmap) {

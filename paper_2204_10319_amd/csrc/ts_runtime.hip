@@ -243,6 +243,7 @@ int ts_set_stream(void *hip_stream) {
 
 int ts_release_cache(void) {
     TS_HIP(hipDeviceSynchronize());
+    ts::release_grid();
     std::lock_guard<std::mutex> lk(ts::g_pool_mu);
     for (auto &s : ts::g_scratch) {
         if (s.p) {

@@ -25,9 +25,9 @@ def gpu_triples(kmap):
     return oracle.sort_triples(tri)
 
 
-def oracle_map(coords, K, s, transposed=False):
+def oracle_map(coords, K, s, transposed=False, boundary=None):
     """(in_coords, out_coords, sorted triples) the library must reproduce for these arguments."""
-    q = oracle.out_coords(coords, K, s)
+    q = oracle.out_coords(coords, K, s, boundary=boundary)
     tri = oracle.kmap(coords, q, K, s)           # (j over coords, k over q, n)
     if transposed:
         tri = tri[:, [1, 0, 2]]                   # inputs are the coarse points, outputs the given fine points
@@ -35,13 +35,22 @@ def oracle_map(coords, K, s, transposed=False):
     return np.asarray(coords, np.int32), q, oracle.sort_triples(tri)
 
 
-def oracle_conv(coords, x, w, K, s, transposed=False):
+def oracle_conv(coords, x, w, K, s, transposed=False, boundary=None):
     """float64 result of the layer on the same inputs."""
+    q = oracle.out_coords(coords, K, s, boundary=boundary) if boundary is not None else None
     if transposed:
-        _, y = oracle.conv_transposed(coords, x, w, K, s)
+        _, y = oracle.conv_transposed(coords, x, w, K, s, coarse_coords=q)
     else:
-        _, y = oracle.conv(coords, x, w, K, s)
+        _, y = oracle.conv(coords, x, w, K, s, out_coords_=q)
     return y
+
+
+def grid_of(coords, margin=0):
+    """(lo, hi, batches) of a coordinate array, as the grid search wants its box stated."""
+    c = np.asarray(coords)
+    if c.shape[0] == 0:
+        return (0, 0, 0), (0, 0, 0), 1
+    return tuple(int(v) - margin for v in c[:, 1:].min(axis=0)), tuple(int(v) + margin for v in c[:, 1:].max(axis=0)), int(c[:, 0].max()) + 1
 
 
 def check_features(y_gpu, y_ref64, dtype, what=""):

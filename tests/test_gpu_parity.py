@@ -11,7 +11,7 @@ import oracle
 from paper_2204_10319_amd import binding as ts
 from workloads import (uniform_grid_coords, box_surface_coords, lidar_scan_coords, features, conv_weights,
                        shuffle_rows)
-from _util import TOL, np_dtype, to_dev, gpu_triples, oracle_map, oracle_conv, check_features
+from _util import TOL, np_dtype, to_dev, gpu_triples, oracle_map, oracle_conv, check_features, grid_of
 
 pytestmark = pytest.mark.gpu
 
@@ -24,9 +24,9 @@ def _rand_coords(seed, n, lo, hi, batches=1):
     return np.stack([b, x + lo, y + lo, z + lo], axis=1).astype(np.int32)
 
 
-def _check_map(coords, K, s, transposed=False):
-    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
-    in_c, out_c, tri = oracle_map(coords, K, s, transposed)
+def _check_map(coords, K, s, transposed=False, grid=None, boundary=None, wait=True):
+    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed, wait=wait, grid=grid, boundary=boundary)
+    in_c, out_c, tri = oracle_map(coords, K, s, transposed, boundary=boundary)
     assert kmap.num_in == in_c.shape[0]
     assert kmap.num_out == out_c.shape[0]
     assert kmap.kernel_volume == K ** 3
@@ -250,6 +250,97 @@ def test_stages_of_alg2(lidar_coords):
     np.add.at(acc, tri[:, 1], Gh)
     assert oracle.rel_l2(y.cpu().numpy(), acc.astype(np.float16)) < 2e-3
     check_features(y, oracle_conv(coords, x, w, 3, 1), torch.float16, "staged")
+
+
+# ---- grid map search (Sec. 4.4) and Alg. 3's boundary -----------------------------------------------------
+
+@pytest.mark.parametrize("K,s,transposed", MAP_CASES)
+@pytest.mark.parametrize("n", [1, 700, 5000])
+def test_kmap_grid_search_small(K, s, transposed, n):
+    """The grid yields the maps the hash table yields: negative coordinates, three batches, a box with slack."""
+    coords = _rand_coords(2000 + n + 10 * K + s, n, -9, 9, batches=3)
+    _check_map(coords, K, s, transposed, grid=grid_of(coords, margin=n % 3))
+
+
+def test_kmap_grid_is_clean_between_builds():
+    """The cells are kept between builds: a build must not see the points of the one before, whatever the boxes
+    (a smaller one, a larger one that makes the buffer grow, one that is moved), nor after a build that failed."""
+    a = _rand_coords(41, 3000, -12, 12, batches=2)
+    b = _rand_coords(42, 500, -5, 5)
+    c = _rand_coords(43, 4000, -30, 30, batches=2)
+    _check_map(a, 3, 1, grid=grid_of(a))
+    _check_map(b, 3, 1, grid=grid_of(b))
+    _check_map(b, 3, 1, grid=((-12, -12, -12), (12, 12, 12), 2))
+    _check_map(c, 3, 2, grid=grid_of(c))
+    _check_map(a, 2, 2, True, grid=grid_of(a, margin=2))
+    _check_map(a, 3, 1, grid=grid_of(a), wait=False)
+    with pytest.raises(ts.TsError) as e:            # a point outside the stated box
+        ts.ts_build_kmap(to_dev(a), 3, 1, grid=((-12, -12, -12), (12, 12, 3), 2))
+    assert e.value.code == ts.TS_ERR_COORD_RANGE
+    _check_map(b, 3, 1, grid=grid_of(a))
+    dup = np.concatenate([b, b[:1]])
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(dup), 3, 1, grid=grid_of(b))
+    assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(dup), 2, 2, grid=grid_of(b))
+    assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
+    _check_map(b, 3, 1, grid=grid_of(b))
+    with pytest.raises(ts.TsError) as e:            # more cells than the library is willing to hold
+        ts.ts_build_kmap(to_dev(b), 3, 1, grid=((-5, -5, -5), (60000, 60000, 5), 1))
+    assert e.value.code == ts.TS_ERR_UNSUPPORTED
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(b), 3, 1, grid=((5, -5, -5), (-5, 5, 5), 1))
+    assert e.value.code == ts.TS_ERR_INVALID_ARG
+    ts.ts_release_cache()
+    _check_map(a, 3, 1, grid=grid_of(a))
+
+
+def test_config3_lidar_map_grid(lidar_coords):
+    """The full ~150k-voxel scene through the grid (a box of ~3e8 cells)."""
+    _check_map(lidar_coords, 3, 1, grid=grid_of(lidar_coords))
+    _check_map(lidar_coords, 3, 2, grid=grid_of(lidar_coords))
+
+
+@pytest.mark.parametrize("K,s,transposed", [(2, 2, False), (3, 2, False), (2, 2, True), (3, 2, True)])
+@pytest.mark.parametrize("use_grid", [False, True])
+def test_kmap_boundary(K, s, transposed, use_grid):
+    """Alg. 3's boundary check: outputs on the grid [0, b) only; inputs beyond it feed nothing."""
+    coords = _rand_coords(3000 + 7 * K + transposed, 4000, -6, 22, batches=2)
+    b = (8, 11, 5)
+    kmap = _check_map(coords, K, s, transposed, grid=grid_of(coords) if use_grid else None, boundary=b)
+    outs = (kmap.in_coords() if transposed else kmap.out_coords()).cpu().numpy()
+    assert outs.shape[0] > 0 and (outs[:, 1:] >= 0).all() and (outs[:, 1:] < np.array(b)).all()
+    free = oracle.out_coords(coords, K, s)
+    assert outs.shape[0] < free.shape[0]
+
+
+def test_kmap_boundary_that_cuts_everything():
+    coords = _rand_coords(3100, 500, 40, 60)
+    for K, s, tr in [(2, 2, False), (3, 2, False), (2, 2, True), (3, 2, True)]:
+        kmap = _check_map(coords, K, s, tr, boundary=(4, 4, 4))
+        assert kmap.num_pairs == 0
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(coords), 3, 2, boundary=(0, 4, 4))
+    assert e.value.code == ts.TS_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("transposed", [False, True])
+def test_detector_style_downsampling_layer(transposed):
+    """K = 3, s = 2 with a boundary on a LiDAR-like scene (the strided layer of a detection backbone, Sec. 5.1):
+    map and features against the oracle, both dataflows."""
+    coords = lidar_scan_coords(33, n_beams=32, n_azimuth=1024)
+    lo, hi, _ = grid_of(coords)
+    b = tuple((h + 1) // 2 * 3 // 4 for h in hi)                 # three quarters of the coarse extent: cuts a rim
+    cin, cout = (32, 64) if not transposed else (64, 32)
+    kmap = _check_map(coords, 3, 2, transposed, grid=grid_of(coords), boundary=b)
+    n_in = kmap.num_in
+    x = features(530, n_in, cin, np.float16)
+    w = conv_weights(531, 27, cin, cout, np.float16)
+    ref = oracle_conv(coords, x, w, 3, 2, transposed, boundary=b)
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+        y = ts.ts_sparse_conv(to_dev(x), to_dev(w), kmap, dataflow=df)
+        check_features(y, ref, torch.float16, f"detector-style layer, dataflow {df}")
 
 
 def _expected_launches(sizes, centre, eps, S):
