@@ -240,6 +240,31 @@ def main():
     kdown = ts.ts_build_kmap(coords, 2, 2)
     grouping["config3_C64_K2s2"] = grouping_report(kdown, N, 64)
     kdown.free()
+    # ---- map search ablation (Sec. 4.4): hash table against the coordinate grid, per level of the network's
+    # pyramid (coordinates halved level by level), submanifold 3x3x3 and the K=3, s=2 strided map with a boundary
+    def grid_box(c_h):
+        return (tuple(int(v) for v in c_h[:, 1:].min(axis=0)), tuple(int(v) for v in c_h[:, 1:].max(axis=0)),
+                int(c_h[:, 0].max()) + 1)
+
+    search = {}
+    level_h = coords_h
+    for level in range(5):
+        cd = torch.from_numpy(np.ascontiguousarray(level_h)).cuda()
+        box = grid_box(level_h)
+        cells = box[2] * int(np.prod([h - l + 1 for l, h in zip(box[0], box[1])]))
+        bnd = tuple((h + 2) // 2 for h in box[1])
+        ts.ts_build_kmap(cd, 3, 1, grid=box).free()          # grows the grid's buffer outside the timing
+        row = {"N": int(level_h.shape[0]), "grid_cells": cells,
+               "K3s1_hash_us": round(time_calls(lambda: ts.ts_build_kmap(cd, 3, 1).free(), 20), 1),
+               "K3s1_grid_us": round(time_calls(lambda: ts.ts_build_kmap(cd, 3, 1, grid=box).free(), 20), 1),
+               "K3s2_boundary_hash_us": round(time_calls(lambda: ts.ts_build_kmap(cd, 3, 2, boundary=bnd, search=ts.TS_SEARCH_HASH).free(), 20), 1),
+               "K3s2_boundary_grid_us": round(time_calls(lambda: ts.ts_build_kmap(cd, 3, 2, grid=box, boundary=bnd).free(), 20), 1),
+               "K3s2_boundary_auto_us": round(time_calls(lambda: ts.ts_build_kmap(cd, 3, 2, boundary=bnd).free(), 20), 1),
+               "K2s2_hash_us": round(time_calls(lambda: ts.ts_build_kmap(cd, 2, 2, search=ts.TS_SEARCH_HASH).free(), 20), 1),
+               "K2s2_auto_us": round(time_calls(lambda: ts.ts_build_kmap(cd, 2, 2).free(), 20), 1)}
+        search[f"level{level}_stride{2 ** level}"] = row
+        nxt = np.unique(np.concatenate([level_h[:, :1], level_h[:, 1:] // 2], axis=1), axis=0).astype(np.int32)
+        level_h = nxt
     # optional ordering of the output rows by offset bitmask (for maps that serve several layers)
     sort_us = time_calls(lambda: ts.ts_build_kmap(coords, K, 1).sort_rows().free(), 20) - kmap_us
     ksorted = ts.ts_build_kmap(coords, K, 1).sort_rows()
@@ -255,6 +280,7 @@ def main():
     breakdown = {"kmap_build_us": round(kmap_us, 1), "kmap_algorithmic_bytes": int(kb),
                  "kmap_GBs": round(kb / kmap_us * 1e-3, 1), "copy_kernel_GBs": round(copy_gbs, 1),
                  "per_kernel_us_per_step": per_kernel, "layers": layers, "grouping_ablation": grouping,
+                 "map_search_ablation": search,
                  "sorted_rows": sorted_rows}
 
     # ---- config 5: MinkUNet-style forward pass on the same scene (maps built once, then the 45 convs)

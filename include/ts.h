@@ -125,11 +125,18 @@ int ts_kmap_status(const ts_kmap *kmap);
 /*
  * ts_build_kmap with the choices the paper leaves to each layer (Sec. 4.4; Alg. 3).  options == NULL
  * is ts_build_kmap.  The map built is the same whatever `search` says.
- *   search        TS_SEARCH_HASH: the open-addressing table.  TS_SEARCH_GRID: the collision-free
+ *   search        TS_SEARCH_AUTO (what ts_build_kmap does): stride 1 searches the hash table; a strided
+ *                 build measures the bounding box of its coordinates on the device (one more host
+ *                 round trip) and, when the box has at most 2^28 cells, takes the grid route below
+ *                 by itself, else the hash route.
+ *                 TS_SEARCH_HASH: the open-addressing table; a strided build finds its output
+ *                 coordinates by sorting the candidates.  TS_SEARCH_GRID: the collision-free
  *                 grid of Sec. 4.4, one int32 cell per coordinate of the box the caller states
  *                 with grid_lo / grid_hi (inclusive bounds of x, y, z over the rows of `coords`) and
  *                 grid_batches (batch indices are below it): one memory access per insertion and per
- *                 lookup.  A coordinate outside the stated box is TS_ERR_COORD_RANGE.  The box may
+ *                 lookup, and a strided build finds its output coordinates by marking the candidates
+ *                 in a bitmap over the box and reading the set bits off in order (no sort).
+ *                 A coordinate outside the stated box is TS_ERR_COORD_RANGE.  The box may
  *                 span at most 2^30 cells (TS_ERR_UNSUPPORTED beyond).  The cells are library memory
  *                 kept between builds (4 bytes per cell of the largest box seen, until
  *                 ts_release_cache): a build writes its points in and takes them out again, so it
@@ -141,7 +148,7 @@ int ts_kmap_status(const ts_kmap *kmap);
  *                 are the inputs.  Inputs all of whose candidates are cut feed no output (forward) or
  *                 get no contribution (transposed).
  */
-enum { TS_SEARCH_HASH = 0, TS_SEARCH_GRID = 1 };
+enum { TS_SEARCH_AUTO = 0, TS_SEARCH_HASH = 1, TS_SEARCH_GRID = 2 };
 typedef struct ts_kmap_options {
     int32_t search;
     int32_t wait;

@@ -33,7 +33,7 @@ EXPORTS = [
 ]
 
 
-TS_SEARCH_HASH, TS_SEARCH_GRID = 0, 1
+TS_SEARCH_AUTO, TS_SEARCH_HASH, TS_SEARCH_GRID = 0, 1, 2
 
 
 class KMapOptions(ctypes.Structure):
@@ -273,20 +273,21 @@ class KMap:
 
 
 def ts_build_kmap(coords: torch.Tensor, kernel_size: int, stride: int = 1, transposed: bool = False,
-                  wait: bool = True, grid=None, boundary=None) -> KMap:
+                  wait: bool = True, grid=None, boundary=None, search: int = TS_SEARCH_AUTO) -> KMap:
     """coords: device int32 [N,4] (batch, x, y, z).  wait=False: ts_build_kmap_async (errors of the input
     surface at ``KMap.status()`` or the first accessor that needs the map's sizes).
     grid=(lo[3], hi[3], batches): search through the coordinate grid over that box (ts_build_kmap_ex,
-    TS_SEARCH_GRID).  boundary=(bx, by, bz): Alg. 3's boundary check for a strided map."""
+    TS_SEARCH_GRID).  search=TS_SEARCH_HASH keeps a strided build on the hash table.  boundary=(bx, by, bz): Alg. 3's boundary check for a strided map."""
     if coords.dtype != torch.int32 or coords.dim() != 2 or coords.shape[1] != 4:
         raise ValueError("coords must be int32 [N,4]")
     if not coords.is_cuda or not coords.is_contiguous():
         raise ValueError("coords must be a contiguous device tensor")
     _use_current_stream()
     h = ctypes.c_void_p()
-    if grid is not None or boundary is not None:
+    if grid is not None or boundary is not None or search != TS_SEARCH_AUTO:
         opt = KMapOptions()
         opt.wait = int(bool(wait))
+        opt.search = int(search)
         if grid is not None:
             lo, hi, batches = grid
             opt.search = TS_SEARCH_GRID

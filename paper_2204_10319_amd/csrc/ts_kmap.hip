@@ -215,17 +215,39 @@ __global__ void k_fill(FillArgs a) {
     }
 }
 
+// Bounding box of the valid coordinates, for builds that choose their search by it: 64 partial boxes
+// on cache lines of their own (atomics on one line are served one after the other), each 7 running
+// maxima: -x, -y, -z, x, y, z, batch.  The host folds the 64.
+constexpr int kBoxSlots = 64, kBoxSlotWords = 32;
+
 // keys[i] = pack(coords[i]); out-of-range rows get the empty key and raise ST_RANGE.
-__global__ void k_pack(const int4 *coords, int64_t n, uint64_t *keys, int *status, Box box) {
+__global__ void __launch_bounds__(kThreads) k_pack(const int4 *coords, int64_t n, uint64_t *keys, int *status, Box box, int32_t *bbox) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    int4 c = coords[i];
-    if (!coord_ok(c) || !in_box(c, box)) {
-        atomicOr(&status[ST_RANGE], 1);
-        keys[i] = kEmptyKey;
-        return;
+    int32_t v[7];
+#pragma unroll
+    for (int q = 0; q < 7; ++q) v[q] = INT32_MIN;
+    if (i < n) {
+        int4 c = coords[i];
+        if (!coord_ok(c) || !in_box(c, box)) {
+            atomicOr(&status[ST_RANGE], 1);
+            keys[i] = kEmptyKey;
+        } else {
+            keys[i] = pack_key(c.x, c.y, c.z, c.w);
+            v[0] = -c.y, v[1] = -c.z, v[2] = -c.w, v[3] = c.y, v[4] = c.z, v[5] = c.w, v[6] = c.x;
+        }
     }
-    keys[i] = pack_key(c.x, c.y, c.z, c.w);
+    if (!bbox) return;
+#pragma unroll
+    for (int q = 0; q < 7; ++q)
+        for (int d = 32; d >= 1; d >>= 1) v[q] = max(v[q], __shfl_xor(v[q], d, 64));
+    const int lane = threadIdx.x & 63;
+    const int slot = (int)((blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) % kBoxSlots);
+    if (lane < 7) {
+        int32_t mine = v[0];
+#pragma unroll
+        for (int q = 1; q < 7; ++q) mine = lane == q ? v[q] : mine;
+        if (mine != INT32_MIN) atomicMax(&bbox[slot * kBoxSlotWords + lane], mine);
+    }
 }
 
 // Insert (keys[i] -> i).
@@ -254,37 +276,51 @@ __global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, Tab
     table_insert(t, key, (int32_t)i, status);
 }
 
-// Alg. 3 stages 1-4 in registers: candidate u = p - delta_n, modular check, key of u/s.
-// One thread per (input, offset); rejected candidates become the empty key (sorts last).
-__global__ void k_candidates(const uint64_t *keys, int64_t n, int K, int s, Bound bound, uint64_t *cand) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int nn = blockIdx.y, K3 = K * K * K;
-    const int dx = offset_component(K, nn, 0), dy = offset_component(K, nn, 1), dz = offset_component(K, nn, 2);
-    uint64_t key = keys[i], out = kEmptyKey;
-    if (key != kEmptyKey) {
-        int32_t c[4];
-        unpack_key(key, c);
-        int ux = c[1] - dx, uy = c[2] - dy, uz = c[3] - dz;
-        const bool inside = !bound.on || (ux >= 0 && ux < bound.hi[0] && uy >= 0 && uy < bound.hi[1] && uz >= 0 && uz < bound.hi[2]);
-        if (ux % s == 0 && uy % s == 0 && uz % s == 0 && inside) out = pack_key(c[0], ux / s, uy / s, uz / s);
+// Alg. 3 stages 1-4 in registers: candidate u = p - delta, modular check, boundary check, key of u/s.
+// Along an axis the admissible offsets are those congruent to p modulo s, at most A = ceil(K/s) of
+// the K; a thread takes one of the A^3 combinations of one input (blockIdx.y), so nothing is formed
+// for the offsets the modular check would throw out.  Returns the empty key when the combination
+// does not exist for this point or falls outside the boundary.
+__device__ __forceinline__ uint64_t candidate_key(uint64_t key, int slot, int K, int s, int A, const Bound &bound) {
+    if (key == kEmptyKey) return kEmptyKey;
+    int32_t c[4];
+    unpack_key(key, c);
+    const int r = (K - 1) / 2;
+    const int t[3] = {slot / (A * A), (slot / A) % A, slot % A};
+    int32_t q[3];
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        const int p = c[1 + a];
+        const int first = -r + (((p + r) % s) + s) % s;   // smallest offset >= -r congruent to p
+        const int d = first + t[a] * s;
+        if (d > K - 1 - r) return kEmptyKey;
+        const int u = p - d;                               // a multiple of s
+        if (bound.on && (u < 0 || u >= bound.hi[a])) return kEmptyKey;
+        q[a] = u / s;
     }
-    cand[i * K3 + nn] = out;
+    return pack_key(c[0], q[0], q[1], q[2]);
 }
 
-// K = s = 2: exactly one admissible offset per input (delta = p mod 2), output floor(p/2).
-__global__ void k_candidates_k2s2(const uint64_t *keys, int64_t n, Bound bound, uint64_t *cand) {
+__global__ void k_candidates(const uint64_t *keys, int64_t n, int K, int s, int A, Bound bound, uint64_t *cand) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    uint64_t key = keys[i], out = kEmptyKey;
-    if (key != kEmptyKey) {
-        int32_t c[4];
-        unpack_key(key, c);
-        const int qx = floor_div(c[1], 2), qy = floor_div(c[2], 2), qz = floor_div(c[3], 2);   // u = 2 q
-        const bool inside = !bound.on || (qx >= 0 && 2 * qx < bound.hi[0] && qy >= 0 && 2 * qy < bound.hi[1] && qz >= 0 && 2 * qz < bound.hi[2]);
-        if (inside) out = pack_key(c[0], qx, qy, qz);
+    cand[i * (int64_t)gridDim.y + blockIdx.y] = candidate_key(keys[i], blockIdx.y, K, s, A, bound);
+}
+
+// The same candidates, marked in a bitmap over the box the outputs can lie in (one bit per cell, cells
+// in (batch, x, y, z) order): Alg. 3's Unique() without a sort, for callers that state their bounds.
+__global__ void k_candidates_mark(const uint64_t *keys, int64_t n, int K, int s, int A, Bound bound, Grid cbox,
+                                  uint32_t *bits, int *status) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t cand = candidate_key(keys[i], blockIdx.y, K, s, A, bound);
+    if (cand == kEmptyKey) return;
+    const int64_t cell = grid_cell(cbox, cand);
+    if (cell < 0) {
+        atomicOr(&status[ST_RANGE], 1);
+        return;
     }
-    cand[i] = out;
+    atomicOr(&bits[cell >> 5], 1u << (cell & 31));
 }
 
 __global__ void k_drop_empty_key(const uint64_t *uniq, int64_t *count) {
@@ -655,6 +691,53 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *total) {
     return base + incl - v;
 }
 
+// ---- marked cells -> sorted distinct keys ------------------------------------------------------------------
+// Bits set per block of 256 words.
+__global__ void __launch_bounds__(kThreads) k_bits_count(const uint64_t *__restrict__ words, int64_t n_words,
+                                                         int32_t *__restrict__ block_total) {
+    const int64_t w = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    int total;
+    block_exclusive_scan(w < n_words ? __popcll(words[w]) : 0, &total);
+    if (threadIdx.x == 0) block_total[blockIdx.x] = total;
+}
+
+// One block: block_total[] -> its exclusive prefix in place, and the grand total.
+__global__ void __launch_bounds__(kThreads) k_bits_scan(int32_t *__restrict__ block_total, int64_t n, int64_t *__restrict__ count) {
+    int64_t run = 0;
+    for (int64_t base = 0; base < n; base += kThreads) {
+        const int64_t i = base + threadIdx.x;
+        const int v = i < n ? block_total[i] : 0;
+        int total;
+        const int before = block_exclusive_scan(v, &total);
+        if (i < n) block_total[i] = (int32_t)(run + before);
+        run += total;
+    }
+    if (threadIdx.x == 0) *count = run;
+}
+
+// Every set bit becomes the key of its cell, at the rank of the bit: cells are numbered in
+// (batch, x, y, z) order, which is the order of the keys.
+__global__ void __launch_bounds__(kThreads) k_bits_expand(const uint64_t *__restrict__ words, int64_t n_words,
+                                                          const int32_t *__restrict__ block_base, Grid cbox,
+                                                          uint64_t *__restrict__ out_keys) {
+    const int64_t w = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    uint64_t bits = w < n_words ? words[w] : 0;
+    int total;
+    int64_t at = block_base[blockIdx.x] + block_exclusive_scan(__popcll(bits), &total);
+    while (bits) {
+        const int bit = __builtin_ctzll(bits);
+        bits &= bits - 1;
+        uint64_t cell = (uint64_t)w * 64 + bit;
+        const int32_t z = (int32_t)(cell % cbox.ext[2]);
+        cell /= cbox.ext[2];
+        const int32_t y = (int32_t)(cell % cbox.ext[1]);
+        cell /= cbox.ext[1];
+        const int32_t x = (int32_t)(cell % cbox.ext[0]);
+        const int32_t b = (int32_t)(cell / cbox.ext[0]);
+        out_keys[at++] = pack_key(b, x + cbox.lo[0], y + cbox.lo[1], z + cbox.lo[2]);
+    }
+}
+
 // Block n: exclusive scan of colcnt[n][*] -> colbase[n][b] = pairs of offset n in the 64-row
 // blocks before b (relative to the start of the offset's list), and the offset's total (the host
 // turns the totals into offs[], the start of each offset's list, and hands them to later kernels
@@ -874,6 +957,7 @@ int make_table(Temps &tmp, int64_t entries, Table *t, FillArgs *fill) {
 // How a build was asked to run.
 struct BuildOpts {
     bool wait = true;
+    bool measure = false;   // strided builds: measure the bounding box on the device and use the grid if it is small enough
     bool grid = false;      // hold the searched set in the coordinate grid instead of the hash table
     Box box = {};           // bounds stated for the caller's coordinates (grid search)
     Bound bound = {};       // Alg. 3's boundary, already multiplied by the stride
@@ -887,7 +971,8 @@ struct Searched {
 };
 
 // The grid's cells: kept between builds, every cell -1 whenever no build is using them.
-constexpr uint64_t kMaxGridCells = 1ull << 30;   // 4 GiB of cells
+constexpr uint64_t kMaxGridCells = 1ull << 30;    // 4 GiB of cells: what a caller may ask for
+constexpr uint64_t kAutoGridCells = 1ull << 28;   // 1 GiB: what a build that measures its own box takes by itself
 int32_t *g_grid = nullptr;
 uint64_t g_grid_cells = 0;
 bool g_grid_dirty = false;   // a build put points in and did not get as far as taking them out
@@ -1216,7 +1301,8 @@ int alloc_outputs(ts_kmap *m, FillArgs *fill) {
 
 int rows_and_scan(ts_kmap *m, Temps &tmp, int32_t *colcnt, int *d_status);   // defined below the build
 
-int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kmap *m, const BuildOpts &opt) {
+int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kmap *m, const BuildOpts &asked) {
+    BuildOpts opt = asked;   // a build that measures its bounding box may turn the grid on
     const bool wait = opt.wait;
     hipStream_t st = stream();
     Temps tmp;
@@ -1251,33 +1337,99 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
         else
             TS_LAUNCH("k_pack_insert", k_pack_insert<Table>, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, table.t, d_status, opt.box);
     } else {
-        TS_TRY(launch_fill(fill));
-        fill = FillArgs();
-        TS_LAUNCH("k_pack", k_pack, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, d_status, opt.box);
-        // coarse set: candidates -> sort -> unique (the empty key, if present, sorts last)
-        const bool one_each = (K == 2 && s == 2);
-        const size_t n_cand = one_each ? (size_t)N : (size_t)N * K3;
-        uint64_t *cand, *sorted, *uniq;
+        // coarse set: the distinct admissible candidates in ascending order (Alg. 3)
+        const int A = (K + s - 1) / s, slots = A * A * A;
+        const size_t n_cand = (size_t)N * slots;
+        uint64_t *uniq;
         int64_t *d_count;
-        TS_TRY(tmp.get(&cand, n_cand));
-        TS_TRY(tmp.get(&sorted, n_cand));
         TS_TRY(tmp.get(&uniq, n_cand));
         TS_TRY(tmp.get(&d_count, 1));
-        if (one_each)
-            TS_LAUNCH("k_candidates_k2s2", k_candidates_k2s2, per_point, block, given, N, opt.bound, cand);
-        else
-            TS_LAUNCH("k_candidates", k_candidates, dim3(blocks_for(N, kThreads), K3), block, given, N, K, s, opt.bound, cand);
-        TS_TRY(sort_keys(tmp, cand, sorted, n_cand));
-        size_t bytes = 0;
-        TS_HIP(rocprim::unique(nullptr, bytes, sorted, uniq, d_count, n_cand, rocprim::equal_to<uint64_t>(), st));
-        void *ws;
-        TS_TRY(tmp.get((char **)&ws, bytes));
-        {
-            ProfScope ps("unique_keys");
-            TS_HIP(rocprim::unique(ws, bytes, sorted, uniq, d_count, n_cand, rocprim::equal_to<uint64_t>(), st));
+        int32_t *d_bbox = nullptr;
+        if (opt.measure && !opt.grid) {
+            TS_TRY(tmp.get(&d_bbox, (size_t)kBoxSlots * kBoxSlotWords));
+            fill.add(d_bbox, (size_t)kBoxSlots * kBoxSlotWords * sizeof(int32_t), 0x80000000u);
         }
-        // the empty key, if any candidate was rejected, is the last unique value: do not count it
-        TS_LAUNCH("k_drop_empty_key", k_drop_empty_key, dim3(1), dim3(1), uniq, d_count);
+        TS_TRY(launch_fill(fill));
+        fill = FillArgs();
+        TS_LAUNCH("k_pack", k_pack, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, d_status, opt.box, d_bbox);
+        if (d_bbox) {
+            // one more host round trip buys a build without a sort and a search without collisions
+            const size_t bytes = (size_t)kBoxSlots * kBoxSlotWords * sizeof(int32_t);
+            int32_t *hb = static_cast<int32_t *>(host_staging(bytes));
+            if (!hb) return TS_ERR_OOM;
+            TS_HIP(hipMemcpyAsync(hb, d_bbox, bytes, hipMemcpyDeviceToHost, st));
+            TS_HIP(hipStreamSynchronize(st));
+            int32_t top[7];
+            for (int q = 0; q < 7; ++q) {
+                top[q] = INT32_MIN;
+                for (int sl = 0; sl < kBoxSlots; ++sl) top[q] = hb[sl * kBoxSlotWords + q] > top[q] ? hb[sl * kBoxSlotWords + q] : top[q];
+            }
+            if (top[6] != INT32_MIN) {   // at least one valid point
+                Box bx = {};
+                uint64_t cells = (uint64_t)top[6] + 1;
+                for (int a = 0; a < 3; ++a) {
+                    bx.lo[a] = -top[a];
+                    bx.hi[a] = top[3 + a];
+                    cells *= (uint64_t)((int64_t)bx.hi[a] - bx.lo[a] + 1);
+                    if (cells > kAutoGridCells) cells = kAutoGridCells + 1;
+                }
+                bx.batches = top[6] + 1;
+                if (cells <= kAutoGridCells) {
+                    opt.grid = true;
+                    opt.box = bx;   // on stays 0: nothing to check, the box is the points' own
+                }
+            }
+        }
+        // the coarse points lie in the box of the fine ones, moved by less than K and divided by s
+        int32_t clo[3] = {0, 0, 0}, chi[3] = {0, 0, 0};
+        for (int a = 0; a < 3; ++a) {
+            clo[a] = floor_div(opt.box.lo[a] - K, s);
+            chi[a] = floor_div(opt.box.hi[a] + K, s);
+        }
+        if (opt.grid) {
+            // bounds are stated: mark the candidates' cells in a bitmap and read the set bits off in
+            // order, which sorts and removes duplicates at once
+            Grid cbox = {};
+            uint64_t cells = (uint64_t)opt.box.batches;
+            for (int a = 0; a < 3; ++a) {
+                cbox.lo[a] = clo[a];
+                cbox.ext[a] = (uint32_t)(chi[a] - clo[a] + 1);
+                cells *= cbox.ext[a];
+                if (cells > kMaxGridCells)
+                    return fail(TS_ERR_UNSUPPORTED, "the grid bounds span more than %llu cells", (unsigned long long)kMaxGridCells);
+            }
+            cbox.batches = (uint32_t)opt.box.batches;
+            const int64_t n_words = (int64_t)((cells + 63) / 64), n_wblocks = (n_words + kThreads - 1) / kThreads;
+            uint64_t *words;
+            int32_t *block_total;
+            TS_TRY(tmp.get(&words, (size_t)n_words));
+            TS_TRY(tmp.get(&block_total, (size_t)n_wblocks));
+            fill.add(words, (size_t)n_words * sizeof(uint64_t), 0u);
+            TS_TRY(launch_fill(fill));
+            fill = FillArgs();
+            TS_LAUNCH("k_candidates_mark", k_candidates_mark, dim3(blocks_for(N, kThreads), slots), block, given, N, K, s, A, opt.bound,
+                      cbox, reinterpret_cast<uint32_t *>(words), d_status);
+            TS_LAUNCH("k_bits_count", k_bits_count, dim3((unsigned)n_wblocks), block, words, n_words, block_total);
+            TS_LAUNCH("k_bits_scan", k_bits_scan, dim3(1), block, block_total, n_wblocks, d_count);
+            TS_LAUNCH("k_bits_expand", k_bits_expand, dim3((unsigned)n_wblocks), block, words, n_words, block_total, cbox, uniq);
+        } else {
+            // candidates -> sort -> unique (the empty key, if present, sorts last)
+            uint64_t *cand, *sorted;
+            TS_TRY(tmp.get(&cand, n_cand));
+            TS_TRY(tmp.get(&sorted, n_cand));
+            TS_LAUNCH("k_candidates", k_candidates, dim3(blocks_for(N, kThreads), slots), block, given, N, K, s, A, opt.bound, cand);
+            TS_TRY(sort_keys(tmp, cand, sorted, n_cand));
+            size_t bytes = 0;
+            TS_HIP(rocprim::unique(nullptr, bytes, sorted, uniq, d_count, n_cand, rocprim::equal_to<uint64_t>(), st));
+            void *ws;
+            TS_TRY(tmp.get((char **)&ws, bytes));
+            {
+                ProfScope ps("unique_keys");
+                TS_HIP(rocprim::unique(ws, bytes, sorted, uniq, d_count, n_cand, rocprim::equal_to<uint64_t>(), st));
+            }
+            // the empty key, if any candidate was rejected, is the last unique value: do not count it
+            TS_LAUNCH("k_drop_empty_key", k_drop_empty_key, dim3(1), dim3(1), uniq, d_count);
+        }
         int64_t *h = static_cast<int64_t *>(host_staging(64));
         if (!h) return TS_ERR_OOM;
         TS_HIP(hipMemcpyAsync(h, d_count, sizeof(int64_t), hipMemcpyDeviceToHost, st));
@@ -1333,12 +1485,6 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             // duplicates among the fine points are found by inserting them as well
             Table fine_table;
             TS_TRY(make_table(tmp, N, &fine_table, &fill));
-            // the coarse points lie in the box of the fine ones, moved by less than K and divided by s
-            int32_t clo[3], chi[3];
-            for (int a = 0; a < 3; ++a) {
-                clo[a] = floor_div(opt.box.lo[a] - K, s);
-                chi[a] = floor_div(opt.box.hi[a] + K, s);
-            }
             TS_TRY(make_searched(tmp, opt, n_coarse, clo, chi, &table, &fill));
             TS_TRY(launch_fill(fill));
             TS_LAUNCH("k_insert", k_insert<Table>, per_point, block, given, N, fine_table, d_status);
@@ -1515,24 +1661,29 @@ static int build_checked(const int32_t *coords, int64_t N, int kernel_size, int 
 
 int ts_build_kmap(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
                   ts_kmap **out_kmap) {
-    return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, BuildOpts());
+    BuildOpts opt;
+    opt.measure = true;
+    return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, opt);
 }
 
 int ts_build_kmap_async(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
                         ts_kmap **out_kmap) {
     BuildOpts opt;
     opt.wait = false;
+    opt.measure = true;
     return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, opt);
 }
 
 int ts_build_kmap_ex(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
                      const ts_kmap_options *options, ts_kmap **out_kmap) {
     BuildOpts opt;
+    opt.measure = true;
     if (out_kmap) *out_kmap = nullptr;
     if (options) {
         opt.wait = options->wait != 0;
-        if (options->search != TS_SEARCH_HASH && options->search != TS_SEARCH_GRID)
-            return fail(TS_ERR_INVALID_ARG, "search must be TS_SEARCH_HASH or TS_SEARCH_GRID");
+        opt.measure = options->search == TS_SEARCH_AUTO;
+        if (options->search != TS_SEARCH_HASH && options->search != TS_SEARCH_GRID && options->search != TS_SEARCH_AUTO)
+            return fail(TS_ERR_INVALID_ARG, "search must be TS_SEARCH_AUTO, TS_SEARCH_HASH or TS_SEARCH_GRID");
         if (options->search == TS_SEARCH_GRID) {
             opt.grid = true;
             opt.box.on = 1;

@@ -24,8 +24,8 @@ def _rand_coords(seed, n, lo, hi, batches=1):
     return np.stack([b, x + lo, y + lo, z + lo], axis=1).astype(np.int32)
 
 
-def _check_map(coords, K, s, transposed=False, grid=None, boundary=None, wait=True):
-    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed, wait=wait, grid=grid, boundary=boundary)
+def _check_map(coords, K, s, transposed=False, grid=None, boundary=None, wait=True, search=ts.TS_SEARCH_AUTO):
+    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed, wait=wait, grid=grid, boundary=boundary, search=search)
     in_c, out_c, tri = oracle_map(coords, K, s, transposed, boundary=boundary)
     assert kmap.num_in == in_c.shape[0]
     assert kmap.num_out == out_c.shape[0]
@@ -262,6 +262,24 @@ def test_kmap_grid_search_small(K, s, transposed, n):
     _check_map(coords, K, s, transposed, grid=grid_of(coords, margin=n % 3))
 
 
+@pytest.mark.parametrize("K,s,transposed", [c for c in MAP_CASES if c[1] > 1])
+@pytest.mark.parametrize("n", [1, 37, 5000])
+def test_kmap_strided_hash_route(K, s, transposed, n):
+    """Strided builds kept on the hash table (candidates sorted); the default measures its box and takes the grid."""
+    coords = _rand_coords(2500 + n + 10 * K + s, n, -9, 9, batches=3)
+    _check_map(coords, K, s, transposed, search=ts.TS_SEARCH_HASH)
+
+
+def test_kmap_strided_box_too_large_for_the_grid():
+    """Two far-apart clusters: the measured box exceeds what a build takes by itself, so it stays on the hash table."""
+    a = _rand_coords(2601, 800, -8, 8)
+    b = a.copy()
+    b[:, 1:] += 40000
+    coords = np.concatenate([a, b])
+    for K, s, tr in [(2, 2, False), (3, 2, False), (2, 2, True)]:
+        _check_map(coords, K, s, tr)
+
+
 def test_kmap_grid_is_clean_between_builds():
     """The cells are kept between builds: a build must not see the points of the one before, whatever the boxes
     (a smaller one, a larger one that makes the buffer grow, one that is moved), nor after a build that failed."""
@@ -303,12 +321,13 @@ def test_config3_lidar_map_grid(lidar_coords):
 
 
 @pytest.mark.parametrize("K,s,transposed", [(2, 2, False), (3, 2, False), (2, 2, True), (3, 2, True)])
-@pytest.mark.parametrize("use_grid", [False, True])
-def test_kmap_boundary(K, s, transposed, use_grid):
+@pytest.mark.parametrize("route", ["auto", "hash", "grid"])
+def test_kmap_boundary(K, s, transposed, route):
     """Alg. 3's boundary check: outputs on the grid [0, b) only; inputs beyond it feed nothing."""
     coords = _rand_coords(3000 + 7 * K + transposed, 4000, -6, 22, batches=2)
     b = (8, 11, 5)
-    kmap = _check_map(coords, K, s, transposed, grid=grid_of(coords) if use_grid else None, boundary=b)
+    kmap = _check_map(coords, K, s, transposed, grid=grid_of(coords) if route == "grid" else None, boundary=b,
+                      search=ts.TS_SEARCH_HASH if route == "hash" else ts.TS_SEARCH_AUTO)
     outs = (kmap.in_coords() if transposed else kmap.out_coords()).cpu().numpy()
     assert outs.shape[0] > 0 and (outs[:, 1:] >= 0).all() and (outs[:, 1:] < np.array(b)).all()
     free = oracle.out_coords(coords, K, s)
