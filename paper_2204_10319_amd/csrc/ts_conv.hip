@@ -433,7 +433,8 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
     auto issue = [&](int s, auto dc) __attribute__((always_inline)) {
         constexpr int d = decltype(dc)::value;
         const bool real = s < nstage;
-        const int r = it_r, ch = it_ch, n = s_nlist[r];
+        // the offset is the same in every lane: saying so keeps its weight slab's address in scalar registers
+        const int r = it_r, ch = it_ch, n = __builtin_amdgcn_readfirstlane(s_nlist[r]);
         if (s + 1 < nstage) {   // stages are issued in order: step the pair, stay on the last one past the end
             if (++it_ch == nchunks) {
                 it_ch = 0;
