@@ -72,6 +72,8 @@ def main():
     ap.add_argument("--pmc-run", action="store_true")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--step-only", action="store_true")
+    ap.add_argument("--strided-run", action="store_true",
+                    help="20 builds each of the K=2,s=2 and K=3,s=2 (with boundary) maps of config 3, then exit (for the kernel-trace profile)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -121,6 +123,16 @@ def main():
         print(json.dumps({"pmc_run": True, "copy_bytes": COPY_BYTES, "N": int(N)}))
         return
 
+    if args.strided_run:
+        hi = coords_h[:, 1:].max(axis=0)
+        bnd = tuple(int(h + 2) // 2 for h in hi)
+        for _ in range(20):
+            ts.ts_build_kmap(coords, 2, 2).free()
+            ts.ts_build_kmap(coords, 3, 2, boundary=bnd).free()
+        torch.cuda.synchronize()
+        print(json.dumps({"strided_run": True, "N": int(N), "boundary": bnd}))
+        return
+
     for _ in range(args.warmup):
         step().free()
     torch.cuda.synchronize()
@@ -163,8 +175,25 @@ def main():
         ts.ts_copy_bytes(dst, src)
     cp = ts.ts_profile_read()["k_copy_bytes"]
     copy_gbs = 2 * COPY_BYTES / (cp[1] / cp[0] * 1e-3) * 1e-9
+    # achievable MFMA rate: register-only loop of the instruction the layer kernels use
+    sink = torch.zeros(1 << 18, dtype=torch.float32, device="cuda")
+    for _ in range(6):
+        mfma_flops = ts.ts_mfma_loop(4096, sink)
+    ml = ts.ts_profile_read()["k_mfma_loop"]
+    mfma_loop_tflops = mfma_flops / (ml[1] / ml[0] * 1e-3) * 1e-12
     ts.ts_profile_enable(False)
-    del src, dst
+    del src, dst, sink
+
+    # spread of single steps: each step bracketed by an event pair of its own
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+    for a_ev, b_ev in evs:
+        a_ev.record()
+        step().free()
+        b_ev.record()
+    torch.cuda.synchronize()
+    step_us = np.sort(np.array([a_ev.elapsed_time(b_ev) * 1e3 for a_ev, b_ev in evs]))
+    step_spread = {"p10_us": round(float(step_us[20]), 1), "p50_us": round(float(step_us[100]), 1),
+                   "p90_us": round(float(step_us[180]), 1), "n": 200}
 
     def time_calls(fn, iters=50):
         for _ in range(5):
@@ -279,6 +308,7 @@ def main():
     kb = kmap_bytes(N, M, K3, table_slots)
     breakdown = {"kmap_build_us": round(kmap_us, 1), "kmap_algorithmic_bytes": int(kb),
                  "kmap_GBs": round(kb / kmap_us * 1e-3, 1), "copy_kernel_GBs": round(copy_gbs, 1),
+                 "mfma_loop_TFLOPs": round(mfma_loop_tflops, 1), "step_spread": step_spread,
                  "per_kernel_us_per_step": per_kernel, "layers": layers, "grouping_ablation": grouping,
                  "map_search_ablation": search,
                  "sorted_rows": sorted_rows}
@@ -312,6 +342,15 @@ def main():
                                   "kmap_build_us": round(time_calls(lambda: ts.ts_build_kmap(big, K, 1).free(), 10), 1),
                                   "C64": layer_report(kbig, big_h.shape[0], kbig.num_pairs, 64)}
         kbig.free()
+        del big
+        huge_h = tile_batches(coords_h, 100)
+        huge = torch.from_numpy(huge_h).cuda()
+        khuge = ts.ts_build_kmap(huge, K, 1)
+        breakdown["sweep_100x"] = {"N": int(huge_h.shape[0]), "M": int(khuge.num_pairs),
+                                   "kmap_build_us": round(time_calls(lambda: ts.ts_build_kmap(huge, K, 1).free(), 5), 1),
+                                   "C64": layer_report(khuge, huge_h.shape[0], khuge.num_pairs, 64)}
+        khuge.free()
+        del huge
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores (whole config-3 layer)
     cpu = None
@@ -324,7 +363,12 @@ def main():
             oracle.kmap(coords_h, coords_h, K, 1)
             oracle.conv(coords_h, x_h, w_h, K, 1, threads=threads)
             best = min(best, time.perf_counter() - c0)
+        c0 = time.perf_counter()
+        oracle.kmap(coords_h, coords_h, K, 1)
+        oracle.conv(coords_h, x_h, w_h, K, 1, threads=1)
+        one_thread_ms = (time.perf_counter() - c0) * 1e3
         cpu = {"value": round(best * 1e3, 1), "unit": "ms", "cores": threads, "kind": "oracle",
+               "value_1_thread": round(one_thread_ms, 1),
                "sample": f"whole config-3 layer (N={N}, C={C}): oracle map search on 1 thread + Eq.1 sum on "
                          f"{threads} threads, best of 3"}
 

@@ -316,6 +316,12 @@ int ts_release_cache(void);
  * achievable-bandwidth reference and to calibrate hardware byte counters against a known size.
  */
 int ts_copy_bytes(void *dst, const void *src, size_t bytes);
+/*
+ * Register-only loop of fp16 MFMA instructions on every matrix pipe (1024 workgroups x 4 waves x iters x
+ * 8 instructions of 16x16x32): the achievable-MFMA reference of the benchmarks.  sink: device, at least
+ * 1 MiB (never written unless the arithmetic misbehaves); *flops (host) receives the FLOPs one call executes.
+ */
+int ts_mfma_loop(int iters, void *sink, double *flops);
 
 /*
  * Per-kernel timing for benchmarks.  While enabled, the library brackets each kernel launch

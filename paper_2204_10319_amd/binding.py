@@ -29,7 +29,7 @@ EXPORTS = [
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
     "ts_sparse_conv_prepared", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
-    "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_bias_act", "ts_concat_cols",
+    "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_mfma_loop", "ts_bias_act", "ts_concat_cols",
 ]
 
 
@@ -120,6 +120,8 @@ def load_library(path: str | None = None):
     lib.ts_concat_cols.restype = ci
     lib.ts_copy_bytes.argtypes = [vp, vp, ctypes.c_size_t]
     lib.ts_copy_bytes.restype = ci
+    lib.ts_mfma_loop.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.ts_mfma_loop.restype = ci
     lib.ts_profile_enable.argtypes = [ci, ctypes.c_char_p]
     lib.ts_profile_enable.restype = ci
     lib.ts_profile_read.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
@@ -160,6 +162,16 @@ def _use_current_stream():
 
 def ts_set_stream(stream: torch.cuda.Stream | None):
     _check(load_library().ts_set_stream(stream.cuda_stream if stream is not None else None))
+
+
+def ts_mfma_loop(iters: int, sink: torch.Tensor) -> float:
+    """Runs the register-only MFMA loop once; returns the FLOPs it executes (time it with ts_profile_enable)."""
+    _use_current_stream()
+    if not sink.is_cuda or sink.numel() * sink.element_size() < (1 << 20):
+        raise ValueError("sink must be a device tensor of at least 1 MiB")
+    flops = ctypes.c_double(0.0)
+    _check(load_library().ts_mfma_loop(int(iters), sink.data_ptr(), ctypes.byref(flops)))
+    return flops.value
 
 
 def ts_release_cache():

@@ -177,7 +177,41 @@ __global__ void k_copy_bytes(const uint4 *__restrict__ src, uint4 *__restrict__ 
     for (; i < n_vec; i += stride) dst[i] = src[i];
 }
 
+// Register-only loop of fp16 MFMAs (v_mfma_f32_16x16x32_f16), eight independent accumulators per wave:
+// what the matrix pipes sustain when nothing else is in the way.
+typedef _Float16 mfma_half8 __attribute__((ext_vector_type(8)));
+typedef float mfma_float4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256) k_mfma_loop(int iters, float *__restrict__ sink) {
+    mfma_half8 a, b;
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (_Float16)(0.001f * (float)((threadIdx.x + e) & 7));
+        b[e] = (_Float16)(0.002f * (float)((threadIdx.x * 3 + e) & 7));
+    }
+    mfma_float4 acc[8];
+    for (int q = 0; q < 8; ++q) acc[q] = mfma_float4{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[q], 0, 0, 0);
+    }
+    float total = 0.f;
+    for (int q = 0; q < 8; ++q) total += acc[q][0] + acc[q][1] + acc[q][2] + acc[q][3];
+    if (total == -1.f) sink[blockIdx.x * blockDim.x + threadIdx.x] = total;   // never true: keeps the loop alive
+}
+
 extern "C" {
+
+int ts_mfma_loop(int iters, void *sink, double *flops) {
+    if (!sink || !flops) return ts::fail(TS_ERR_INVALID_ARG, "NULL pointer");
+    if (iters < 1 || iters > (1 << 20)) return ts::fail(TS_ERR_INVALID_ARG, "iters must be in [1, 2^20]");
+    const int blocks = 256 * 4;   // four workgroups of four waves per CU: four waves per SIMD
+    {
+        ts::ProfScope ps("k_mfma_loop");
+        hipLaunchKernelGGL(k_mfma_loop, dim3(blocks), dim3(256), 0, ts::g_stream, iters, static_cast<float *>(sink));
+    }
+    TS_HIP(hipGetLastError());
+    *flops = (double)blocks * 4.0 * (double)iters * 8.0 * (2.0 * 16 * 16 * 32);
+    return TS_OK;
+}
 
 int ts_copy_bytes(void *dst, const void *src, size_t bytes) {
     if (!dst || !src) return ts::fail(TS_ERR_INVALID_ARG, "NULL pointer");
