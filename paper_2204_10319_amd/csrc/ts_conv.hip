@@ -346,38 +346,41 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
     if (threadIdx.x == 0) ticket = atomicAdd(&sched[xcd * 32], 1);
 
     // Neighbour rows of the tile's outputs -> LDS (offset-major), and the OR of their offset
-    // bitmasks.  Two threads share an output row and read half of its table row each.
+    // bitmasks.  The 16-byte chunks of a table row go to neighbouring lanes, so that one load
+    // instruction covers whole rows (a row touched by several instructions costs a request each).
     if (threadIdx.x == 0) s_mask = 0;
     __syncthreads();
     {
-        const int half = threadIdx.x >> 7, col = threadIdx.x & 127;
-        const int64_t pos = tile * kTileRows + col;
-        const int32_t k = perm ? perm[pos] : (pos < n_out ? (int32_t)pos : -1);
-        const int chunks = stride / 4, cph = chunks >= 2 ? chunks / 2 : 1;
-        const int4 *src = reinterpret_cast<const int4 *>(nbr + (int64_t)(k >= 0 ? k : 0) * stride);
+        const int chunks = stride / 4;                       // 8, 4 or 1 lanes per row
+        const int ch = threadIdx.x % chunks, sub = threadIdx.x / chunks;
+        const int rows_per_pass = kThreads / chunks;         // 32, 64 or 256
         int4 v[4];
+        int32_t kk[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int ch = half * cph + i;
+            const int col = i * rows_per_pass + sub;
+            const int64_t pos = tile * kTileRows + col;
+            kk[i] = -2;                                      // -2: no row of the tile in this pass
+            if (col < kTileRows) kk[i] = perm ? perm[pos] : (pos < n_out ? (int32_t)pos : -1);
             v[i] = make_int4(-1, -1, -1, -1);
-            if (k >= 0 && i < cph && ch < chunks) v[i] = src[ch];
+            if (kk[i] >= 0) v[i] = reinterpret_cast<const int4 *>(nbr + (int64_t)kk[i] * stride)[ch];
         }
         uint32_t mm = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int ch = half * cph + i;
-            if (i < cph && ch < chunks) {
-                const int32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+            if (kk[i] == -2) continue;
+            const int col = i * rows_per_pass + sub;
+            const int32_t k = kk[i];
+            const int32_t e[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int idx = ch * 4 + q;
-                    // the row's offsets are read off its entries (the bitmask word of the table and
-                    // the centre entry may not have been written yet: a map's row pass runs on demand)
-                    if (idx < K3) {
-                        const int32_t j = idx == centre ? k : (k >= 0 ? e[q] : -1);
-                        lds_j[idx][col] = j;
-                        if (j >= 0) mm |= 1u << idx;
-                    }
+            for (int q = 0; q < 4; ++q) {
+                const int idx = ch * 4 + q;
+                // the row's offsets are read off its entries (the bitmask word of the table and
+                // the centre entry may not have been written yet: a map's row pass runs on demand)
+                if (idx < K3) {
+                    const int32_t j = idx == centre ? k : (k >= 0 ? e[q] : -1);
+                    lds_j[idx][col] = j;
+                    if (j >= 0) mm |= 1u << idx;
                 }
             }
         }
