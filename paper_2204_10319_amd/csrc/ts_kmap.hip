@@ -49,6 +49,10 @@ enum {
     ST_WORDS = 40
 };
 
+// Error flags are raised with a plain store of 1: every writer stores the same value, and the word may
+// live in pinned host memory (a build nobody waits for reports straight to the host, without a copy).
+__device__ __forceinline__ void raise_flag(int *status, int which) { *reinterpret_cast<volatile int *>(&status[which]) = 1; }
+
 // ---- coordinate hash table ------------------------------------------------------------------------
 // Open addressing over two arrays: 64-bit keys (what lookups read) and 32-bit values (read on a
 // hit only).  Random lookups cost about twice as much once the array they walk no longer fits a
@@ -95,7 +99,7 @@ __device__ __forceinline__ void table_insert(const Table &t, uint64_t key, int32
             return;
         }
         if (prev == key) {
-            atomicOr(&status[ST_DUP], 1);
+            raise_flag(status, ST_DUP);
             return;
         }
         slot = next_slot(slot, t.mask);   // the table is at most half full, so an empty slot exists
@@ -138,10 +142,10 @@ __device__ __forceinline__ int64_t grid_cell(const Grid &g, uint64_t key) {
 __device__ __forceinline__ void table_insert(const Grid &g, uint64_t key, int32_t value, int *status) {
     const int64_t cell = grid_cell(g, key);
     if (cell < 0) {
-        atomicOr(&status[ST_RANGE], 1);
+        raise_flag(status, ST_RANGE);
         return;
     }
-    if (atomicCAS(&g.vals[cell], -1, value) != -1) atomicOr(&status[ST_DUP], 1);
+    if (atomicCAS(&g.vals[cell], -1, value) != -1) raise_flag(status, ST_DUP);
 }
 
 __device__ __forceinline__ int32_t table_find(const Grid &g, uint64_t want) {
@@ -230,7 +234,7 @@ __global__ void __launch_bounds__(kThreads) k_pack(const int4 *coords, int64_t n
     if (i < n) {
         int4 c = coords[i];
         if (!coord_ok(c) || !in_box(c, box)) {
-            atomicOr(&status[ST_RANGE], 1);
+            raise_flag(status, ST_RANGE);
             keys[i] = kEmptyKey;
         } else {
             keys[i] = pack_key(c.x, c.y, c.z, c.w);
@@ -268,7 +272,7 @@ __global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, Tab
     if (i >= n) return;
     int4 c = coords[i];
     if (!coord_ok(c) || !in_box(c, box)) {
-        atomicOr(&status[ST_RANGE], 1);
+        raise_flag(status, ST_RANGE);
         keys[i] = kEmptyKey;
         return;
     }
@@ -318,7 +322,7 @@ __global__ void k_candidates_mark(const uint64_t *keys, int64_t n, int K, int s,
     if (cand == kEmptyKey) return;
     const int64_t cell = grid_cell(cbox, cand);
     if (cell < 0) {
-        atomicOr(&status[ST_RANGE], 1);
+        raise_flag(status, ST_RANGE);
         return;
     }
     atomicOr(&bits[cell >> 5], 1u << (cell & 31));
@@ -1051,6 +1055,7 @@ int make_mask_hash(Temps &tmp, MaskHash *mh, FillArgs *fill) {
 // (ts_build_kmap_async), each with the event that says the copy has arrived.
 struct StatusSlot {
     int32_t *host = nullptr;
+    int32_t *dev = nullptr;     // the same words as kernels address them
     hipEvent_t ev = nullptr;
     bool busy = false;          // a copy is in flight or has not been read yet
     const ts_kmap *owner = nullptr;   // NULL while busy: the map was freed before anyone asked
@@ -1066,7 +1071,15 @@ int slot_acquire() {
             mem = nullptr;
             return -1;
         }
-        for (int i = 0; i < kStatusSlots; ++i) g_slots[i].host = mem + i * ST_WORDS;
+        void *dview = nullptr;
+        if (hipHostGetDevicePointer(&dview, mem, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            dview = nullptr;
+        }
+        for (int i = 0; i < kStatusSlots; ++i) {
+            g_slots[i].host = mem + i * ST_WORDS;
+            g_slots[i].dev = dview ? static_cast<int32_t *>(dview) + i * ST_WORDS : nullptr;
+        }
     }
     for (int i = 0; i < kStatusSlots; ++i) {
         StatusSlot &s = g_slots[i];
@@ -1140,7 +1153,7 @@ void launch_probe(const ts_kmap *m, const Searched &sd, int32_t *colcnt, uint32_
 // Map search and everything after it.  `table` holds the searched point set (the map's inputs);
 // m->d_out_keys the outputs; the clearing of the status words (and of the neighbour table where the
 // search writes hits only) has been enqueued.
-int search_and_finish(ts_kmap *m, Temps &tmp, const Searched &table, int *d_status, bool wait) {
+int search_and_finish(ts_kmap *m, Temps &tmp, const Searched &table, int *d_status, bool wait, int early_slot = -1) {
     hipStream_t st = stream();
     const int K3 = m->K3, K = m->K;
     const int64_t n_out = m->n_out;
@@ -1170,10 +1183,11 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Searched &table, int *d_stat
             // A caller that does not wait gets the map with its search done: what the fused layer
             // kernel reads.  The row pass and the scan (bitmask words, rank bitmaps, sizes, tile order)
             // run when something first needs them (ts::resolve).  Error flags are known already.
-            const int slot = slot_acquire();
+            // (early_slot: the kernels raised their flags in the slot's pinned words themselves.)
+            const int slot = early_slot >= 0 ? early_slot : slot_acquire();
             if (slot >= 0) {
                 StatusSlot &sl = g_slots[slot];
-                TS_HIP(hipMemcpyAsync(sl.host, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+                if (early_slot < 0) TS_HIP(hipMemcpyAsync(sl.host, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
                 TS_HIP(hipEventRecord(sl.ev, st));
                 sl.busy = true;
                 sl.owner = m;
@@ -1333,9 +1347,20 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
 
     Searched table;
     const dim3 per_point(blocks_for(N, kThreads)), block(kThreads);
+    int early_slot = -1;
     if (s == 1) {
         m->n_in = m->n_out = N;
         m->d_out_keys = given;
+        if (!wait && K == 3) {
+            // Nobody waits for this build: its error flags go straight into pinned host words (plain
+            // stores, raised on bad input only), which saves the copy at the end of the build.
+            const int slot = slot_acquire();
+            if (slot >= 0 && g_slots[slot].dev) {
+                std::memset(g_slots[slot].host, 0, ST_WORDS * sizeof(int32_t));
+                d_status = g_slots[slot].dev;
+                early_slot = slot;
+            }
+        }
         TS_TRY(alloc_outputs(m, &fill));
         TS_TRY(make_searched(tmp, opt, N, opt.box.lo, opt.box.hi, &table, &fill));
         TS_TRY(launch_fill(fill));
@@ -1501,7 +1526,7 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
         }
     }
     TS_HIP(hipGetLastError());
-    return search_and_finish(m, tmp, table, d_status, wait);
+    return search_and_finish(m, tmp, table, d_status, wait, early_slot);
 }
 
 }  // namespace
