@@ -317,14 +317,16 @@ __global__ void k_candidates(const uint64_t *keys, int64_t n, int K, int s, int 
 __global__ void k_candidates_mark(const uint64_t *keys, int64_t n, int K, int s, int A, Bound bound, Grid cbox,
                                   uint32_t *bits, int *status) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const uint64_t cand = candidate_key(keys[i], blockIdx.y, K, s, A, bound);
+    const uint64_t cand = i < n ? candidate_key(keys[i], blockIdx.y, K, s, A, bound) : kEmptyKey;
+    const int64_t cell = cand == kEmptyKey ? -1 : grid_cell(cbox, cand);
+    // neighbours in row order are often neighbours in space: a lane whose predecessor marks the same cell stays silent
+    const int64_t before = __shfl_up(cell, 1, 64);
     if (cand == kEmptyKey) return;
-    const int64_t cell = grid_cell(cbox, cand);
     if (cell < 0) {
         raise_flag(status, ST_RANGE);
         return;
     }
+    if ((threadIdx.x & 63) != 0 && before == cell) return;
     atomicOr(&bits[cell >> 5], 1u << (cell & 31));
 }
 
@@ -733,17 +735,30 @@ __global__ void __launch_bounds__(kThreads) k_bits_expand(const uint64_t *__rest
     uint64_t bits = w < n_words ? words[w] : 0;
     int total;
     int64_t at = block_base[blockIdx.x] + block_exclusive_scan(__popcll(bits), &total);
+    if (bits == 0) return;
+    // coordinates of the word's first cell once (a box holds at most 2^30 cells: 32-bit arithmetic),
+    // then every set bit is that cell moved along z, carrying into y, x and the batch index
+    uint32_t cell = (uint32_t)w * 64u;
+    uint32_t z0 = cell % cbox.ext[2];
+    cell /= cbox.ext[2];
+    uint32_t y0 = cell % cbox.ext[1];
+    cell /= cbox.ext[1];
+    uint32_t x0 = cell % cbox.ext[0], b0 = cell / cbox.ext[0];
     while (bits) {
         const int bit = __builtin_ctzll(bits);
         bits &= bits - 1;
-        uint64_t cell = (uint64_t)w * 64 + bit;
-        const int32_t z = (int32_t)(cell % cbox.ext[2]);
-        cell /= cbox.ext[2];
-        const int32_t y = (int32_t)(cell % cbox.ext[1]);
-        cell /= cbox.ext[1];
-        const int32_t x = (int32_t)(cell % cbox.ext[0]);
-        const int32_t b = (int32_t)(cell / cbox.ext[0]);
-        out_keys[at++] = pack_key(b, x + cbox.lo[0], y + cbox.lo[1], z + cbox.lo[2]);
+        uint32_t z = z0 + (uint32_t)bit, y = y0, x = x0, b = b0;
+        while (z >= cbox.ext[2]) {
+            z -= cbox.ext[2];
+            if (++y == cbox.ext[1]) {
+                y = 0;
+                if (++x == cbox.ext[0]) {
+                    x = 0;
+                    ++b;
+                }
+            }
+        }
+        out_keys[at++] = pack_key((int32_t)b, (int32_t)x + cbox.lo[0], (int32_t)y + cbox.lo[1], (int32_t)z + cbox.lo[2]);
     }
 }
 
