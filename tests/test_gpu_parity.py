@@ -125,6 +125,30 @@ def test_layer_narrow_input(c_in):
     _layer_case(coords, c_in, 32, 3, 1, False, torch.float16, seed=c_in)
 
 
+@pytest.mark.parametrize("c_in,c_out", [(96, 96), (160, 64), (224, 32), (72, 32)])
+@pytest.mark.parametrize("K,s,transposed", [(3, 1, False), (2, 2, True)])
+def test_layer_channel_counts_that_are_odd_multiples_of_32(c_in, c_out, K, s, transposed):
+    """Rows of 96, 160, 224 channels (and 72, padded to 96): chunking by 32 channels; nothing read past a
+    row's end (the start of the next row) may count."""
+    coords = _rand_coords(91 + c_in, 1300, -6, 6, batches=2)
+    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
+    x = features(910 + c_in, kmap.num_in, c_in, np.float16)
+    w = conv_weights(911 + c_in, K ** 3, c_in, c_out, np.float16)
+    ref = oracle_conv(coords, x, w, K, s, transposed)
+    pw = ts.ts_weights_prepare(to_dev(w))
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+        check_features(ts.ts_sparse_conv(to_dev(x), to_dev(w), kmap, dataflow=df), ref, torch.float16, f"C {c_in}->{c_out} dataflow {df}")
+    check_features(ts.ts_sparse_conv_prepared(to_dev(x), pw, kmap), ref, torch.float16, f"C {c_in}->{c_out} prepared")
+    # a large value in the first channel of every row, with zero weights: a step that multiplied the next row's
+    # start into the sums would show
+    x2 = x.copy()
+    x2[:, 0] = np.float16(60000.0)
+    w2 = w.copy()
+    w2[:, 0, :] = 0
+    ref2 = oracle_conv(coords, x2, w2, K, s, transposed)
+    check_features(ts.ts_sparse_conv(to_dev(x2), to_dev(w2), kmap, dataflow=ts.TS_DATAFLOW_FUSED), ref2, torch.float16, "large first channel")
+
+
 def test_layer_empty():
     kmap = ts.ts_build_kmap(torch.zeros((0, 4), dtype=torch.int32, device="cuda"), 3, 1)
     x = torch.zeros((0, 32), dtype=torch.float16, device="cuda")
