@@ -427,6 +427,34 @@ def test_adaptive_grouping_same_result_in_the_launches_of_alg4(K, s):
         assert stats["launches"] == 2 and stats["padded_rows"] == 26 * int(sizes[:13].max()) + int(sizes[13])
 
 
+def test_group_search_on_the_device():
+    """Appendix B, Alg. 5 with the measured cost: the pair it returns is the cheapest of its own table."""
+    from paper_2204_10319_amd import tuner
+    coords = lidar_scan_coords(34, n_beams=16, n_azimuth=512)
+    kmap = ts.ts_build_kmap(to_dev(coords), 3, 1)
+    x = to_dev(features(540, coords.shape[0], 32, np.float16))
+    w = to_dev(conv_weights(541, 27, 32, 32, np.float16))
+    F = ts.ts_gather(x, kmap)
+    G = torch.empty((kmap.num_pairs, 32), dtype=torch.float32, device="cuda")
+    eps, S, cost, table = tuner.adaptive_group_search([(F, x, w, kmap, G)], eps_space=(0.0, 0.5, 1.0), S_space=(0, 1 << 40),
+                                                      cost=tuner.measured_cost(iters=3, warmup=1))
+    assert len(table) == 6 and (eps, S) in table and cost == min(table.values()) and cost > 0
+    assert torch.equal(G, ts.ts_grouped_matmul(F, x, w, kmap))
+
+
+def test_reference_kernels_of_the_benchmark():
+    """The copy and MFMA-loop kernels bench.py measures achievable rates with."""
+    src = torch.arange(1 << 18, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    ts.ts_copy_bytes(dst, src)
+    assert torch.equal(dst, src)
+    sink = torch.zeros(1 << 18, dtype=torch.float32, device="cuda")
+    flops = ts.ts_mfma_loop(16, sink)
+    torch.cuda.synchronize()
+    assert flops == 1024 * 4 * 16 * 8 * 2 * 16 * 16 * 32
+    assert float(sink.abs().sum()) == 0.0
+
+
 def test_results_are_deterministic(lidar_coords):
     kmap_a = ts.ts_build_kmap(to_dev(lidar_coords), 3, 1)
     kmap_b = ts.ts_build_kmap(to_dev(lidar_coords), 3, 1)
