@@ -330,6 +330,11 @@ def main():
         del graph
         SparseNet.free_maps(maps)
         net_report["maps_build_ms" + tag] = round(maps_us * 1e-3, 3)
+        if not srt:
+            # the same maps through the coordinate grid over the voxel grid of the recipe (2048 x 2048 x 80 cells)
+            vbox = ((0, 0, 0), (2047, 2047, 79), 1)
+            SparseNet.free_maps(net.build_maps(coords, False, vbox)[0])
+            net_report["maps_build_ms_grid"] = round(time_calls(lambda: SparseNet.free_maps(net.build_maps(coords, False, vbox)[0]), 5) * 1e-3, 3)
         net_report["forward_ms" + tag] = round(fwd_us * 1e-3, 3)
         net_report["forward_graph_ms" + tag] = round(graph_us * 1e-3, 3)
     breakdown["config5_network"] = net_report

@@ -20,29 +20,35 @@ class SparseNet:
         # weights do not change between passes: repack them for the kernels once
         self.prepared = {name: ts.ts_weights_prepare(w) for name, (w, _) in params.items()}
 
-    def build_maps(self, coords: torch.Tensor, sort_rows: bool = False):
+    def build_maps(self, coords: torch.Tensor, sort_rows: bool = False, box=None):
         """Kernel maps for every (kind, level) of the plan, plus the coordinates of each level.
         With ``sort_rows`` the 3x3x3 maps, which serve 4 to 9 layers each, get their output rows
-        ordered by offset bitmask (``ts_kmap_sort_rows``)."""
+        ordered by offset bitmask (``ts_kmap_sort_rows``).  ``box`` = (lo[3], hi[3], batches), the
+        voxel grid the coordinates were quantised to, if the caller knows it: every build then
+        searches through the coordinate grid (Sec. 4.4) over the box of its level (halved per
+        level), and the strided builds need not measure theirs."""
         kinds = []
         for k, op in self.ops:
             if k == "conv" and op["map"] not in kinds:
                 kinds.append(op["map"])
         levels = {0: coords}
+        boxes = {0: box}
         maps = {}
         top = max(level for _, level in kinds)
         for level in range(top + 1):
             if ("down", level) in kinds or ("up", level) in kinds:
-                down = ts.ts_build_kmap(levels[level], 2, 2, False, wait=False)
+                down = ts.ts_build_kmap(levels[level], 2, 2, False, wait=False, grid=boxes[level])
                 maps[("down", level)] = down
                 levels[level + 1] = down.out_coords()
+                b = boxes[level]
+                boxes[level + 1] = None if b is None else (tuple(v // 2 for v in b[0]), tuple(v // 2 for v in b[1]), b[2])
         for kind, level in kinds:
             if kind == "sub":
-                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 3, 1, False, wait=False)
+                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 3, 1, False, wait=False, grid=boxes.get(level))
                 if sort_rows:
                     maps[(kind, level)].sort_rows()
             elif kind == "id":
-                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 1, 1, False, wait=False)
+                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 1, 1, False, wait=False, grid=boxes.get(level))
             elif kind == "up":
                 maps[(kind, level)] = maps[("down", level)].transpose()
         for m in maps.values():

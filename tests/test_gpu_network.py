@@ -19,14 +19,14 @@ from _util import to_dev
 pytestmark = pytest.mark.gpu
 
 
-def _run_both(coords, seed):
+def _run_both(coords, seed, box=None):
     ops, output = build_plan(4)
     params = make_params(seed, ops)
     x = features(seed + 1, coords.shape[0], 4, np.float16)
     ref = {}
     y_ref, levels = run_plan(ops, output, params, coords, x, hook=lambda n, v: ref.__setitem__(n, v))
     net = SparseNet(ops, output, {k: (to_dev(w), to_dev(b)) for k, (w, b) in params.items()})
-    maps, dev_levels = net.build_maps(to_dev(coords))
+    maps, dev_levels = net.build_maps(to_dev(coords), box=box)
     for level, c in levels.items():
         assert np.array_equal(dev_levels[level].cpu().numpy(), c), f"level {level} coordinates"
     got = {}
@@ -52,6 +52,13 @@ def test_network_small_scene():
     coords = lidar_scan_coords(4, n_sweeps=1)
     worst, n = _run_both(coords, seed=40)
     print(f"config 5 (1 sweep): {n} tensors, worst rel L2 {worst:.2e}")
+
+
+def test_network_maps_through_the_coordinate_grid():
+    """The same pass with every map built through the grid over the recipe's voxel grid (2048 x 2048 x 80 cells)."""
+    coords = lidar_scan_coords(4, n_sweeps=1)
+    worst, n = _run_both(coords, seed=41, box=((0, 0, 0), (2047, 2047, 79), 1))
+    print(f"config 5 (1 sweep, grid search): {n} tensors, worst rel L2 {worst:.2e}")
 
 
 @pytest.mark.timeout(600)
