@@ -323,7 +323,6 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
     __shared__ u32x4 lds_w[2][SLAB];
     __shared__ int32_t lds_j[kMaxK3][kTileRows];
     __shared__ uint32_t s_mask;
-    __shared__ int s_nlist[32];
     __shared__ int s_tile;
     // The launch holds as many workgroups as stay resident at once.  Workgroup b starts with tile b;
     // the tiles beyond the grid are handed out through counters, so nobody waits for a second
@@ -388,13 +387,8 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
         if (lane == 0 && mm) atomicOr(&s_mask, mm);
     }
     __syncthreads();
-    const uint32_t mask = s_mask;
-    if (threadIdx.x < 32) {
-        // offsets present in the tile, ascending: s_nlist[r] = r-th set bit of the mask
-        const uint32_t below = mask & ((1u << threadIdx.x) - 1u);
-        if ((mask >> threadIdx.x) & 1u) s_nlist[__builtin_popcount(below)] = threadIdx.x;
-    }
-    __syncthreads();
+    // the offsets present in the tile, as a bitmask in a scalar register: the stages walk its set bits
+    const uint32_t mask = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_mask);
     const int nchunks = cin / KC;
     const int nstage = __builtin_popcount(mask) * nchunks;
     const int cblocks = cout / 16;
@@ -428,7 +422,11 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
         if (SLAB % kThreads != 0) idx = idx < SLAB ? idx : SLAB - 1;   // surplus threads repeat the last vector
         wlane[v] = idx * 16;
     }
-    int it_r = 0, it_ch = 0;   // (offset rank, chunk) of the next stage to issue
+    uint32_t it_rem = mask ? mask : 1u;   // offsets not issued yet; the lowest set bit is the one being issued
+    int it_ch = 0;                        // its chunk
+    // neighbour rows of the lane's two outputs for the stage issued next: read out of LDS one stage
+    // ahead, so that no stage waits for them
+    int32_t pj0 = lds_j[__builtin_ctz(it_rem)][r0], pj1 = lds_j[__builtin_ctz(it_rem)][r1];
     // Issue the loads of stage s into register set d (a compile-time constant at every call).
     // Every call issues the same loads, unconditionally (past the last stage it repeats that
     // stage): the compiler counts outstanding loads to place its waits, and a load it cannot count
@@ -436,18 +434,19 @@ __global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restri
     auto issue = [&](int s, auto dc) __attribute__((always_inline)) {
         constexpr int d = decltype(dc)::value;
         const bool real = s < nstage;
-        // the offset is the same in every lane: saying so keeps its weight slab's address in scalar registers
-        const int r = it_r, ch = it_ch, n = __builtin_amdgcn_readfirstlane(s_nlist[r]);
+        const int ch = it_ch, n = __builtin_ctz(it_rem);   // scalar: the weight slab's address stays in scalar registers
+        const int32_t j0 = pj0, j1 = pj1;
         if (s + 1 < nstage) {   // stages are issued in order: step the pair, stay on the last one past the end
             if (++it_ch == nchunks) {
                 it_ch = 0;
-                ++it_r;
+                it_rem &= it_rem - 1;
             }
         }
+        pj0 = lds_j[__builtin_ctz(it_rem)][r0];
+        pj1 = lds_j[__builtin_ctz(it_rem)][r1];
         const int wsoff = (((n * nchunks + ch) * cblocks + cb0) * KSTEPS) * 1024;
 #pragma unroll
         for (int v = 0; v < WV; ++v) wreg[d][v] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane[v], wsoff, 0);
-        const int32_t j0 = lds_j[n][r0], j1 = lds_j[n][r1];
         xlive[d] = real && __ballot(j0 >= 0 || j1 >= 0) != 0;   // false: none of the wave's rows has this offset
         const int off0 = j0 >= 0 ? j0 * row_bytes + xlane : kNoRow;
         const int off1 = j1 >= 0 ? j1 * row_bytes + xlane : kNoRow;
