@@ -17,7 +17,8 @@
  *            K=2: {0,1}^3.
  *   stride 1: P_out = P_in, same row order (output k is input k).
  *   stride>1: P_out = distinct candidates (p - delta)/s with s | (p - delta),
- *            in ascending (batch, x, y, z) order; no boundary clipping.
+ *            in ascending (batch, x, y, z) order; clipped to the grid [0, b) when
+ *            a boundary b is given (Alg. 3; ts_build_kmap_ex), else not at all.
  *   transposed: coords are the FINE coordinates (the outputs of the transposed
  *            layer).  The map is the forward (K, s) map fine -> coarse with the
  *            roles swapped: inputs are the coarse points in ascending order,
@@ -96,9 +97,11 @@ typedef struct ts_kmap ts_kmap;
  *   kernel_size  1, 2 or 3 (stride 1 requires odd kernel_size); stride 1 or 2.
  *   transposed   0 or 1 (1 requires stride > 1), see the header comment.
  *   out_kmap     receives the new map; *out_kmap = NULL on error.
- * Internally: pack coordinates to 64-bit keys, (stride>1: candidate keys, sort, unique),
- * insert inputs into an open-addressing hash table, probe s*q_k + delta_n for every
- * output and offset (one row of neighbour indices per output), count per offset.  The
+ * Internally: pack coordinates to 64-bit keys, insert inputs into an open-addressing hash
+ * table, probe s*q_k + delta_n for every output and offset (one row of neighbour indices
+ * per output), count per offset.  A strided build first finds its output coordinates
+ * (Alg. 3) and chooses its route by the bounding box of its input, see ts_build_kmap_ex
+ * (TS_SEARCH_AUTO).  The
  * per-offset pair lists are derived from that when first asked for (ts_kmap_pairs, the
  * explicit dataflow).  Synchronises the stream (it must learn N_out and the map sizes and
  * report bad input).  The map may be reused by any number of ts_sparse_conv calls.
