@@ -358,6 +358,24 @@ def test_kmap_boundary(K, s, transposed, route):
     assert outs.shape[0] < free.shape[0]
 
 
+@pytest.mark.parametrize("K", [2, 3])
+def test_transpose_of_a_map_with_boundary(K):
+    """ts_kmap_transpose of a forward map built with a boundary: the transposed map the oracle gives for the same
+    boundary (fine points all of whose candidates were cut are outputs without a neighbour)."""
+    coords = _rand_coords(3200 + K, 3000, -6, 22, batches=2)
+    b = (8, 11, 5)
+    fwd = ts.ts_build_kmap(to_dev(coords), K, 2, boundary=b)
+    tr = fwd.transpose()
+    in_c, out_c, tri = oracle_map(coords, K, 2, True, boundary=b)
+    assert tr.num_in == in_c.shape[0] and tr.num_out == out_c.shape[0] and tr.num_pairs == tri.shape[0]
+    assert np.array_equal(tr.in_coords().cpu().numpy(), in_c)
+    assert np.array_equal(tr.out_coords().cpu().numpy(), out_c)
+    assert np.array_equal(gpu_triples(tr), tri)
+    hit = np.zeros(coords.shape[0], bool)
+    hit[tri[:, 1]] = True
+    assert 0 < hit.sum() < coords.shape[0]
+
+
 def test_kmap_boundary_that_cuts_everything():
     coords = _rand_coords(3100, 500, 40, 60)
     for K, s, tr in [(2, 2, False), (3, 2, False), (2, 2, True), (3, 2, True)]:
