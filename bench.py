@@ -195,6 +195,24 @@ def main():
     step_spread = {"p10_us": round(float(step_us[20]), 1), "p50_us": round(float(step_us[100]), 1),
                    "p90_us": round(float(step_us[180]), 1), "n": 200}
 
+    # the same step with the map searched through the coordinate grid over the recipe's voxel grid (Sec. 4.4:
+    # the choice the paper makes per layer); not the headline, which stays on the hash table
+    vgrid = ((0, 0, 0), (2047, 2047, 79), 1)
+
+    def step_grid():
+        km = ts.ts_build_kmap(coords, K, 1, wait=False, grid=vgrid)
+        ts.ts_sparse_conv_prepared(x, pw, km, out=out)
+        return km
+
+    for _ in range(10):
+        step_grid().free()
+    torch.cuda.synchronize()
+    g0 = time.perf_counter()
+    for _ in range(200):
+        step_grid().free()
+    torch.cuda.synchronize()
+    step_grid_ms = (time.perf_counter() - g0) * 1e3 / 200
+
     def time_calls(fn, iters=50):
         for _ in range(5):
             fn()
@@ -309,6 +327,7 @@ def main():
     breakdown = {"kmap_build_us": round(kmap_us, 1), "kmap_algorithmic_bytes": int(kb),
                  "kmap_GBs": round(kb / kmap_us * 1e-3, 1), "copy_kernel_GBs": round(copy_gbs, 1),
                  "mfma_loop_TFLOPs": round(mfma_loop_tflops, 1), "step_spread": step_spread,
+                 "step_with_grid_search_ms": round(step_grid_ms, 4),
                  "per_kernel_us_per_step": per_kernel, "layers": layers, "grouping_ablation": grouping,
                  "map_search_ablation": search,
                  "sorted_rows": sorted_rows}
