@@ -309,8 +309,10 @@ __device__ __forceinline__ void static_for(Fn &&fn) {
     static_for_impl(fn, std::make_integer_sequence<int, N>{});
 }
 
+// (Three waves per SIMD are asked for wherever the accumulators leave room: left to itself the compiler
+// takes a few registers more than that allows for the six- and eight-block single-step variants.)
 template <int NCO, int KSTEPS, int DEPTH>
-__global__ void __launch_bounds__(kThreads) k_conv_tile(const _Float16 *__restrict__ X, const u32x4 *__restrict__ Wf,
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NCO * KSTEPS <= 8 ? 3 : 2))) k_conv_tile(const _Float16 *__restrict__ X, const u32x4 *__restrict__ Wf,
                                                         const int32_t *__restrict__ nbr, int stride,
                                                         const int32_t *__restrict__ perm,
                                                         const int32_t *__restrict__ tile_order, int64_t n_out,
