@@ -124,6 +124,14 @@ int ts_build_kmap_async(const int32_t *coords, int64_t N, int kernel_size, int s
                         ts_kmap **out_kmap);
 /* Waits for an asynchronous build's verdict: TS_OK, TS_ERR_DUPLICATE_COORD or TS_ERR_COORD_RANGE. */
 int ts_kmap_status(const ts_kmap *kmap);
+/*
+ * Optional, for a map from ts_build_kmap_async that will serve more than a fused layer: enqueues, without
+ * waiting, the part of the build that was put off (the pass that counts each offset's pairs), so that a
+ * later ts_kmap_status / accessor / explicit-dataflow call only waits instead of running it then.  A caller
+ * that builds several maps calls this on each and then ts_kmap_status on each: the waits overlap.
+ * No effect on maps that have nothing put off.
+ */
+int ts_kmap_prepare(const ts_kmap *kmap);
 
 /*
  * ts_build_kmap with the choices the paper leaves to each layer (Sec. 4.4; Alg. 3).  options == NULL

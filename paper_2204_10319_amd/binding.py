@@ -25,7 +25,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libts.so")
 _lib = None
 
 EXPORTS = [
-    "ts_build_kmap", "ts_build_kmap_async", "ts_build_kmap_ex", "ts_kmap_status", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
+    "ts_build_kmap", "ts_build_kmap_async", "ts_build_kmap_ex", "ts_kmap_status", "ts_kmap_prepare", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
     "ts_sparse_conv_prepared", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
@@ -70,6 +70,8 @@ def load_library(path: str | None = None):
     lib.ts_build_kmap.restype = ci
     lib.ts_build_kmap_async.argtypes = [vp, i64, ci, ci, ci, ctypes.POINTER(vp)]
     lib.ts_build_kmap_async.restype = ci
+    lib.ts_kmap_prepare.argtypes = [vp]
+    lib.ts_kmap_prepare.restype = ci
     lib.ts_build_kmap_ex.argtypes = [vp, i64, ci, ci, ci, ctypes.POINTER(KMapOptions), ctypes.POINTER(vp)]
     lib.ts_build_kmap_ex.restype = ci
     lib.ts_kmap_status.argtypes = [vp]
@@ -263,6 +265,12 @@ class KMap:
     def status(self):
         """Waits for an asynchronous build's verdict; raises TsError if the input was bad."""
         _check(load_library().ts_kmap_status(self.handle))
+        return self
+
+    def prepare(self):
+        """Enqueues, without waiting, what an asynchronous build put off (ts_kmap_prepare)."""
+        _use_current_stream()
+        _check(load_library().ts_kmap_prepare(self.handle))
         return self
 
     def transpose(self) -> "KMap":

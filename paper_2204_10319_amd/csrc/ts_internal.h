@@ -67,6 +67,9 @@ inline int alloc_n(T **p, size_t n) {
 // ts_build_kmap_async, and fills in M / sizes / offs.  Returns TS_OK or the build's error.
 int resolve(const struct ::ts_kmap *kmap);
 
+// Enqueues, without waiting, what an asynchronous build put off (ts_kmap_prepare).
+int prepare(const struct ::ts_kmap *kmap);
+
 // Makes sure the offset-major pair lists of a map exist (they are derived on first use).
 int ensure_pairs(const struct ::ts_kmap *kmap);
 
@@ -124,6 +127,7 @@ struct ts_kmap {
     int centre = -1;            // index of the identity offset (odd K, stride 1), else -1
     int stride = 0;             // nbr_stride(K3)
     int64_t n_in = 0, n_out = 0, M = 0;   // M, sizes, offs: valid once ts::resolve has run
+    bool rows_enqueued = false; // the put-off row pass and scan have been enqueued (ts_kmap_prepare); resolve only waits
     bool rows_done = true;      // false: the row pass (bitmask words, centre entries, rank bitmaps, tile order) and the
                                 // scan have not run yet; ts::resolve runs them (the fused kernel needs none of it)
     int pending_slot = -1;      // >= 0: sizes and error flags are still on their way to the host

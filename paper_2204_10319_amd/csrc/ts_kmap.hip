@@ -1614,6 +1614,10 @@ int resolve(const ts_kmap *kmap) {
         sl.busy = false;
         sl.owner = nullptr;
         m->pending_slot = -1;
+        if (m->rows_enqueued) {   // ts_kmap_prepare ran the row pass and the scan behind the build; their sizes came with the flags
+            m->rows_enqueued = false;
+            m->rows_done = true;
+        }
     }
     if (!m->rows_done && m->error == TS_OK) {
         // the part of a stride-1 build that was put off: row pass, scan, sizes
@@ -1647,6 +1651,28 @@ void release_grid() {
     g_grid = nullptr;
     g_grid_cells = 0;
     g_grid_dirty = false;
+}
+
+// The part of a 3x3x3 stride-1 build that ts_build_kmap_async put off, enqueued without a wait: its
+// sizes land in the pinned words the build's flags went to, and the event is recorded again behind it.
+int prepare(const ts_kmap *kmap) {
+    ts_kmap *m = const_cast<ts_kmap *>(kmap);
+    if (m->rows_done || m->rows_enqueued || m->pending_slot < 0) return TS_OK;   // nothing put off, or resolve will do it
+    StatusSlot &sl = g_slots[m->pending_slot];
+    if (!sl.dev) return TS_OK;
+    Temps tmp;
+    int32_t *colcnt;
+    uint32_t *wavemask;
+    TS_TRY(tmp.get(&colcnt, (size_t)m->K3 * m->n_blocks));
+    TS_TRY(tmp.get(&wavemask, (size_t)m->n_blocks));
+    TS_LAUNCH("k_rows", (k_rows<27, true>), dim3(blocks_for(m->n_out, kThreads)), dim3(kThreads), m->d_nbr, m->d_out_keys,
+              m->n_out, m->d_colbits, colcnt, wavemask, m->n_blocks);
+    TS_LAUNCH("k_scan", k_scan, dim3(m->K3 + 1), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, sl.dev, m->K3, wavemask,
+              m->n_tiles, m->d_tile_order);
+    TS_HIP(hipEventRecord(sl.ev, stream()));
+    TS_HIP(hipGetLastError());
+    m->rows_enqueued = true;
+    return TS_OK;
 }
 
 Offs offs_of(const ts_kmap *kmap) {
@@ -1759,6 +1785,11 @@ int ts_build_kmap_ex(const int32_t *coords, int64_t N, int kernel_size, int stri
 int ts_kmap_status(const ts_kmap *kmap) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
     return ts::resolve(kmap);
+}
+
+int ts_kmap_prepare(const ts_kmap *kmap) {
+    if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    return ts::prepare(kmap);
 }
 
 void ts_free(ts_kmap *kmap) { destroy(kmap); }

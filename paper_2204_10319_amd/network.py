@@ -52,6 +52,8 @@ class SparseNet:
             elif kind == "up":
                 maps[(kind, level)] = maps[("down", level)].transpose()
         for m in maps.values():
+            m.prepare()     # these maps serve several layers each: the put-off parts of their builds, enqueued together
+        for m in maps.values():
             m.status()      # builds did not wait one by one; bad coordinates are reported here
         return maps, levels
 

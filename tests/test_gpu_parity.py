@@ -445,6 +445,34 @@ def test_adaptive_grouping_same_result_in_the_launches_of_alg4(K, s):
         assert stats["launches"] == 2 and stats["padded_rows"] == 26 * int(sizes[:13].max()) + int(sizes[13])
 
 
+def test_prepare_after_an_asynchronous_build(lidar_coords):
+    """ts_kmap_prepare enqueues the put-off row pass of asynchronous builds; the maps, their sizes and the
+    verdicts are those of the waiting build, also when several builds are prepared before any is asked."""
+    small = _rand_coords(61, 3000, -10, 10, batches=2)
+    dup = np.concatenate([small, small[:1]])
+    ms = [ts.ts_build_kmap(to_dev(c), 3, 1, wait=False) for c in (lidar_coords, small, dup, small[:1])]
+    for m in ms:
+        m.prepare()
+    for m in ms:
+        m.prepare()                                   # a second call has nothing left to do
+    for m, c in zip(ms, (lidar_coords, small, dup, small[:1])):
+        if c is dup:
+            with pytest.raises(ts.TsError) as e:
+                m.status()
+            assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
+            continue
+        m.status()
+        tri = oracle_map(c, 3, 1)[2]
+        assert m.num_pairs == tri.shape[0]
+        assert np.array_equal(m.sizes(), np.bincount(tri[:, 2], minlength=27))
+        assert np.array_equal(gpu_triples(m), tri)
+    x = to_dev(features(610, small.shape[0], 32, np.float16))
+    w = to_dev(conv_weights(611, 27, 32, 32, np.float16))
+    ref = oracle_conv(small, x.cpu().numpy(), w.cpu().numpy(), 3, 1)
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+        check_features(ts.ts_sparse_conv(x, w, ms[1], dataflow=df), ref, torch.float16, f"prepared map, dataflow {df}")
+
+
 def test_group_search_on_the_device():
     """Appendix B, Alg. 5 with the measured cost: the pair it returns is the cheapest of its own table."""
     from paper_2204_10319_amd import tuner
