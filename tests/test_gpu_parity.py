@@ -445,6 +445,60 @@ def test_adaptive_grouping_same_result_in_the_launches_of_alg4(K, s):
         assert stats["launches"] == 2 and stats["padded_rows"] == 26 * int(sizes[:13].max()) + int(sizes[13])
 
 
+@pytest.mark.parametrize("c", [32, 64, 128, 96])
+def test_layers_on_a_map_nobody_waited_for(c):
+    """A 3x3x3 stride-1 map from the asynchronous build, used in every order: fused first, fused again, explicit,
+    accessors, an epilogue, sorted rows; whatever the build put off runs when it is first needed."""
+    coords = lidar_scan_coords(35, n_beams=32, n_azimuth=1024)
+    n = coords.shape[0]
+    x_h, w_h = features(620 + c, n, c, np.float16), conv_weights(621 + c, 27, c, c, np.float16)
+    x, w = to_dev(x_h), to_dev(w_h)
+    ref = oracle_conv(coords, x_h, w_h, 3, 1)
+    bias = to_dev(features(622, 1, c, np.float16)[0])
+    kmap = ts.ts_build_kmap(to_dev(coords), 3, 1, wait=False)
+    y1 = ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_FUSED)
+    check_features(y1, ref, torch.float16, "first fused layer")
+    y2 = ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_FUSED)
+    assert torch.equal(y1, y2)
+    y3 = ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_EXPLICIT)
+    check_features(y3, ref, torch.float16, "explicit afterwards")
+    kmap.status()
+    tri = oracle_map(coords, 3, 1)[2]
+    assert np.array_equal(gpu_triples(kmap), tri)
+    # with an epilogue, and a map used by the explicit dataflow or an accessor first
+    k2 = ts.ts_build_kmap(to_dev(coords), 3, 1, wait=False)
+    ya = ts.ts_sparse_conv_act(x, w, k2, bias=bias, relu=True)
+    kw = ts.ts_build_kmap(to_dev(coords), 3, 1)
+    assert torch.equal(ya, ts.ts_sparse_conv_act(x, w, kw, bias=bias, relu=True))
+    k3 = ts.ts_build_kmap(to_dev(coords), 3, 1, wait=False)
+    check_features(ts.ts_sparse_conv(x, w, k3, dataflow=ts.TS_DATAFLOW_EXPLICIT), ref, torch.float16, "explicit first")
+    k4 = ts.ts_build_kmap(to_dev(coords), 3, 1, wait=False)
+    assert k4.num_pairs == tri.shape[0]
+    assert torch.equal(ts.ts_sparse_conv(x, w, k4, dataflow=ts.TS_DATAFLOW_FUSED), y1)
+    k5 = ts.ts_build_kmap(to_dev(coords), 3, 1, wait=False).sort_rows()
+    check_features(ts.ts_sparse_conv(x, w, k5, dataflow=ts.TS_DATAFLOW_FUSED), ref, torch.float16, "sorted rows on an asynchronous build")
+
+
+def test_layer_on_an_asynchronous_build_with_bad_input():
+    small = _rand_coords(62, 2000, -10, 10, batches=2)
+    dup = np.concatenate([small, small[:1]])
+    x = to_dev(features(630, dup.shape[0], 32, np.float16))
+    w = to_dev(conv_weights(631, 27, 32, 32, np.float16))
+    m = ts.ts_build_kmap(to_dev(dup), 3, 1, wait=False)
+    ts.ts_sparse_conv(x, w, m, dataflow=ts.TS_DATAFLOW_FUSED)                  # runs (results meaningless), must not fault
+    with pytest.raises(ts.TsError) as e:
+        m.status()
+    assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
+    m.free()
+    far = small.copy()
+    far[3, 1] = ts.TS_COORD_MAX + 5
+    m = ts.ts_build_kmap(to_dev(far), 3, 1, wait=False)
+    ts.ts_sparse_conv(x[:2000].contiguous(), w, m, dataflow=ts.TS_DATAFLOW_FUSED)
+    with pytest.raises(ts.TsError) as e:
+        m.status()
+    assert e.value.code == ts.TS_ERR_COORD_RANGE
+
+
 def test_prepare_after_an_asynchronous_build(lidar_coords):
     """ts_kmap_prepare enqueues the put-off row pass of asynchronous builds; the maps, their sizes and the
     verdicts are those of the waiting build, also when several builds are prepared before any is asked."""
