@@ -139,7 +139,7 @@ def main():
 
     # ---- timed region: exactly `steps` steps; the dominant kernel is bracketed by HIP events
     # recorded by the library on its stream
-    dominant = "k_conv_tile"
+    dominant = "k_conv_"   # k_conv_tile, or k_conv_res for layers of at most 32 channels
     ts.ts_profile_enable(True, dominant)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -236,7 +236,7 @@ def main():
             ts.ts_sparse_conv(xc, wc, km, oc, ts.TS_DATAFLOW_FUSED)
         pk = {k: v[1] * 1e3 / v[0] for k, v in ts.ts_profile_read().items()}
         ts.ts_profile_enable(False)
-        fused_name = [k for k in pk if k.startswith("k_conv_tile") or k.startswith("k_fused")][0]
+        fused_name = [k for k in pk if k.startswith("k_conv_") or k.startswith("k_fused")][0]
         fu = pk[fused_name]
         gb, mb, sb = explicit_stage_bytes(n, n, m, m - n, c, c, K3, 2)   # the centre offset is not gathered
         fb = fused_conv_bytes(n, n, m, c, c, K3, 2)
