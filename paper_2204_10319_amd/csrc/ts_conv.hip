@@ -533,7 +533,8 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(N
 }
 
 // ---- fused kernel for narrow layers: all weights resident in LDS -----------------------------------
-// With C_in <= 32 and C_out = 16 NCO <= 64 the whole weight tensor, in operand order, is K^3 NCO KiB:
+// With C_in = 32 KSTEPS and a slice of 16 NCO output channels the weights, in operand order, are
+// K^3 NCO KSTEPS KiB (used with C_in <= 32 and C_out = 32 or 64: 54 or 108 KiB):
 // it is loaded into LDS once per workgroup and stays.  Nothing is shared between waves after that,
 // so there is no barrier in the loop and the unit of work is a wave's own 32 output rows: its
 // neighbour rows sit in a slice of LDS that only this wave touches, the offsets it walks are the
@@ -543,27 +544,34 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(N
 // (8 to 16 waves per workgroup and 2 to 8 stages of loads in flight all land within 10 % of each other on
 // 153 k points; 12 waves with 3 stages was the fastest.)
 constexpr int kResWaves = 12, kResDepth = 3, kResThreads = kResWaves * 64, kResRows = 32;
-template <int NCO>
+template <int FRAGS>
 constexpr size_t res_lds_bytes() {
-    return (size_t)kMaxK3 * NCO * 64 * 16 + (size_t)kResWaves * kMaxK3 * kResRows * 4;
+    return (size_t)kMaxK3 * FRAGS * 64 * 16 + (size_t)kResWaves * kMaxK3 * kResRows * 4;
 }
 
-template <int NCO, int DEPTH>
+template <int NCO, int KSTEPS, int DEPTH>
 __global__ void __launch_bounds__(kResThreads) k_conv_res(const _Float16 *__restrict__ X, const u32x4 *__restrict__ Wf,
                                                           const int32_t *__restrict__ nbr, int stride,
                                                           const int32_t *__restrict__ perm, int64_t n_out,
-                                                          _Float16 *__restrict__ out, int *__restrict__ sched, int K3,
+                                                          _Float16 *__restrict__ out, int *__restrict__ sched, int K3, int cout,
                                                           const _Float16 *__restrict__ bias,
                                                           const _Float16 *__restrict__ residual, int relu, int x_bytes,
                                                           int centre) {
     extern __shared__ u32x4 lds_res[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m16 = lane & 15, g = lane >> 4;
-    u32x4 *lds_w = lds_res;                                                         // [K3][NCO][64]
-    int32_t *lds_j = reinterpret_cast<int32_t *>(lds_res + kMaxK3 * NCO * 64) + wave * (kMaxK3 * kResRows);   // [K3][32], this wave's
-    for (int i = threadIdx.x; i < K3 * NCO * 64; i += kResThreads) lds_w[i] = Wf[i];
+    constexpr int FRAGS = NCO * KSTEPS;
+    const int cb0 = blockIdx.y * NCO, cblocks = cout / 16;
+    sched += kSchedWords * blockIdx.y;
+    u32x4 *lds_w = lds_res;                                                         // [K3][NCO][KSTEPS][64]
+    int32_t *lds_j = reinterpret_cast<int32_t *>(lds_res + kMaxK3 * FRAGS * 64) + wave * (kMaxK3 * kResRows);   // [K3][32], this wave's
+    // the fragments of this slice of output channels are contiguous within an offset
+    for (int i = threadIdx.x; i < K3 * FRAGS * 64; i += kResThreads) {
+        const int n = i / (FRAGS * 64), rem = i % (FRAGS * 64);
+        lds_w[i] = Wf[(n * cblocks + cb0) * KSTEPS * 64 + rem];
+    }
     __syncthreads();
 
-    constexpr int cout = NCO * 16, row_bytes = 64;
+    constexpr int row_bytes = KSTEPS * 64;
     const int64_t n_units = (n_out + kResRows - 1) / kResRows;
     const int64_t n_waves = (int64_t)gridDim.x * kResWaves;
     const int xcd = blockIdx.x & 7;
@@ -622,7 +630,7 @@ __global__ void __launch_bounds__(kResThreads) k_conv_res(const _Float16 *__rest
         for (int cb = 0; cb < NCO; ++cb)
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2) acc[cb][c2] = floatx4{0.f, 0.f, 0.f, 0.f};
-        half8v xreg[DEPTH][2];
+        half8v xreg[DEPTH][2][KSTEPS];
         int nn[DEPTH];
         bool xlive[DEPTH];
         uint32_t it_rem = mask ? mask : 1u;
@@ -638,24 +646,31 @@ __global__ void __launch_bounds__(kResThreads) k_conv_res(const _Float16 *__rest
             pj1 = lds_j[__builtin_ctz(it_rem) * kResRows + r1];
             const int off0 = j0 >= 0 ? j0 * row_bytes + xlane : kNoRow;
             const int off1 = j1 >= 0 ? j1 * row_bytes + xlane : kNoRow;
-            const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off0, 0, 0);
-            const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off1, 0, 0);
-            __builtin_memcpy(&xreg[d][0], &v0, 16);
-            __builtin_memcpy(&xreg[d][1], &v1, 16);
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off0, ks * 64, 0);
+                const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off1, ks * 64, 0);
+                __builtin_memcpy(&xreg[d][0][ks], &v0, 16);
+                __builtin_memcpy(&xreg[d][1][ks], &v1, 16);
+            }
         };
         auto run = [&](int s, auto dc) __attribute__((always_inline)) {
             constexpr int d = decltype(dc)::value;
             if (xlive[d]) {
-                u32x4 raw[NCO];
+                u32x4 raw[NCO][KSTEPS];
 #pragma unroll
-                for (int cb = 0; cb < NCO; ++cb) raw[cb] = lds_w[(nn[d] * NCO + cb) * 64 + lane];
+                for (int cb = 0; cb < NCO; ++cb)
 #pragma unroll
-                for (int cb = 0; cb < NCO; ++cb) {
-                    half8v a;
-                    __builtin_memcpy(&a, &raw[cb], 16);
-                    acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xreg[d][0], acc[cb][0], 0, 0, 0);
-                    acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xreg[d][1], acc[cb][1], 0, 0, 0);
-                }
+                    for (int ks = 0; ks < KSTEPS; ++ks) raw[cb][ks] = lds_w[((nn[d] * NCO + cb) * KSTEPS + ks) * 64 + lane];
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+                    for (int cb = 0; cb < NCO; ++cb) {
+                        half8v a;
+                        __builtin_memcpy(&a, &raw[cb][ks], 16);
+                        acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xreg[d][0][ks], acc[cb][0], 0, 0, 0);
+                        acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xreg[d][1][ks], acc[cb][1], 0, 0, 0);
+                    }
             }
             issue(s + DEPTH, dc);
         };
@@ -671,14 +686,14 @@ __global__ void __launch_bounds__(kResThreads) k_conv_res(const _Float16 *__rest
             const int64_t pos = unit * kResRows + (c2 ? r1 : r0);
             const int64_t row = perm ? perm[pos] : (pos < n_out ? pos : -1);
             if (row < 0) continue;
-            const int64_t at = row * cout + g * 4;
+            const int64_t at = row * cout + cb0 * 16 + g * 4;
 #pragma unroll
             for (int cb = 0; cb < NCO; ++cb) {
                 half4 v = {(_Float16)acc[cb][c2][0], (_Float16)acc[cb][c2][1], (_Float16)acc[cb][c2][2], (_Float16)acc[cb][c2][3]};
                 if (bias || residual || relu) {
                     float f[4] = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
                     if (bias) {
-                        const half4 b = *reinterpret_cast<const half4 *>(bias + cb * 16 + g * 4);
+                        const half4 b = *reinterpret_cast<const half4 *>(bias + cb0 * 16 + cb * 16 + g * 4);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) f[e] += (float)b[e];
                     }
@@ -1056,12 +1071,12 @@ void launch_conv_tile(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap
 
 // Narrow layers (C_in <= 32, C_out = 32): the kernel that keeps all weights in LDS.  False if this
 // device does not give a workgroup that much LDS: the caller then takes k_conv_tile.
-template <int NCO>
+template <int NCO, int KSTEPS>
 bool launch_conv_res(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap, ts_tensor *out, const Epilogue &ep) {
     static int usable = -1;   // per instantiation
-    constexpr size_t lds = res_lds_bytes<NCO>();
+    constexpr size_t lds = res_lds_bytes<NCO * KSTEPS>();
     if (usable < 0) {
-        usable = hipFuncSetAttribute(reinterpret_cast<const void *>(k_conv_res<NCO, kResDepth>),
+        usable = hipFuncSetAttribute(reinterpret_cast<const void *>(k_conv_res<NCO, KSTEPS, kResDepth>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
         if (!usable) (void)hipGetLastError();
     }
@@ -1070,10 +1085,10 @@ bool launch_conv_res(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap,
     const int64_t wgs = (n_units + kResWaves - 1) / kResWaves;
     const int64_t cus = compute_units();
     ts::ProfScope ps("k_conv_res");
-    hipLaunchKernelGGL((k_conv_res<NCO, kResDepth>), dim3((unsigned)(wgs < cus ? wgs : cus)), dim3(kResThreads), lds, ts::stream(),
+    hipLaunchKernelGGL((k_conv_res<NCO, KSTEPS, kResDepth>), dim3((unsigned)(wgs < cus ? wgs : cus), out->cols / (NCO * 16)), dim3(kResThreads), lds, ts::stream(),
                        x, reinterpret_cast<const u32x4 *>(wf), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->n_out,
-                       static_cast<_Float16 *>(out->data), kmap->d_sched, kmap->K3, static_cast<const _Float16 *>(ep.bias),
-                       static_cast<const _Float16 *>(ep.residual), ep.relu, (int)((size_t)kmap->n_in * 32 * 2), kmap->centre);
+                       static_cast<_Float16 *>(out->data), kmap->d_sched, kmap->K3, out->cols, static_cast<const _Float16 *>(ep.bias),
+                       static_cast<const _Float16 *>(ep.residual), ep.relu, (int)((size_t)kmap->n_in * KSTEPS * 64), kmap->centre);
     return true;
 }
 
@@ -1107,9 +1122,15 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
         x = xp;
     }
     const int cblocks = cout / 16;
-    if (cin_pad == 32 && cout == 32 && kmap->n_out > 0 && launch_conv_res<2>(x, wf, kmap, out, ep)) {
-        TS_HIP(hipGetLastError());
-        return TS_OK;
+    // 32 input channels and 27 offsets: the kernel with resident weights (for 2x2x2 maps and for 64 -> 32 it
+    // measured no faster than k_conv_tile, and 64 -> 64 in two slices of output channels much slower: every
+    // slice gathers all rows again)
+    if (cin_pad == 32 && kmap->K3 > 8 && kmap->n_out > 0 && (cout == 32 || cout == 64)) {
+        const bool done = cout == 32 ? launch_conv_res<2, 1>(x, wf, kmap, out, ep) : launch_conv_res<4, 1>(x, wf, kmap, out, ep);
+        if (done) {
+            TS_HIP(hipGetLastError());
+            return TS_OK;
+        }
     }
     int nco = 2;
     for (int c : {8, 6, 4, 2})

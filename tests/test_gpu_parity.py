@@ -616,24 +616,25 @@ def test_sorted_rows_many_distinct_masks():
 
 
 @pytest.mark.parametrize("K,s,transposed", [(3, 1, False), (2, 2, False), (2, 2, True), (1, 1, False)])
-@pytest.mark.parametrize("c_in", [32, 4])
-def test_narrow_layer_with_more_work_than_resident_waves(K, s, transposed, c_in):
-    """C_in <= 32 -> C_out = 32 in fp16 runs in the kernel that keeps all weights in LDS and hands 32-row
-    units to waves: enough rows here that units come out of the counters too; rows in input order and
-    sorted by bitmask; with the epilogue; twice on one map (the counters rearm)."""
+@pytest.mark.parametrize("c_in,c_out", [(32, 32), (4, 32), (32, 64)])
+def test_narrow_layer_with_more_work_than_resident_waves(K, s, transposed, c_in, c_out):
+    """C_in <= 32 -> C_out = 32 or 64 in fp16 on a 3x3x3 map runs in the kernel that keeps all weights in LDS
+    and hands 32-row units to waves: enough rows here that units come out of the counters too; rows in input
+    order and sorted by bitmask; with the epilogue; twice on one map (the counters rearm).  The other maps
+    take the tile kernel on the same inputs."""
     coords = _rand_coords(4242 + K, 160000, 0, 90, batches=2)
     kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
     assert kmap.num_out > 256 * 12 * 32 or K == 2 and not transposed
     x = features(77, kmap.num_in, c_in, np.float16)
-    w = conv_weights(78, K ** 3, c_in, 32, np.float16)
+    w = conv_weights(78, K ** 3, c_in, c_out, np.float16)
     ref = oracle_conv(coords, x, w, K, s, transposed)
     xd, wd = to_dev(x), to_dev(w)
     y = ts.ts_sparse_conv(xd, wd, kmap, dataflow=ts.TS_DATAFLOW_FUSED)
     check_features(y, ref, torch.float16, f"narrow layer K{K} s{s} t{transposed} C{c_in}")
     assert torch.equal(y, ts.ts_sparse_conv(xd, wd, kmap, dataflow=ts.TS_DATAFLOW_FUSED))
     assert oracle.rel_l2(ts.ts_sparse_conv(xd, wd, kmap, dataflow=ts.TS_DATAFLOW_FUSED_STAGED).cpu().numpy(), y.cpu().numpy()) < 1e-3
-    bias = to_dev(features(79, 1, 32, np.float16).reshape(-1))
-    res = to_dev(features(80, kmap.num_out, 32, np.float16))
+    bias = to_dev(features(79, 1, c_out, np.float16).reshape(-1))
+    res = to_dev(features(80, kmap.num_out, c_out, np.float16))
     want = ts.ts_bias_act(y.clone(), bias, res, True)
     assert torch.equal(ts.ts_sparse_conv_act(xd, wd, kmap, bias, res, True), want)
     kmap.sort_rows()
