@@ -1348,7 +1348,7 @@ bool prefer_explicit(const ts_kmap *kmap, int cin, int cout, size_t elem) {
     const double tile_offsets = kmap->K3 < 20 ? kmap->K3 : 20;
     const double fused_weight_bytes = (double)kmap->n_tiles * tile_offsets * cin * cout * elem;
     const double explicit_bytes = (double)kmap->M * (2.0 * cin * elem + 2.0 * cout * sizeof(float));
-    return fused_weight_bytes > 0.45 * explicit_bytes;
+    return fused_weight_bytes > 0.75 * explicit_bytes;
 }
 
 extern "C" {
