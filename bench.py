@@ -230,6 +230,7 @@ def main():
         oc = torch.empty((n, c), dtype=torch.float16, device="cuda")
         fused_us = time_calls(lambda: ts.ts_sparse_conv(xc, wc, km, oc, ts.TS_DATAFLOW_FUSED), 30)
         expl_us = time_calls(lambda: ts.ts_sparse_conv(xc, wc, km, oc, ts.TS_DATAFLOW_EXPLICIT), 30)
+        fetch_us = time_calls(lambda: ts.ts_sparse_conv(xc, wc, km, oc, ts.TS_DATAFLOW_FETCH), 30)
         ts.ts_profile_enable(True)
         for _ in range(20):
             ts.ts_sparse_conv(xc, wc, km, oc, ts.TS_DATAFLOW_EXPLICIT)
@@ -242,7 +243,7 @@ def main():
         fb = fused_conv_bytes(n, n, m, c, c, K3, 2)
         flops = 2.0 * m * c * c
         return {
-            "fused_layer_us": round(fused_us, 2), "explicit_layer_us": round(expl_us, 2),
+            "fused_layer_us": round(fused_us, 2), "explicit_layer_us": round(expl_us, 2), "fetch_layer_us": round(fetch_us, 2),
             "fused_kernel": fused_name, "k_fused_us": round(fu, 2),
             "k_fused_GBs": round(fb / fu * 1e-3, 1), "k_fused_frac_hbm": round(fb / fu * 1e-3 / HBM_PEAK_GBS, 4),
             "k_fused_TFLOPs": round(flops / fu * 1e-6, 1),

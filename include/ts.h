@@ -73,9 +73,14 @@ enum {
     TS_DATAFLOW_EXPLICIT = 1, /* Alg. 2 as three launches: gather -> grouped matmul -> scatter-accumulate */
     TS_DATAFLOW_FUSED = 2,    /* one output-stationary kernel: gather into the MFMA operand, accumulate
                                  over offsets in registers, write each output row once                    */
-    TS_DATAFLOW_FUSED_STAGED = 3 /* the same dataflow by the older kernel that stages weight slabs and
+    TS_DATAFLOW_FUSED_STAGED = 3, /* the same dataflow by the older kernel that stages weight slabs and
                                  neighbour indices per tile in LDS with 32x32 MFMAs: what TS_F32 always
                                  runs, and TS_F16 when features or weights reach 2 GiB                    */
+    TS_DATAFLOW_FETCH = 4     /* Alg. 2 without the buffer F: the grouped matmul fetches X_in[j] through
+                                 the map itself (the fetch-on-demand dataflow that Sec. 5.2 and the
+                                 related work name as the better one on small workloads), then the
+                                 scatter-accumulate: two launches.  Same bits as TS_DATAFLOW_EXPLICIT.
+                                 TS_DATAFLOW_AUTO takes it for wide layers on small maps.                 */
 };
 
 /* Dense row-major matrix: rows x cols elements of dtype, device memory. */

@@ -13,7 +13,7 @@ import numpy as np
 import torch
 
 TS_F32, TS_F16 = 0, 1
-TS_DATAFLOW_AUTO, TS_DATAFLOW_EXPLICIT, TS_DATAFLOW_FUSED, TS_DATAFLOW_FUSED_STAGED = 0, 1, 2, 3
+TS_DATAFLOW_AUTO, TS_DATAFLOW_EXPLICIT, TS_DATAFLOW_FUSED, TS_DATAFLOW_FUSED_STAGED, TS_DATAFLOW_FETCH = 0, 1, 2, 3, 4
 
 TS_OK = 0
 TS_ERR_INVALID_ARG, TS_ERR_SHAPE, TS_ERR_COORD_RANGE, TS_ERR_DUPLICATE_COORD = -1, -2, -3, -4

@@ -780,7 +780,8 @@ template <class T, int NCB, int KC>
 __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F, const T *__restrict__ X,
                                                          const T *__restrict__ Wt, Offs offs, MmPlan plan,
                                                          float *__restrict__ G, const T *__restrict__ zero_row,
-                                                         int cin, int cout, int centre) {
+                                                         int cin, int cout, int centre,
+                                                         const int32_t *__restrict__ in_idx) {
     typedef Shape<T, NCB, KC> S;
     typedef typename S::vec vec;
     __shared__ __attribute__((aligned(16))) T lds_w[S::SLAB];
@@ -796,7 +797,7 @@ __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
     const int64_t p = (int64_t)lo + (int64_t)t * kTileRows + wave * kWaveRows + m;   // row of F and G
     const bool valid = p < hi;
-    const T *src = !valid ? zero_row : (n == centre ? X + (p - lo) * cin : F + p * cin);
+    const T *src = !valid ? zero_row : (n == centre ? X + (p - lo) * cin : (in_idx ? X + (int64_t)in_idx[p] * cin : F + p * cin));
     const int kstride = valid ? 1 : 0;   // the zero row is one chunk long
     floatx16 acc[NCB];
 #pragma unroll
@@ -823,7 +824,9 @@ __global__ void __launch_bounds__(kThreads) k_scatter_reduce(const float *__rest
                                                              int stride, const uint64_t *__restrict__ colbits,
                                                              const int32_t *__restrict__ colbase, Offs offs,
                                                              int64_t n_blocks,
-                                                             T *__restrict__ out, int64_t n_out, int cout, int K3) {
+                                                             T *__restrict__ out, int64_t n_out, int cout, int K3,
+                                                             const T *__restrict__ bias, const T *__restrict__ residual,
+                                                             int relu) {
     const int quads = cout / 4;
     int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t k = g / quads;
@@ -854,11 +857,36 @@ __global__ void __launch_bounds__(kThreads) k_scatter_reduce(const float *__rest
         for (int u = 0; u < 4; ++u)
             if (p[u] >= 0) acc += v[u];
     }
+    // the layer's own result in T, then, if asked for, what ts_bias_act would do with it: fp32 sum
+    // (bias first, then the residual), ReLU, one rounding
+    const int64_t at = k * cout + q * 4;
+    const bool tail = bias || residual || relu;
     if constexpr (sizeof(T) == 2) {
         half4 v = {(_Float16)acc[0], (_Float16)acc[1], (_Float16)acc[2], (_Float16)acc[3]};
-        *reinterpret_cast<half4 *>(out + k * cout + q * 4) = v;
+        if (tail) {
+            float f[4] = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+            if (bias) {
+                const half4 b = *reinterpret_cast<const half4 *>(bias + q * 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) f[e] += (float)b[e];
+            }
+            if (residual) {
+                const half4 r = *reinterpret_cast<const half4 *>(residual + at);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) f[e] += (float)r[e];
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (_Float16)(relu && f[e] < 0.f ? 0.f : f[e]);
+        }
+        *reinterpret_cast<half4 *>(out + at) = v;
     } else {
-        *reinterpret_cast<floatx4 *>(out + k * cout + q * 4) = acc;
+        if (tail) {
+            if (bias) acc += *reinterpret_cast<const floatx4 *>(bias + q * 4);
+            if (residual) acc += *reinterpret_cast<const floatx4 *>(residual + at);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = relu && acc[e] < 0.f ? 0.f : acc[e];
+        }
+        *reinterpret_cast<floatx4 *>(out + at) = acc;
     }
 }
 
@@ -1185,12 +1213,13 @@ struct GroupedLaunch {
     float *G;
     const T *zero;
     int cin_pad, cout;
+    const int32_t *in_idx;
     template <int NCB, int KSTEPS>
     void operator()() const {
         constexpr int KC = KSTEPS * Elem<T>::KSTEP;
         dim3 grid((unsigned)plan_tiles(plan), cout / (NCB * 32));
         TS_LAUNCH("k_grouped_mm", (k_grouped_mm<T, NCB, KC>), grid, dim3(kThreads), F, X, wt, offs_of(kmap), plan, G, zero,
-                  cin_pad, cout, kmap->centre);
+                  cin_pad, cout, kmap->centre, in_idx);
     }
 };
 
@@ -1210,13 +1239,13 @@ int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const t
 
 template <class T>
 int grouped_mm_launch(const void *F, const void *X, const void *wt, const ts_kmap *kmap, const MmPlan &plan, float *G,
-                      int cin_pad, int cout) {
+                      int cin_pad, int cout, const int32_t *in_idx = nullptr) {
     if (plan_tiles(plan) == 0) return TS_OK;
     const T *zero = static_cast<const T *>(zero_row());
     if (!zero) return TS_ERR_OOM;
     dispatch_shape(pick_ncb(cout), pick_ksteps(cin_pad, Elem<T>::KSTEP),
                    GroupedLaunch<T>{static_cast<const T *>(F), static_cast<const T *>(X), static_cast<const T *>(wt),
-                                    kmap, plan, G, zero, cin_pad, cout});
+                                    kmap, plan, G, zero, cin_pad, cout, in_idx});
     TS_HIP(hipGetLastError());
     return TS_OK;
 }
@@ -1311,34 +1340,42 @@ int grouped_mm_adaptive(const void *F, const void *X, const void *wt, const ts_k
 }
 
 template <class T>
-int reduce_impl(const float *G, const ts_kmap *kmap, ts_tensor *out) {
+int reduce_impl(const float *G, const ts_kmap *kmap, ts_tensor *out, const Epilogue &ep = Epilogue()) {
     if (kmap->n_out == 0) return TS_OK;
     int64_t threads = kmap->n_out * (out->cols / 4);
-    TS_LAUNCH("k_scatter_reduce", k_scatter_reduce<T>, dim3(blocks_for(threads, kThreads)), dim3(kThreads), G, kmap->d_nbr, kmap->stride, kmap->d_colbits, kmap->d_colbase, offs_of(kmap), kmap->n_blocks, static_cast<T *>(out->data), kmap->n_out, out->cols, kmap->K3);
+    TS_LAUNCH("k_scatter_reduce", k_scatter_reduce<T>, dim3(blocks_for(threads, kThreads)), dim3(kThreads), G, kmap->d_nbr, kmap->stride, kmap->d_colbits, kmap->d_colbase, offs_of(kmap), kmap->n_blocks, static_cast<T *>(out->data), kmap->n_out, out->cols, kmap->K3, static_cast<const T *>(ep.bias), static_cast<const T *>(ep.residual), ep.relu);
     TS_HIP(hipGetLastError());
     return TS_OK;
 }
 
 template <class T>
 int run_explicit(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
-                 const ts_weights *pw = nullptr) {
+                 const ts_weights *pw = nullptr, bool fetch = false, const Epilogue &ep = Epilogue()) {
     TS_TRY(resolve(kmap));
     Prepared pr;
     TS_TRY(prepare<T>(feats, weights, kmap, &pr, pw));
     const int64_t M = kmap->M;
-    void *F = scratch(0, (size_t)(M ? M : 1) * pr.cin_pad * sizeof(T));
     float *G = static_cast<float *>(scratch(1, (size_t)(M ? M : 1) * out->cols * sizeof(float)));
-    if (!F || !G) return TS_ERR_OOM;
+    if (!G) return TS_ERR_OOM;
+    if (fetch) {   // the matmul reads X_in[j] through the pair lists: no buffer F, no gather launch
+        if (M == 0) return reduce_impl<T>(G, kmap, out, ep);
+        TS_TRY(ensure_pairs(kmap));
+        TS_TRY(grouped_mm_launch<T>(nullptr, pr.x, pr.wt, kmap, whole_plan(kmap), G, pr.cin_pad, out->cols, kmap->d_in_idx));
+        return reduce_impl<T>(G, kmap, out, ep);
+    }
+    void *F = scratch(0, (size_t)(M ? M : 1) * pr.cin_pad * sizeof(T));
+    if (!F) return TS_ERR_OOM;
     TS_TRY(gather_impl(pr.x, feats->rows, pr.cin_pad, feats->dtype, kmap, F));
     TS_TRY(grouped_mm_impl<T>(F, pr.x, pr.wt, kmap, G, pr.cin_pad, out->cols));
-    return reduce_impl<T>(G, kmap, out);
+    return reduce_impl<T>(G, kmap, out, ep);
 }
 
 }  // namespace
 
 // TS_DATAFLOW_AUTO.  The fused kernel re-reads a layer's weights for every tile of 128 outputs
 // (about 20 of the 27 offsets meet an input somewhere in a tile); the explicit dataflow reads
-// them once but moves every pair's rows through the buffers F and G.  Wide layers on point sets too
+// them once but moves every pair's rows through the buffer G (and F, unless the matmul fetches
+// the rows itself, which is the form taken here).  Wide layers on point sets too
 // small to fill the machine with tiles (the coarse levels of a U-Net) are cheaper explicit,
 // everything else fused; the factor and the size limit come from timing both on the layers of
 // the MinkUNet-style benchmark network.
@@ -1348,7 +1385,7 @@ bool prefer_explicit(const ts_kmap *kmap, int cin, int cout, size_t elem) {
     const double tile_offsets = kmap->K3 < 20 ? kmap->K3 : 20;
     const double fused_weight_bytes = (double)kmap->n_tiles * tile_offsets * cin * cout * elem;
     const double explicit_bytes = (double)kmap->M * (2.0 * cin * elem + 2.0 * cout * sizeof(float));
-    return fused_weight_bytes > 0.75 * explicit_bytes;
+    return fused_weight_bytes > 0.6 * explicit_bytes;
 }
 
 extern "C" {
@@ -1357,13 +1394,16 @@ int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts
                       int dataflow) {
     TS_TRY(check_layer(feats, weights, kmap, out));
     if (dataflow != TS_DATAFLOW_AUTO && dataflow != TS_DATAFLOW_EXPLICIT && dataflow != TS_DATAFLOW_FUSED &&
-        dataflow != TS_DATAFLOW_FUSED_STAGED)
+        dataflow != TS_DATAFLOW_FUSED_STAGED && dataflow != TS_DATAFLOW_FETCH)
         return fail(TS_ERR_INVALID_ARG, "unknown dataflow %d", dataflow);
     if (kmap->n_out == 0) return TS_OK;
     const bool f16 = feats->dtype == TS_F16;
-    if (dataflow == TS_DATAFLOW_AUTO && prefer_explicit(kmap, feats->cols, out->cols, f16 ? 2 : 4)) dataflow = TS_DATAFLOW_EXPLICIT;
-    if (dataflow == TS_DATAFLOW_EXPLICIT)
-        return f16 ? run_explicit<_Float16>(feats, weights, kmap, out) : run_explicit<float>(feats, weights, kmap, out);
+    if (dataflow == TS_DATAFLOW_AUTO && prefer_explicit(kmap, feats->cols, out->cols, f16 ? 2 : 4)) dataflow = TS_DATAFLOW_FETCH;
+    if (dataflow == TS_DATAFLOW_EXPLICIT || dataflow == TS_DATAFLOW_FETCH) {
+        const bool fetch = dataflow == TS_DATAFLOW_FETCH;
+        return f16 ? run_explicit<_Float16>(feats, weights, kmap, out, nullptr, fetch)
+                   : run_explicit<float>(feats, weights, kmap, out, nullptr, fetch);
+    }
     if (dataflow == TS_DATAFLOW_FUSED_STAGED)
         return f16 ? run_fused_staged<_Float16>(feats, weights, kmap, out) : run_fused_staged<float>(feats, weights, kmap, out);
     return f16 ? run_fused<_Float16>(feats, weights, kmap, out) : run_fused<float>(feats, weights, kmap, out);
@@ -1387,18 +1427,16 @@ static int conv_act(const ts_tensor *feats, const ts_tensor *weights, const ts_w
     if (kmap->n_out == 0) return TS_OK;
     const bool f16 = feats->dtype == TS_F16;
     const bool go_explicit = prefer_explicit(kmap, feats->cols, out->cols, f16 ? 2 : 4);
-    if (f16 && !go_explicit) {
-        Epilogue ep;
-        ep.bias = bias;
-        ep.residual = residual ? residual->data : nullptr;
-        ep.relu = relu != 0;
-        return run_fused_f16(feats, weights, kmap, out, ep, pw);
-    }
-    // otherwise: the layer, then the elementwise step on its output
+    Epilogue ep;
+    ep.bias = bias;
+    ep.residual = residual ? residual->data : nullptr;
+    ep.relu = relu != 0;
+    if (f16 && !go_explicit) return run_fused_f16(feats, weights, kmap, out, ep, pw);
+    // fetch-on-demand: the tail runs in the scatter-accumulate kernel
     if (go_explicit)
-        TS_TRY(f16 ? run_explicit<_Float16>(feats, weights, kmap, out, pw) : run_explicit<float>(feats, weights, kmap, out, pw));
-    else
-        TS_TRY(run_fused<float>(feats, weights, kmap, out, pw));
+        return f16 ? run_explicit<_Float16>(feats, weights, kmap, out, pw, true, ep) : run_explicit<float>(feats, weights, kmap, out, pw, true, ep);
+    // otherwise (fp32, fused): the layer, then the elementwise step on its output
+    TS_TRY(run_fused<float>(feats, weights, kmap, out, pw));
     if (!bias && !residual && !relu) return TS_OK;
     return ts_bias_act(out, bias, residual, relu, out);
 }

@@ -90,7 +90,7 @@ def test_kmap_errors():
 
 
 def _layer_case(coords, c_in, c_out, K, s, transposed, dtype, seed,
-                dataflows=(ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FUSED_STAGED, ts.TS_DATAFLOW_AUTO)):
+                dataflows=(ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FUSED_STAGED, ts.TS_DATAFLOW_FETCH, ts.TS_DATAFLOW_AUTO)):
     kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
     x = features(seed, kmap.num_in, c_in, np_dtype(dtype))
     w = conv_weights(seed + 1, K ** 3, c_in, c_out, np_dtype(dtype))
@@ -136,7 +136,7 @@ def test_layer_channel_counts_that_are_odd_multiples_of_32(c_in, c_out, K, s, tr
     w = conv_weights(911 + c_in, K ** 3, c_in, c_out, np.float16)
     ref = oracle_conv(coords, x, w, K, s, transposed)
     pw = ts.ts_weights_prepare(to_dev(w))
-    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FETCH):
         check_features(ts.ts_sparse_conv(to_dev(x), to_dev(w), kmap, dataflow=df), ref, torch.float16, f"C {c_in}->{c_out} dataflow {df}")
     check_features(ts.ts_sparse_conv_prepared(to_dev(x), pw, kmap), ref, torch.float16, f"C {c_in}->{c_out} prepared")
     # a large value in the first channel of every row, with zero weights: a step that multiplied the next row's
@@ -153,7 +153,7 @@ def test_layer_empty():
     kmap = ts.ts_build_kmap(torch.zeros((0, 4), dtype=torch.int32, device="cuda"), 3, 1)
     x = torch.zeros((0, 32), dtype=torch.float16, device="cuda")
     w = torch.zeros((27, 32, 32), dtype=torch.float16, device="cuda")
-    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FETCH):
         assert ts.ts_sparse_conv(x, w, kmap, dataflow=df).shape == (0, 32)
 
 
@@ -243,7 +243,7 @@ def test_config4_down_up_pair(lidar_coords):
     # the oracle runs the pair on its own: its down result, rounded to fp16, feeds its up layer
     ref_down = oracle_conv(lidar_coords, x, w_down, 2, 2)
     ref_up = oracle_conv(lidar_coords, oracle.round_to(ref_down, np.float16), w_up, 2, 2, transposed=True)
-    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FETCH):
         y = ts.ts_sparse_conv(to_dev(x), to_dev(w_down), down, dataflow=df)
         check_features(y, ref_down, dtype, "down")
         z = ts.ts_sparse_conv(y, to_dev(w_up), up, dataflow=df)
@@ -399,7 +399,7 @@ def test_detector_style_downsampling_layer(transposed):
     x = features(530, n_in, cin, np.float16)
     w = conv_weights(531, 27, cin, cout, np.float16)
     ref = oracle_conv(coords, x, w, 3, 2, transposed, boundary=b)
-    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FETCH):
         y = ts.ts_sparse_conv(to_dev(x), to_dev(w), kmap, dataflow=df)
         check_features(y, ref, torch.float16, f"detector-style layer, dataflow {df}")
 
@@ -523,7 +523,7 @@ def test_prepare_after_an_asynchronous_build(lidar_coords):
     x = to_dev(features(610, small.shape[0], 32, np.float16))
     w = to_dev(conv_weights(611, 27, 32, 32, np.float16))
     ref = oracle_conv(small, x.cpu().numpy(), w.cpu().numpy(), 3, 1)
-    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FETCH):
         check_features(ts.ts_sparse_conv(x, w, ms[1], dataflow=df), ref, torch.float16, f"prepared map, dataflow {df}")
 
 
@@ -562,7 +562,7 @@ def test_results_are_deterministic(lidar_coords):
     assert torch.equal(pa[0], pb[0]) and torch.equal(pa[1], pb[1])
     x = to_dev(features(600, lidar_coords.shape[0], 64, np.float16))
     w = to_dev(conv_weights(601, 27, 64, 64, np.float16))
-    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FETCH):
         y1 = ts.ts_sparse_conv(x, w, kmap_a, dataflow=df)
         y2 = ts.ts_sparse_conv(x, w, kmap_b, dataflow=df)
         assert torch.equal(y1, y2)
@@ -613,6 +613,24 @@ def test_sorted_rows_many_distinct_masks():
     assert torch.equal(y1, y2)
     y3 = ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_EXPLICIT)
     assert oracle.rel_l2(y3.cpu().numpy(), y1.cpu().numpy()) < 1e-3
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("K,s,transposed,c_in,c_out", [(3, 1, False, 64, 64), (3, 2, False, 24, 96), (2, 2, True, 256, 128), (1, 1, False, 128, 32)])
+def test_fetch_dataflow_gives_the_bits_of_the_explicit_one(dtype, K, s, transposed, c_in, c_out):
+    """TS_DATAFLOW_FETCH is Alg. 2 with the gather folded into the matmul: same products, same sums in the same
+    order as the three-launch form; also as the first use of a map nobody waited for."""
+    coords = _rand_coords(515 + K, 5000, -12, 12, batches=2)
+    nd = np_dtype(dtype)
+    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
+    x = to_dev(features(516, kmap.num_in, c_in, nd))
+    w = to_dev(conv_weights(517, K ** 3, c_in, c_out, nd))
+    want = ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_EXPLICIT)
+    assert torch.equal(ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_FETCH), want)
+    if not transposed:
+        lazy = ts.ts_build_kmap(to_dev(coords), K, s, wait=False)
+        assert torch.equal(ts.ts_sparse_conv(x, w, lazy, dataflow=ts.TS_DATAFLOW_FETCH), want)
+    check_features(want, oracle_conv(coords, x.cpu().numpy(), w.cpu().numpy(), K, s, transposed), dtype, "fetch dataflow")
 
 
 @pytest.mark.parametrize("K,s,transposed", [(3, 1, False), (2, 2, False), (2, 2, True), (1, 1, False)])
@@ -681,7 +699,7 @@ def test_transposed_map_derived_from_forward_map(K, n):
     assert torch.equal(pa[0], pb[0]) and torch.equal(pa[1], pb[1])
     x = to_dev(features(310, built.num_in, 64, np.float16))
     w = to_dev(conv_weights(311, K ** 3, 64, 32, np.float16))
-    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT):
+    for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FETCH):
         assert torch.equal(ts.ts_sparse_conv(x, w, derived, dataflow=df), ts.ts_sparse_conv(x, w, built, dataflow=df))
     fwd.free()   # the derived map does not depend on the forward map's memory
     assert torch.equal(ts.ts_sparse_conv(x, w, derived), ts.ts_sparse_conv(x, w, built))
