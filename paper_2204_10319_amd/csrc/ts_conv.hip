@@ -1160,9 +1160,15 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
             return TS_OK;
         }
     }
-    int nco = 2;
+    // Output channels per workgroup: as many as divide C_out (every slice gathers the rows again), fewer
+    // when the launch would leave most of the chip idle: a lone workgroup per CU walks its stages one
+    // after the other, and a stage of eight output blocks takes twice as long as one of four.
+    int nco = 2, cap = 8;
+    const int64_t cus = compute_units(), wgs8 = kmap->n_tiles * ((cblocks + 7) / 8);
+    if (wgs8 <= cus / 2 || (wgs8 <= cus && kmap->K3 > 8)) cap = 4;
+    if (cap == 4 && kmap->n_tiles * ((cblocks + 3) / 4) <= cus / 2) cap = 2;
     for (int c : {8, 6, 4, 2})
-        if (cblocks % c == 0) {
+        if (c <= cap && cblocks % c == 0) {
             nco = c;
             break;
         }
