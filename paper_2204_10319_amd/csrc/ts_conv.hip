@@ -904,13 +904,22 @@ __global__ void k_pack_weights(const T *__restrict__ W, T *__restrict__ Wt, int 
 }
 
 // Xp[row][c] = X[row][c] for c < cin, 0 up to cin_pad.
+// A thread writes 8 consecutive elements of a padded row (cin_pad is a multiple of 8) with 16-byte stores.
 template <class T>
 __global__ void k_pad_rows(const T *__restrict__ X, T *__restrict__ Xp, int64_t rows, int cin, int cin_pad) {
+    const int per_row = cin_pad / 8;
     int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (g >= rows * cin_pad) return;
-    int64_t r = g / cin_pad;
-    int c = (int)(g - r * cin_pad);
-    Xp[g] = c < cin ? X[r * cin + c] : (T)0;
+    if (g >= rows * per_row) return;
+    int64_t r = g / per_row;
+    const int c0 = (int)(g - r * per_row) * 8;
+    T v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = c0 + e < cin ? X[r * cin + c0 + e] : (T)0;
+    u32x4 raw[sizeof(T) / 2];
+    __builtin_memcpy(raw, v, sizeof(v));
+    u32x4 *dst = reinterpret_cast<u32x4 *>(Xp + r * cin_pad + c0);
+#pragma unroll
+    for (unsigned i = 0; i < sizeof(T) / 2; ++i) dst[i] = raw[i];
 }
 
 inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
@@ -992,7 +1001,7 @@ int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kma
         size_t xn = (size_t)feats->rows * cin_pad;
         T *xp = static_cast<T *>(scratch(3, xn * sizeof(T)));
         if (!xp) return TS_ERR_OOM;
-        TS_LAUNCH("k_pad_rows", k_pad_rows<T>, dim3(blocks_for((int64_t)xn, kThreads)), dim3(kThreads), static_cast<const T *>(feats->data), xp, feats->rows, cin, cin_pad);
+        TS_LAUNCH("k_pad_rows", k_pad_rows<T>, dim3(blocks_for((int64_t)xn / 8, kThreads)), dim3(kThreads), static_cast<const T *>(feats->data), xp, feats->rows, cin, cin_pad);
         pr->x = xp;
     }
     return TS_OK;
@@ -1146,7 +1155,7 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
         const size_t xn = (size_t)feats->rows * cin_pad;
         T *xp = static_cast<T *>(scratch(3, xn * sizeof(T)));
         if (!xp) return TS_ERR_OOM;
-        TS_LAUNCH("k_pad_rows", k_pad_rows<T>, dim3(blocks_for((int64_t)xn, kThreads)), dim3(kThreads), x, xp, feats->rows, cin, cin_pad);
+        TS_LAUNCH("k_pad_rows", k_pad_rows<T>, dim3(blocks_for((int64_t)xn / 8, kThreads)), dim3(kThreads), x, xp, feats->rows, cin, cin_pad);
         x = xp;
     }
     const int cblocks = cout / 16;

@@ -36,6 +36,18 @@ __global__ void k_concat_cols(const T *__restrict__ a, const T *__restrict__ b, 
     out[i] = col < ca ? a[r * ca + col] : b[r * cb + (col - ca)];
 }
 
+// The same in 16-byte vectors, when both widths are whole vectors: va, vb = vectors per row of a, b.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__global__ void k_concat_cols_vec(const u32x4 *__restrict__ a, const u32x4 *__restrict__ b, u32x4 *__restrict__ out,
+                                  int64_t rows, int va, int vb) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int v = va + vb;
+    if (i >= rows * v) return;
+    int64_t r = i / v;
+    int col = (int)(i - r * v);
+    out[i] = col < va ? a[r * va + col] : b[r * vb + (col - va)];
+}
+
 int check(const ts_tensor *t, const char *name) {
     if (!t) return fail(TS_ERR_INVALID_ARG, "%s is NULL", name);
     if (t->dtype != TS_F32 && t->dtype != TS_F16) return fail(TS_ERR_INVALID_ARG, "%s: unknown dtype", name);
@@ -85,7 +97,16 @@ int ts_concat_cols(const ts_tensor *a, const ts_tensor *b, ts_tensor *out) {
         return fail(TS_ERR_SHAPE, "out must be [rows, cols(a) + cols(b)] of the common dtype");
     const int64_t total = out->rows * out->cols;
     if (total == 0) return TS_OK;
-    if (a->dtype == TS_F16)
+    const size_t elem = a->dtype == TS_F16 ? 2 : 4;
+    const bool whole_vectors = a->cols * elem % 16 == 0 && b->cols * elem % 16 == 0 &&
+                               ((reinterpret_cast<uintptr_t>(a->data) | reinterpret_cast<uintptr_t>(b->data) |
+                                 reinterpret_cast<uintptr_t>(out->data)) & 15) == 0;
+    if (whole_vectors) {
+        const int va = (int)(a->cols * elem / 16), vb = (int)(b->cols * elem / 16);
+        TS_LAUNCH("k_concat_cols", k_concat_cols_vec, dim3(blocks_for(out->rows * (va + vb))), dim3(kThreads),
+                  static_cast<const u32x4 *>(a->data), static_cast<const u32x4 *>(b->data),
+                  static_cast<u32x4 *>(out->data), out->rows, va, vb);
+    } else if (a->dtype == TS_F16)
         TS_LAUNCH("k_concat_cols", k_concat_cols<_Float16>, dim3(blocks_for(total)), dim3(kThreads),
                   static_cast<const _Float16 *>(a->data), static_cast<const _Float16 *>(b->data),
                   static_cast<_Float16 *>(out->data), out->rows, a->cols, b->cols);

@@ -616,6 +616,28 @@ def test_sorted_rows_many_distinct_masks():
 
 
 @pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("ca,cb,skip", [(96, 32, 0), (32, 256, 0), (20, 12, 0), (8, 8, 1), (4, 36, 3)])
+def test_concat_cols_is_a_copy(dtype, ca, cb, skip):
+    """ts_concat_cols moves bits (skip connections of a U-Net): whole 16-byte vectors where widths and
+    addresses allow, element by element otherwise (odd widths; views that start off a 16-byte boundary)."""
+    g = torch.Generator().manual_seed(ca * 100 + cb)
+    a = torch.randn((1003 + skip, ca), generator=g).to(dtype).cuda()[skip:]
+    b = torch.randn((1003 + skip, cb), generator=g).to(dtype).cuda()[skip:]
+    assert torch.equal(ts.ts_concat_cols(a, b), torch.cat([a, b], dim=1))
+    empty = ts.ts_concat_cols(a[:0], b[:0])
+    assert empty.shape == (0, ca + cb)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("c_in", [1, 3, 4, 9, 17, 40])
+def test_layer_with_input_channels_that_need_padding(dtype, c_in):
+    """C_in that is not a multiple of the operand step is zero-extended by the library (16-byte stores of
+    8 elements): every dataflow against the oracle."""
+    coords = _rand_coords(808 + c_in, 1100, -6, 6, batches=2)
+    _layer_case(coords, c_in, 32, 3, 1, False, dtype, seed=800 + c_in)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
 @pytest.mark.parametrize("K,s,transposed,c_in,c_out", [(3, 1, False, 64, 64), (3, 2, False, 24, 96), (2, 2, True, 256, 128), (1, 1, False, 128, 32)])
 def test_fetch_dataflow_gives_the_bits_of_the_explicit_one(dtype, K, s, transposed, c_in, c_out):
     """TS_DATAFLOW_FETCH is Alg. 2 with the gather folded into the matmul: same products, same sums in the same
