@@ -235,9 +235,11 @@ int ts_sparse_conv(const ts_tensor *feats, const ts_tensor *weights, const ts_km
  * out = act(sparse convolution + bias + residual): ts_sparse_conv followed by ts_bias_act (below)
  * in one call.  bias (device, [C_out], dtype of out) and residual ([num_out][C_out], dtype of out,
  * must not alias out) may be NULL; relu != 0 clamps at zero.  The result equals, bit for bit, that
- * of the two calls made one after the other (the layer's sum is rounded to the I/O dtype first);
- * for TS_F16 it is computed in the layer kernel's epilogue, so the activation tensor is written
- * once and not read back (the paper's Principle II: data movement is what to cut, Sec. 3).
+ * of the two calls made one after the other (the layer's sum is rounded to the I/O dtype first).
+ * It is computed where the layer's sums are formed - the fused kernel's epilogue (TS_F16), or the
+ * scatter-accumulate kernel where the library takes the fetch-on-demand dataflow - so the
+ * activation tensor is written once and not read back (the paper's Principle II: data movement is
+ * what to cut, Sec. 3); only TS_F32 layers that run fused take a second launch for it.
  */
 int ts_sparse_conv_act(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
                        const void *bias, const ts_tensor *residual, int relu, ts_tensor *out);
