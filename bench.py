@@ -348,6 +348,14 @@ def main():
         graph, _, _ = net.capture(maps, x4)
         graph_us = time_calls(graph.replay, 20)
         del graph
+        if not srt:
+            # where a pass spends its time: launches and microseconds per kernel (HIP events around every launch)
+            ts.ts_profile_enable(True)
+            for _ in range(3):
+                net.forward(maps, x4)
+            net_report["forward_kernels"] = {k: {"launches": v[0] // 3, "us": round(v[1] * 1e3 / 3, 1)}
+                                             for k, v in ts.ts_profile_read().items()}
+            ts.ts_profile_enable(False)
         SparseNet.free_maps(maps)
         net_report["maps_build_ms" + tag] = round(maps_us * 1e-3, 3)
         if not srt:
