@@ -72,6 +72,8 @@ def main():
     ap.add_argument("--pmc-run", action="store_true")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--step-only", action="store_true")
+    ap.add_argument("--network-run", action="store_true",
+                    help="only 10 passes of the config-5 network (17 map builds + 45 layers each), for profiling")
     ap.add_argument("--strided-run", action="store_true",
                     help="20 builds each of the K=2,s=2 and K=3,s=2 (with boundary) maps of config 3, then exit (for the kernel-trace profile)")
     args = ap.parse_args()
@@ -121,6 +123,21 @@ def main():
             step().free()
         torch.cuda.synchronize()
         print(json.dumps({"pmc_run": True, "copy_bytes": COPY_BYTES, "N": int(N)}))
+        return
+
+    if args.network_run:
+        from paper_2204_10319_amd.network import SparseNet
+        from workloads.minkunet import build_plan, make_params
+        ops, net_out = build_plan(4)
+        params = {k: (torch.from_numpy(wt).cuda(), torch.from_numpy(bs).cuda()) for k, (wt, bs) in make_params(50, ops).items()}
+        net = SparseNet(ops, net_out, params)
+        x4 = torch.from_numpy(features(51, N, 4, np.float16)).cuda()
+        for _ in range(10):
+            maps, _ = net.build_maps(coords)
+            net.forward(maps, x4)
+            SparseNet.free_maps(maps)
+        torch.cuda.synchronize()
+        print(json.dumps({"network_run": True, "N": int(N), "passes": 10}))
         return
 
     if args.strided_run:

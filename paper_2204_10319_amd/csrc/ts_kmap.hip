@@ -744,10 +744,15 @@ __global__ void __launch_bounds__(kThreads) k_bits_expand(const uint64_t *__rest
     uint32_t y0 = cell % cbox.ext[1];
     cell /= cbox.ext[1];
     uint32_t x0 = cell % cbox.ext[0], b0 = cell / cbox.ext[0];
+    // (the bits come in ascending order, so the cell only ever moves forward: a word costs 64 / ext z
+    // carries in all, not that many per set bit, which on the flat boxes of coarse levels was the whole kernel)
+    uint32_t z = z0, y = y0, x = x0, b = b0;
+    int prev = 0;
     while (bits) {
         const int bit = __builtin_ctzll(bits);
         bits &= bits - 1;
-        uint32_t z = z0 + (uint32_t)bit, y = y0, x = x0, b = b0;
+        z += (uint32_t)(bit - prev);
+        prev = bit;
         while (z >= cbox.ext[2]) {
             z -= cbox.ext[2];
             if (++y == cbox.ext[1]) {
