@@ -139,6 +139,17 @@ int ts_kmap_status(const ts_kmap *kmap);
 int ts_kmap_prepare(const ts_kmap *kmap);
 
 /*
+ * The map of a 1x1x1 convolution at stride 1 over n distinct points, made without coordinates: by
+ * Eq. 1 with delta = 0 output k takes input k and nothing else, so M = {(k, k, 0)} whatever the points
+ * are, as long as no two of them coincide (which the caller knows from any other build on the same
+ * points; nothing is checked here).  n_in = n_out = |M| = n, kernel volume 1.  Two launches, no host
+ * wait, no search; every layer call accepts the map.  It holds no coordinates: ts_kmap_out_coords and
+ * ts_kmap_in_coords fail on it with TS_ERR_UNSUPPORTED.  Errors: TS_ERR_INVALID_ARG (NULL out_kmap, n < 0
+ * or n >= 2^31), TS_ERR_OOM.  Free with ts_free.
+ */
+int ts_identity_kmap(int64_t n, ts_kmap **out_kmap);
+
+/*
  * ts_build_kmap with the choices the paper leaves to each layer (Sec. 4.4; Alg. 3).  options == NULL
  * is ts_build_kmap.  The map built is the same whatever `search` says.
  *   search        TS_SEARCH_AUTO (what ts_build_kmap does): stride 1 searches the hash table; a strided

@@ -25,7 +25,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libts.so")
 _lib = None
 
 EXPORTS = [
-    "ts_build_kmap", "ts_build_kmap_async", "ts_build_kmap_ex", "ts_kmap_status", "ts_kmap_prepare", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
+    "ts_build_kmap", "ts_build_kmap_async", "ts_build_kmap_ex", "ts_identity_kmap", "ts_kmap_status", "ts_kmap_prepare", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
     "ts_sparse_conv_prepared", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
@@ -82,6 +82,8 @@ def load_library(path: str | None = None):
     lib.ts_kmap_sort_rows.restype = ci
     lib.ts_kmap_transpose.argtypes = [vp, ctypes.POINTER(vp)]
     lib.ts_kmap_transpose.restype = ci
+    lib.ts_identity_kmap.argtypes = [i64, ctypes.POINTER(vp)]
+    lib.ts_identity_kmap.restype = ci
     for name in ("ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs"):
         getattr(lib, name).argtypes = [vp]
         getattr(lib, name).restype = i64
@@ -327,6 +329,14 @@ def ts_build_kmap(coords: torch.Tensor, kernel_size: int, stride: int = 1, trans
             int(bool(transposed)), ctypes.byref(h))
     _check(rc)
     return KMap(h.value)
+
+
+def ts_identity_kmap(n: int) -> KMap:
+    """The map of a 1x1x1, stride-1 convolution over n distinct points (output k <- input k); holds no coordinates."""
+    _use_current_stream()
+    handle = ctypes.c_void_p()
+    _check(load_library().ts_identity_kmap(int(n), ctypes.byref(handle)))
+    return KMap(handle.value)
 
 
 def ts_kmap_transpose(forward: KMap) -> KMap:

@@ -1134,6 +1134,26 @@ int report(const ts_kmap *m) {
     return m->error;
 }
 
+// The map of a 1x1x1 convolution at stride 1 over n distinct points, written out directly: output k
+// takes input k through the only offset (Eq. 1 with delta = 0).  One pass fills the neighbour rows
+// (entry, then the bitmask word), the rank structure (every row present: bitmap words of ones, base 64 b)
+// and the tile order.
+__global__ void __launch_bounds__(kThreads) k_identity_map(int32_t *__restrict__ nbr, int stride, uint64_t *__restrict__ colbits,
+                                                           int32_t *__restrict__ colbase, int32_t *__restrict__ tile_order,
+                                                           int64_t n, int64_t n_blocks, int64_t n_tiles) {
+    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (g < n) {
+        int4 row = make_int4((int32_t)g, 1, -1, -1);
+        *reinterpret_cast<int4 *>(nbr + g * stride) = row;
+    }
+    if (g < n_blocks) {
+        const int64_t left = n - g * 64;
+        colbits[g] = left >= 64 ? ~0ull : ((1ull << left) - 1ull);
+        colbase[g] = (int32_t)(g * 64);
+    }
+    if (g < n_tiles) tile_order[g] = (int32_t)g;
+}
+
 void destroy(ts_kmap *m) {
     if (!m) return;
     if (m->pending_slot >= 0) g_slots[m->pending_slot].owner = nullptr;   // the slot frees itself when its copy has landed
@@ -1752,6 +1772,40 @@ int ts_build_kmap_async(const int32_t *coords, int64_t N, int kernel_size, int s
     return build_checked(coords, N, kernel_size, stride, transposed, out_kmap, opt);
 }
 
+int ts_identity_kmap(int64_t n, ts_kmap **out_kmap) {
+    if (!out_kmap) return fail(TS_ERR_INVALID_ARG, "out_kmap is NULL");
+    *out_kmap = nullptr;
+    if (n < 0 || n > INT32_MAX) return fail(TS_ERR_INVALID_ARG, "n must be in [0, 2^31)");
+    ts_kmap *m = new (std::nothrow) ts_kmap();
+    if (!m) return fail(TS_ERR_OOM, "host allocation failed");
+    m->K = 1;
+    m->s = 1;
+    m->K3 = 1;
+    m->centre = 0;
+    m->stride = ts::nbr_stride(1);
+    m->n_in = m->n_out = m->M = n;
+    m->sizes[0] = n;
+    m->offs[1] = n;
+    auto body = [&]() -> int {
+        if (n == 0) return TS_OK;
+        FillArgs fill;
+        TS_TRY(alloc_outputs(m, &fill));
+        TS_TRY(launch_fill(fill));
+        TS_LAUNCH("k_identity_map", k_identity_map, dim3(blocks_for(n, kThreads)), dim3(kThreads), m->d_nbr, m->stride,
+                  m->d_colbits, m->d_colbase, m->d_tile_order, n, m->n_blocks, m->n_tiles);
+        TS_HIP(hipGetLastError());
+        return TS_OK;
+    };
+    const int rc = body();
+    if (rc != TS_OK) {
+        (void)hipStreamSynchronize(ts::stream());
+        destroy(m);
+        return rc;
+    }
+    *out_kmap = m;
+    return TS_OK;
+}
+
 int ts_build_kmap_ex(const int32_t *coords, int64_t N, int kernel_size, int stride, int transposed,
                      const ts_kmap_options *options, ts_kmap **out_kmap) {
     BuildOpts opt;
@@ -1832,6 +1886,7 @@ int ts_kmap_kernel_volume(const ts_kmap *kmap) { return kmap ? kmap->K3 : -1; }
 int ts_kmap_out_coords(const ts_kmap *kmap, int32_t *dst) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
     if (kmap->n_out == 0) return TS_OK;
+    if (!kmap->d_out_keys) return fail(TS_ERR_UNSUPPORTED, "a map made by ts_identity_kmap holds no coordinates");
     if (!dst || (reinterpret_cast<uintptr_t>(dst) & 15)) return fail(TS_ERR_INVALID_ARG, "dst is NULL or not 16-byte aligned");
     TS_LAUNCH("k_unpack", k_unpack, dim3(blocks_for(kmap->n_out, kThreads)), dim3(kThreads), kmap->d_out_keys, kmap->n_out, reinterpret_cast<int4 *>(dst));
     TS_HIP(hipGetLastError());
@@ -1841,6 +1896,7 @@ int ts_kmap_out_coords(const ts_kmap *kmap, int32_t *dst) {
 int ts_kmap_in_coords(const ts_kmap *kmap, int32_t *dst) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
     if (kmap->n_in == 0) return TS_OK;
+    if (!kmap->d_in_keys) return fail(TS_ERR_UNSUPPORTED, "a map made by ts_identity_kmap holds no coordinates");
     if (!dst || (reinterpret_cast<uintptr_t>(dst) & 15)) return fail(TS_ERR_INVALID_ARG, "dst is NULL or not 16-byte aligned");
     TS_LAUNCH("k_unpack", k_unpack, dim3(blocks_for(kmap->n_in, kThreads)), dim3(kThreads), kmap->d_in_keys, kmap->n_in, reinterpret_cast<int4 *>(dst));
     TS_HIP(hipGetLastError());

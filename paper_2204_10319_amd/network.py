@@ -48,7 +48,9 @@ class SparseNet:
                 if sort_rows:
                     maps[(kind, level)].sort_rows()
             elif kind == "id":
-                maps[(kind, level)] = ts.ts_build_kmap(levels[level], 1, 1, False, wait=False, grid=boxes.get(level))
+                # a 1x1x1 convolution takes input k to output k whatever the coordinates are; that the points of
+                # the level are distinct is checked by the other builds on them
+                maps[(kind, level)] = ts.ts_identity_kmap(levels[level].shape[0])
             elif kind == "up":
                 maps[(kind, level)] = maps[("down", level)].transpose()
         for m in maps.values():

@@ -615,6 +615,47 @@ def test_sorted_rows_many_distinct_masks():
     assert oracle.rel_l2(y3.cpu().numpy(), y1.cpu().numpy()) < 1e-3
 
 
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 40000])
+def test_identity_map_is_the_1x1x1_map_of_distinct_points(n):
+    """ts_identity_kmap(n) = what the search finds for K = 1, s = 1 on n distinct points (Eq. 1 with delta = 0):
+    same triples as the oracle's map, same sizes, and every dataflow gives the oracle's layer on it."""
+    coords = _rand_coords(900 + n, n, -20, 20, batches=2)
+    ident = ts.ts_identity_kmap(n)
+    assert (ident.num_in, ident.num_out, ident.num_pairs, ident.kernel_volume) == (n, n, n, 1)
+    _, _, want = oracle_map(coords, 1, 1)
+    assert np.array_equal(gpu_triples(ident), want)
+    assert ident.sizes().tolist() == [n]
+    searched = ts.ts_build_kmap(to_dev(coords), 1, 1)
+    for dtype in (torch.float16, torch.float32):
+        nd = np_dtype(dtype)
+        x = features(901, n, 48, nd)
+        w = conv_weights(902, 1, 48, 64, nd)
+        ref = oracle_conv(coords, x, w, 1, 1)
+        for df in (ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FETCH, ts.TS_DATAFLOW_AUTO):
+            y = ts.ts_sparse_conv(to_dev(x), to_dev(w), ident, dataflow=df)
+            check_features(y, ref, dtype, f"identity map, dataflow {df}")
+            assert torch.equal(y, ts.ts_sparse_conv(to_dev(x), to_dev(w), searched, dataflow=df))
+    ident.sort_rows()
+    ident.prepare().status()
+    with pytest.raises(ts.TsError):
+        ident.out_coords()
+    with pytest.raises(ts.TsError):
+        ident.in_coords()
+    with pytest.raises(ts.TsError):
+        ident.transpose()
+    ident.free()
+
+
+def test_identity_map_of_nothing():
+    m = ts.ts_identity_kmap(0)
+    assert (m.num_in, m.num_out, m.num_pairs) == (0, 0, 0)
+    x = torch.zeros((0, 32), dtype=torch.float16, device="cuda")
+    w = torch.zeros((1, 32, 32), dtype=torch.float16, device="cuda")
+    assert ts.ts_sparse_conv(x, w, m).shape == (0, 32)
+    with pytest.raises(ts.TsError):
+        ts.ts_identity_kmap(-1)
+
+
 @pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
 @pytest.mark.parametrize("ca,cb,skip", [(96, 32, 0), (32, 256, 0), (20, 12, 0), (8, 8, 1), (4, 36, 3)])
 def test_concat_cols_is_a_copy(dtype, ca, cb, skip):
