@@ -27,7 +27,11 @@ equal sizes together, tolerance 1 makes one group), by the invariants of the par
 covering, every group within the tolerance, no group extensible) and by exhaustive comparison with
 a search over all contiguous partitions on small inputs.  :func:`adaptive_group_search` is pinned by
 numpy's argmin over a table of costs, ties included.
-Parity status: every function above is pinned by at least one of these.
+The comparison helpers are pinned too: :func:`rel_l2` and :func:`row_rel_err` by hand-computed
+vectors (3-4-5 triangles, zero references, a single wrong row among many), :func:`round_to` by the
+tie points of binary16 and binary32 written out by hand (round-to-nearest-even, overflow to inf),
+:func:`sort_triples` by a hand-ordered list and by Python's ``sorted`` on the key ``(n, k, j)``.
+Parity status: every function of this package is pinned by at least one of these.
 """
 from __future__ import annotations
 
@@ -207,11 +211,36 @@ def rel_l2(y, y_ref) -> float:
     """``||y - y_ref||_F / ||y_ref||_F`` in float64 (0 when both are empty or zero)."""
     y = np.asarray(y, dtype=np.float64)
     y_ref = np.asarray(y_ref, dtype=np.float64)
+    if y.shape != y_ref.shape:
+        raise ValueError(f"rel_l2: shapes differ, {y.shape} vs {y_ref.shape}")
     den = float(np.linalg.norm(y_ref))
     num = float(np.linalg.norm(y - y_ref))
     if den == 0.0:
         return 0.0 if num == 0.0 else float("inf")
     return num / den
+
+
+def row_rel_err(y, y_ref) -> np.ndarray:
+    """Per-row error ``||y_k - ref_k|| / max(||ref_k||, ||ref||_F / sqrt(rows))`` in float64, one value
+    per row: the whole-tensor norm of :func:`rel_l2` cannot see a handful of wrong rows among 10^5, this
+    can.  The floor (the root-mean-square row norm) keeps rows that are nearly zero from dividing by
+    nothing.  Empty input gives an empty array; an all-zero reference gives 0 where ``y`` is zero too
+    and inf elsewhere."""
+    y = np.asarray(y, dtype=np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    if y.shape != y_ref.shape or y.ndim != 2:
+        raise ValueError("row_rel_err: two [rows, cols] arrays of one shape")
+    if y.shape[0] == 0:
+        return np.zeros(0)
+    num = np.sqrt(((y - y_ref) ** 2).sum(axis=1))
+    ref_rows = np.sqrt((y_ref ** 2).sum(axis=1))
+    floor = float(np.sqrt((ref_rows ** 2).sum() / y.shape[0]))
+    den = np.maximum(ref_rows, floor)
+    out = np.zeros_like(num)
+    nz = den > 0
+    out[nz] = num[nz] / den[nz]
+    out[~nz & (num > 0)] = np.inf
+    return out
 
 
 def adaptive_groups(sizes, eps: float) -> list[list[int]]:

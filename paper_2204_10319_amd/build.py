@@ -27,18 +27,54 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+OBJDIR = os.path.join(HERE, "_build")
+
+
+def _object_stale(src: str, obj: str) -> bool:
+    if not os.path.exists(obj):
+        return True
+    t = os.path.getmtime(obj)
+    deps = [src, os.path.join(CSRC, "ts_internal.h"), os.path.join(HERE, "..", "include", "ts.h"),
+            os.path.join(HERE, "..", "include", "ts_bench.h")]
+    return any(os.path.exists(d) and os.path.getmtime(d) > t for d in deps)
+
+
 def build_library(force: bool = True, verbose: bool = False) -> str:
-    """Compile the library; returns the path of the shared object."""
+    """Compile the library (one object per source, side by side, then one link); returns the path of the
+    shared object.  With force every source is compiled again, otherwise only those older than what they
+    include."""
     if not force and not is_stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + sources() + ["-o", LIB]
-    res = subprocess.run(cmd, capture_output=True, text=True)
+    os.makedirs(OBJDIR, exist_ok=True)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    jobs, objs = [], []
+    for src in sources():
+        obj = os.path.join(OBJDIR, os.path.basename(src) + ".o")
+        objs.append(obj)
+        if force or _object_stale(src, obj):
+            jobs.append((src, subprocess.Popen([hipcc] + compile_flags + ["-c", src, "-o", obj],
+                                               stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    failed = False
+    for src, proc in jobs:
+        out, _ = proc.communicate()
+        if verbose or proc.returncode != 0:
+            print(out)
+        if proc.returncode != 0:
+            failed = True
+            try:
+                os.remove(os.path.join(OBJDIR, os.path.basename(src) + ".o"))
+            except OSError:
+                pass
+    if failed:
+        raise RuntimeError("hipcc failed building libts.so")
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared"] + objs + ["-o", LIB],
+                         capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(res.stdout)
         print(res.stderr)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed building libts.so")
+        raise RuntimeError("hipcc failed linking libts.so")
     return LIB
 
 

@@ -14,7 +14,7 @@ from paper_2204_10319_amd.network import SparseNet
 from workloads import lidar_scan_coords, features
 from workloads.minkunet import build_plan, make_params
 from _net_oracle import run_plan
-from _util import to_dev
+from _util import to_dev, check_features
 
 pytestmark = pytest.mark.gpu
 
@@ -32,7 +32,9 @@ def _run_both(coords, seed, box=None):
     got = {}
     y = net.forward(maps, to_dev(x), hook=lambda n, v: got.__setitem__(n, v.cpu().numpy()))
     torch.cuda.synchronize()
-    SparseNet.free_maps(maps)
+    # (1) the free-running pass: every tensor within the stated norm; its rows within ten times that (the
+    # two runs have drifted apart by the rounding differences of up to 45 layers, so rows are not held to
+    # the single-layer bound here; a row that lost a neighbour term is off by tens of percent)
     worst = 0.0
     for name, r in ref.items():
         g = got[name]
@@ -43,7 +45,33 @@ def _run_both(coords, seed, box=None):
         err = oracle.rel_l2(g, r)
         worst = max(worst, err)
         assert err <= 2e-3, f"{name}: relative L2 error {err:.3e}"
+        rows = oracle.row_rel_err(g, r)
+        k = int(np.argmax(rows))
+        assert rows[k] <= 2e-2, f"{name}: row {k} off by {rows[k]:.3e}"
     assert oracle.rel_l2(y.cpu().numpy(), y_ref) <= 2e-3
+    # (2) layer by layer on the ORACLE's activations: each GPU layer gets the oracle's input (and residual)
+    # tensor, so its output is held to the single-layer bounds, row by row and element by element (plus one
+    # ulp of the layer's sum, which both sides round to fp16 before bias / residual / ReLU).
+    dev = {"input": to_dev(x)}
+    def on_dev(name):
+        if name not in dev:
+            dev[name] = to_dev(ref[name])
+        return dev[name]
+    for kind, op in ops:
+        if kind == "concat":
+            g = ts.ts_concat_cols(on_dev(op["a"]), on_dev(op["b"]))
+            assert np.array_equal(g.cpu().numpy(), ref[op["dst"]]), op["dst"]
+            continue
+        _, b = net.params[op["name"]]
+        res = on_dev(op["residual"]) if op["residual"] else None
+        g = ts.ts_sparse_conv_prepared(on_dev(op["src"]), net.prepared[op["name"]], maps[op["map"]], b, res, op["relu"])
+        r = ref[op["dst"]].astype(np.float64)
+        mag = np.abs(r) + np.abs(params[op["name"]][1].astype(np.float64))[None, :]
+        if op["residual"]:
+            mag = mag + np.abs(ref[op["residual"]].astype(np.float64))
+        check_features(g, r, torch.float16, f"{op['name']} on the oracle's input", pre_mag=mag)
+    torch.cuda.synchronize()
+    SparseNet.free_maps(maps)
     return worst, len(ref)
 
 

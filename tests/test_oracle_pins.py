@@ -494,3 +494,106 @@ def test_adaptive_group_search_is_the_argmin_of_the_summed_cost():
         total = costs.sum(axis=0)
         ie, js = np.unravel_index(np.argmin(total), total.shape)
         assert got == (eps_space[ie], S_space[js], total[ie, js])
+
+
+# ---------------------------------------------------------------------------------------------
+# The comparison helpers every feature-parity assertion goes through.  Expected values are worked
+# out by hand (Pythagorean triples, binary16/binary32 tie points), not recomputed with the formula.
+# ---------------------------------------------------------------------------------------------
+
+def test_rel_l2_hand_computed():
+    # ||(3,4) - (0,0)|| / ||(0,0)||: nothing to divide by and a non-zero difference
+    assert oracle.rel_l2([3.0, 4.0], [0.0, 0.0]) == float("inf")
+    assert oracle.rel_l2([0.0, 0.0], [0.0, 0.0]) == 0.0
+    assert oracle.rel_l2(np.zeros((0, 8)), np.zeros((0, 8))) == 0.0
+    # difference (0,1) has norm 1, reference (1,0) has norm 1
+    assert oracle.rel_l2([1.0, 1.0], [1.0, 0.0]) == 1.0
+    # the reference is the second argument: difference (0,1), reference (1,1) of norm sqrt 2
+    assert oracle.rel_l2([1.0, 0.0], [1.0, 1.0]) == pytest.approx(1.0 / np.sqrt(2.0), rel=1e-15)
+    # the norm itself, not its square: difference (3,4) -> 5, reference (6,8) -> 10
+    assert oracle.rel_l2([9.0, 12.0], [6.0, 8.0]) == 0.5
+    # Frobenius over all entries of a matrix: difference [[3,0],[0,4]] -> 5, reference [[0,5],[12,0]] -> 13
+    assert oracle.rel_l2([[3.0, 5.0], [12.0, 4.0]], [[0.0, 5.0], [12.0, 0.0]]) == pytest.approx(5.0 / 13.0, rel=1e-15)
+    # no silent broadcasting of a mismatched shape into a small number
+    with pytest.raises(ValueError):
+        oracle.rel_l2(np.ones((4, 3)), np.ones((4, 2)))
+    with pytest.raises(ValueError):
+        oracle.rel_l2(np.ones((4, 3)), np.ones((1, 3)))
+    # half-precision inputs are widened before the subtraction (65504 - (-65504) overflows fp16)
+    a = np.array([65504.0], np.float16)
+    assert oracle.rel_l2(a, -a) == 2.0
+
+
+def test_row_rel_err_hand_computed():
+    ref = np.array([[3.0, 4.0], [0.0, 0.0], [6.0, 8.0], [0.0, 5.0]])
+    # row norms 5, 0, 10, 5 -> squares 25 + 0 + 100 + 25 = 150, rms row norm sqrt(150 / 4)
+    floor = np.sqrt(37.5)
+    got = ref.copy()
+    got[0] += [0.0, 1.0]        # error 1 on a row of norm 5 (below the floor 6.12)
+    got[1] += [0.6, 0.8]        # error 1 on a zero row: divided by the floor
+    got[2] += [3.0, 4.0]        # error 5 on a row of norm 10 (above the floor)
+    want = np.array([1.0 / floor, 1.0 / floor, 0.5, 0.0])
+    assert np.allclose(oracle.row_rel_err(got, ref), want, rtol=1e-15, atol=0)
+    # one wrong row among 10 000 is invisible to the whole-tensor norm and plain here
+    rng = _rng(5)
+    ref = rng.standard_normal((10000, 16))
+    got = ref.copy()
+    got[1234] = 0.0
+    assert oracle.rel_l2(got, ref) < 2e-2
+    e = oracle.row_rel_err(got, ref)
+    assert int(np.argmax(e)) == 1234 and e[1234] > 0.5 and np.count_nonzero(e) == 1
+    assert oracle.row_rel_err(np.zeros((0, 4)), np.zeros((0, 4))).shape == (0,)
+    z = oracle.row_rel_err(np.array([[0.0, 0.0], [1.0, 0.0]]), np.zeros((2, 2)))
+    assert z[0] == 0.0 and z[1] == np.inf
+    with pytest.raises(ValueError):
+        oracle.row_rel_err(np.ones((3, 2)), np.ones((3, 1)))
+
+
+def test_round_to_is_round_to_nearest_even_once():
+    # binary16 has 11 significant bits: spacing 2^-10 in [1, 2), 1 in [1024, 2048), 2 in [2048, 4096)
+    h = 2.0 ** -11
+    cases16 = [
+        (1.0 + h, 1.0),                      # tie between 1 and 1 + 2^-10: the even mantissa is 1
+        (1.0 + 3 * h, 1.0 + 2.0 ** -9),      # tie between 1 + 2^-10 (odd) and 1 + 2^-9 (even)
+        (1.0 + h + 2.0 ** -30, 1.0 + 2.0 ** -10),   # just above the tie: up
+        (1.0 + h - 2.0 ** -30, 1.0),                # just below: down
+        (2049.0, 2048.0), (2051.0, 2052.0),  # ties at spacing 2
+        (-2049.0, -2048.0),
+        (65519.0, 65504.0),                  # below the overflow threshold 65520: largest finite value
+        (65520.0, np.inf),                   # the tie at the top rounds to infinity
+        (2.0 ** -25, 0.0),                   # half the smallest subnormal 2^-24: tie to even = 0
+        (3 * 2.0 ** -25, 2.0 ** -23),        # tie between 2^-24 (odd) and 2^-23 (even)
+    ]
+    for x, want in cases16:
+        got = oracle.round_to(np.array([x], np.float64), np.float16)
+        assert got.dtype == np.float16
+        assert float(got[0]) == want, (x, float(got[0]), want)
+    # binary32: 24 significant bits, spacing 2^-23 in [1, 2)
+    g = 2.0 ** -24
+    for x, want in [(1.0 + g, 1.0), (1.0 + 3 * g, 1.0 + 2.0 ** -22), (1.0 + g + 2.0 ** -50, 1.0 + 2.0 ** -23),
+                    (16777217.0, 16777216.0), (16777219.0, 16777220.0)]:
+        got = oracle.round_to(np.array([x], np.float64), np.float32)
+        assert got.dtype == np.float32 and float(got[0]) == want, (x, float(got[0]), want)
+    # one rounding, not two: 1 + 2^-11 + 2^-26 is above the binary16 tie and must go up, while rounding
+    # to binary32 first (spacing 2^-23) would land exactly on the tie and then go down to 1
+    x = 1.0 + 2.0 ** -11 + 2.0 ** -26
+    assert float(oracle.round_to(np.array([x]), np.float16)[0]) == 1.0 + 2.0 ** -10
+    assert float(np.array([x]).astype(np.float32).astype(np.float16)[0]) == 1.0
+    # shape is kept
+    assert oracle.round_to(np.zeros((3, 5)), np.float16).shape == (3, 5)
+
+
+def test_sort_triples_orders_by_offset_then_output_then_input():
+    tri = np.array([[5, 1, 2], [0, 7, 0], [9, 0, 2], [3, 1, 2], [4, 7, 0], [1, 0, 26], [2, 3, 1]], np.int32)
+    want = np.array([[0, 7, 0], [4, 7, 0], [2, 3, 1], [9, 0, 2], [3, 1, 2], [5, 1, 2], [1, 0, 26]], np.int32)
+    got = oracle.sort_triples(tri)
+    assert got.dtype == np.int32 and got.flags["C_CONTIGUOUS"]
+    assert np.array_equal(got, want)
+    # against Python's sorted on the key (n, k, j), random triples with repeats
+    rng = _rng(17)
+    tri = rng.integers(0, 6, size=(500, 3)).astype(np.int32)
+    want = np.array(sorted(map(tuple, tri.tolist()), key=lambda t: (t[2], t[1], t[0])), np.int32)
+    assert np.array_equal(oracle.sort_triples(tri), want)
+    assert oracle.sort_triples(np.zeros((0, 3), np.int32)).shape == (0, 3)
+    # a flat list of 3k numbers is read as k triples
+    assert np.array_equal(oracle.sort_triples(np.array([1, 1, 1, 0, 0, 0])), np.array([[0, 0, 0], [1, 1, 1]], np.int32))
