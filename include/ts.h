@@ -275,6 +275,24 @@ int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts
                       ts_tensor *out, int dataflow);
 
 /*
+ * ts_sparse_conv for callers that cannot allocate: code under HIP graph capture, serving loops and
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels (the fused dataflow), same bits; but the one
+ * piece of memory ts_sparse_conv takes from the library's grow-on-demand scratch - the weights repacked
+ * into the order the kernels read, plus a row of zeros for TS_F32 - lives in a fixed array inside the
+ * library's code object (4 MiB + 4 KiB on every GPU the library runs on, held until the process ends).
+ * The call reaches no hipMalloc, hipFree or other allocating routine, and never synchronises.
+ * Limits (TS_ERR_UNSUPPORTED beyond them, with the figures in ts_last_error):
+ *   K^3 * C_in * C_out * element size <= 4 MiB (e.g. 27 x 256 x 256 fp16, 27 x 192 x 192 fp32);
+ *   C_in a multiple of 32 (TS_F16) or 8 (TS_F32): narrower rows would need a padded copy of feats;
+ *   features and weights below 2 GiB each.
+ * The map must come from a build that has finished its own allocations (any map ts_build_kmap* returned).
+ * The first call on a device looks the array's address up (hipGetSymbolAddress); make that call outside a
+ * capture.  Every call on a GPU shares that GPU's array and overwrites it: calls that overlap on one GPU
+ * (two streams, two host threads) race; calls on one stream are ordered and safe.
+ */
+int ts_sparse_conv_static(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out);
+
+/*
  * The three stages of Alg. 2 on their own (what TS_DATAFLOW_EXPLICIT runs), for per-stage
  * tests and timing.  The buffers F and G are offset-major like ts_kmap_pairs.
  *

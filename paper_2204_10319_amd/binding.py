@@ -27,7 +27,7 @@ _lib = None
 EXPORTS = [
     "ts_build_kmap", "ts_build_kmap_async", "ts_build_kmap_ex", "ts_identity_kmap", "ts_kmap_status", "ts_kmap_prepare", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
-    "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
+    "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_static", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
     "ts_sparse_conv_prepared", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
     "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_mfma_loop", "ts_bias_act", "ts_concat_cols",
 ]
@@ -95,6 +95,8 @@ def load_library(path: str | None = None):
     lib.ts_kmap_pairs.argtypes = [vp, vp, vp]
     lib.ts_sparse_conv.argtypes = [tp, tp, vp, tp]
     lib.ts_sparse_conv_ex.argtypes = [tp, tp, vp, tp, ci]
+    lib.ts_sparse_conv_static.argtypes = [tp, tp, vp, tp]
+    lib.ts_sparse_conv_static.restype = ci
     lib.ts_sparse_conv_act.argtypes = [tp, tp, vp, vp, tp, ci, tp]
     lib.ts_sparse_conv_act.restype = ci
     lib.ts_weights_prepare.argtypes = [tp, ci, ctypes.POINTER(vp)]
@@ -406,6 +408,15 @@ def ts_sparse_conv(feats: torch.Tensor, weights: torch.Tensor, kmap: KMap, out: 
     else:
         rc = lib.ts_sparse_conv_ex(ctypes.byref(f), ctypes.byref(w), kmap.handle, ctypes.byref(o), int(dataflow))
     _check(rc)
+    return out
+
+
+def ts_sparse_conv_static(feats: torch.Tensor, weights: torch.Tensor, kmap: KMap, out: torch.Tensor) -> torch.Tensor:
+    """ts_sparse_conv for callers that cannot allocate: ``out`` is required, and neither this wrapper nor the
+    library allocates device memory (the library's staging area is a fixed array inside libts.so)."""
+    _use_current_stream()
+    f, w, o = _as_ts(feats), _weights_ts(weights), _as_ts(out)
+    _check(load_library().ts_sparse_conv_static(ctypes.byref(f), ctypes.byref(w), kmap.handle, ctypes.byref(o)))
     return out
 
 

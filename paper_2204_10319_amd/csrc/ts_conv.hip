@@ -983,15 +983,16 @@ int check_layer(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap 
 // the operand step.
 template <class T>
 int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, Prepared *pr,
-            const ts_weights *pw = nullptr) {
+            const ts_weights *pw = nullptr, void *wbuf = nullptr) {
     const int cin = feats->cols, cout = weights->cols, ks = Elem<T>::KSTEP;
     const int cin_pad = (cin + ks - 1) / ks * ks;
     pr->cin_pad = cin_pad;
+    if (wbuf && cin_pad != cin) return fail(TS_ERR_UNSUPPORTED, "C_in must be a multiple of %d here", ks);
     if (pw) {
         pr->wt = pw->wt;
     } else {
         size_t wn = (size_t)kmap->K3 * cout * cin_pad;
-        T *wt = static_cast<T *>(scratch(2, wn * sizeof(T)));
+        T *wt = static_cast<T *>(wbuf ? wbuf : scratch(2, wn * sizeof(T)));
         if (!wt) return TS_ERR_OOM;
         TS_LAUNCH("k_pack_weights", k_pack_weights<T>, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads), static_cast<const T *>(weights->data), wt, kmap->K3, cin, cin_pad, cout);
         pr->wt = wt;
@@ -1053,10 +1054,10 @@ struct FusedLaunch {
 
 template <class T>
 int run_fused_staged(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
-                     const ts_weights *pw = nullptr) {
+                     const ts_weights *pw = nullptr, void *wbuf = nullptr, const void *zeros = nullptr) {
     Prepared pr;
-    TS_TRY(prepare<T>(feats, weights, kmap, &pr, pw));
-    const T *zero = static_cast<const T *>(zero_row());
+    TS_TRY(prepare<T>(feats, weights, kmap, &pr, pw, wbuf));
+    const T *zero = static_cast<const T *>(zeros ? zeros : zero_row());
     if (!zero) return TS_ERR_OOM;
     dispatch_shape(pick_ncb(out->cols), pick_ksteps(pr.cin_pad, Elem<T>::KSTEP), FusedLaunch<T>{pr, kmap, out, zero});
     TS_HIP(hipGetLastError());
@@ -1131,7 +1132,7 @@ bool launch_conv_res(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap,
 
 // fp16: input channels padded to a multiple of 32 (one MFMA step), chunks of 64 where possible.
 int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
-                  const Epilogue &ep, const ts_weights *pw = nullptr) {
+                  const Epilogue &ep, const ts_weights *pw = nullptr, void *wbuf = nullptr) {
     typedef _Float16 T;
     const int cin = feats->cols, cout = out->cols;
     const int cin_pad = (cin + 31) / 32 * 32;
@@ -1139,12 +1140,14 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
     // the kernel addresses features and weights with 31-bit byte offsets
     if ((size_t)kmap->n_in * cin_pad * 2 >= (1ull << 31) || (size_t)kmap->K3 * cin_pad * cout * 2 >= (1ull << 31)) {
         if (ep.any()) return fail(TS_ERR_UNSUPPORTED, "feature matrix of 2 GiB or more: call ts_sparse_conv and ts_bias_act");
+        if (wbuf) return fail(TS_ERR_UNSUPPORTED, "feature matrix of 2 GiB or more");
         return run_fused_staged<_Float16>(feats, weights, kmap, out, pw);
     }
+    if (wbuf && cin_pad != cin) return fail(TS_ERR_UNSUPPORTED, "C_in must be a multiple of 32 here");
     const T *wf = pw ? static_cast<const T *>(pw->tile) : nullptr;
     if (!wf) {
         const size_t wn = (size_t)kmap->K3 * cout * cin_pad;
-        T *buf = static_cast<T *>(scratch(2, wn * sizeof(T)));
+        T *buf = static_cast<T *>(wbuf ? wbuf : scratch(2, wn * sizeof(T)));
         if (!buf) return TS_ERR_OOM;
         TS_LAUNCH("k_pack_weights", k_pack_weights_tile, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads),
                   static_cast<const T *>(weights->data), buf, kmap->K3, cin, cin_pad, cout, ksteps);
@@ -1403,7 +1406,60 @@ bool prefer_explicit(const ts_kmap *kmap, int cin, int cout, size_t elem) {
     return fused_weight_bytes > 0.6 * explicit_bytes;
 }
 
+// ---- the layer for callers that cannot allocate -----------------------------------------------------------
+// ts_sparse_conv's kernels take two pieces of memory beyond their inputs and outputs: the weights repacked
+// into operand order (a staging buffer written by k_pack_weights* and read by the layer kernel) and, for
+// TS_F32, a row of zeros that stands in for absent neighbours.  Here both live in one array that is part of
+// the library's code object, so that a call reaches no allocator: [0, 4 KiB) zeros, then the packed weights.
+constexpr size_t kStaticZeroBytes = 4096;
+constexpr size_t kStaticWeightBytes = size_t(4) << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticZeroBytes + kStaticWeightBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+unsigned char *g_static_ptr[kMaxDevices] = {nullptr};   // per device: where that device holds its copy of the array
+
+__global__ void k_clear_words(uint32_t *p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// The device address of the array on the current device (looked up once per device).
+int static_scratch(unsigned char **ptr) {
+    int dev = -1;
+    TS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(TS_ERR_UNSUPPORTED, "device ordinal %d is beyond %d", dev, kMaxDevices - 1);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        TS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)));
+        if (!p) return fail(TS_ERR_HIP, "hipGetSymbolAddress gave no address");
+        g_static_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    *ptr = g_static_ptr[dev];
+    return TS_OK;
+}
+}  // namespace
+
 extern "C" {
+
+int ts_sparse_conv_static(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out) {
+    TS_TRY(check_layer(feats, weights, kmap, out));
+    const bool f16 = feats->dtype == TS_F16;
+    const int cin = feats->cols, cout = out->cols, step = f16 ? 32 : Elem<float>::KSTEP;
+    if (cin % step != 0) return fail(TS_ERR_UNSUPPORTED, "ts_sparse_conv_static: C_in must be a multiple of %d, got %d (ts_sparse_conv pads narrower rows, in memory it allocates)", step, cin);
+    const size_t wbytes = (size_t)kmap->K3 * cin * cout * (f16 ? 2 : 4);
+    if (wbytes > kStaticWeightBytes)
+        return fail(TS_ERR_UNSUPPORTED, "ts_sparse_conv_static: the weights take %zu bytes, the static area holds %zu (K^3 * C_in * C_out * element size)", wbytes, kStaticWeightBytes);
+    if (kmap->n_out == 0) return TS_OK;
+    unsigned char *base = nullptr;
+    TS_TRY(static_scratch(&base));
+    void *wbuf = base + kStaticZeroBytes;
+    if (f16) return run_fused_f16(feats, weights, kmap, out, Epilogue(), nullptr, wbuf);
+    // the zeros are never written by a layer kernel; they are cleared all the same, so that nothing rests on
+    // what an earlier user of the array left there (a fill kernel, not a memset: a caller may be capturing)
+    TS_LAUNCH("k_clear_words", k_clear_words, dim3((unsigned)(kStaticZeroBytes / 4 / kThreads)), dim3(kThreads), reinterpret_cast<uint32_t *>(base), (int)(kStaticZeroBytes / 4));
+    return run_fused_staged<float>(feats, weights, kmap, out, nullptr, wbuf, base);
+}
 
 int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
                       int dataflow) {
