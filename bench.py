@@ -2,14 +2,19 @@
 """Benchmark of the sparse-convolution hot path on one MI355X.
 
 A "step" is one pass of the whole path over the ~150k-voxel LiDAR-like workload
-(config 3): ts_build_kmap (pack + hash build, map search, rank bitmaps, per-offset
-compaction) followed by ts_sparse_conv (fused output-stationary kernel), C_in = C_out = 64,
-fp16 in / fp32 accumulate, inputs resident in HBM.  Prints ONE JSON line.
+(config 3): the kernel-map build in its non-waiting form (keys packed and inserted into the
+hash table, the symmetric map search that fills the out-major neighbour table; the per-offset
+counts, rank bitmaps and pair lists are derived only when something asks for them, and the fused
+layer does not) followed by the fused output-stationary layer kernel, C_in = C_out = 64,
+fp16 in / fp32 accumulate, inputs resident in HBM, no host round trip inside a step.
+`ms_per_step_waiting` is the same step with the waiting build (row pass, scan, sizes and error
+flags brought to the host) in its place.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--channels C] [--no-cpu-baseline]
     python bench.py --pmc-run      # short run for `rocprofv3 --pmc ...`: a few steps plus three
                                    # 256 MiB plain copies that calibrate the byte counters
-    python bench.py --sweep        # adds the layer at 10x the voxels (batch-tiled scene)
+    python bench.py --no-sweep     # leaves out the 10x / 100x scenes (batch-tiled config 3)
+    python bench.py --no-configs   # leaves out the per-config rows (configs 1, 2, 2b, 4)
     python bench.py --step-only    # the timed steps and nothing else (what the kernel-trace profile runs)
 """
 import argparse
@@ -26,6 +31,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA, vendor figure
+F32_PEAK_TFLOPS = 157.3        # fp32 (vector and matrix), vendor figure
 COPY_BYTES = 256 << 20
 
 
@@ -44,22 +50,35 @@ def explicit_stage_bytes(n_in, n_out, m, m_moved, c_in, c_out, k3, b):
 
 
 def kmap_bytes(n, m, k3, table_slots):
-    """Algorithmic bytes of a stride-1 map build: coordinates in, table init + fill, one 8-byte
-    probe per (point, half of the offsets), pair lists out (in, out) plus the position table."""
-    return 16 * n + 12 * table_slots + 12 * n + (k3 - 1) // 2 * n * 8 + 8 * m + 8 * m
+    """Algorithmic bytes of the stride-1 map build that is timed (ts_build_kmap, waiting form): coordinates
+    in, table init + fill, one 8-byte probe per (point, half of the offsets), and what it writes: one
+    4-byte neighbour entry per pair, a bitmask word per row, and the rank bitmaps (12 bytes per offset and
+    64-row block).  The offset-major pair lists are not part of it: they are derived on first use."""
+    return 16 * n + 12 * table_slots + 12 * n + (k3 - 1) // 2 * n * 8 + 4 * m + 4 * n + 12 * k3 * ((n + 63) // 64)
+
+
+def source_tag():
+    """First 12 hex digits of the SHA-256 of the layer kernels' source: what a measured traffic figure
+    belongs to."""
+    import hashlib
+    path = os.path.join(ROOT, "paper_2204_10319_amd", "csrc", "ts_conv.hip")
+    return hashlib.sha256(open(path, "rb").read()).hexdigest()[:12]
 
 
 def read_traffic(kernel, workload):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, calibrated);
-    kept in profiles/traffic.txt as 'kernel workload fetch_bytes write_bytes'."""
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, calibrated); kept in
+    profiles/traffic.txt as 'kernel workload fetch_bytes write_bytes source_tag'.  A figure counted on
+    another version of the kernel source is not reported: (None, its tag)."""
     path = os.path.join(ROOT, "profiles", "traffic.txt")
     if not os.path.exists(path):
-        return None
+        return None, None
     for line in open(path):
         parts = line.split()
-        if len(parts) == 4 and parts[0] == kernel and parts[1] == workload:
-            return int(float(parts[2]) + float(parts[3]))
-    return None
+        if len(parts) == 5 and parts[0] == kernel and parts[1] == workload:
+            if parts[4] != source_tag():
+                return None, parts[4]
+            return int(float(parts[2]) + float(parts[3])), parts[4]
+    return None, None
 
 
 def main():
@@ -70,7 +89,8 @@ def main():
     ap.add_argument("--channels", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-run", action="store_true")
-    ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-configs", action="store_true")
     ap.add_argument("--step-only", action="store_true")
     ap.add_argument("--network-run", action="store_true",
                     help="only 10 passes of the config-5 network (17 map builds + 45 layers each), for profiling")
@@ -84,7 +104,7 @@ def main():
 
     import torch
     from paper_2204_10319_amd import binding as ts
-    from workloads import lidar_scan_coords, tile_batches, features, conv_weights
+    from workloads import lidar_scan_coords, tile_batches, features, conv_weights, uniform_grid_coords, box_surface_coords
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -109,6 +129,11 @@ def main():
         # the build does not wait for its sizes to reach the host (nothing in this step needs them): map
         # build and layer run back to back on the device
         kmap = ts.ts_build_kmap(coords, K, 1, wait=False)
+        ts.ts_sparse_conv_prepared(x, pw, kmap, out=out)
+        return kmap
+
+    def step_waiting():
+        kmap = ts.ts_build_kmap(coords, K, 1)      # waits: row pass, scan, sizes and error flags on the host
         ts.ts_sparse_conv_prepared(x, pw, kmap, out=out)
         return kmap
 
@@ -171,6 +196,15 @@ def main():
     dom_name = [k for k in prof if k.startswith(dominant)][0]
     launches, total_ms = prof[dom_name]
     dom_us = total_ms * 1e3 / launches
+
+    for _ in range(5):
+        step_waiting().free()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_waiting().free()
+    torch.cuda.synchronize()
+    ms_per_step_waiting = (time.perf_counter() - t0) * 1e3 / args.steps
 
     kmap = ts.ts_build_kmap(coords, K, 1)
     M = kmap.num_pairs
@@ -241,8 +275,13 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) * 1e3 / iters   # us
 
-    def layer_report(km, n, m, c):
-        xc = torch.from_numpy(features(300 + c, n, c, np.float16)).cuda()
+    def layer_report(km, n, m, c, device_features=False):
+        if device_features:   # timing only, at sizes where drawing the features on the host would take longer than the run
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(300 + c)
+            xc = torch.randn((n, c), generator=gen, device="cuda", dtype=torch.float32).to(torch.float16)
+        else:
+            xc = torch.from_numpy(features(300 + c, n, c, np.float16)).cuda()
         wc = torch.from_numpy(conv_weights(301 + c, K3, c, c, np.float16)).cuda()
         oc = torch.empty((n, c), dtype=torch.float16, device="cuda")
         fused_us = time_calls(lambda: ts.ts_sparse_conv(xc, wc, km, oc, ts.TS_DATAFLOW_FUSED), 30)
@@ -384,13 +423,16 @@ def main():
         net_report["forward_graph_ms" + tag] = round(graph_us * 1e-3, 3)
     breakdown["config5_network"] = net_report
 
-    if args.sweep:
+    if not args.no_sweep:
         big_h = tile_batches(coords_h, 10)
         big = torch.from_numpy(big_h).cuda()
         kbig = ts.ts_build_kmap(big, K, 1)
         breakdown["sweep_10x"] = {"N": int(big_h.shape[0]), "M": int(kbig.num_pairs),
                                   "kmap_build_us": round(time_calls(lambda: ts.ts_build_kmap(big, K, 1).free(), 10), 1),
-                                  "C64": layer_report(kbig, big_h.shape[0], kbig.num_pairs, 64)}
+                                  "C64": layer_report(kbig, big_h.shape[0], kbig.num_pairs, 64, True)}
+        sl = 1 << int(np.ceil(np.log2(2 * big_h.shape[0])))
+        kb10 = kmap_bytes(big_h.shape[0], breakdown["sweep_10x"]["M"], K3, sl)
+        breakdown["sweep_10x"]["kmap_frac_hbm"] = round(kb10 / breakdown["sweep_10x"]["kmap_build_us"] * 1e-3 / HBM_PEAK_GBS, 4)
         kbig.free()
         del big
         huge_h = tile_batches(coords_h, 100)
@@ -398,9 +440,74 @@ def main():
         khuge = ts.ts_build_kmap(huge, K, 1)
         breakdown["sweep_100x"] = {"N": int(huge_h.shape[0]), "M": int(khuge.num_pairs),
                                    "kmap_build_us": round(time_calls(lambda: ts.ts_build_kmap(huge, K, 1).free(), 5), 1),
-                                   "C64": layer_report(khuge, huge_h.shape[0], khuge.num_pairs, 64)}
+                                   "C64": layer_report(khuge, huge_h.shape[0], khuge.num_pairs, 64, True)}
+        sl = 1 << int(np.ceil(np.log2(2 * huge_h.shape[0])))
+        kb100 = kmap_bytes(huge_h.shape[0], breakdown["sweep_100x"]["M"], K3, sl)
+        breakdown["sweep_100x"]["kmap_frac_hbm"] = round(kb100 / breakdown["sweep_100x"]["kmap_build_us"] * 1e-3 / HBM_PEAK_GBS, 4)
         khuge.free()
         del huge
+
+    # ---- one row per benchmark configuration other than the headline: sizes, map build, layer, fractions of the
+    # rooflines, and the oracle on the host beside them
+    def config_row(coords_c, K_, s_, transposed, c_in, c_out, np_dt, seed, gain=1.0):
+        import oracle
+        f16 = np_dt == np.float16
+        cd = torch.from_numpy(np.ascontiguousarray(coords_c)).cuda()
+        build_us = time_calls(lambda: ts.ts_build_kmap(cd, K_, s_, transposed).free(), 20)
+        km = ts.ts_build_kmap(cd, K_, s_, transposed)
+        n_in, n_out, m = km.num_in, km.num_out, km.num_pairs
+        xh = features(seed, n_in, c_in, np_dt)
+        wh = conv_weights(seed + 1, K_ ** 3, c_in, c_out, np_dt, gain=gain)
+        xc, wc = torch.from_numpy(xh).cuda(), torch.from_numpy(wh).cuda()
+        oc = torch.empty((n_out, c_out), dtype=xc.dtype, device="cuda")
+        layer_us = time_calls(lambda: ts.ts_sparse_conv(xc, wc, km, oc), 30)
+        ts.ts_profile_enable(True)
+        for _ in range(20):
+            ts.ts_sparse_conv(xc, wc, km, oc)
+        pk = {k: round(v[1] * 1e3 / v[0], 2) for k, v in ts.ts_profile_read().items()}
+        ts.ts_profile_enable(False)
+        main_k = max((k for k in pk if not k.startswith("k_pack") and not k.startswith("k_pad")), key=lambda k: pk[k])
+        b = 2 if f16 else 4
+        fb = fused_conv_bytes(n_in, n_out, m, c_in, c_out, K_ ** 3, b)
+        flops = 2.0 * m * c_in * c_out
+        peak_tf = MFMA_F16_PEAK_TFLOPS if f16 else F32_PEAK_TFLOPS
+        row = {"N_in": int(n_in), "N_out": int(n_out), "M": int(m), "C_in": c_in, "C_out": c_out, "K": K_, "stride": s_,
+               "transposed": bool(transposed), "dtype": "f16" if f16 else "f32",
+               "kmap_build_us": round(build_us, 1), "layer_us": round(layer_us, 2), "kernels_us": pk,
+               "layer_kernel": main_k, "algorithmic_bytes": int(fb),
+               "layer_kernel_GBs": round(fb / pk[main_k] * 1e-3, 1),
+               "layer_kernel_frac_hbm": round(fb / pk[main_k] * 1e-3 / HBM_PEAK_GBS, 4),
+               "layer_kernel_TFLOPs": round(flops / pk[main_k] * 1e-6, 2),
+               "layer_kernel_frac_matrix_peak": round(flops / pk[main_k] * 1e-6 / peak_tf, 5),
+               "matrix_peak_TFLOPs": peak_tf}
+        if s_ == 1:
+            slots = 1 << int(np.ceil(np.log2(max(2 * n_in, 1024))))
+            row["kmap_frac_hbm"] = round(kmap_bytes(n_in, m, K_ ** 3, slots) / build_us * 1e-3 / HBM_PEAK_GBS, 4)
+        km.free()
+        if not args.no_cpu_baseline:
+            th = oracle.default_threads()
+            c0 = time.perf_counter()
+            q = oracle.out_coords(coords_c, K_, s_)
+            oracle.kmap(coords_c, q, K_, s_)
+            c1 = time.perf_counter()
+            if transposed:
+                oracle.conv_transposed(coords_c, xh, wh, K_, s_, coarse_coords=q, threads=th)
+            else:
+                oracle.conv(coords_c, xh, wh, K_, s_, out_coords_=q, threads=th)
+            c2 = time.perf_counter()
+            row["oracle_map_ms_1_thread"] = round((c1 - c0) * 1e3, 1)
+            row["oracle_layer_ms"] = round((c2 - c1) * 1e3, 1)
+            row["oracle_threads"] = th
+        return row
+
+    if not args.no_configs:
+        cfg = {}
+        cfg["config1_uniform_grid_fp32_C32"] = config_row(uniform_grid_coords(0), 3, 1, False, 32, 32, np.float32, 100)
+        cfg["config2_box_surfaces_9_boxes_C64"] = config_row(box_surface_coords(1, n_boxes=9), 3, 1, False, 64, 64, np.float16, 200)
+        cfg["config2b_box_surfaces_40_boxes_C64"] = config_row(box_surface_coords(1, n_boxes=40), 3, 1, False, 64, 64, np.float16, 200)
+        cfg["config4_down_K2s2_64to128"] = config_row(coords_h, 2, 2, False, 64, 128, np.float16, 400, gain=8.0)
+        cfg["config4_up_K2s2_transposed_128to64"] = config_row(coords_h, 2, 2, True, 128, 64, np.float16, 402, gain=8.0)
+        breakdown["configs"] = cfg
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores (whole config-3 layer)
     cpu = None
@@ -425,17 +532,19 @@ def main():
     fb = fused_conv_bytes(N, N, M, C, C, K3, 2)
     achieved = fb / dom_us * 1e-3   # GB/s
     workload = f"config3_C{C}"
+    traffic, traffic_tag = read_traffic(dom_name, workload)
     result = {
         "metric": "sparse_conv_layer_latency_ms (kernel-map build + one 3x3x3 submanifold layer, ~150k voxels)",
         "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak",
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_waiting": round(ms_per_step_waiting, 4),
+        "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": "config 3: simulated 64-beam LiDAR, 5 sweeps, 0.05 m voxels", "N": int(N),
                    "M": int(M), "C_in": C, "C_out": C, "kernel": 3, "stride": 1,
                    "map_sizes": [int(s) for s in sizes]},
         "roofline": {"kernel": dom_name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": read_traffic(dom_name, workload),
+                     "traffic": traffic, "traffic_source_tag": traffic_tag, "source_tag": source_tag(),
                      "avg_us": round(dom_us, 2), "algorithmic_bytes": int(fb),
                      "mfma_tflops": round(2.0 * M * C * C / dom_us * 1e-6, 1),
                      "mfma_frac": round(2.0 * M * C * C / dom_us * 1e-6 / MFMA_F16_PEAK_TFLOPS, 4)},
