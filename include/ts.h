@@ -270,6 +270,22 @@ void ts_weights_free(ts_weights *weights);
 int  ts_sparse_conv_prepared(const ts_tensor *feats, const ts_weights *weights, const ts_kmap *kmap,
                              const void *bias, const ts_tensor *residual, int relu, ts_tensor *out);
 
+/*
+ * ts_sparse_conv_prepared on an input that is the channel concatenation [feats | feats2] of two tensors
+ * (a U-Net decoder's skip connection), without forming it: the layer kernels read input channels below
+ * feats->cols from feats and the others from feats2 (the paper's Principle II, Sec. 3: data movement is what
+ * to cut; the concatenated tensor would be written once and read by every layer that takes it).
+ *   feats   [num_in][C1], feats2 [num_in][C2], same dtype; weights prepared from [K^3 * (C1 + C2)][C_out],
+ *           rows of a weight slice in the order of the concatenation.
+ * The result equals, bit for bit, ts_sparse_conv_prepared on the concatenated tensor.  The parts are read in
+ * place when C1 and C2 are multiples of 32 (TS_F16) or, where the library takes the fetch-on-demand dataflow,
+ * of 16 (TS_F16) / 8 (TS_F32); any other pair of widths is concatenated into library scratch first.
+ * feats2 == NULL is ts_sparse_conv_prepared.
+ */
+int ts_sparse_conv_prepared2(const ts_tensor *feats, const ts_tensor *feats2, const ts_weights *weights,
+                             const ts_kmap *kmap, const void *bias, const ts_tensor *residual, int relu,
+                             ts_tensor *out);
+
 /* Same as ts_sparse_conv, with the dataflow chosen by the caller (TS_DATAFLOW_*). */
 int ts_sparse_conv_ex(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
                       ts_tensor *out, int dataflow);

@@ -28,7 +28,7 @@ EXPORTS = [
     "ts_build_kmap", "ts_build_kmap_async", "ts_build_kmap_ex", "ts_identity_kmap", "ts_kmap_status", "ts_kmap_prepare", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_static", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
-    "ts_sparse_conv_prepared", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
+    "ts_sparse_conv_prepared", "ts_sparse_conv_prepared2", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
     "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_mfma_loop", "ts_bias_act", "ts_concat_cols",
 ]
 
@@ -105,6 +105,8 @@ def load_library(path: str | None = None):
     lib.ts_weights_free.restype = None
     lib.ts_sparse_conv_prepared.argtypes = [tp, vp, vp, vp, tp, ci, tp]
     lib.ts_sparse_conv_prepared.restype = ci
+    lib.ts_sparse_conv_prepared2.argtypes = [tp, tp, vp, vp, vp, tp, ci, tp]
+    lib.ts_sparse_conv_prepared2.restype = ci
     lib.ts_gather.argtypes = [tp, vp, tp]
     lib.ts_grouped_matmul.argtypes = [tp, tp, tp, vp, tp]
     lib.ts_scatter_reduce.argtypes = [tp, vp, tp]
@@ -483,6 +485,24 @@ def ts_sparse_conv_prepared(feats: torch.Tensor, weights: Weights, kmap: KMap, b
                                                   bias.data_ptr() if bias is not None else None,
                                                   ctypes.byref(r) if r is not None else None, int(bool(relu)),
                                                   ctypes.byref(o)))
+    return out
+
+
+def ts_sparse_conv_prepared2(feats: torch.Tensor, feats2: torch.Tensor | None, weights: Weights, kmap: KMap,
+                             bias: torch.Tensor | None = None, residual: torch.Tensor | None = None,
+                             relu: bool = False, out: torch.Tensor | None = None) -> torch.Tensor:
+    """ts_sparse_conv_prepared on the channel concatenation [feats | feats2], which is never formed."""
+    _use_current_stream()
+    if out is None:
+        out = torch.empty((kmap.num_out, weights.c_out), dtype=feats.dtype, device=feats.device)
+    f, o = _as_ts(feats), _as_ts(out)
+    f2 = _as_ts(feats2) if feats2 is not None else None
+    r = _as_ts(residual) if residual is not None else None
+    _check(load_library().ts_sparse_conv_prepared2(ctypes.byref(f), ctypes.byref(f2) if f2 is not None else None,
+                                                   weights.handle, kmap.handle,
+                                                   bias.data_ptr() if bias is not None else None,
+                                                   ctypes.byref(r) if r is not None else None, int(bool(relu)),
+                                                   ctypes.byref(o)))
     return out
 
 

@@ -311,7 +311,7 @@ __device__ __forceinline__ void static_for(Fn &&fn) {
 
 // (Three waves per SIMD are asked for wherever the accumulators leave room: left to itself the compiler
 // takes a few registers more than that allows for the six- and eight-block single-step variants.)
-template <int NCO, int KSTEPS, int DEPTH>
+template <int NCO, int KSTEPS, int DEPTH, bool TWO = false>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NCO * KSTEPS <= 8 ? 3 : 2))) k_conv_tile(const _Float16 *__restrict__ X, const u32x4 *__restrict__ Wf,
                                                         const int32_t *__restrict__ nbr, int stride,
                                                         const int32_t *__restrict__ perm,
@@ -319,7 +319,12 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(N
                                                         _Float16 *__restrict__ out, int *__restrict__ sched,
                                                         int cin, int cout, int K3, const _Float16 *__restrict__ bias,
                                                         const _Float16 *__restrict__ residual, int relu, int x_bytes,
-                                                        int w_bytes, int centre) {
+                                                        int w_bytes, int centre, const _Float16 *__restrict__ X2,
+                                                        int x2_bytes, int cin1) {
+    // TWO: the layer's input is the channel concatenation [X | X2], which is never formed: input channels
+    // below cin1 are read from X (rows of cin1 channels), the others from X2 (rows of cin - cin1 channels);
+    // cin1 is a multiple of 32, so each 32-channel operand step lies in one of the two.  Otherwise X2,
+    // x2_bytes are unused and cin1 = cin.
     constexpr int KC = KSTEPS * 32, FRAGS = NCO * KSTEPS, SLAB = FRAGS * 64;   // slab in 16-byte vectors
     constexpr int WV = (SLAB + kThreads - 1) / kThreads;
     __shared__ u32x4 lds_w[2][SLAB];
@@ -414,9 +419,11 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(N
     // short on purpose: with ~200 vector instructions per stage around 16 MFMAs this kernel was
     // bound by instruction issue.
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16 *>(X), 0, x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t xrsrc2 = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16 *>(TWO ? X2 : X), 0, TWO ? x2_bytes : x_bytes, 0x00020000);
+    const int row_bytes2 = (cin - cin1) * 2;
     const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4 *>(Wf), 0, w_bytes, 0x00020000);
     constexpr int kNoRow = (int)0x80000000u;   // beyond any buffer this kernel is launched with
-    const int row_bytes = cin * 2, xlane = g * 16;
+    const int row_bytes = cin1 * 2, xlane = g * 16;
     int wlane[WV];
 #pragma unroll
     for (int v = 0; v < WV; ++v) {
@@ -453,10 +460,24 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(N
         const int off0 = j0 >= 0 ? j0 * row_bytes + xlane : kNoRow;
         const int off1 = j1 >= 0 ? j1 * row_bytes + xlane : kNoRow;
         const int xsoff = ch * (KC * 2);
+        int offb0 = 0, offb1 = 0;
+        if constexpr (TWO) {
+            offb0 = j0 >= 0 ? j0 * row_bytes2 + xlane : kNoRow;
+            offb1 = j1 >= 0 ? j1 * row_bytes2 + xlane : kNoRow;
+        }
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
-            const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off0, xsoff + ks * 64, 0);
-            const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off1, xsoff + ks * 64, 0);
+            u32x4 v0, v1;
+            if constexpr (TWO) {
+                const int c0 = ch * KC + ks * 32;        // first input channel of this operand step
+                const bool second = c0 >= cin1;          // wave-uniform: the step lies in X2
+                const int so = second ? (c0 - cin1) * 2 : c0 * 2;
+                v0 = __builtin_amdgcn_raw_buffer_load_b128(second ? xrsrc2 : xrsrc, second ? offb0 : off0, so, 0);
+                v1 = __builtin_amdgcn_raw_buffer_load_b128(second ? xrsrc2 : xrsrc, second ? offb1 : off1, so, 0);
+            } else {
+                v0 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off0, xsoff + ks * 64, 0);
+                v1 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off1, xsoff + ks * 64, 0);
+            }
             __builtin_memcpy(&xreg[d][0][ks], &v0, 16);
             __builtin_memcpy(&xreg[d][1][ks], &v1, 16);
         }
@@ -781,7 +802,10 @@ __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F
                                                          const T *__restrict__ Wt, Offs offs, MmPlan plan,
                                                          float *__restrict__ G, const T *__restrict__ zero_row,
                                                          int cin, int cout, int centre,
-                                                         const int32_t *__restrict__ in_idx) {
+                                                         const int32_t *__restrict__ in_idx,
+                                                         const T *__restrict__ X2, int cin1) {
+    // X2 != nullptr (rows fetched through the map only: F is not used then): the input is the channel
+    // concatenation [X | X2], never formed; channels below cin1 come from X, the others from X2.
     typedef Shape<T, NCB, KC> S;
     typedef typename S::vec vec;
     __shared__ __attribute__((aligned(16))) T lds_w[S::SLAB];
@@ -797,7 +821,9 @@ __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, m = lane & 31, h = lane >> 5;
     const int64_t p = (int64_t)lo + (int64_t)t * kTileRows + wave * kWaveRows + m;   // row of F and G
     const bool valid = p < hi;
-    const T *src = !valid ? zero_row : (n == centre ? X + (p - lo) * cin : (in_idx ? X + (int64_t)in_idx[p] * cin : F + p * cin));
+    const int64_t j = !valid ? 0 : (n == centre ? p - lo : (in_idx ? (int64_t)in_idx[p] : p));
+    const T *src = !valid ? zero_row : ((n == centre || in_idx) ? X + j * cin1 : F + p * cin);
+    const T *src2 = (!valid || !X2) ? zero_row : X2 + j * (cin - cin1) - cin1;   // indexed with k0 >= cin1
     const int kstride = valid ? 1 : 0;   // the zero row is one chunk long
     floatx16 acc[NCB];
 #pragma unroll
@@ -806,7 +832,7 @@ __global__ void __launch_bounds__(kThreads) k_grouped_mm(const T *__restrict__ F
     vec wreg[S::WV], bx[S::NKB];
     for (int k0 = 0; k0 < cin; k0 += KC) {
         load_w_regs<S, T>(wreg, Wt, n, co0, k0, cin, cout);
-        load_x_regs<S, T>(bx, src + k0 * kstride + h * S::VEC);
+        load_x_regs<S, T>(bx, (k0 < cin1 ? src : src2) + k0 * kstride + h * S::VEC);
         __syncthreads();
         store_w_regs<S, T>(wreg, lds_w);
         __syncthreads();
@@ -1085,14 +1111,21 @@ inline int compute_units() {
     return n;
 }
 
-template <int NCO, int KSTEPS>
+// The second half of a layer input that is the channel concatenation [x | x2] of two tensors (never
+// formed): x has cin1 channels per row, x2 the rest.  x2 == nullptr: one tensor, as usual.
+struct Second {
+    const void *x2 = nullptr;
+    int cin1 = 0;
+};
+
+template <int NCO, int KSTEPS, bool TWO = false>
 void launch_conv_tile(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap, ts_tensor *out, int cin_pad,
-                      const Epilogue &ep) {
+                      const Epilogue &ep, const Second &sec = Second()) {
     // as many workgroups as stay resident at once, fewer for small maps
     static int per_cu = 0;   // per instantiation
     if (per_cu == 0) {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_conv_tile<NCO, KSTEPS, kTileDepth>, kThreads, 0) != hipSuccess || n <= 0) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_conv_tile<NCO, KSTEPS, kTileDepth, TWO>, kThreads, 0) != hipSuccess || n <= 0) {
             (void)hipGetLastError();
             n = 2;
         }
@@ -1100,11 +1133,13 @@ void launch_conv_tile(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap
     }
     const int64_t resident = (int64_t)compute_units() * per_cu;
     dim3 grid((unsigned)(kmap->n_tiles < resident ? kmap->n_tiles : resident), out->cols / (NCO * 16));
-    TS_LAUNCH("k_conv_tile", (k_conv_tile<NCO, KSTEPS, kTileDepth>), grid, dim3(kThreads), x,
+    const int cin1 = TWO ? sec.cin1 : cin_pad;
+    TS_LAUNCH("k_conv_tile", (k_conv_tile<NCO, KSTEPS, kTileDepth, TWO>), grid, dim3(kThreads), x,
               reinterpret_cast<const u32x4 *>(wf), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->rows_done ? kmap->d_tile_order : nullptr,
               kmap->n_out, static_cast<_Float16 *>(out->data), kmap->d_sched, cin_pad, out->cols, kmap->K3,
               static_cast<const _Float16 *>(ep.bias), static_cast<const _Float16 *>(ep.residual), ep.relu,
-              (int)((size_t)kmap->n_in * cin_pad * 2), (int)((size_t)kmap->K3 * cin_pad * out->cols * 2), kmap->centre);
+              (int)((size_t)kmap->n_in * cin1 * 2), (int)((size_t)kmap->K3 * cin_pad * out->cols * 2), kmap->centre,
+              static_cast<const _Float16 *>(sec.x2), (int)((size_t)kmap->n_in * (cin_pad - cin1) * 2), cin1);
 }
 
 // Narrow layers (C_in <= 32, C_out = 32): the kernel that keeps all weights in LDS.  False if this
@@ -1131,8 +1166,10 @@ bool launch_conv_res(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap,
 }
 
 // fp16: input channels padded to a multiple of 32 (one MFMA step), chunks of 64 where possible.
+// feats->cols is the layer's C_in; with sec.x2 set, feats->data holds only the first sec.cin1 channels of
+// every row (both parts multiples of 32 channels: nothing is padded then).
 int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
-                  const Epilogue &ep, const ts_weights *pw = nullptr, void *wbuf = nullptr) {
+                  const Epilogue &ep, const ts_weights *pw = nullptr, void *wbuf = nullptr, const Second &sec = Second()) {
     typedef _Float16 T;
     const int cin = feats->cols, cout = out->cols;
     const int cin_pad = (cin + 31) / 32 * 32;
@@ -1165,7 +1202,7 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
     // 32 input channels and 27 offsets: the kernel with resident weights (for 2x2x2 maps and for 64 -> 32 it
     // measured no faster than k_conv_tile, and 64 -> 64 in two slices of output channels much slower: every
     // slice gathers all rows again)
-    if (cin_pad == 32 && kmap->K3 > 8 && kmap->n_out > 0 && (cout == 32 || cout == 64)) {
+    if (cin_pad == 32 && kmap->K3 > 8 && kmap->n_out > 0 && (cout == 32 || cout == 64) && !sec.x2) {
         const bool done = cout == 32 ? launch_conv_res<2, 1>(x, wf, kmap, out, ep) : launch_conv_res<4, 1>(x, wf, kmap, out, ep);
         if (done) {
             TS_HIP(hipGetLastError());
@@ -1184,10 +1221,13 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
             nco = c;
             break;
         }
-#define TS_TILE_CASE(N)                                                                    \
-    if (nco == N) {                                                                        \
-        if (ksteps == 2) launch_conv_tile<N, 2>(x, wf, kmap, out, cin_pad, ep);          \
-        else launch_conv_tile<N, 1>(x, wf, kmap, out, cin_pad, ep);                      \
+#define TS_TILE_CASE(N)                                                                            \
+    if (nco == N) {                                                                                \
+        if (sec.x2) {                                                                              \
+            if (ksteps == 2) launch_conv_tile<N, 2, true>(x, wf, kmap, out, cin_pad, ep, sec);    \
+            else launch_conv_tile<N, 1, true>(x, wf, kmap, out, cin_pad, ep, sec);                \
+        } else if (ksteps == 2) launch_conv_tile<N, 2>(x, wf, kmap, out, cin_pad, ep);            \
+        else launch_conv_tile<N, 1>(x, wf, kmap, out, cin_pad, ep);                                \
     }
     TS_TILE_CASE(8) TS_TILE_CASE(6) TS_TILE_CASE(4) TS_TILE_CASE(2)
 #undef TS_TILE_CASE
@@ -1232,12 +1272,14 @@ struct GroupedLaunch {
     const T *zero;
     int cin_pad, cout;
     const int32_t *in_idx;
+    const T *X2;
+    int cin1;
     template <int NCB, int KSTEPS>
     void operator()() const {
         constexpr int KC = KSTEPS * Elem<T>::KSTEP;
         dim3 grid((unsigned)plan_tiles(plan), cout / (NCB * 32));
         TS_LAUNCH("k_grouped_mm", (k_grouped_mm<T, NCB, KC>), grid, dim3(kThreads), F, X, wt, offs_of(kmap), plan, G, zero,
-                  cin_pad, cout, kmap->centre, in_idx);
+                  cin_pad, cout, kmap->centre, in_idx, X2, cin1);
     }
 };
 
@@ -1257,13 +1299,20 @@ int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const t
 
 template <class T>
 int grouped_mm_launch(const void *F, const void *X, const void *wt, const ts_kmap *kmap, const MmPlan &plan, float *G,
-                      int cin_pad, int cout, const int32_t *in_idx = nullptr) {
+                      int cin_pad, int cout, const int32_t *in_idx = nullptr, const Second &sec = Second()) {
     if (plan_tiles(plan) == 0) return TS_OK;
     const T *zero = static_cast<const T *>(zero_row());
     if (!zero) return TS_ERR_OOM;
-    dispatch_shape(pick_ncb(cout), pick_ksteps(cin_pad, Elem<T>::KSTEP),
+    // the chunk of input channels a step takes must divide both parts of a two-part input
+    int ksteps = pick_ksteps(cin_pad, Elem<T>::KSTEP);
+    const int cin1 = sec.x2 ? sec.cin1 : cin_pad;
+    if (sec.x2) {
+        const int k1 = pick_ksteps(cin1, Elem<T>::KSTEP), k2 = pick_ksteps(cin_pad - cin1, Elem<T>::KSTEP);
+        ksteps = k1 < k2 ? k1 : k2;
+    }
+    dispatch_shape(pick_ncb(cout), ksteps,
                    GroupedLaunch<T>{static_cast<const T *>(F), static_cast<const T *>(X), static_cast<const T *>(wt),
-                                    kmap, plan, G, zero, cin_pad, cout, in_idx});
+                                    kmap, plan, G, zero, cin_pad, cout, in_idx, static_cast<const T *>(sec.x2), cin1});
     TS_HIP(hipGetLastError());
     return TS_OK;
 }
@@ -1368,17 +1417,19 @@ int reduce_impl(const float *G, const ts_kmap *kmap, ts_tensor *out, const Epilo
 
 template <class T>
 int run_explicit(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap, ts_tensor *out,
-                 const ts_weights *pw = nullptr, bool fetch = false, const Epilogue &ep = Epilogue()) {
+                 const ts_weights *pw = nullptr, bool fetch = false, const Epilogue &ep = Epilogue(),
+                 const Second &sec = Second()) {
     TS_TRY(resolve(kmap));
     Prepared pr;
     TS_TRY(prepare<T>(feats, weights, kmap, &pr, pw));
+    if (sec.x2 && (!fetch || pr.cin_pad != feats->cols)) return fail(TS_ERR_UNSUPPORTED, "a two-part input needs the fetch-on-demand dataflow and unpadded rows");
     const int64_t M = kmap->M;
     float *G = static_cast<float *>(scratch(1, (size_t)(M ? M : 1) * out->cols * sizeof(float)));
     if (!G) return TS_ERR_OOM;
     if (fetch) {   // the matmul reads X_in[j] through the pair lists: no buffer F, no gather launch
         if (M == 0) return reduce_impl<T>(G, kmap, out, ep);
         TS_TRY(ensure_pairs(kmap));
-        TS_TRY(grouped_mm_launch<T>(nullptr, pr.x, pr.wt, kmap, whole_plan(kmap), G, pr.cin_pad, out->cols, kmap->d_in_idx));
+        TS_TRY(grouped_mm_launch<T>(nullptr, pr.x, pr.wt, kmap, whole_plan(kmap), G, pr.cin_pad, out->cols, kmap->d_in_idx, sec));
         return reduce_impl<T>(G, kmap, out, ep);
     }
     void *F = scratch(0, (size_t)(M ? M : 1) * pr.cin_pad * sizeof(T));
@@ -1485,8 +1536,26 @@ int ts_sparse_conv(const ts_tensor *feats, const ts_tensor *weights, const ts_km
 }
 
 // The layer with its optional elementwise tail; pw, when given, holds the weights already packed.
-static int conv_act(const ts_tensor *feats, const ts_tensor *weights, const ts_weights *pw, const ts_kmap *kmap,
-                    const void *bias, const ts_tensor *residual, int relu, ts_tensor *out) {
+static int conv_act(const ts_tensor *feats_in, const ts_tensor *weights, const ts_weights *pw, const ts_kmap *kmap,
+                    const void *bias, const ts_tensor *residual, int relu, ts_tensor *out,
+                    const ts_tensor *feats2 = nullptr) {
+    // With feats2 the layer's input is [feats_in | feats2] along the channels.  Where the kernels can read
+    // the two parts in place (fp16 fused: both parts multiples of 32 channels; fetch-on-demand: multiples of
+    // the operand step) the concatenation is never formed; otherwise it is formed in scratch memory first.
+    ts_tensor cat;
+    const ts_tensor *feats = feats_in;
+    Second sec;
+    if (feats2) {
+        TS_TRY(check_tensor(feats_in, "feats"));
+        TS_TRY(check_tensor(feats2, "feats2"));
+        if (feats2->rows != feats_in->rows || feats2->dtype != feats_in->dtype)
+            return fail(TS_ERR_SHAPE, "feats2 must have the rows and dtype of feats");
+        cat = *feats_in;
+        cat.cols = feats_in->cols + feats2->cols;
+        feats = &cat;
+        sec.x2 = feats2->data;
+        sec.cin1 = feats_in->cols;
+    }
     TS_TRY(check_layer(feats, weights, kmap, out));
     if (residual) {
         TS_TRY(check_tensor(residual, "residual"));
@@ -1498,14 +1567,26 @@ static int conv_act(const ts_tensor *feats, const ts_tensor *weights, const ts_w
     if (kmap->n_out == 0) return TS_OK;
     const bool f16 = feats->dtype == TS_F16;
     const bool go_explicit = prefer_explicit(kmap, feats->cols, out->cols, f16 ? 2 : 4);
+    if (feats2) {
+        const int step = go_explicit ? kstep(feats->dtype) : 32;
+        const bool in_place = (f16 || go_explicit) && feats_in->cols % step == 0 && feats2->cols % step == 0 &&
+                              (go_explicit || ((size_t)kmap->n_in * feats->cols * 2 < (1ull << 31)));
+        if (!in_place) {
+            void *buf = scratch(4, (size_t)(feats->rows ? feats->rows : 1) * feats->cols * (f16 ? 2 : 4));
+            if (!buf) return TS_ERR_OOM;
+            cat.data = buf;
+            TS_TRY(ts_concat_cols(feats_in, feats2, &cat));
+            sec = Second();
+        }
+    }
     Epilogue ep;
     ep.bias = bias;
     ep.residual = residual ? residual->data : nullptr;
     ep.relu = relu != 0;
-    if (f16 && !go_explicit) return run_fused_f16(feats, weights, kmap, out, ep, pw);
+    if (f16 && !go_explicit) return run_fused_f16(feats, weights, kmap, out, ep, pw, nullptr, sec);
     // fetch-on-demand: the tail runs in the scatter-accumulate kernel
     if (go_explicit)
-        return f16 ? run_explicit<_Float16>(feats, weights, kmap, out, pw, true, ep) : run_explicit<float>(feats, weights, kmap, out, pw, true, ep);
+        return f16 ? run_explicit<_Float16>(feats, weights, kmap, out, pw, true, ep, sec) : run_explicit<float>(feats, weights, kmap, out, pw, true, ep, sec);
     // otherwise (fp32, fused): the layer, then the elementwise step on its output
     TS_TRY(run_fused<float>(feats, weights, kmap, out, pw));
     if (!bias && !residual && !relu) return TS_OK;
@@ -1573,6 +1654,14 @@ int ts_sparse_conv_prepared(const ts_tensor *feats, const ts_weights *w, const t
     if (kmap && w->K3 != kmap->K3) return fail(TS_ERR_SHAPE, "weights were prepared for kernel volume %d, the map has %d", w->K3, kmap->K3);
     const ts_tensor desc = {w->wt, (int64_t)w->K3 * w->cin, w->cout, w->dtype};   // shape and dtype for the checks
     return conv_act(feats, &desc, w, kmap, bias, residual, relu, out);
+}
+
+int ts_sparse_conv_prepared2(const ts_tensor *feats, const ts_tensor *feats2, const ts_weights *w, const ts_kmap *kmap,
+                             const void *bias, const ts_tensor *residual, int relu, ts_tensor *out) {
+    if (!w) return fail(TS_ERR_INVALID_ARG, "weights is NULL");
+    if (kmap && w->K3 != kmap->K3) return fail(TS_ERR_SHAPE, "weights were prepared for kernel volume %d, the map has %d", w->K3, kmap->K3);
+    const ts_tensor desc = {w->wt, (int64_t)w->K3 * w->cin, w->cout, w->dtype};
+    return conv_act(feats, &desc, w, kmap, bias, residual, relu, out, feats2);
 }
 
 int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F) {

@@ -34,7 +34,8 @@ void *dev_alloc(size_t bytes);
 void dev_free(void *p);
 
 // Grow-only scratch areas for ts_sparse_conv (slot 0: gather buffer F, 1: partial sums G,
-// 2: packed weights, 3: padded features).  Contents do not survive across calls.
+// 2: packed weights, 3: padded features, 4: a two-part input concatenated where the kernels cannot read the
+// parts in place).  Contents do not survive across calls.
 void *scratch(int slot, size_t bytes);
 
 // 4 KiB of device zeros (a feature row of any supported width), allocated once.

@@ -1,8 +1,9 @@
 """Runs a layer plan (see ``workloads/minkunet.py``) on the GPU through the C-ABI binding.
 
-Only sequencing lives here: kernel maps per resolution level, one ``ts_sparse_conv_act`` per conv op,
-bias / residual / ReLU in the layer kernel's epilogue (``ts_sparse_conv_act``), ``ts_concat_cols`` for
-skip connections.  Maps are
+Only sequencing lives here: kernel maps per resolution level, one ``ts_sparse_conv_prepared`` per conv op,
+bias / residual / ReLU in the layer kernel's epilogue.  A skip connection's concatenation is not formed:
+the layers that take it read its two parts in place (``ts_sparse_conv_prepared2``); ``ts_concat_cols`` runs
+only if something other than a conv asks for the concatenated tensor (a hook, the network's output).  Maps are
 built once per (kind, level) and reused by every layer that needs them (the paper builds maps
 per downsampling block, Sec. 2.3).
 """
@@ -60,19 +61,33 @@ class SparseNet:
         return maps, levels
 
     def forward(self, maps, feats: torch.Tensor, hook=None):
-        """Executes the plan; ``hook(name, tensor)`` (optional) sees every tensor written."""
+        """Executes the plan; ``hook(name, tensor)`` (optional) sees every tensor written (and makes every
+        concatenation materialise, since it asks for the tensor)."""
         t = {"input": feats}
+        parts = {}          # name of a concatenation -> its two source tensors; formed only on demand
+
+        def whole(name):
+            if name not in t:
+                a, b = parts[name]
+                t[name] = ts.ts_concat_cols(a, b)
+            return t[name]
+
         for kind, op in self.ops:
             if kind == "concat":
-                t[op["dst"]] = ts.ts_concat_cols(t[op["a"]], t[op["b"]])
+                parts[op["dst"]] = (whole(op["a"]), whole(op["b"]))
             else:
-                w, b = self.params[op["name"]]
-                res = t[op["residual"]] if op["residual"] else None
-                t[op["dst"]] = ts.ts_sparse_conv_prepared(t[op["src"]], self.prepared[op["name"]], maps[op["map"]], b, res,
-                                                          op["relu"])
+                _, b = self.params[op["name"]]
+                res = whole(op["residual"]) if op["residual"] else None
+                if op["src"] in parts and op["src"] not in t:
+                    xa, xb = parts[op["src"]]
+                    t[op["dst"]] = ts.ts_sparse_conv_prepared2(xa, xb, self.prepared[op["name"]], maps[op["map"]], b, res,
+                                                               op["relu"])
+                else:
+                    t[op["dst"]] = ts.ts_sparse_conv_prepared(whole(op["src"]), self.prepared[op["name"]], maps[op["map"]],
+                                                              b, res, op["relu"])
             if hook:
-                hook(op["dst"], t[op["dst"]])
-        return t[self.output]
+                hook(op["dst"], whole(op["dst"]))
+        return whole(self.output)
 
     def capture(self, maps, feats: torch.Tensor):
         """Records one forward pass into a HIP graph and returns (graph, input buffer, output).

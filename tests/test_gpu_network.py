@@ -32,6 +32,10 @@ def _run_both(coords, seed, box=None):
     got = {}
     y = net.forward(maps, to_dev(x), hook=lambda n, v: got.__setitem__(n, v.cpu().numpy()))
     torch.cuda.synchronize()
+    # without a hook nobody asks for the concatenated tensors: the layers behind a skip connection read its two
+    # parts in place, and the pass must give the same bits
+    y_plain = net.forward(maps, to_dev(x))
+    assert torch.equal(y_plain, y), "the concat-free pass differs from the pass that forms the concatenations"
     # (1) the free-running pass: every tensor within the stated norm; its rows within ten times that (the
     # two runs have drifted apart by the rounding differences of up to 45 layers, so rows are not held to
     # the single-layer bound here; a row that lost a neighbour term is off by tens of percent)
@@ -57,14 +61,22 @@ def _run_both(coords, seed, box=None):
         if name not in dev:
             dev[name] = to_dev(ref[name])
         return dev[name]
+    cat_parts = {}
     for kind, op in ops:
         if kind == "concat":
             g = ts.ts_concat_cols(on_dev(op["a"]), on_dev(op["b"]))
             assert np.array_equal(g.cpu().numpy(), ref[op["dst"]]), op["dst"]
+            cat_parts[op["dst"]] = (op["a"], op["b"])
             continue
         _, b = net.params[op["name"]]
         res = on_dev(op["residual"]) if op["residual"] else None
-        g = ts.ts_sparse_conv_prepared(on_dev(op["src"]), net.prepared[op["name"]], maps[op["map"]], b, res, op["relu"])
+        if op["src"] in cat_parts:      # as the network driver runs it: the two parts read in place
+            pa, pb = cat_parts[op["src"]]
+            g = ts.ts_sparse_conv_prepared2(on_dev(pa), on_dev(pb), net.prepared[op["name"]], maps[op["map"]], b, res, op["relu"])
+            g1 = ts.ts_sparse_conv_prepared(on_dev(op["src"]), net.prepared[op["name"]], maps[op["map"]], b, res, op["relu"])
+            assert torch.equal(g, g1), f"{op['name']}: two-part input differs from the concatenated one"
+        else:
+            g = ts.ts_sparse_conv_prepared(on_dev(op["src"]), net.prepared[op["name"]], maps[op["map"]], b, res, op["relu"])
         r = ref[op["dst"]].astype(np.float64)
         mag = np.abs(r) + np.abs(params[op["name"]][1].astype(np.float64))[None, :]
         if op["residual"]:

@@ -865,3 +865,51 @@ def test_async_build_reports_bad_input_late():
     del maps
     fresh = ts.ts_build_kmap(ok, 3, 1, wait=False)
     assert fresh.num_pairs == ts.ts_build_kmap(ok, 3, 1).num_pairs
+
+
+# ---- a layer on a two-part input (the skip connection of a U-Net decoder), the concatenation never formed ----
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+@pytest.mark.parametrize("K,s,transposed", [(3, 1, False), (1, 1, False), (2, 2, True), (2, 2, False)])
+@pytest.mark.parametrize("c1,c2,c_out", [(96, 32, 96), (96, 64, 96), (128, 128, 128), (32, 96, 64), (64, 64, 32),
+                                          (48, 16, 32), (24, 40, 64), (256, 256, 256)])
+def test_two_part_input_equals_the_concatenated_input(dtype, K, s, transposed, c1, c2, c_out):
+    """ts_sparse_conv_prepared2(a, b) against ts_sparse_conv_prepared([a | b]) bit for bit, and against the
+    oracle on the concatenated input; widths the kernels read in place (multiples of 32), widths only the
+    fetch-on-demand dataflow reads in place (multiples of 16 / 8: wide layers on few points take it), and
+    widths that are concatenated in scratch (24 + 40); with and without the elementwise tail."""
+    n = 600 if c1 + c2 >= 256 else 2500          # few points + wide layers: the library takes fetch-on-demand
+    coords = _rand_coords(4000 + c1 + 3 * c2 + K, n, -8, 8, batches=2)
+    kmap = ts.ts_build_kmap(to_dev(coords), K, s, transposed)
+    nd = np_dtype(dtype)
+    a_h, b_h = features(4100 + c1, kmap.num_in, c1, nd), features(4200 + c2, kmap.num_in, c2, nd)
+    w_h = conv_weights(4300 + c_out, K ** 3, c1 + c2, c_out, nd)
+    a, b, w = to_dev(a_h), to_dev(b_h), to_dev(w_h)
+    cat_h = np.concatenate([a_h, b_h], axis=1)
+    cat = to_dev(cat_h)
+    pw = ts.ts_weights_prepare(w)
+    bias = to_dev(features(4400, 1, c_out, nd).reshape(-1))
+    res = to_dev(features(4401, kmap.num_out, c_out, nd))
+    for bb, rr, relu in [(None, None, False), (bias, res, True)]:
+        want = ts.ts_sparse_conv_prepared(cat, pw, kmap, bb, rr, relu)
+        got = ts.ts_sparse_conv_prepared2(a, b, pw, kmap, bb, rr, relu)
+        assert torch.equal(got, want), (c1, c2, c_out, relu)
+    assert torch.equal(ts.ts_sparse_conv_prepared2(cat, None, pw, kmap), ts.ts_sparse_conv_prepared(cat, pw, kmap))
+    check_features(ts.ts_sparse_conv_prepared2(a, b, pw, kmap), oracle_conv(coords, cat_h, w_h, K, s, transposed), dtype,
+                   f"two-part input {c1}+{c2}->{c_out} K{K} s{s} t{int(transposed)}")
+
+
+def test_two_part_input_errors():
+    coords = _rand_coords(4500, 300, 0, 8)
+    kmap = ts.ts_build_kmap(to_dev(coords), 3, 1)
+    a = torch.zeros((300, 32), dtype=torch.float16, device="cuda")
+    pw = ts.ts_weights_prepare(torch.zeros((27, 64, 32), dtype=torch.float16, device="cuda"))
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_sparse_conv_prepared2(a, torch.zeros((299, 32), dtype=torch.float16, device="cuda"), pw, kmap)
+    assert e.value.code == ts.TS_ERR_SHAPE
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_sparse_conv_prepared2(a, torch.zeros((300, 32), dtype=torch.float32, device="cuda"), pw, kmap)
+    assert e.value.code == ts.TS_ERR_SHAPE
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_sparse_conv_prepared2(a, torch.zeros((300, 64), dtype=torch.float16, device="cuda"), pw, kmap)
+    assert e.value.code == ts.TS_ERR_SHAPE          # 32 + 64 channels against weights prepared for 64
