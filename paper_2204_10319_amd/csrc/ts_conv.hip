@@ -496,6 +496,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(N
                 u32x4 raw[NCO];
 #pragma unroll
                 for (int cb = 0; cb < NCO; ++cb) raw[cb] = slab[(cb * KSTEPS + ks) * 64 + lane];
+                __builtin_amdgcn_s_setprio(1);
 #pragma unroll
                 for (int cb = 0; cb < NCO; ++cb) {
                     half8v a;
@@ -503,6 +504,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(N
                     acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xreg[d][0][ks], acc[cb][0], 0, 0, 0);
                     acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xreg[d][1][ks], acc[cb][1], 0, 0, 0);
                 }
+                __builtin_amdgcn_s_setprio(0);
             }
         }
         issue(s + DEPTH, dc);
