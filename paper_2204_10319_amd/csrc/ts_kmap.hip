@@ -727,14 +727,31 @@ __global__ void __launch_bounds__(kThreads) k_bits_scan(int32_t *__restrict__ bl
 }
 
 // Every set bit becomes the key of its cell, at the rank of the bit: cells are numbered in
-// (batch, x, y, z) order, which is the order of the keys.
+// (batch, x, y, z) order, which is the order of the keys.  word_base[w] receives the rank of word w's
+// first set bit (the number of set bits before the word): the rank of any marked cell is then one load
+// of it, one of the word, and a popcount.  self_scan: block_total[] still holds the per-block counts and
+// every block sums the ones before it itself (a few thousand L2-resident words), which saves the scan
+// launch in between; the last block then also writes the grand total.
 __global__ void __launch_bounds__(kThreads) k_bits_expand(const uint64_t *__restrict__ words, int64_t n_words,
                                                           const int32_t *__restrict__ block_base, Grid cbox,
-                                                          uint64_t *__restrict__ out_keys) {
+                                                          uint64_t *__restrict__ out_keys, int32_t *__restrict__ word_base,
+                                                          int self_scan, int64_t *__restrict__ count) {
     const int64_t w = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     uint64_t bits = w < n_words ? words[w] : 0;
+    int64_t before = 0;
+    if (self_scan) {
+        int part = 0;
+        for (int i = threadIdx.x; i < (int)blockIdx.x; i += kThreads) part += block_base[i];
+        int sum;
+        block_exclusive_scan(part, &sum);
+        before = sum;
+    } else {
+        before = block_base[blockIdx.x];
+    }
     int total;
-    int64_t at = block_base[blockIdx.x] + block_exclusive_scan(__popcll(bits), &total);
+    int64_t at = before + block_exclusive_scan(__popcll(bits), &total);
+    if (self_scan && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *count = before + total;
+    if (w < n_words) word_base[w] = (int32_t)at;
     if (bits == 0) return;
     // coordinates of the word's first cell once (a box holds at most 2^30 cells: 32-bit arithmetic),
     // then every set bit is that cell moved along z, carrying into y, x and the batch index
@@ -764,6 +781,40 @@ __global__ void __launch_bounds__(kThreads) k_bits_expand(const uint64_t *__rest
             }
         }
         out_keys[at++] = pack_key((int32_t)b, (int32_t)x + cbox.lo[0], (int32_t)y + cbox.lo[1], (int32_t)z + cbox.lo[2]);
+    }
+}
+
+// Strided maps without a search.  Every admissible candidate (p_j - delta_n) / s of an input p_j that
+// Alg. 3 keeps IS an output point, so the pair (j, k, n) of Alg. 1 follows from the candidate alone: k is
+// the rank of the candidate's cell among the marked cells (outputs are numbered in cell order).  A lane per
+// (input, admissible offset combination), as in k_candidates_mark.
+//   forward     nbr[k][n] = j, written with a compare-and-swap against -1: two inputs with one coordinate
+//               meet in one entry, which is how duplicates are found
+//   transposed  nbr[j][n] = k (rows belong to the given fine points; the roles are swapped)
+// Rows start out as -1; the row pass (k_rows) adds bitmasks and presence bitmaps afterwards.
+template <bool TRANSPOSED>
+__global__ void __launch_bounds__(kThreads) k_rank_scatter(const uint64_t *__restrict__ keys, int64_t n, int K, int s, int A,
+                                                           Bound bound, Grid cbox, const uint64_t *__restrict__ words,
+                                                           const int32_t *__restrict__ word_base, int32_t *__restrict__ nbr,
+                                                           int stride, int *status) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t key = keys[i];
+    const uint64_t cand = candidate_key(key, blockIdx.y, K, s, A, bound);
+    if (cand == kEmptyKey) return;
+    const int64_t cell = grid_cell(cbox, cand);
+    if (cell < 0) return;                       // k_candidates_mark has raised the flag
+    const int32_t k = word_base[cell >> 6] + __popcll(words[cell >> 6] & ((1ull << (cell & 63)) - 1ull));
+    // the offset: delta = p - s * q per axis
+    int32_t p[4], q[4];
+    unpack_key(key, p);
+    unpack_key(cand, q);
+    const int r = (K - 1) / 2;
+    const int nidx = ((p[1] - s * q[1] + r) * K + (p[2] - s * q[2] + r)) * K + (p[3] - s * q[3] + r);
+    if (TRANSPOSED) {
+        nbr[i * stride + nidx] = k;
+    } else {
+        if (atomicCAS(&nbr[(int64_t)k * stride + nidx], -1, (int32_t)i) != -1) raise_flag(status, ST_DUP);
     }
 }
 
@@ -1001,7 +1052,8 @@ struct Searched {
 
 // The grid's cells: kept between builds, every cell -1 whenever no build is using them.
 constexpr uint64_t kMaxGridCells = 1ull << 30;    // 4 GiB of cells: what a caller may ask for
-constexpr uint64_t kAutoGridCells = 1ull << 28;   // 1 GiB: what a build that measures its own box takes by itself
+constexpr uint64_t kAutoGridCells = 1ull << 28;   // output cells (bits of the bitmap: 32 MiB) up to which a strided build
+                                                  // that measures its own box marks its candidates instead of sorting them
 int32_t *g_grid = nullptr;
 uint64_t g_grid_cells = 0;
 bool g_grid_dirty = false;   // a build put points in and did not get as far as taking them out
@@ -1193,6 +1245,7 @@ void launch_probe(const ts_kmap *m, const Searched &sd, int32_t *colcnt, uint32_
 // Map search and everything after it.  `table` holds the searched point set (the map's inputs);
 // m->d_out_keys the outputs; the clearing of the status words (and of the neighbour table where the
 // search writes hits only) has been enqueued.
+int deliver_status(ts_kmap *m, int *d_status, bool wait);
 int search_and_finish(ts_kmap *m, Temps &tmp, const Searched &table, int *d_status, bool wait, int early_slot = -1) {
     hipStream_t st = stream();
     const int K3 = m->K3, K = m->K;
@@ -1251,9 +1304,13 @@ int search_and_finish(ts_kmap *m, Temps &tmp, const Searched &table, int *d_stat
 
     TS_LAUNCH("k_scan", k_scan, dim3(K3 + 1), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status, K3, wavemask,
               m->n_tiles, m->d_tile_order);
+    return deliver_status(m, d_status, wait);
+}
 
-    // the one host round trip: error flags and map sizes.  A caller that does not wait gets them
-    // when it first asks (ts::resolve); the copy lands in a pinned slot of its own meanwhile.
+// The one host round trip at the end of a build: error flags and map sizes.  A caller that does not wait
+// gets them when it first asks (ts::resolve); the copy lands in a pinned slot of its own meanwhile.
+int deliver_status(ts_kmap *m, int *d_status, bool wait) {
+    hipStream_t st = stream();
     const int slot = wait ? -1 : slot_acquire();
     if (slot >= 0) {
         StatusSlot &sl = g_slots[slot];
@@ -1437,12 +1494,13 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
                 for (int sl = 0; sl < kBoxSlots; ++sl) top[q] = hb[sl * kBoxSlotWords + q] > top[q] ? hb[sl * kBoxSlotWords + q] : top[q];
             }
             if (top[6] != INT32_MIN) {   // at least one valid point
+                // the bitmap has one bit per cell of the box the outputs can lie in
                 Box bx = {};
                 uint64_t cells = (uint64_t)top[6] + 1;
                 for (int a = 0; a < 3; ++a) {
                     bx.lo[a] = -top[a];
                     bx.hi[a] = top[3 + a];
-                    cells *= (uint64_t)((int64_t)bx.hi[a] - bx.lo[a] + 1);
+                    cells *= (uint64_t)((int64_t)floor_div(bx.hi[a] + K, s) - floor_div(bx.lo[a] - K, s) + 1);
                     if (cells > kAutoGridCells) cells = kAutoGridCells + 1;
                 }
                 bx.batches = top[6] + 1;
@@ -1458,10 +1516,13 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             clo[a] = floor_div(opt.box.lo[a] - K, s);
             chi[a] = floor_div(opt.box.hi[a] + K, s);
         }
+        Grid cbox = {};
+        uint64_t *words = nullptr;
+        int32_t *word_base = nullptr;
+        const bool ranked = opt.grid;   // outputs found through the bitmap: the map follows without a search
         if (opt.grid) {
             // bounds are stated: mark the candidates' cells in a bitmap and read the set bits off in
             // order, which sorts and removes duplicates at once
-            Grid cbox = {};
             uint64_t cells = (uint64_t)opt.box.batches;
             for (int a = 0; a < 3; ++a) {
                 cbox.lo[a] = clo[a];
@@ -1472,9 +1533,9 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             }
             cbox.batches = (uint32_t)opt.box.batches;
             const int64_t n_words = (int64_t)((cells + 63) / 64), n_wblocks = (n_words + kThreads - 1) / kThreads;
-            uint64_t *words;
             int32_t *block_total;
             TS_TRY(tmp.get(&words, (size_t)n_words));
+            TS_TRY(tmp.get(&word_base, (size_t)n_words));
             TS_TRY(tmp.get(&block_total, (size_t)n_wblocks));
             fill.add(words, (size_t)n_words * sizeof(uint64_t), 0u);
             TS_TRY(launch_fill(fill));
@@ -1482,8 +1543,11 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             TS_LAUNCH("k_candidates_mark", k_candidates_mark, dim3(blocks_for(N, kThreads), slots), block, given, N, K, s, A, opt.bound,
                       cbox, reinterpret_cast<uint32_t *>(words), d_status);
             TS_LAUNCH("k_bits_count", k_bits_count, dim3((unsigned)n_wblocks), block, words, n_words, block_total);
-            TS_LAUNCH("k_bits_scan", k_bits_scan, dim3(1), block, block_total, n_wblocks, d_count);
-            TS_LAUNCH("k_bits_expand", k_bits_expand, dim3((unsigned)n_wblocks), block, words, n_words, block_total, cbox, uniq);
+            // up to a few thousand blocks every block sums the totals before it by itself; beyond, a scan launch
+            const int self_scan = n_wblocks <= 8192;
+            if (!self_scan) TS_LAUNCH("k_bits_scan", k_bits_scan, dim3(1), block, block_total, n_wblocks, d_count);
+            TS_LAUNCH("k_bits_expand", k_bits_expand, dim3((unsigned)n_wblocks), block, words, n_words, block_total, cbox, uniq,
+                      word_base, self_scan, d_count);
         } else {
             // candidates -> sort -> unique (the empty key, if present, sorts last)
             uint64_t *cand, *sorted;
@@ -1539,6 +1603,50 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
         uint64_t *coarse;
         TS_TRY(alloc_n(&coarse, (size_t)n_coarse));
         TS_HIP(hipMemcpyAsync(coarse, uniq, (size_t)n_coarse * sizeof(uint64_t), hipMemcpyDeviceToDevice, st));
+        if (ranked) {
+            // No search: an input's admissible candidates are outputs, and an output's row number is the rank
+            // of its cell among the marked ones (k_rank_scatter).  Neither hash table nor coordinate grid.
+            const dim3 per_cand(blocks_for(N, kThreads), slots);
+            int32_t *colcnt;
+            if (!transposed) {
+                m->n_in = N;
+                m->n_out = n_coarse;
+                m->d_out_keys = coarse;
+            } else {
+                m->n_in = n_coarse;
+                m->n_out = N;
+                m->d_in_keys = coarse;
+                m->d_out_keys = given;
+            }
+            TS_TRY(alloc_outputs(m, &fill));
+            fill.add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);
+            TS_TRY(tmp.get(&colcnt, (size_t)K3 * m->n_blocks));
+            if (!transposed && !opt.bound.on) {
+                TS_TRY(launch_fill(fill));
+                TS_LAUNCH("k_rank_scatter", k_rank_scatter<false>, per_cand, block, given, N, K, s, A, opt.bound, cbox, words, word_base,
+                          m->d_nbr, m->stride, d_status);
+            } else if (!transposed) {
+                // with a boundary an input may lose all its candidates and then meets nobody in the table: equal
+                // points are found through a hash table here as well
+                Table fine_table;
+                TS_TRY(make_table(tmp, N, &fine_table, &fill));
+                TS_TRY(launch_fill(fill));
+                TS_LAUNCH("k_insert", k_insert<Table>, per_point, block, given, N, fine_table, d_status);
+                TS_LAUNCH("k_rank_scatter", k_rank_scatter<false>, per_cand, block, given, N, K, s, A, opt.bound, cbox, words, word_base,
+                          m->d_nbr, m->stride, d_status);
+            } else {
+                // rows belong to the given points here, so equal points do not meet in an entry: they are found
+                // by inserting the points into a hash table, which nothing else uses
+                Table fine_table;
+                TS_TRY(make_table(tmp, N, &fine_table, &fill));
+                TS_TRY(launch_fill(fill));
+                TS_LAUNCH("k_insert", k_insert<Table>, per_point, block, given, N, fine_table, d_status);
+                TS_LAUNCH("k_rank_scatter", k_rank_scatter<true>, per_cand, block, given, N, K, s, A, opt.bound, cbox, words, word_base,
+                          m->d_nbr, m->stride, d_status);
+            }
+            TS_TRY(rows_and_scan(m, tmp, colcnt, d_status));
+            return deliver_status(m, d_status, wait);
+        }
         if (!transposed) {
             m->n_in = N;
             m->n_out = n_coarse;

@@ -308,6 +308,39 @@ def test_kmap_strided_box_too_large_for_the_grid():
         _check_map(coords, K, s, tr)
 
 
+def test_kmap_strided_wide_box_through_the_bitmap():
+    """Two clusters 700 cells apart: 3.7e8 cells of input box, 4.7e7 cells of output box.  The build marks its
+    candidates in a bitmap over the output box (no coordinate grid over the input box is involved) and derives
+    the map from the ranks of the marked cells; three batches, negative coordinates, a ragged last word."""
+    a = _rand_coords(2611, 3000, -10, 10, batches=3)
+    b = a.copy()
+    b[:, 1:] += 700
+    coords = np.concatenate([a, b[:1777]])
+    for K, s, tr in MAP_CASES:
+        if s > 1:
+            _check_map(coords, K, s, tr)
+            _check_map(coords, K, s, tr, wait=False)
+
+
+def test_kmap_strided_duplicates_are_found_on_every_route():
+    """Equal input points must be reported whether they share an output entry (forward), own a row each
+    (transposed) or lose all their candidates to the boundary."""
+    base = _rand_coords(2621, 500, 0, 12)
+    dup = np.concatenate([base, base[17:18]])
+    for K, s, tr, bnd in [(2, 2, False, None), (3, 2, False, None), (2, 2, True, None), (3, 2, True, None),
+                          (3, 2, False, (3, 3, 3)), (3, 2, True, (3, 3, 3))]:
+        for search in (ts.TS_SEARCH_AUTO, ts.TS_SEARCH_HASH):
+            with pytest.raises(ts.TsError) as e:
+                ts.ts_build_kmap(to_dev(dup), K, s, tr, boundary=bnd, search=search)
+            assert e.value.code == ts.TS_ERR_DUPLICATE_COORD, (K, s, tr, bnd, search)
+    # both copies outside the boundary (every candidate cut): still duplicates
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(np.concatenate([_rand_coords(2622, 50, 0, 4), np.array([[0, 11, 11, 11], [0, 11, 11, 11]], np.int32)])),
+                         3, 2, False, boundary=(2, 2, 2))
+    assert e.value.code == ts.TS_ERR_DUPLICATE_COORD
+    _check_map(base, 3, 2, boundary=(3, 3, 3))
+
+
 def test_kmap_grid_is_clean_between_builds():
     """The cells are kept between builds: a build must not see the points of the one before, whatever the boxes
     (a smaller one, a larger one that makes the buffer grow, one that is moved), nor after a build that failed."""
