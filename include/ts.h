@@ -152,17 +152,22 @@ int ts_identity_kmap(int64_t n, ts_kmap **out_kmap);
 /*
  * ts_build_kmap with the choices the paper leaves to each layer (Sec. 4.4; Alg. 3).  options == NULL
  * is ts_build_kmap.  The map built is the same whatever `search` says.
- *   search        TS_SEARCH_AUTO (what ts_build_kmap does): stride 1 searches the hash table; a strided
+ *   search        TS_SEARCH_AUTO (what ts_build_kmap does): stride 1 searches the hash table.  A strided
  *                 build measures the bounding box of its coordinates on the device (one more host
- *                 round trip) and, when the box has at most 2^28 cells, takes the grid route below
- *                 by itself, else the hash route.
+ *                 round trip; none if the caller states the box: grid_batches > 0 with grid_lo / grid_hi
+ *                 as below, ignored at stride 1) and, when its outputs can lie in at most 2^28 cells,
+ *                 marks its candidates in a bitmap over those cells (32 MiB at most, a temporary) and
+ *                 reads the set bits off in order: the sorted distinct outputs without a sort.  The map
+ *                 then follows without a search either: every kept candidate of an input is an output,
+ *                 whose row number is the rank of its cell among the marked ones.  Larger boxes take the
+ *                 hash route.
  *                 TS_SEARCH_HASH: the open-addressing table; a strided build finds its output
  *                 coordinates by sorting the candidates.  TS_SEARCH_GRID: the collision-free
  *                 grid of Sec. 4.4, one int32 cell per coordinate of the box the caller states
  *                 with grid_lo / grid_hi (inclusive bounds of x, y, z over the rows of `coords`) and
  *                 grid_batches (batch indices are below it): one memory access per insertion and per
- *                 lookup, and a strided build finds its output coordinates by marking the candidates
- *                 in a bitmap over the box and reading the set bits off in order (no sort).
+ *                 lookup; a strided build with a stated box takes the bitmap route described above
+ *                 (no cells of the grid are involved).
  *                 A coordinate outside the stated box is TS_ERR_COORD_RANGE.  The box may
  *                 span at most 2^30 cells (TS_ERR_UNSUPPORTED beyond).  The cells are library memory
  *                 kept between builds (4 bytes per cell of the largest box seen, until
@@ -216,6 +221,15 @@ int     ts_kmap_kernel_volume(const ts_kmap *kmap); /* K^3                      
 
 /* Output coordinates P_out: dst is device int32 [num_out][4].  (For a transposed map: the fine coords.) */
 int ts_kmap_out_coords(const ts_kmap *kmap, int32_t *dst);
+/*
+ * A box that holds every output coordinate of a strided forward map, known on the host without a wait
+ * when the build marked its candidates in a bitmap over such a box (the default route and TS_SEARCH_GRID):
+ * lo, hi (host, 3 values each, inclusive x, y, z) and *batches (batch indices are below it).  It is what
+ * the build of the next level of a pyramid can be given as its box (ts_kmap_options: TS_SEARCH_AUTO with
+ * grid_lo / grid_hi / grid_batches stated), which then need not measure one.  TS_ERR_UNSUPPORTED for maps
+ * whose build bounded nothing (stride 1, transposed, the sort route, empty inputs).
+ */
+int ts_kmap_out_box(const ts_kmap *kmap, int32_t *lo, int32_t *hi, int32_t *batches);
 /* Input coordinates in the row order X_in must have: dst is device int32 [num_in][4]. */
 int ts_kmap_in_coords(const ts_kmap *kmap, int32_t *dst);
 /* Per-offset map sizes |M[W_n]|: dst is HOST int64 [K^3]. */

@@ -26,7 +26,7 @@ _lib = None
 
 EXPORTS = [
     "ts_build_kmap", "ts_build_kmap_async", "ts_build_kmap_ex", "ts_identity_kmap", "ts_kmap_status", "ts_kmap_prepare", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
-    "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
+    "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_out_box", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_static", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
     "ts_sparse_conv_prepared", "ts_sparse_conv_prepared2", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
     "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_mfma_loop", "ts_bias_act", "ts_concat_cols",
@@ -91,6 +91,8 @@ def load_library(path: str | None = None):
     lib.ts_kmap_kernel_volume.restype = ci
     lib.ts_kmap_out_coords.argtypes = [vp, vp]
     lib.ts_kmap_in_coords.argtypes = [vp, vp]
+    lib.ts_kmap_out_box.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+    lib.ts_kmap_out_box.restype = ci
     lib.ts_kmap_sizes.argtypes = [vp, ctypes.POINTER(i64)]
     lib.ts_kmap_pairs.argtypes = [vp, vp, vp]
     lib.ts_sparse_conv.argtypes = [tp, tp, vp, tp]
@@ -118,7 +120,7 @@ def load_library(path: str | None = None):
     lib.ts_grouped_matmul_adaptive.restype = ci
     lib.ts_set_stream.argtypes = [vp]
     lib.ts_release_cache.argtypes = []
-    for name in ("ts_kmap_out_coords", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs", "ts_sparse_conv",
+    for name in ("ts_kmap_out_coords", "ts_kmap_out_box", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs", "ts_sparse_conv",
                  "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_set_stream",
                  "ts_release_cache"):
         getattr(lib, name).restype = ci
@@ -262,6 +264,15 @@ class KMap:
     def in_coords(self) -> torch.Tensor:
         return ts_kmap_in_coords(self)
 
+    def out_box(self):
+        """(lo[3], hi[3], batches) holding every output coordinate, or None when the build bounded nothing."""
+        lo, hi, b = (ctypes.c_int32 * 3)(), (ctypes.c_int32 * 3)(), ctypes.c_int32()
+        rc = load_library().ts_kmap_out_box(self.handle, lo, hi, ctypes.byref(b))
+        if rc == TS_ERR_UNSUPPORTED:
+            return None
+        _check(rc)
+        return tuple(lo), tuple(hi), int(b.value)
+
     def sizes(self) -> np.ndarray:
         return ts_kmap_sizes(self)
 
@@ -299,21 +310,28 @@ class KMap:
 
 
 def ts_build_kmap(coords: torch.Tensor, kernel_size: int, stride: int = 1, transposed: bool = False,
-                  wait: bool = True, grid=None, boundary=None, search: int = TS_SEARCH_AUTO) -> KMap:
+                  wait: bool = True, grid=None, boundary=None, search: int = TS_SEARCH_AUTO, box=None) -> KMap:
     """coords: device int32 [N,4] (batch, x, y, z).  wait=False: ts_build_kmap_async (errors of the input
     surface at ``KMap.status()`` or the first accessor that needs the map's sizes).
     grid=(lo[3], hi[3], batches): search through the coordinate grid over that box (ts_build_kmap_ex,
-    TS_SEARCH_GRID).  search=TS_SEARCH_HASH keeps a strided build on the hash table.  boundary=(bx, by, bz): Alg. 3's boundary check for a strided map."""
+    TS_SEARCH_GRID).  search=TS_SEARCH_HASH keeps a strided build on the hash table.  boundary=(bx, by, bz): Alg. 3's boundary check for a strided map.
+    box=(lo[3], hi[3], batches): a box holding the coordinates, stated so that a strided build on the default route
+    need not measure one (ignored at stride 1)."""
     if coords.dtype != torch.int32 or coords.dim() != 2 or coords.shape[1] != 4:
         raise ValueError("coords must be int32 [N,4]")
     if not coords.is_cuda or not coords.is_contiguous():
         raise ValueError("coords must be a contiguous device tensor")
     _use_current_stream()
     h = ctypes.c_void_p()
-    if grid is not None or boundary is not None or search != TS_SEARCH_AUTO:
+    if grid is not None or boundary is not None or search != TS_SEARCH_AUTO or box is not None:
         opt = KMapOptions()
         opt.wait = int(bool(wait))
         opt.search = int(search)
+        if box is not None and grid is None:
+            lo, hi, batches = box
+            opt.grid_lo = (ctypes.c_int32 * 3)(*[int(v) for v in lo])
+            opt.grid_hi = (ctypes.c_int32 * 3)(*[int(v) for v in hi])
+            opt.grid_batches = int(batches)
         if grid is not None:
             lo, hi, batches = grid
             opt.search = TS_SEARCH_GRID

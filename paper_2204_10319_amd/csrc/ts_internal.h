@@ -66,7 +66,8 @@ inline int alloc_n(T **p, size_t n) {
 
 // Waits, if it has not happened yet, for the sizes and error flags of a map built with
 // ts_build_kmap_async, and fills in M / sizes / offs.  Returns TS_OK or the build's error.
-int resolve(const struct ::ts_kmap *kmap);
+// need_sizes == false: only the error flags are awaited; the put-off part of a stride-1 build is not run.
+int resolve(const struct ::ts_kmap *kmap, bool need_sizes = true);
 
 // Enqueues, without waiting, what an asynchronous build put off (ts_kmap_prepare).
 int prepare(const struct ::ts_kmap *kmap);
@@ -133,6 +134,8 @@ struct ts_kmap {
                                 // scan have not run yet; ts::resolve runs them (the fused kernel needs none of it)
     int pending_slot = -1;      // >= 0: sizes and error flags are still on their way to the host
     int error = 0;              // TS_OK, or what the build found wrong with its input
+    int32_t out_box_lo[3] = {0, 0, 0}, out_box_hi[3] = {0, 0, 0}, out_box_batches = 0;   // a box that holds every output
+                                // coordinate (a strided forward build that marked its candidates in one); batches 0: unknown
     int64_t n_blocks = 0;       // ceil(n_out / 64): 64-row blocks of the rank structure
     int64_t sizes[ts::kMaxK3] = {0};      // |M[W_n]|
     int64_t offs[ts::kMaxK3 + 1] = {0};   // exclusive prefix of sizes

@@ -1407,12 +1407,14 @@ int alloc_outputs(ts_kmap *m, FillArgs *fill) {
     m->stride = nbr_stride(K3);
     m->n_blocks = (m->n_out + 63) / 64;
     m->n_tiles = (m->n_out + kTileRows - 1) / kTileRows;
-    TS_TRY(alloc_n(&m->d_nbr, (size_t)m->n_out * m->stride));
+    if (!m->d_nbr) TS_TRY(alloc_n(&m->d_nbr, (size_t)m->n_out * m->stride));   // (a build may have made it early, for a bound on n_out)
     TS_TRY(alloc_n(&m->d_colbits, (size_t)K3 * m->n_blocks));
     TS_TRY(alloc_n(&m->d_colbase, (size_t)K3 * m->n_blocks));
     TS_TRY(alloc_n(&m->d_tile_order, (size_t)m->n_tiles));
-    TS_TRY(alloc_n(&m->d_sched, (size_t)kMaxSchedSlices * kSchedWords));
-    fill->add(m->d_sched, (size_t)kMaxSchedSlices * kSchedWords * sizeof(int32_t), 0u);
+    if (!m->d_sched) {
+        TS_TRY(alloc_n(&m->d_sched, (size_t)kMaxSchedSlices * kSchedWords));
+        fill->add(m->d_sched, (size_t)kMaxSchedSlices * kSchedWords * sizeof(int32_t), 0u);
+    }
     if (m->s == 1 && K3 == 27) fill->add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);   // the symmetric probe writes hits only
     return TS_OK;
 }
@@ -1478,6 +1480,41 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             TS_TRY(tmp.get(&d_bbox, (size_t)kBoxSlots * kBoxSlotWords));
             fill.add(d_bbox, (size_t)kBoxSlots * kBoxSlotWords * sizeof(int32_t), 0x80000000u);
         }
+        // Box known before the first launch, one candidate per input (K <= s), forward map: there are at most N
+        // outputs, so the neighbour table is made for N rows now and everything that must start at a known
+        // value - status words, bitmap, table rows, tile counters - is cleared by the one launch below.
+        const bool early = opt.grid && slots == 1 && !transposed && !opt.bound.on;
+        Grid cbox = {};
+        uint64_t *words = nullptr;
+        int32_t *word_base = nullptr, *block_total = nullptr;
+        int64_t n_words = 0, n_wblocks = 0;
+        auto bitmap_over_box = [&]() -> int {
+            // the coarse points lie in the box of the fine ones, moved by less than K and divided by s
+            uint64_t cells = (uint64_t)opt.box.batches;
+            for (int a = 0; a < 3; ++a) {
+                cbox.lo[a] = floor_div(opt.box.lo[a] - K, s);
+                cbox.ext[a] = (uint32_t)(floor_div(opt.box.hi[a] + K, s) - cbox.lo[a] + 1);
+                cells *= cbox.ext[a];
+                if (cells > kMaxGridCells)
+                    return fail(TS_ERR_UNSUPPORTED, "the grid bounds span more than %llu cells", (unsigned long long)kMaxGridCells);
+            }
+            cbox.batches = (uint32_t)opt.box.batches;
+            n_words = (int64_t)((cells + 63) / 64);
+            n_wblocks = (n_words + kThreads - 1) / kThreads;
+            TS_TRY(tmp.get(&words, (size_t)n_words));
+            TS_TRY(tmp.get(&word_base, (size_t)n_words));
+            TS_TRY(tmp.get(&block_total, (size_t)n_wblocks));
+            fill.add(words, (size_t)n_words * sizeof(uint64_t), 0u);
+            return TS_OK;
+        };
+        if (early) {
+            TS_TRY(bitmap_over_box());
+            m->stride = nbr_stride(K3);
+            TS_TRY(alloc_n(&m->d_nbr, (size_t)N * m->stride));
+            TS_TRY(alloc_n(&m->d_sched, (size_t)kMaxSchedSlices * kSchedWords));
+            fill.add(m->d_nbr, (size_t)N * m->stride * sizeof(int32_t), 0xFFFFFFFFu);
+            fill.add(m->d_sched, (size_t)kMaxSchedSlices * kSchedWords * sizeof(int32_t), 0u);
+        }
         TS_TRY(launch_fill(fill));
         fill = FillArgs();
         TS_LAUNCH("k_pack", k_pack, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, d_status, opt.box, d_bbox);
@@ -1516,30 +1553,15 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             clo[a] = floor_div(opt.box.lo[a] - K, s);
             chi[a] = floor_div(opt.box.hi[a] + K, s);
         }
-        Grid cbox = {};
-        uint64_t *words = nullptr;
-        int32_t *word_base = nullptr;
         const bool ranked = opt.grid;   // outputs found through the bitmap: the map follows without a search
         if (opt.grid) {
-            // bounds are stated: mark the candidates' cells in a bitmap and read the set bits off in
-            // order, which sorts and removes duplicates at once
-            uint64_t cells = (uint64_t)opt.box.batches;
-            for (int a = 0; a < 3; ++a) {
-                cbox.lo[a] = clo[a];
-                cbox.ext[a] = (uint32_t)(chi[a] - clo[a] + 1);
-                cells *= cbox.ext[a];
-                if (cells > kMaxGridCells)
-                    return fail(TS_ERR_UNSUPPORTED, "the grid bounds span more than %llu cells", (unsigned long long)kMaxGridCells);
+            // bounds are stated or measured: mark the candidates' cells in a bitmap and read the set bits
+            // off in order, which sorts and removes duplicates at once
+            if (!early) {
+                TS_TRY(bitmap_over_box());
+                TS_TRY(launch_fill(fill));
+                fill = FillArgs();
             }
-            cbox.batches = (uint32_t)opt.box.batches;
-            const int64_t n_words = (int64_t)((cells + 63) / 64), n_wblocks = (n_words + kThreads - 1) / kThreads;
-            int32_t *block_total;
-            TS_TRY(tmp.get(&words, (size_t)n_words));
-            TS_TRY(tmp.get(&word_base, (size_t)n_words));
-            TS_TRY(tmp.get(&block_total, (size_t)n_wblocks));
-            fill.add(words, (size_t)n_words * sizeof(uint64_t), 0u);
-            TS_TRY(launch_fill(fill));
-            fill = FillArgs();
             TS_LAUNCH("k_candidates_mark", k_candidates_mark, dim3(blocks_for(N, kThreads), slots), block, given, N, K, s, A, opt.bound,
                       cbox, reinterpret_cast<uint32_t *>(words), d_status);
             TS_LAUNCH("k_bits_count", k_bits_count, dim3((unsigned)n_wblocks), block, words, n_words, block_total);
@@ -1619,7 +1641,7 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
                 m->d_out_keys = given;
             }
             TS_TRY(alloc_outputs(m, &fill));
-            fill.add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);
+            if (!early) fill.add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);   // (early: cleared by the first launch)
             TS_TRY(tmp.get(&colcnt, (size_t)K3 * m->n_blocks));
             if (!transposed && !opt.bound.on) {
                 TS_TRY(launch_fill(fill));
@@ -1643,6 +1665,14 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
                 TS_LAUNCH("k_insert", k_insert<Table>, per_point, block, given, N, fine_table, d_status);
                 TS_LAUNCH("k_rank_scatter", k_rank_scatter<true>, per_cand, block, given, N, K, s, A, opt.bound, cbox, words, word_base,
                           m->d_nbr, m->stride, d_status);
+            }
+            // where the next level's points can lie, for a caller that builds a pyramid
+            if (!transposed) {
+                m->out_box_batches = (int32_t)cbox.batches;
+                for (int a = 0; a < 3; ++a) {
+                    m->out_box_lo[a] = cbox.lo[a];
+                    m->out_box_hi[a] = cbox.lo[a] + (int32_t)cbox.ext[a] - 1;
+                }
             }
             TS_TRY(rows_and_scan(m, tmp, colcnt, d_status));
             return deliver_status(m, d_status, wait);
@@ -1738,7 +1768,7 @@ int transpose(const ts_kmap *f, ts_kmap *m) {
 
 namespace ts {
 
-int resolve(const ts_kmap *kmap) {
+int resolve(const ts_kmap *kmap, bool need_sizes) {
     ts_kmap *m = const_cast<ts_kmap *>(kmap);
     if (m->pending_slot >= 0) {
         StatusSlot &sl = g_slots[m->pending_slot];
@@ -1752,7 +1782,7 @@ int resolve(const ts_kmap *kmap) {
             m->rows_done = true;
         }
     }
-    if (!m->rows_done && m->error == TS_OK) {
+    if (need_sizes && !m->rows_done && m->error == TS_OK) {
         // the part of a stride-1 build that was put off: row pass, scan, sizes
         hipStream_t st = stream();
         Temps tmp;
@@ -1924,7 +1954,10 @@ int ts_build_kmap_ex(const int32_t *coords, int64_t N, int kernel_size, int stri
         opt.measure = options->search == TS_SEARCH_AUTO;
         if (options->search != TS_SEARCH_HASH && options->search != TS_SEARCH_GRID && options->search != TS_SEARCH_AUTO)
             return fail(TS_ERR_INVALID_ARG, "search must be TS_SEARCH_AUTO, TS_SEARCH_HASH or TS_SEARCH_GRID");
-        if (options->search == TS_SEARCH_GRID) {
+        // TS_SEARCH_AUTO with a box stated (grid_batches > 0): a strided build takes the box instead of measuring
+        // one (one host round trip less); a stride-1 build stays on the hash table and ignores it
+        const bool hinted = options->search == TS_SEARCH_AUTO && options->grid_batches > 0 && stride > 1;
+        if (options->search == TS_SEARCH_GRID || hinted) {
             opt.grid = true;
             opt.box.on = 1;
             opt.box.batches = options->grid_batches;
@@ -1951,7 +1984,7 @@ int ts_build_kmap_ex(const int32_t *coords, int64_t N, int kernel_size, int stri
 
 int ts_kmap_status(const ts_kmap *kmap) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
-    return ts::resolve(kmap);
+    return ts::resolve(kmap, false);   // the verdict only: what a build put off stays put off
 }
 
 int ts_kmap_prepare(const ts_kmap *kmap) {
@@ -1998,6 +2031,17 @@ int ts_kmap_out_coords(const ts_kmap *kmap, int32_t *dst) {
     if (!dst || (reinterpret_cast<uintptr_t>(dst) & 15)) return fail(TS_ERR_INVALID_ARG, "dst is NULL or not 16-byte aligned");
     TS_LAUNCH("k_unpack", k_unpack, dim3(blocks_for(kmap->n_out, kThreads)), dim3(kThreads), kmap->d_out_keys, kmap->n_out, reinterpret_cast<int4 *>(dst));
     TS_HIP(hipGetLastError());
+    return TS_OK;
+}
+
+int ts_kmap_out_box(const ts_kmap *kmap, int32_t *lo, int32_t *hi, int32_t *batches) {
+    if (!kmap || !lo || !hi || !batches) return fail(TS_ERR_INVALID_ARG, "NULL argument");
+    if (kmap->out_box_batches <= 0) return fail(TS_ERR_UNSUPPORTED, "this map's build did not bound its output coordinates");
+    for (int a = 0; a < 3; ++a) {
+        lo[a] = kmap->out_box_lo[a];
+        hi[a] = kmap->out_box_hi[a];
+    }
+    *batches = kmap->out_box_batches;
     return TS_OK;
 }
 

@@ -36,11 +36,14 @@ class SparseNet:
         boxes = {0: box}
         maps = {}
         top = max(level for _, level in kinds)
+        hint = None     # where a level's points can lie, as the strided build of the level above bounded them
         for level in range(top + 1):
             if ("down", level) in kinds or ("up", level) in kinds:
-                down = ts.ts_build_kmap(levels[level], 2, 2, False, wait=False, grid=boxes[level])
+                down = ts.ts_build_kmap(levels[level], 2, 2, False, wait=False, grid=boxes[level],
+                                        box=hint if boxes[level] is None else None)
                 maps[("down", level)] = down
                 levels[level + 1] = down.out_coords()
+                hint = down.out_box()     # the next strided build need not measure its box
                 b = boxes[level]
                 boxes[level + 1] = None if b is None else (tuple(v // 2 for v in b[0]), tuple(v // 2 for v in b[1]), b[2])
         for kind, level in kinds:
@@ -55,7 +58,11 @@ class SparseNet:
             elif kind == "up":
                 maps[(kind, level)] = maps[("down", level)].transpose()
         for m in maps.values():
-            m.prepare()     # these maps serve several layers each: the put-off parts of their builds, enqueued together
+            # The put-off part of a build (per-offset counts, ranks) serves the fetch-on-demand dataflow, which
+            # the library takes for wide layers on maps of at most 256 tiles of 128 rows; larger maps run fused
+            # layers only, which need none of it.
+            if m.num_out <= 256 * 128:
+                m.prepare()
         for m in maps.values():
             m.status()      # builds did not wait one by one; bad coordinates are reported here
         return maps, levels

@@ -341,6 +341,33 @@ def test_kmap_strided_duplicates_are_found_on_every_route():
     _check_map(base, 3, 2, boundary=(3, 3, 3))
 
 
+@pytest.mark.parametrize("K", [2, 3])
+def test_kmap_pyramid_with_the_box_handed_down(K):
+    """A strided forward build reports a box holding its outputs; the next level's build takes it instead of
+    measuring one.  Three levels, each map against the oracle; a box that misses a point is a range error."""
+    coords = _rand_coords(2700 + K, 6000, -40, 40, batches=2)
+    hint = None
+    for level in range(3):
+        kmap = ts.ts_build_kmap(to_dev(coords), K, 2, False, wait=False, box=hint)
+        in_c, out_c, tri = oracle_map(coords, K, 2)
+        assert np.array_equal(kmap.out_coords().cpu().numpy(), out_c)
+        assert np.array_equal(gpu_triples(kmap), tri)
+        hint = kmap.out_box()
+        assert hint is not None
+        lo, hi, batches = hint
+        assert (out_c[:, 1:] >= np.array(lo)).all() and (out_c[:, 1:] <= np.array(hi)).all() and out_c[:, 0].max() < batches
+        # stride-1 builds ignore a stated box on the default route
+        sub = ts.ts_build_kmap(to_dev(out_c), 3, 1, box=((0, 0, 0), (0, 0, 0), 1))
+        assert np.array_equal(gpu_triples(sub), oracle_map(out_c, 3, 1)[2])
+        coords = out_c
+    assert ts.ts_build_kmap(to_dev(coords), 3, 1).out_box() is None
+    assert ts.ts_build_kmap(to_dev(coords), K, 2, True).out_box() is None
+    lo, hi, batches = hint
+    with pytest.raises(ts.TsError) as e:
+        ts.ts_build_kmap(to_dev(coords), K, 2, False, box=(lo, tuple(h - 3 for h in hi), batches)).status()
+    assert e.value.code == ts.TS_ERR_COORD_RANGE
+
+
 def test_kmap_grid_is_clean_between_builds():
     """The cells are kept between builds: a build must not see the points of the one before, whatever the boxes
     (a smaller one, a larger one that makes the buffer grow, one that is moved), nor after a build that failed."""
