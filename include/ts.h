@@ -35,8 +35,12 @@
  * usable HIP device every call fails with TS_ERR_HIP.
  *
  * Threading/streams: work is enqueued on the stream set by ts_set_stream()
- * (default: the null stream).  Calls on one ts_kmap from several host threads
- * at once are not supported.
+ * (default: the null stream).  The stream, the scratch areas and the memory pool are per process: one
+ * stream is in use at a time.  Changing the stream is allowed between calls; memory the library freed
+ * on the previous stream is reused on the new one only after the previous stream has drained (the
+ * library waits for it then, except under stream capture, where it allocates instead).  A ts_kmap must
+ * be used on the stream it was built on, or after that stream has been synchronised.  Calls from several
+ * host threads at once are not supported.
  */
 #ifndef TS_H
 #define TS_H
@@ -251,7 +255,12 @@ int ts_kmap_pairs(const ts_kmap *kmap, int32_t *in_idx, int32_t *out_idx);
  * C_in and over all offsets, rounding once when the row is stored; TS_F32 uses fp32 throughout.
  * C_in and C_out must be multiples of 16 for the MFMA kernels (TS_F16: C_in of 4 or 8 is also
  * accepted and zero-extended internally); at most 256.
- * Never synchronises.  Uses library-owned scratch memory that is grown on demand.
+ * Never synchronises.  Uses library-owned scratch memory (repacked weights, padded features, the
+ * buffers F and G of the explicit dataflows) that grows on demand with hipMalloc; an outgrown area stays
+ * allocated, unused, until ts_release_cache, because work already enqueued or a HIP graph captured earlier
+ * may still address it.  While the stream is being captured nothing can grow: a call that would need to
+ * fails with TS_ERR_UNSUPPORTED, so run the same call once eagerly before capturing (or take
+ * ts_sparse_conv_static, which owns no growable memory).
  */
 int ts_sparse_conv(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kmap,
                    ts_tensor *out);

@@ -1021,7 +1021,7 @@ int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kma
     } else {
         size_t wn = (size_t)kmap->K3 * cout * cin_pad;
         T *wt = static_cast<T *>(wbuf ? wbuf : scratch(2, wn * sizeof(T)));
-        if (!wt) return TS_ERR_OOM;
+        if (!wt) return last_fail_code();
         TS_LAUNCH("k_pack_weights", k_pack_weights<T>, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads), static_cast<const T *>(weights->data), wt, kmap->K3, cin, cin_pad, cout);
         pr->wt = wt;
     }
@@ -1029,7 +1029,7 @@ int prepare(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap *kma
     if (cin_pad != cin && feats->rows > 0) {
         size_t xn = (size_t)feats->rows * cin_pad;
         T *xp = static_cast<T *>(scratch(3, xn * sizeof(T)));
-        if (!xp) return TS_ERR_OOM;
+        if (!xp) return last_fail_code();
         TS_LAUNCH("k_pad_rows", k_pad_rows<T>, dim3(blocks_for((int64_t)xn / 8, kThreads)), dim3(kThreads), static_cast<const T *>(feats->data), xp, feats->rows, cin, cin_pad);
         pr->x = xp;
     }
@@ -1086,7 +1086,7 @@ int run_fused_staged(const ts_tensor *feats, const ts_tensor *weights, const ts_
     Prepared pr;
     TS_TRY(prepare<T>(feats, weights, kmap, &pr, pw, wbuf));
     const T *zero = static_cast<const T *>(zeros ? zeros : zero_row());
-    if (!zero) return TS_ERR_OOM;
+    if (!zero) return last_fail_code();
     dispatch_shape(pick_ncb(out->cols), pick_ksteps(pr.cin_pad, Elem<T>::KSTEP), FusedLaunch<T>{pr, kmap, out, zero});
     TS_HIP(hipGetLastError());
     return TS_OK;
@@ -1187,7 +1187,7 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
     if (!wf) {
         const size_t wn = (size_t)kmap->K3 * cout * cin_pad;
         T *buf = static_cast<T *>(wbuf ? wbuf : scratch(2, wn * sizeof(T)));
-        if (!buf) return TS_ERR_OOM;
+        if (!buf) return last_fail_code();
         TS_LAUNCH("k_pack_weights", k_pack_weights_tile, dim3(blocks_for((int64_t)wn, kThreads)), dim3(kThreads),
                   static_cast<const T *>(weights->data), buf, kmap->K3, cin, cin_pad, cout, ksteps);
         wf = buf;
@@ -1196,7 +1196,7 @@ int run_fused_f16(const ts_tensor *feats, const ts_tensor *weights, const ts_kma
     if (cin_pad != cin) {
         const size_t xn = (size_t)feats->rows * cin_pad;
         T *xp = static_cast<T *>(scratch(3, xn * sizeof(T)));
-        if (!xp) return TS_ERR_OOM;
+        if (!xp) return last_fail_code();
         TS_LAUNCH("k_pad_rows", k_pad_rows<T>, dim3(blocks_for((int64_t)xn / 8, kThreads)), dim3(kThreads), x, xp, feats->rows, cin, cin_pad);
         x = xp;
     }
@@ -1304,7 +1304,7 @@ int grouped_mm_launch(const void *F, const void *X, const void *wt, const ts_kma
                       int cin_pad, int cout, const int32_t *in_idx = nullptr, const Second &sec = Second()) {
     if (plan_tiles(plan) == 0) return TS_OK;
     const T *zero = static_cast<const T *>(zero_row());
-    if (!zero) return TS_ERR_OOM;
+    if (!zero) return last_fail_code();
     // the chunk of input channels a step takes must divide both parts of a two-part input
     int ksteps = pick_ksteps(cin_pad, Elem<T>::KSTEP);
     const int cin1 = sec.x2 ? sec.cin1 : cin_pad;
@@ -1427,7 +1427,7 @@ int run_explicit(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap
     if (sec.x2 && (!fetch || pr.cin_pad != feats->cols)) return fail(TS_ERR_UNSUPPORTED, "a two-part input needs the fetch-on-demand dataflow and unpadded rows");
     const int64_t M = kmap->M;
     float *G = static_cast<float *>(scratch(1, (size_t)(M ? M : 1) * out->cols * sizeof(float)));
-    if (!G) return TS_ERR_OOM;
+    if (!G) return last_fail_code();
     if (fetch) {   // the matmul reads X_in[j] through the pair lists: no buffer F, no gather launch
         if (M == 0) return reduce_impl<T>(G, kmap, out, ep);
         TS_TRY(ensure_pairs(kmap));
@@ -1435,7 +1435,7 @@ int run_explicit(const ts_tensor *feats, const ts_tensor *weights, const ts_kmap
         return reduce_impl<T>(G, kmap, out, ep);
     }
     void *F = scratch(0, (size_t)(M ? M : 1) * pr.cin_pad * sizeof(T));
-    if (!F) return TS_ERR_OOM;
+    if (!F) return last_fail_code();
     TS_TRY(gather_impl(pr.x, feats->rows, pr.cin_pad, feats->dtype, kmap, F));
     TS_TRY(grouped_mm_impl<T>(F, pr.x, pr.wt, kmap, G, pr.cin_pad, out->cols));
     return reduce_impl<T>(G, kmap, out, ep);
@@ -1575,7 +1575,7 @@ static int conv_act(const ts_tensor *feats_in, const ts_tensor *weights, const t
                               (go_explicit || ((size_t)kmap->n_in * feats->cols * 2 < (1ull << 31)));
         if (!in_place) {
             void *buf = scratch(4, (size_t)(feats->rows ? feats->rows : 1) * feats->cols * (f16 ? 2 : 4));
-            if (!buf) return TS_ERR_OOM;
+            if (!buf) return last_fail_code();
             cat.data = buf;
             TS_TRY(ts_concat_cols(feats_in, feats2, &cat));
             sec = Second();

@@ -11,6 +11,9 @@ namespace ts {
 
 // ---- errors -------------------------------------------------------------------------------
 int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+// The code of this thread's last fail(): what a caller returns when a helper that reports through a
+// null pointer (dev_alloc, scratch, zero_row, host_staging) has failed.
+int last_fail_code();
 
 #define TS_HIP(call)                                                                        \
     do {                                                                                    \
@@ -29,11 +32,15 @@ int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 hipStream_t stream();
 
 // Pooled device memory: freed blocks are kept and handed out again, so steady-state
-// calls do not reach hipMalloc/hipFree.  Returns nullptr on failure (error text is set).
+// calls do not reach hipMalloc/hipFree.  A block is handed out again only in stream order: at once on the
+// stream it was freed on, after that stream has drained on another.  Returns nullptr on failure (error
+// text is set).
 void *dev_alloc(size_t bytes);
 void dev_free(void *p);
 
-// Grow-only scratch areas for ts_sparse_conv (slot 0: gather buffer F, 1: partial sums G,
+// Grow-only scratch areas for ts_sparse_conv; an outgrown area is kept, unused, until ts_release_cache
+// (enqueued work or a captured graph may still address it), and growth fails while the stream is being
+// captured (slot 0: gather buffer F, 1: partial sums G,
 // 2: packed weights, 3: padded features, 4: a two-part input concatenated where the kernels cannot read the
 // parts in place).  Contents do not survive across calls.
 void *scratch(int slot, size_t bytes);
@@ -61,7 +68,7 @@ struct ProfScope {
 template <class T>
 inline int alloc_n(T **p, size_t n) {
     *p = static_cast<T *>(dev_alloc((n ? n : 1) * sizeof(T)));
-    return *p ? TS_OK : TS_ERR_OOM;
+    return *p ? TS_OK : last_fail_code();
 }
 
 // Waits, if it has not happened yet, for the sizes and error flags of a map built with
@@ -80,7 +87,7 @@ void release_grid();
 
 // ---- 64-bit coordinate keys ----------------------------------------------------------------
 // key = batch<<51 | (x+B)<<34 | (y+B)<<17 | (z+B), B = 2^16: order-preserving in (b,x,y,z)
-// ("flattening the coordinate of each dimension into an integer", paper Sec. 2.1.2).
+// (the hash key of a coordinate is one integer made of its components, paper Sec. 2.1.2).
 // With x,y,z in [TS_COORD_MIN, TS_COORD_MAX] a field never borrows or carries when a kernel
 // offset (|d| <= 7) is added, so key(p + d) = key(p) + key_delta(d).
 constexpr int kFieldBits = 17;

@@ -2,7 +2,7 @@
 //
 // Pipeline on the device, one stream:
 //   fill     one launch clears the hash table, the counters and (stride 1) the neighbour table
-//   pack     (b,x,y,z) -> order-preserving 64-bit keys       ("flattening the coordinate", Sec. 2.1.2)
+//   pack     (b,x,y,z) -> order-preserving 64-bit keys       (one integer per coordinate, Sec. 2.1.2)
 //   stride>1: candidate keys (p - delta)/s, radix sort, unique -> P_out           (Alg. 3, stages 1-4)
 //   insert   the searched point set into an open-addressing table (64-bit CAS)
 //   search   s*q_k + delta_n for every output k and offset n (Alg. 1).  Stride 1, K = 3: one thread
@@ -1321,7 +1321,7 @@ int deliver_status(ts_kmap *m, int *d_status, bool wait) {
         m->pending_slot = slot;
     } else {
         int32_t *h = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
-        if (!h) return TS_ERR_OOM;
+        if (!h) return last_fail_code();
         TS_HIP(hipMemcpyAsync(h, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
         TS_HIP(hipStreamSynchronize(st));
         if (take_status(m, h) != TS_OK) return report(m);
@@ -1522,7 +1522,7 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             // one more host round trip buys a build without a sort and a search without collisions
             const size_t bytes = (size_t)kBoxSlots * kBoxSlotWords * sizeof(int32_t);
             int32_t *hb = static_cast<int32_t *>(host_staging(bytes));
-            if (!hb) return TS_ERR_OOM;
+            if (!hb) return last_fail_code();
             TS_HIP(hipMemcpyAsync(hb, d_bbox, bytes, hipMemcpyDeviceToHost, st));
             TS_HIP(hipStreamSynchronize(st));
             int32_t top[7];
@@ -1589,7 +1589,7 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             TS_LAUNCH("k_drop_empty_key", k_drop_empty_key, dim3(1), dim3(1), uniq, d_count);
         }
         int64_t *h = static_cast<int64_t *>(host_staging(64));
-        if (!h) return TS_ERR_OOM;
+        if (!h) return last_fail_code();
         TS_HIP(hipMemcpyAsync(h, d_count, sizeof(int64_t), hipMemcpyDeviceToHost, st));
         TS_HIP(hipStreamSynchronize(st));
         const int64_t n_coarse = h[0];
@@ -1615,7 +1615,7 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
             TS_LAUNCH("k_insert", k_insert<Table>, per_point, block, given, N, t0, d_status);
             if (transposed) TS_TRY(rows_and_scan(m, tmp, colcnt, d_status));
             int32_t *hs = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
-            if (!hs) return TS_ERR_OOM;
+            if (!hs) return last_fail_code();
             TS_HIP(hipMemcpyAsync(hs, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
             TS_HIP(hipStreamSynchronize(st));
             if (hs[ST_RANGE]) m->error = TS_ERR_COORD_RANGE;
@@ -1800,7 +1800,7 @@ int resolve(const ts_kmap *kmap, bool need_sizes) {
         TS_LAUNCH("k_scan", k_scan, dim3(m->K3 + 1), dim3(kScanThreads), colcnt, m->d_colbase, m->n_blocks, d_status, m->K3, wavemask,
                   m->n_tiles, m->d_tile_order);
         int32_t *h = static_cast<int32_t *>(host_staging(ST_WORDS * sizeof(int32_t)));
-        if (!h) return TS_ERR_OOM;
+        if (!h) return last_fail_code();
         TS_HIP(hipMemcpyAsync(h, d_status, ST_WORDS * sizeof(int32_t), hipMemcpyDeviceToHost, st));
         TS_HIP(hipStreamSynchronize(st));
         take_status(m, h);

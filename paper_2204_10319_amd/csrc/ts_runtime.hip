@@ -13,6 +13,7 @@
 namespace ts {
 
 static thread_local std::string g_error;
+static thread_local int g_error_code = TS_OK;
 static hipStream_t g_stream = nullptr;
 
 int fail(int code, const char *fmt, ...) {
@@ -22,16 +23,24 @@ int fail(int code, const char *fmt, ...) {
     vsnprintf(buf, sizeof(buf), fmt, ap);
     va_end(ap);
     g_error = buf;
+    g_error_code = code;
     return code;
 }
+
+int last_fail_code() { return g_error_code != TS_OK ? g_error_code : TS_ERR_OOM; }
 
 hipStream_t stream() { return g_stream; }
 
 // ---- pooled device memory -------------------------------------------------------------------
 namespace {
 std::mutex g_pool_mu;
-std::multimap<size_t, void *> g_free_blocks;          // size -> block
+struct FreeBlock {
+    void *p;
+    hipStream_t stream;   // the library stream when the block was given back: work enqueued there may still use it
+};
+std::multimap<size_t, FreeBlock> g_free_blocks;       // size -> block
 std::unordered_map<void *, size_t> g_live_blocks;     // block -> size
+std::vector<void *> g_retired;                        // outgrown scratch areas, kept until ts_release_cache
 
 // Round a request so that similar sizes land in the same bin: 256 B granules below 1 MiB,
 // then 1/8-octave steps.
@@ -50,18 +59,46 @@ struct Scratch {
 Scratch g_scratch[8];
 void *g_host = nullptr;
 size_t g_host_bytes = 0;
+
+bool capturing() {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(g_stream, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return st != hipStreamCaptureStatusNone;
+}
 }  // namespace
 
+// A freed block goes back to work only in stream order.  Blocks given back on the stream the library is on
+// now are reused at once (later work on that stream comes after whatever still uses them).  A block given
+// back on another stream is taken only after that stream has drained, and never while the current stream
+// is being captured (a wait is not allowed there): then fresh memory is asked for instead.
 void *dev_alloc(size_t bytes) {
     size_t sz = bin_size(bytes);
     {
-        std::lock_guard<std::mutex> lk(g_pool_mu);
-        auto it = g_free_blocks.lower_bound(sz);
-        if (it != g_free_blocks.end() && it->first <= sz + sz / 4) {
-            void *p = it->second;
-            g_live_blocks[p] = it->first;
-            g_free_blocks.erase(it);
-            return p;
+        std::unique_lock<std::mutex> lk(g_pool_mu);
+        auto foreign = g_free_blocks.end();
+        for (auto it = g_free_blocks.lower_bound(sz); it != g_free_blocks.end() && it->first <= sz + sz / 4; ++it) {
+            if (it->second.stream == g_stream) {
+                void *p = it->second.p;
+                g_live_blocks[p] = it->first;
+                g_free_blocks.erase(it);
+                return p;
+            }
+            if (foreign == g_free_blocks.end()) foreign = it;
+        }
+        if (foreign != g_free_blocks.end() && !capturing()) {
+            const FreeBlock b = foreign->second;
+            const size_t bsz = foreign->first;
+            g_free_blocks.erase(foreign);
+            g_live_blocks[b.p] = bsz;
+            lk.unlock();
+            if (hipStreamSynchronize(b.stream) != hipSuccess) {   // e.g. a stream that no longer exists
+                (void)hipGetLastError();
+                (void)hipDeviceSynchronize();
+            }
+            return b.p;
         }
     }
     void *p = nullptr;
@@ -82,24 +119,41 @@ void dev_free(void *p) {
     std::lock_guard<std::mutex> lk(g_pool_mu);
     auto it = g_live_blocks.find(p);
     if (it == g_live_blocks.end()) return;
-    g_free_blocks.emplace(it->second, p);
+    g_free_blocks.emplace(it->second, FreeBlock{p, g_stream});
     g_live_blocks.erase(it);
 }
 
+// A scratch area that is too small is replaced by a larger one (half as large again, so that the areas
+// left behind add up to less than twice the last).  The old area is NOT reused for anything until
+// ts_release_cache: work already enqueued, or a HIP graph captured earlier, may still address it.  Nothing
+// waits here.  While the stream is being captured no memory can be asked for: the call fails instead, and
+// the caller sizes the areas with one eager pass first.
 void *scratch(int slot, size_t bytes) {
     Scratch &s = g_scratch[slot];
     if (s.bytes >= bytes && s.p) return s.p;
-    // Work already enqueued may still read the old area: stream-ordered reuse is safe through
-    // the pool only after the stream has drained.
-    if (s.p) {
-        (void)hipStreamSynchronize(g_stream);
-        dev_free(s.p);
-        s.p = nullptr;
-        s.bytes = 0;
+    if (capturing()) {
+        fail(TS_ERR_UNSUPPORTED, "library scratch area %d must grow to %zu bytes, which cannot happen while the stream is being captured: run the same call once before capturing", slot, bytes);
+        return nullptr;
     }
-    size_t want = bytes + bytes / 8;
-    s.p = dev_alloc(want);
-    if (s.p) s.bytes = want;
+    size_t want = bytes + bytes / 2;
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, want);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        want = bytes;
+        e = hipMalloc(&p, want);
+    }
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        fail(e == hipErrorOutOfMemory ? TS_ERR_OOM : TS_ERR_HIP, "hipMalloc(%zu) failed: %s", want, hipGetErrorString(e));
+        return nullptr;
+    }
+    if (s.p) {
+        std::lock_guard<std::mutex> lk(g_pool_mu);
+        g_retired.push_back(s.p);
+    }
+    s.p = p;
+    s.bytes = want;
     return s.p;
 }
 
@@ -280,15 +334,13 @@ int ts_release_cache(void) {
     ts::release_grid();
     std::lock_guard<std::mutex> lk(ts::g_pool_mu);
     for (auto &s : ts::g_scratch) {
-        if (s.p) {
-            auto it = ts::g_live_blocks.find(s.p);
-            if (it != ts::g_live_blocks.end()) ts::g_live_blocks.erase(it);
-            (void)hipFree(s.p);
-        }
+        if (s.p) (void)hipFree(s.p);
         s.p = nullptr;
         s.bytes = 0;
     }
-    for (auto &kv : ts::g_free_blocks) (void)hipFree(kv.second);
+    for (void *p : ts::g_retired) (void)hipFree(p);
+    ts::g_retired.clear();
+    for (auto &kv : ts::g_free_blocks) (void)hipFree(kv.second.p);
     ts::g_free_blocks.clear();
     return TS_OK;
 }

@@ -131,5 +131,50 @@ def test_graph_replay_equals_eager():
             ts.ts_sparse_conv(to_dev(features(70, 5000, 32, np.float16)), to_dev(np.zeros((27, 32, 32), np.float16)), other)
             torch.cuda.synchronize()
             other.free()
+        if rep == 0:
+            # An eager layer that outgrows every scratch area the graph recorded (buffers F and G of the explicit
+            # dataflow at 256 channels on the whole scene, its repacked weights): the areas the graph addresses
+            # must stay untouched, whatever is built and freed afterwards.
+            big = ts.ts_build_kmap(to_dev(coords), 3, 1)
+            ts.ts_sparse_conv(to_dev(features(71, coords.shape[0], 256, np.float16)), to_dev(np.ones((27, 256, 256), np.float16)), big,
+                              dataflow=ts.TS_DATAFLOW_EXPLICIT)
+            torch.cuda.synchronize()
+            big.free()
+            for i in range(4):
+                ts.ts_build_kmap(to_dev(coords[: 20000 * (i + 1)]), 3, 1).free()
     del graph
     SparseNet.free_maps(maps)
+
+
+def test_scratch_cannot_grow_under_capture_and_says_so():
+    """A layer whose scratch areas have no room yet fails cleanly while its stream is being captured (nothing
+    may allocate there); after one eager call the same capture works and replays the eager result."""
+    coords = lidar_scan_coords(4, n_sweeps=1)[:20000]
+    kmap = ts.ts_build_kmap(to_dev(coords), 3, 1)
+    x = to_dev(features(80, 20000, 64, np.float16))
+    w = to_dev(features(81, 27 * 64, 64, np.float16).reshape(27, 64, 64) * np.float16(0.05))
+    out = torch.zeros((20000, 64), dtype=torch.float16, device="cuda")
+    torch.cuda.synchronize()
+    ts.ts_release_cache()                       # the areas are gone: the next layer call must allocate
+    side = torch.cuda.Stream()
+    err = None
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        try:
+            ts.ts_sparse_conv(x, w, kmap, out)  # the plain call repacks its weights into library scratch
+        except ts.TsError as e:
+            err = e
+    assert err is not None and err.code == ts.TS_ERR_UNSUPPORTED and "captured" in str(err)
+    del graph
+    with torch.cuda.stream(side):
+        want = ts.ts_sparse_conv(x, w, kmap).clone()   # sizes the area
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ts.ts_sparse_conv(x, w, kmap, out)
+    out.zero_()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
+    del graph
+    kmap.free()
