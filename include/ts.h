@@ -253,8 +253,9 @@ int ts_kmap_pairs(const ts_kmap *kmap, int32_t *in_idx, int32_t *out_idx);
  *   out      [num_out][C_out], caller-allocated, fully overwritten.
  * All three share one dtype.  TS_F16 multiplies fp16 operands and accumulates in fp32 over
  * C_in and over all offsets, rounding once when the row is stored; TS_F32 uses fp32 throughout.
- * C_in and C_out must be multiples of 16 for the MFMA kernels (TS_F16: C_in of 4 or 8 is also
- * accepted and zero-extended internally); at most 256.
+ * C_out must be a multiple of 32; C_in may be anything (rows narrower than the kernels' operand step -
+ * 32 channels for TS_F16, 8 for TS_F32 - are zero-extended in library scratch: the 4-channel stem of a
+ * network); both at most 1024 (TS_ERR_UNSUPPORTED beyond).
  * Never synchronises.  Uses library-owned scratch memory (repacked weights, padded features, the
  * buffers F and G of the explicit dataflows) that grows on demand with hipMalloc; an outgrown area stays
  * allocated, unused, until ts_release_cache, because work already enqueued or a HIP graph captured earlier
@@ -396,28 +397,7 @@ int ts_concat_cols(const ts_tensor *a, const ts_tensor *b, ts_tensor *out);
 int ts_set_stream(void *hip_stream);
 /* Free the library's cached scratch and pooled device memory (synchronises the device). */
 int ts_release_cache(void);
-/*
- * Plain device-to-device streaming copy kernel (dst, src: device, 16-byte aligned; bytes a
- * multiple of 16; buffers must not overlap).  Not part of the layer: benchmarks use it as the
- * achievable-bandwidth reference and to calibrate hardware byte counters against a known size.
- */
-int ts_copy_bytes(void *dst, const void *src, size_t bytes);
-/*
- * Register-only loop of fp16 MFMA instructions on every matrix pipe (1024 workgroups x 4 waves x iters x
- * 8 instructions of 16x16x32): the achievable-MFMA reference of the benchmarks.  sink: device, at least
- * 1 MiB (never written unless the arithmetic misbehaves); *flops (host) receives the FLOPs one call executes.
- */
-int ts_mfma_loop(int iters, void *sink, double *flops);
 
-/*
- * Per-kernel timing for benchmarks.  While enabled, the library brackets each kernel launch
- * (or library sort) with a hipEvent pair on its stream; `only`, when not NULL/empty, restricts
- * this to the kernels whose name starts with it.  ts_profile_read synchronises the stream, writes one
- * line per kernel name, "name launches total_ms\n", into buf (host, cap bytes), and clears
- * the records.  Not thread-safe; off by default.
- */
-int ts_profile_enable(int on, const char *only);
-int ts_profile_read(char *buf, size_t cap);
 /* Text of the last error on this thread ("" if none). Valid until the next failing call. */
 const char *ts_last_error(void);
 /* Library version string. */

@@ -6,6 +6,7 @@
 #include <stddef.h>
 
 #include "../../include/ts.h"
+#include "../../include/ts_bench.h"
 
 namespace ts {
 

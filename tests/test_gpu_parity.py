@@ -149,6 +149,26 @@ def test_layer_channel_counts_that_are_odd_multiples_of_32(c_in, c_out, K, s, tr
     check_features(ts.ts_sparse_conv(to_dev(x2), to_dev(w2), kmap, dataflow=ts.TS_DATAFLOW_FUSED), ref2, torch.float16, "large first channel")
 
 
+@pytest.mark.parametrize("c_in,c_out", [(512, 512), (1024, 64), (64, 1024), (1024, 1024)])
+def test_layer_widest_channels(c_in, c_out):
+    """The widest layers the library accepts (1024 channels either side), every dataflow, fp16; beyond: an error."""
+    coords = _rand_coords(600 + c_in, 400, -5, 5)
+    _layer_case(coords, c_in, c_out, 3, 1, False, torch.float16, seed=c_in + c_out,
+                dataflows=(ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_FETCH, ts.TS_DATAFLOW_AUTO))
+    _layer_case(coords, c_in, c_out, 2, 2, True, torch.float16, seed=c_in + c_out + 1,
+                dataflows=(ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT))
+
+
+def test_layer_too_wide_is_refused():
+    coords = _rand_coords(9, 200, 0, 8)
+    kmap = ts.ts_build_kmap(to_dev(coords), 1, 1)
+    for c_in, c_out in [(1056, 32), (32, 1056)]:
+        with pytest.raises(ts.TsError) as e:
+            ts.ts_sparse_conv(torch.zeros((200, c_in), dtype=torch.float16, device="cuda"),
+                              torch.zeros((1, c_in, c_out), dtype=torch.float16, device="cuda"), kmap)
+        assert e.value.code == ts.TS_ERR_UNSUPPORTED
+
+
 def test_layer_empty():
     kmap = ts.ts_build_kmap(torch.zeros((0, 4), dtype=torch.int32, device="cuda"), 3, 1)
     x = torch.zeros((0, 32), dtype=torch.float16, device="cuda")
