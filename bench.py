@@ -294,6 +294,12 @@ def main():
         pk = {k: v[1] * 1e3 / v[0] for k, v in ts.ts_profile_read().items()}
         ts.ts_profile_enable(False)
         fused_name = [k for k in pk if k.startswith("k_conv_") or k.startswith("k_fused")][0]
+        gname = [k for k in pk if k.startswith("k_gather")][0]     # k_gather (output order) or k_gather_in (input-stationary)
+        # the gather stage in both orders (Sec. 4.3.2), on its own
+        Fb = torch.empty((m, c), dtype=torch.float16, device="cuda")
+        g_out = time_calls(lambda: ts.ts_gather(xc, km, Fb, order=ts.TS_GATHER_OUTPUT_ORDER), 20)
+        g_in = time_calls(lambda: ts.ts_gather(xc, km, Fb, order=ts.TS_GATHER_INPUT_STATIONARY), 20)
+        del Fb
         fu = pk[fused_name]
         gb, mb, sb = explicit_stage_bytes(n, n, m, m - n, c, c, K3, 2)   # the centre offset is not gathered
         fb = fused_conv_bytes(n, n, m, c, c, K3, 2)
@@ -304,13 +310,17 @@ def main():
             "k_fused_GBs": round(fb / fu * 1e-3, 1), "k_fused_frac_hbm": round(fb / fu * 1e-3 / HBM_PEAK_GBS, 4),
             "k_fused_TFLOPs": round(flops / fu * 1e-6, 1),
             "k_fused_frac_mfma": round(flops / fu * 1e-6 / MFMA_F16_PEAK_TFLOPS, 4),
-            "k_gather_us": round(pk["k_gather"], 2), "k_gather_GBs": round(gb / pk["k_gather"] * 1e-3, 1),
+            "gather_kernel": gname, "k_gather_us": round(pk[gname], 2), "k_gather_GBs": round(gb / pk[gname] * 1e-3, 1),
+            "k_gather_frac_hbm": round(gb / pk[gname] * 1e-3 / HBM_PEAK_GBS, 4),
+            "gather_output_order_us": round(g_out, 2), "gather_input_stationary_us": round(g_in, 2),
             "k_grouped_mm_us": round(pk["k_grouped_mm"], 2),
             "k_grouped_mm_GBs": round(mb / pk["k_grouped_mm"] * 1e-3, 1),
             "k_grouped_mm_TFLOPs": round(flops / pk["k_grouped_mm"] * 1e-6, 1),
             "k_grouped_mm_frac_mfma": round(flops / pk["k_grouped_mm"] * 1e-6 / MFMA_F16_PEAK_TFLOPS, 4),
             "k_scatter_reduce_us": round(pk["k_scatter_reduce"], 2),
             "k_scatter_reduce_GBs": round(sb / pk["k_scatter_reduce"] * 1e-3, 1),
+            "k_scatter_reduce_frac_hbm": round(sb / pk["k_scatter_reduce"] * 1e-3 / HBM_PEAK_GBS, 4),
+            "k_grouped_mm_frac_hbm": round(mb / pk["k_grouped_mm"] * 1e-3 / HBM_PEAK_GBS, 4),
         }
 
     kmap_us = time_calls(lambda: ts.ts_build_kmap(coords, K, 1).free(), 30)

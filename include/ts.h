@@ -348,6 +348,21 @@ int ts_sparse_conv_static(const ts_tensor *feats, const ts_tensor *weights, cons
  *                   row is reduced in registers in offset order and written once).
  */
 int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F);
+/*
+ * ts_gather with the order of the copy chosen by the caller; F is the same whatever the order.
+ *   TS_GATHER_OUTPUT_ORDER      walks F's rows in order and fetches each pair's input row (sequential
+ *                               writes, gathered reads: an input row is read once per pair it is in).
+ *   TS_GATHER_INPUT_STATIONARY  the locality-aware order of Sec. 4.3.2: walks the input rows in order,
+ *                               reads each once and writes it to every row of F it belongs in
+ *                               (positions from the map's rank bitmaps).  Built for 3x3x3 stride-1 maps
+ *                               and rows of 64, 128, 256 or 512 bytes; other requests run in output order.
+ *   TS_GATHER_AUTO              what ts_gather and the explicit dataflow do: input-stationary where it is
+ *                               built and rows have 128 bytes or more, or the feature matrix exceeds the
+ *                               256 MB last-level cache (every re-read of a 64-byte row then comes from
+ *                               memory); else output order.
+ */
+enum { TS_GATHER_AUTO = 0, TS_GATHER_OUTPUT_ORDER = 1, TS_GATHER_INPUT_STATIONARY = 2 };
+int ts_gather_ex(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F, int order);
 int ts_grouped_matmul(const ts_tensor *F, const ts_tensor *feats, const ts_tensor *weights,
                       const ts_kmap *kmap, ts_tensor *G);
 int ts_scatter_reduce(const ts_tensor *G, const ts_kmap *kmap, ts_tensor *out);

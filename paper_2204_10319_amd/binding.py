@@ -28,7 +28,7 @@ EXPORTS = [
     "ts_build_kmap", "ts_build_kmap_async", "ts_build_kmap_ex", "ts_identity_kmap", "ts_kmap_status", "ts_kmap_prepare", "ts_free", "ts_kmap_sort_rows", "ts_kmap_transpose", "ts_kmap_num_in", "ts_kmap_num_out", "ts_kmap_num_pairs",
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_out_box", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_static", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
-    "ts_sparse_conv_prepared", "ts_sparse_conv_prepared2", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
+    "ts_sparse_conv_prepared", "ts_sparse_conv_prepared2", "ts_gather", "ts_gather_ex", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
     "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_mfma_loop", "ts_bias_act", "ts_concat_cols",
 ]
 
@@ -110,6 +110,8 @@ def load_library(path: str | None = None):
     lib.ts_sparse_conv_prepared2.argtypes = [tp, tp, vp, vp, vp, tp, ci, tp]
     lib.ts_sparse_conv_prepared2.restype = ci
     lib.ts_gather.argtypes = [tp, vp, tp]
+    lib.ts_gather_ex.argtypes = [tp, vp, tp, ci]
+    lib.ts_gather_ex.restype = ci
     lib.ts_grouped_matmul.argtypes = [tp, tp, tp, vp, tp]
     lib.ts_scatter_reduce.argtypes = [tp, vp, tp]
     lib.ts_adaptive_groups.argtypes = [ctypes.POINTER(ctypes.c_int64), ctypes.c_int32, ctypes.c_double,
@@ -528,12 +530,18 @@ def ts_sparse_conv_ex(feats, weights, kmap, out=None, dataflow: int = TS_DATAFLO
     return ts_sparse_conv(feats, weights, kmap, out, dataflow)
 
 
-def ts_gather(feats: torch.Tensor, kmap: KMap, F: torch.Tensor | None = None) -> torch.Tensor:
+TS_GATHER_AUTO, TS_GATHER_OUTPUT_ORDER, TS_GATHER_INPUT_STATIONARY = 0, 1, 2
+
+
+def ts_gather(feats: torch.Tensor, kmap: KMap, F: torch.Tensor | None = None, order: int = TS_GATHER_AUTO) -> torch.Tensor:
     _use_current_stream()
     if F is None:
         F = torch.zeros((kmap.num_pairs, feats.shape[1]), dtype=feats.dtype, device=feats.device)
     f, b = _as_ts(feats), _as_ts(F)
-    _check(load_library().ts_gather(ctypes.byref(f), kmap.handle, ctypes.byref(b)))
+    if order == TS_GATHER_AUTO:
+        _check(load_library().ts_gather(ctypes.byref(f), kmap.handle, ctypes.byref(b)))
+    else:
+        _check(load_library().ts_gather_ex(ctypes.byref(f), kmap.handle, ctypes.byref(b), int(order)))
     return F
 
 

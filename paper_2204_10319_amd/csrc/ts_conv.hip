@@ -787,6 +787,47 @@ __global__ void __launch_bounds__(kThreads) k_gather(const u32x4 *__restrict__ X
         if (at[u] >= 0) __builtin_nontemporal_store(v[u], &F[at[u]]);
 }
 
+// The same gather in input-stationary order (the locality-aware order of Sec. 4.3.2: an input row is read
+// once and written to every place it is needed), for 3x3x3 stride-1 maps.  VPR lanes share an input row j
+// and hold 16 bytes of it each.  By the symmetry of Sec. 4.2.1 row j of the out-major table also lists
+// where j is an input: nbr[j][n'] = k means input j feeds output k through offset n = 26 - n', and that
+// pair's row in F is offs[n] + (rank of k among the outputs with offset n), read off the rank bitmaps.
+// The lanes of a group first work out those rows for the offsets they own (n' = c, c + VPR, ...), all
+// lookups in flight together, then the group walks the 27 offsets and stores.  Reads X sequentially and
+// once; F's rows are written whole but scattered.  Centre rows are left out, as in k_gather.
+template <int VPR>
+__global__ void __launch_bounds__(kThreads) k_gather_in(const u32x4 *__restrict__ X, const int32_t *__restrict__ nbr,
+                                                        const uint64_t *__restrict__ colbits,
+                                                        const int32_t *__restrict__ colbase, Offs offs, int64_t n_blocks,
+                                                        u32x4 *__restrict__ F, int64_t n_in) {
+    constexpr int K3 = 27, STRIDE = 32, PER = (K3 + VPR - 1) / VPR;
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t j = t / VPR;
+    const int c = (int)(t % VPR), lane = threadIdx.x & 63, first = lane - c;   // first: the group's lane 0
+    const bool ok = j < n_in;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (ok) v = X[j * VPR + c];
+    int32_t pos[PER];
+#pragma unroll
+    for (int r = 0; r < PER; ++r) {
+        const int np = c + r * VPR;     // this lane's offset n' of row j
+        pos[r] = -1;
+        if (ok && np < K3 && np != K3 / 2) {
+            const int32_t k = nbr[j * STRIDE + np];
+            if (k >= 0) {
+                const int n = K3 - 1 - np;
+                const int64_t b = (int64_t)n * n_blocks + (k >> 6);
+                pos[r] = offs.v[n] + colbase[b] + __popcll(colbits[b] & ((1ull << (k & 63)) - 1ull));
+            }
+        }
+    }
+#pragma unroll
+    for (int np = 0; np < K3; ++np) {
+        const int32_t p = __shfl(pos[np / VPR], first + np % VPR, 64);
+        if (p >= 0) __builtin_nontemporal_store(v, &F[(int64_t)p * VPR + c]);
+    }
+}
+
 // One launch of the grouped matmul: the offsets it covers and how many 128-row blocks each gets.
 // An offset given more blocks than its list fills stands for a list padded to a longer one
 // (the batched matmul of Appendix B, Alg. 4): the surplus blocks multiply zero rows and store nothing.
@@ -1285,10 +1326,36 @@ struct GroupedLaunch {
     }
 };
 
-int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const ts_kmap *kmap, void *F) {
+// order: 0 = the library's choice, 1 = output order (k_gather), 2 = input-stationary (k_gather_in) where it applies.
+int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const ts_kmap *kmap, void *F, int order = 0) {
     if (kmap->M == 0) return TS_OK;
-    TS_TRY(ensure_pairs(kmap));
     const int vec_per_row = (int)(cin_pad * elem_size(dtype) / 16);
+    // Input-stationary order reads every input row once instead of once per pair, and writes whole rows of F
+    // at scattered places.  Measured on the LiDAR-like scene at 153 k, 1.5 M and 15 M points: with rows of 128
+    // bytes or more it wins at every size (C = 64: 31 against 35 us at 153 k, 3.0 against 4.4 ms at 15 M;
+    // C = 128: 51 against 67 us, 5.4 against 8.8 ms); with 64-byte rows (half a cache line per scattered
+    // write) only once the feature matrix no longer fits the 256 MB last-level cache.
+    const bool can_in = kmap->K3 == 27 && kmap->centre >= 0 && kmap->stride == 32 &&
+                        (vec_per_row == 4 || vec_per_row == 8 || vec_per_row == 16 || vec_per_row == 32) &&
+                        kmap->M < (int64_t)1 << 31;
+    const size_t x_bytes = (size_t)kmap->n_in * vec_per_row * 16;
+    if (can_in && (order == 2 || (order == 0 && (vec_per_row >= 8 || x_bytes > ((size_t)256 << 20))))) {
+        TS_TRY(resolve(kmap));
+        const int64_t threads = kmap->n_in * vec_per_row;
+        const dim3 grid(blocks_for(threads, kThreads)), block(kThreads);
+        const u32x4 *xs = static_cast<const u32x4 *>(x);
+        u32x4 *fs = static_cast<u32x4 *>(F);
+        ts::ProfScope ps("k_gather_in");
+#define TS_GATHER_IN(V) hipLaunchKernelGGL(k_gather_in<V>, grid, block, 0, ts::stream(), xs, kmap->d_nbr, kmap->d_colbits, kmap->d_colbase, offs_of(kmap), kmap->n_blocks, fs, kmap->n_in)
+        if (vec_per_row == 4) TS_GATHER_IN(4);
+        else if (vec_per_row == 8) TS_GATHER_IN(8);
+        else if (vec_per_row == 16) TS_GATHER_IN(16);
+        else TS_GATHER_IN(32);
+#undef TS_GATHER_IN
+        TS_HIP(hipGetLastError());
+        return TS_OK;
+    }
+    TS_TRY(ensure_pairs(kmap));
     int64_t lo = 0, hi = 0;
     if (kmap->centre >= 0) {
         lo = kmap->offs[kmap->centre];
@@ -1666,8 +1733,10 @@ int ts_sparse_conv_prepared2(const ts_tensor *feats, const ts_tensor *feats2, co
     return conv_act(feats, &desc, w, kmap, bias, residual, relu, out, feats2);
 }
 
-int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F) {
+int ts_gather_ex(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F, int order) {
     if (!kmap) return fail(TS_ERR_INVALID_ARG, "kmap is NULL");
+    if (order != TS_GATHER_AUTO && order != TS_GATHER_OUTPUT_ORDER && order != TS_GATHER_INPUT_STATIONARY)
+        return fail(TS_ERR_INVALID_ARG, "unknown gather order %d", order);
     TS_TRY(resolve(kmap));
     TS_TRY(check_tensor(feats, "feats"));
     TS_TRY(check_tensor(F, "F"));
@@ -1676,8 +1745,10 @@ int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F) {
         return fail(TS_ERR_SHAPE, "F must be [num_pairs, C_in] of the dtype of feats");
     if ((feats->cols * elem_size(feats->dtype)) % 16 != 0)
         return fail(TS_ERR_UNSUPPORTED, "rows must be a multiple of 16 bytes");
-    return gather_impl(feats->data, feats->rows, feats->cols, feats->dtype, kmap, F->data);
+    return gather_impl(feats->data, feats->rows, feats->cols, feats->dtype, kmap, F->data, order);
 }
+
+int ts_gather(const ts_tensor *feats, const ts_kmap *kmap, ts_tensor *F) { return ts_gather_ex(feats, kmap, F, TS_GATHER_AUTO); }
 
 int ts_adaptive_groups(const int64_t *sizes, int32_t count, double epsilon, int32_t *group_of, int32_t *num_groups) {
     if (!sizes || !group_of || !num_groups) return fail(TS_ERR_INVALID_ARG, "sizes, group_of and num_groups must not be NULL");

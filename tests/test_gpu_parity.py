@@ -300,6 +300,31 @@ def test_stages_of_alg2(lidar_coords):
     check_features(y, oracle_conv(coords, x, w, 3, 1), torch.float16, "staged")
 
 
+@pytest.mark.parametrize("c,dtype", [(32, torch.float16), (64, torch.float16), (128, torch.float16), (256, torch.float16),
+                                     (16, torch.float32), (64, torch.float32), (96, torch.float16)])
+@pytest.mark.parametrize("n", [1, 700, 9000])
+def test_gather_input_stationary_equals_output_order(c, dtype, n):
+    """The locality-aware gather (Sec. 4.3.2: every input row read once, written wherever it is needed) fills
+    the buffer F exactly as the output-order gather does, and as the oracle's pair list says: F[p] = X[in(p)]
+    for every pair p outside the centre offset.  96 channels has no input-stationary kernel and runs in output
+    order; a map of an asynchronous build gets its rank bitmaps on demand."""
+    coords = _rand_coords(5000 + n + c, n, -9, 9, batches=2)
+    kmap = ts.ts_build_kmap(to_dev(coords), 3, 1, wait=(n != 700))
+    x_h = features(5100 + c, n, c, np_dtype(dtype))
+    x = to_dev(x_h)
+    tri = oracle_map(coords, 3, 1)[2]                         # sorted by (n, k, j): the library's pair order
+    keep = tri[:, 2] != 13
+    outs = []
+    for order in (ts.TS_GATHER_INPUT_STATIONARY, ts.TS_GATHER_OUTPUT_ORDER, ts.TS_GATHER_AUTO):
+        F = torch.full((kmap.num_pairs, c), -7.0, dtype=dtype, device="cuda")
+        ts.ts_gather(x, kmap, F, order=order)
+        Fh = F.cpu().numpy()
+        assert np.array_equal(Fh[keep], x_h[tri[keep, 0]]), order
+        assert (Fh[~keep] == -7.0).all(), "centre rows are not materialised"
+        outs.append(Fh)
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[1], outs[2])
+
+
 # ---- grid map search (Sec. 4.4) and Alg. 3's boundary -----------------------------------------------------
 
 @pytest.mark.parametrize("K,s,transposed", MAP_CASES)
