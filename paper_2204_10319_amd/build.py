@@ -78,5 +78,54 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+SAN_LIB = os.path.join(OBJDIR, "libts_hostsan.so")
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+             "-fno-omit-frame-pointer", "-Xarch_host", "-fno-sanitize-recover=undefined"]
+
+
+def build_host_sanitized(force: bool = False) -> str:
+    """The same library with its HOST code compiled under AddressSanitizer and UndefinedBehaviorSanitizer
+    (device code as usual): for the host-side checks of tests/host/host_checks.cpp, which need no GPU.
+    Goes to _build/, never next to the product library."""
+    os.makedirs(OBJDIR, exist_ok=True)
+    if not force and os.path.exists(SAN_LIB) and not any(_object_stale(src, SAN_LIB) for src in sources()):
+        return SAN_LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in FLAGS if f not in ("-O3", "-shared")] + ["-O1", "-g"] + SAN_FLAGS
+    jobs, objs = [], []
+    for src in sources():
+        obj = os.path.join(OBJDIR, os.path.basename(src) + ".san.o")
+        objs.append(obj)
+        jobs.append(subprocess.Popen([hipcc] + flags + ["-c", src, "-o", obj], stdout=subprocess.PIPE,
+                                     stderr=subprocess.STDOUT, text=True))
+    for proc in jobs:
+        out, _ = proc.communicate()
+        if proc.returncode != 0:
+            print(out)
+            raise RuntimeError("hipcc failed building the host-sanitized library")
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-fsanitize=address", "-fsanitize=undefined",
+                          "-fno-gpu-sanitize"] + objs + ["-o", SAN_LIB], capture_output=True, text=True)
+    if res.returncode != 0:
+        print(res.stdout, res.stderr)
+        raise RuntimeError("hipcc failed linking the host-sanitized library")
+    return SAN_LIB
+
+
+def build_host_checks(force: bool = False) -> str:
+    """tests/host/host_checks.cpp linked against the host-sanitized library; returns the executable's path."""
+    lib = build_host_sanitized(force)
+    exe = os.path.join(OBJDIR, "host_checks")
+    src = os.path.join(HERE, "..", "tests", "host", "host_checks.cpp")
+    if force or not os.path.exists(exe) or os.path.getmtime(exe) < max(os.path.getmtime(src), os.path.getmtime(lib)):
+        hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+        cmd = [hipcc, "-O1", "-g", "-std=c++17", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+               "-fno-sanitize-recover=undefined", "-x", "c++", src, "-x", "none", lib, "-Wl,-rpath," + OBJDIR, "-o", exe]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            print(res.stdout, res.stderr)
+            raise RuntimeError("building tests/host/host_checks.cpp failed")
+    return exe
+
+
 if __name__ == "__main__":
     print(build_library(force=True, verbose=True))
