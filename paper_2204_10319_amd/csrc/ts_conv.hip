@@ -1200,8 +1200,7 @@ bool launch_conv_res(const _Float16 *x, const _Float16 *wf, const ts_kmap *kmap,
     const int64_t n_units = (kmap->n_out + kResRows - 1) / kResRows;
     const int64_t wgs = (n_units + kResWaves - 1) / kResWaves;
     const int64_t cus = compute_units();
-    ts::ProfScope ps("k_conv_res");
-    hipLaunchKernelGGL((k_conv_res<NCO, KSTEPS, kResDepth>), dim3((unsigned)(wgs < cus ? wgs : cus), out->cols / (NCO * 16)), dim3(kResThreads), lds, ts::stream(),
+    TS_LAUNCH_SHM("k_conv_res", (k_conv_res<NCO, KSTEPS, kResDepth>), dim3((unsigned)(wgs < cus ? wgs : cus), out->cols / (NCO * 16)), dim3(kResThreads), lds,
                        x, reinterpret_cast<const u32x4 *>(wf), kmap->d_nbr, kmap->stride, kmap->d_perm, kmap->n_out,
                        static_cast<_Float16 *>(out->data), kmap->d_sched, kmap->K3, out->cols, static_cast<const _Float16 *>(ep.bias),
                        static_cast<const _Float16 *>(ep.residual), ep.relu, (int)((size_t)kmap->n_in * KSTEPS * 64), kmap->centre);
@@ -1345,8 +1344,7 @@ int gather_impl(const void *x, int64_t /*rows*/, int cin_pad, int dtype, const t
         const dim3 grid(blocks_for(threads, kThreads)), block(kThreads);
         const u32x4 *xs = static_cast<const u32x4 *>(x);
         u32x4 *fs = static_cast<u32x4 *>(F);
-        ts::ProfScope ps("k_gather_in");
-#define TS_GATHER_IN(V) hipLaunchKernelGGL(k_gather_in<V>, grid, block, 0, ts::stream(), xs, kmap->d_nbr, kmap->d_colbits, kmap->d_colbase, offs_of(kmap), kmap->n_blocks, fs, kmap->n_in)
+#define TS_GATHER_IN(V) TS_LAUNCH("k_gather_in", k_gather_in<V>, grid, block, xs, kmap->d_nbr, kmap->d_colbits, kmap->d_colbase, offs_of(kmap), kmap->n_blocks, fs, kmap->n_in)
         if (vec_per_row == 4) TS_GATHER_IN(4);
         else if (vec_per_row == 8) TS_GATHER_IN(8);
         else if (vec_per_row == 16) TS_GATHER_IN(16);

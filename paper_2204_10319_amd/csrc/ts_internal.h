@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -59,12 +60,22 @@ struct ProfScope {
     int rec_;
 };
 
-// Launch on the library stream inside a timing scope named after the kernel.
-#define TS_LAUNCH(name, kernel, grid, block, ...)                                   \
-    do {                                                                            \
-        ts::ProfScope ts_ps_(name);                                                 \
-        hipLaunchKernelGGL(kernel, grid, block, 0, ts::stream(), __VA_ARGS__);      \
+// The same for a single kernel launch, without the two marker packets that recorded events put into the
+// stream (each costs the stream a few microseconds between kernels): the launch itself carries the event
+// pair, which then holds the dispatch's own start and end time.  Both null: this launch is not timed.
+struct ProfPair {
+    hipEvent_t a = nullptr, b = nullptr;
+};
+ProfPair prof_pair(const char *name);
+
+// Launch on the library stream, timed under the kernel's name while per-kernel timing is on.
+#define TS_LAUNCH_SHM(name, kernel, grid, block, shm, ...)                                                   \
+    do {                                                                                                     \
+        const ts::ProfPair ts_pp_ = ts::prof_pair(name);                                                     \
+        if (ts_pp_.a) hipExtLaunchKernelGGL(kernel, grid, block, shm, ts::stream(), ts_pp_.a, ts_pp_.b, 0, __VA_ARGS__); \
+        else hipLaunchKernelGGL(kernel, grid, block, shm, ts::stream(), __VA_ARGS__);                        \
     } while (0)
+#define TS_LAUNCH(name, kernel, grid, block, ...) TS_LAUNCH_SHM(name, kernel, grid, block, 0, __VA_ARGS__)
 
 template <class T>
 inline int alloc_n(T **p, size_t n) {

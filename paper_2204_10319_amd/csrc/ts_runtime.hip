@@ -222,6 +222,18 @@ ProfScope::~ProfScope() {
     if (rec_ >= 0) (void)hipEventRecord(g_prof_recs[rec_].b, g_stream);
 }
 
+ProfPair prof_pair(const char *name) {
+    ProfPair pp;
+    if (!g_prof_on) return pp;
+    if (!g_prof_filter.empty() && strncmp(name, g_prof_filter.c_str(), g_prof_filter.size()) != 0) return pp;
+    ProfRec r{name, prof_event(), prof_event()};
+    if (!r.a || !r.b) return pp;
+    g_prof_recs.push_back(r);
+    pp.a = r.a;
+    pp.b = r.b;
+    return pp;
+}
+
 }  // namespace ts
 
 // Plain streaming copy, 16 bytes per thread per step (grid-stride).
@@ -258,10 +270,7 @@ int ts_mfma_loop(int iters, void *sink, double *flops) {
     if (!sink || !flops) return ts::fail(TS_ERR_INVALID_ARG, "NULL pointer");
     if (iters < 1 || iters > (1 << 20)) return ts::fail(TS_ERR_INVALID_ARG, "iters must be in [1, 2^20]");
     const int blocks = 256 * 4;   // four workgroups of four waves per CU: four waves per SIMD
-    {
-        ts::ProfScope ps("k_mfma_loop");
-        hipLaunchKernelGGL(k_mfma_loop, dim3(blocks), dim3(256), 0, ts::g_stream, iters, static_cast<float *>(sink));
-    }
+    TS_LAUNCH("k_mfma_loop", k_mfma_loop, dim3(blocks), dim3(256), iters, static_cast<float *>(sink));
     TS_HIP(hipGetLastError());
     *flops = (double)blocks * 4.0 * (double)iters * 8.0 * (2.0 * 16 * 16 * 32);
     return TS_OK;
@@ -275,11 +284,8 @@ int ts_copy_bytes(void *dst, const void *src, size_t bytes) {
     const size_t n_vec = bytes / 16;
     size_t blocks = (n_vec + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;   // 32 workgroups per CU, grid-stride beyond that
-    {
-        ts::ProfScope ps("k_copy_bytes");
-        hipLaunchKernelGGL(k_copy_bytes, dim3((unsigned)blocks), dim3(256), 0, ts::g_stream,
-                           static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n_vec);
-    }
+    TS_LAUNCH("k_copy_bytes", k_copy_bytes, dim3((unsigned)blocks), dim3(256), static_cast<const uint4 *>(src),
+              static_cast<uint4 *>(dst), n_vec);
     TS_HIP(hipGetLastError());
     return TS_OK;
 }
