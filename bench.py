@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--step-only", action="store_true")
     ap.add_argument("--network-run", action="store_true",
                     help="only 10 passes of the config-5 network (17 map builds + 45 layers each), for profiling")
+    ap.add_argument("--build-run", type=int, default=0, metavar="COPIES",
+                    help="only 4 waiting 3x3x3 stride-1 map builds of the config-3 scene tiled COPIES times over the batch index, then exit (for counter passes)")
     ap.add_argument("--strided-run", action="store_true",
                     help="20 builds each of the K=2,s=2 and K=3,s=2 (with boundary) maps of config 3, then exit (for the kernel-trace profile)")
     args = ap.parse_args()
@@ -163,6 +165,15 @@ def main():
             SparseNet.free_maps(maps)
         torch.cuda.synchronize()
         print(json.dumps({"network_run": True, "N": int(N), "passes": 10}))
+        return
+
+    if args.build_run:
+        # map builds of the batch-tiled scene (waiting form), for the counter passes of the large build
+        big = torch.from_numpy(tile_batches(coords_h, args.build_run)).cuda()
+        for _ in range(4):
+            ts.ts_build_kmap(big, K, 1).free()
+        torch.cuda.synchronize()
+        print(json.dumps({"build_run": True, "copies": args.build_run, "N": int(big.shape[0])}))
         return
 
     if args.strided_run:

@@ -80,6 +80,11 @@ __device__ __forceinline__ uint32_t home_sub(uint64_t key) {
     return ((uint32_t)key & ((1u << kBz) - 1)) | (((uint32_t)(key >> kFieldBits) & ((1u << kBy) - 1)) << kBz) |
            (((uint32_t)(key >> (2 * kFieldBits)) & ((1u << kBx) - 1)) << (kBz + kBy));
 }
+// (Placing the buckets of neighbouring boxes next to each other - hashing only a region of 4, 8 or 16 boxes
+// per axis and using a box's position in its region as the low part of the bucket number - was measured as
+// well, for the sake of the large scenes whose table no longer fits the caches: occupied boxes then crowd
+// into few stretches of the table, probe chains grow, and both insertion and search take 1.3 to 6 times as
+// long at every size from 20 k to 15 M points.  Scattering the boxes is worth more than keeping them together.)
 __device__ __forceinline__ uint32_t home_slot(uint64_t key, int shift) {
     const uint64_t cell = key & ~kSubBits;
     return ((uint32_t)((cell * 0x9E3779B97F4A7C15ull) >> shift) << kBucketLog2) + home_sub(key);   // multiplicative (Fibonacci) hashing
