@@ -214,6 +214,17 @@ def test_config2_box_surfaces_fp16():
     print("config 2 rel L2:", errs)
 
 
+@pytest.mark.timeout(600)
+def test_config2b_box_surfaces_40_boxes_fp16():
+    """The literal recipe of config 2 (40 boxes): ~470k box-surface voxels, C 64->64 fp16 - the map bit for bit,
+    the fused layer row by row and element by element, on more tiles than any other single-layer case."""
+    coords = box_surface_coords(1, n_boxes=40)
+    assert 400000 <= coords.shape[0] <= 550000
+    _check_map(coords, 3, 1)
+    errs = _layer_case(coords, 64, 64, 3, 1, False, torch.float16, seed=210, dataflows=(ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT))
+    print("config 2b rel L2:", errs)
+
+
 @pytest.fixture(scope="module")
 def lidar_coords():
     return lidar_scan_coords(2, n_sweeps=5)
