@@ -410,6 +410,19 @@ int ts_concat_cols(const ts_tensor *a, const ts_tensor *b, ts_tensor *out);
 
 /* Stream (hipStream_t) all later calls enqueue on; NULL = the null stream. */
 int ts_set_stream(void *hip_stream);
+/*
+ * Lets the caller's allocator own the library's device memory (for PyTorch: its caching allocator, so that
+ * the memory shows in its statistics and is shared with the rest of the program).  From the call on every
+ * block the library needs - map storage, temporaries of a build, scratch areas when they grow - is asked
+ * for with alloc(bytes, ctx), which returns device memory aligned to 256 bytes or NULL (reported as
+ * TS_ERR_OOM), and given back with release(ptr, ctx) when the library is done with it; the library's own
+ * pool is bypassed.  The allocator must make a released block safe to hand out again in stream order, as a
+ * caching allocator keyed on the current stream does: the library releases a block as soon as the work
+ * that uses it has been enqueued on its stream.  alloc == release == NULL goes back to the library's pool.
+ * Blocks are returned to where they came from, so the setting may change while maps exist.  The
+ * coordinate grid of TS_SEARCH_GRID and the fixed array of ts_sparse_conv_static are not covered.
+ */
+int ts_set_allocator(void *(*alloc)(size_t bytes, void *ctx), void (*release)(void *ptr, void *ctx), void *ctx);
 /* Free the library's cached scratch and pooled device memory (synchronises the device). */
 int ts_release_cache(void);
 

@@ -29,7 +29,7 @@ EXPORTS = [
     "ts_kmap_kernel_volume", "ts_kmap_out_coords", "ts_kmap_out_box", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs",
     "ts_sparse_conv", "ts_sparse_conv_ex", "ts_sparse_conv_static", "ts_sparse_conv_act", "ts_weights_prepare", "ts_weights_free",
     "ts_sparse_conv_prepared", "ts_sparse_conv_prepared2", "ts_gather", "ts_gather_ex", "ts_grouped_matmul", "ts_scatter_reduce", "ts_adaptive_groups", "ts_grouped_matmul_adaptive",
-    "ts_set_stream", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_mfma_loop", "ts_bias_act", "ts_concat_cols",
+    "ts_set_stream", "ts_set_allocator", "ts_release_cache", "ts_last_error", "ts_version", "ts_profile_enable", "ts_profile_read", "ts_copy_bytes", "ts_mfma_loop", "ts_bias_act", "ts_concat_cols",
 ]
 
 
@@ -121,6 +121,8 @@ def load_library(path: str | None = None):
                                                ctypes.POINTER(ctypes.c_int64)]
     lib.ts_grouped_matmul_adaptive.restype = ci
     lib.ts_set_stream.argtypes = [vp]
+    lib.ts_set_allocator.argtypes = [vp, vp, vp]
+    lib.ts_set_allocator.restype = ci
     lib.ts_release_cache.argtypes = []
     for name in ("ts_kmap_out_coords", "ts_kmap_out_box", "ts_kmap_in_coords", "ts_kmap_sizes", "ts_kmap_pairs", "ts_sparse_conv",
                  "ts_sparse_conv_ex", "ts_gather", "ts_grouped_matmul", "ts_scatter_reduce", "ts_set_stream",
@@ -524,6 +526,33 @@ def ts_sparse_conv_prepared2(feats: torch.Tensor, feats2: torch.Tensor | None, w
                                                    ctypes.byref(r) if r is not None else None, int(bool(relu)),
                                                    ctypes.byref(o)))
     return out
+
+
+_ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
+_RELEASE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
+_allocator_refs = None      # keeps the callbacks alive while the library may call them
+
+
+def ts_set_allocator(alloc=None, release=None):
+    """``alloc(bytes) -> device address (int) or 0`` and ``release(address)``; both None: the library's own pool."""
+    global _allocator_refs
+    lib = load_library()
+    if alloc is None and release is None:
+        _check(lib.ts_set_allocator(None, None, None))
+        return
+    a = _ALLOC_FN(lambda n, ctx: alloc(n) or 0)
+    r = _RELEASE_FN(lambda p, ctx: release(p))
+    keep = (_allocator_refs, a, r)      # earlier callbacks stay alive: blocks they handed out may still come back
+    _check(lib.ts_set_allocator(ctypes.cast(a, ctypes.c_void_p), ctypes.cast(r, ctypes.c_void_p), None))
+    _allocator_refs = keep
+
+
+def use_torch_allocator(on: bool = True):
+    """Route the library's device memory through PyTorch's caching allocator (on the current stream)."""
+    if not on:
+        ts_set_allocator(None, None)
+        return
+    ts_set_allocator(lambda n: torch.cuda.caching_allocator_alloc(n), lambda p: torch.cuda.caching_allocator_delete(p))
 
 
 def ts_sparse_conv_ex(feats, weights, kmap, out=None, dataflow: int = TS_DATAFLOW_AUTO):

@@ -119,7 +119,7 @@ def build_host_checks(force: bool = False) -> str:
     if force or not os.path.exists(exe) or os.path.getmtime(exe) < max(os.path.getmtime(src), os.path.getmtime(lib)):
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
         cmd = [hipcc, "-O1", "-g", "-std=c++17", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
-               "-fno-sanitize-recover=undefined", "-x", "c++", src, "-x", "none", lib, "-Wl,-rpath," + OBJDIR, "-o", exe]
+               "-fno-sanitize-recover=undefined", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-x", "c++", src, "-x", "none", lib, "-Wl,-rpath," + OBJDIR, "-o", exe]
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
             print(res.stdout, res.stderr)

@@ -40,7 +40,23 @@ struct FreeBlock {
 };
 std::multimap<size_t, FreeBlock> g_free_blocks;       // size -> block
 std::unordered_map<void *, size_t> g_live_blocks;     // block -> size
-std::vector<void *> g_retired;                        // outgrown scratch areas, kept until ts_release_cache
+// The caller's allocator, if one is set (ts_set_allocator): every block then comes from it and goes back to it,
+// and the pool above is not used.  A block remembers where it came from, so the setting may change while
+// blocks are out.
+struct Foreign {
+    void (*release)(void *, void *);
+    void *ctx;
+};
+void *(*g_user_alloc)(size_t, void *) = nullptr;
+void (*g_user_release)(void *, void *) = nullptr;
+void *g_user_ctx = nullptr;
+std::unordered_map<void *, Foreign> g_foreign_blocks;  // block -> how to give it back
+struct Retired {
+    void *p;
+    bool foreign;
+    Foreign how;
+};
+std::vector<Retired> g_retired;                       // outgrown scratch areas, kept until ts_release_cache
 
 // Round a request so that similar sizes land in the same bin: 256 B granules below 1 MiB,
 // then 1/8-octave steps.
@@ -55,6 +71,8 @@ size_t bin_size(size_t bytes) {
 struct Scratch {
     void *p = nullptr;
     size_t bytes = 0;
+    bool foreign = false;
+    Foreign how = {nullptr, nullptr};
 };
 Scratch g_scratch[8];
 void *g_host = nullptr;
@@ -76,6 +94,16 @@ bool capturing() {
 // is being captured (a wait is not allowed there): then fresh memory is asked for instead.
 void *dev_alloc(size_t bytes) {
     size_t sz = bin_size(bytes);
+    if (g_user_alloc) {
+        void *p = g_user_alloc(sz, g_user_ctx);
+        if (!p) {
+            fail(TS_ERR_OOM, "the caller's allocator returned NULL for %zu bytes", sz);
+            return nullptr;
+        }
+        std::lock_guard<std::mutex> lk(g_pool_mu);
+        g_foreign_blocks[p] = Foreign{g_user_release, g_user_ctx};
+        return p;
+    }
     {
         std::unique_lock<std::mutex> lk(g_pool_mu);
         auto foreign = g_free_blocks.end();
@@ -116,6 +144,17 @@ void *dev_alloc(size_t bytes) {
 
 void dev_free(void *p) {
     if (!p) return;
+    {
+        std::unique_lock<std::mutex> lk(g_pool_mu);
+        auto f = g_foreign_blocks.find(p);
+        if (f != g_foreign_blocks.end()) {
+            const Foreign how = f->second;
+            g_foreign_blocks.erase(f);
+            lk.unlock();
+            if (how.release) how.release(p, how.ctx);
+            return;
+        }
+    }
     std::lock_guard<std::mutex> lk(g_pool_mu);
     auto it = g_live_blocks.find(p);
     if (it == g_live_blocks.end()) return;
@@ -137,23 +176,37 @@ void *scratch(int slot, size_t bytes) {
     }
     size_t want = bytes + bytes / 2;
     void *p = nullptr;
-    hipError_t e = hipMalloc(&p, want);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        want = bytes;
-        e = hipMalloc(&p, want);
-    }
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        fail(e == hipErrorOutOfMemory ? TS_ERR_OOM : TS_ERR_HIP, "hipMalloc(%zu) failed: %s", want, hipGetErrorString(e));
-        return nullptr;
+    bool foreign = false;
+    Foreign how = {nullptr, nullptr};
+    if (g_user_alloc) {
+        p = g_user_alloc(want, g_user_ctx);
+        if (!p) {
+            fail(TS_ERR_OOM, "the caller's allocator returned NULL for %zu bytes", want);
+            return nullptr;
+        }
+        foreign = true;
+        how = Foreign{g_user_release, g_user_ctx};
+    } else {
+        hipError_t e = hipMalloc(&p, want);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            want = bytes;
+            e = hipMalloc(&p, want);
+        }
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            fail(e == hipErrorOutOfMemory ? TS_ERR_OOM : TS_ERR_HIP, "hipMalloc(%zu) failed: %s", want, hipGetErrorString(e));
+            return nullptr;
+        }
     }
     if (s.p) {
         std::lock_guard<std::mutex> lk(g_pool_mu);
-        g_retired.push_back(s.p);
+        g_retired.push_back(Retired{s.p, s.foreign, s.how});
     }
     s.p = p;
     s.bytes = want;
+    s.foreign = foreign;
+    s.how = how;
     return s.p;
 }
 
@@ -335,16 +388,36 @@ int ts_set_stream(void *hip_stream) {
     return TS_OK;
 }
 
+int ts_set_allocator(void *(*alloc)(size_t, void *), void (*release)(void *, void *), void *ctx) {
+    if ((alloc == nullptr) != (release == nullptr)) return ts::fail(TS_ERR_INVALID_ARG, "alloc and release must both be given, or both be NULL");
+    std::lock_guard<std::mutex> lk(ts::g_pool_mu);
+    ts::g_user_alloc = alloc;
+    ts::g_user_release = release;
+    ts::g_user_ctx = ctx;
+    return TS_OK;
+}
+
 int ts_release_cache(void) {
     TS_HIP(hipDeviceSynchronize());
     ts::release_grid();
     std::lock_guard<std::mutex> lk(ts::g_pool_mu);
     for (auto &s : ts::g_scratch) {
-        if (s.p) (void)hipFree(s.p);
-        s.p = nullptr;
-        s.bytes = 0;
+        if (s.p) {
+            if (s.foreign) {
+                if (s.how.release) s.how.release(s.p, s.how.ctx);
+            } else {
+                (void)hipFree(s.p);
+            }
+        }
+        s = ts::Scratch();
     }
-    for (void *p : ts::g_retired) (void)hipFree(p);
+    for (auto &r : ts::g_retired) {
+        if (r.foreign) {
+            if (r.how.release) r.how.release(r.p, r.how.ctx);
+        } else {
+            (void)hipFree(r.p);
+        }
+    }
     ts::g_retired.clear();
     for (auto &kv : ts::g_free_blocks) (void)hipFree(kv.second.p);
     ts::g_free_blocks.clear();

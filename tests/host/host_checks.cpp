@@ -5,7 +5,10 @@
 // device it must fail with an error code, never crash: this program also runs on machines without one.
 #include <cstdint>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
+
+#include <hip/hip_runtime_api.h>
 
 #include "../../include/ts.h"
 #include "../../include/ts_bench.h"
@@ -127,6 +130,44 @@ int main() {
             CHECK(ts_gather_ex(&x0, m, &y0, 9) == TS_ERR_INVALID_ARG);
             ts_free(m);
         }
+    }
+
+    // ---- the caller's allocator: every block handed out comes back, whatever happens to the call
+    {
+        static int handed_out = 0, returned = 0;
+        auto alloc = [](size_t bytes, void *ctx) -> void * {
+            ++*static_cast<int *>(ctx);
+            return std::malloc(bytes ? bytes : 1);      // host memory: without a device nothing ever touches it
+        };
+        auto release = [](void *p, void *) {
+            ++returned;
+            std::free(p);
+        };
+        CHECK(ts_set_allocator(alloc, nullptr, nullptr) == TS_ERR_INVALID_ARG);
+        CHECK(ts_set_allocator(nullptr, release, nullptr) == TS_ERR_INVALID_ARG);
+        CHECK(ts_set_allocator(alloc, release, &handed_out) == TS_OK);
+        alignas(16) static int32_t coords[4 * 64];
+        for (int i = 0; i < 64; ++i) {
+            coords[4 * i] = 0;
+            coords[4 * i + 1] = i;
+            coords[4 * i + 2] = 2 * i;
+            coords[4 * i + 3] = 3;
+        }
+        ts_kmap *m = nullptr;
+        // with a device this pointer would have to be device memory; here the build can only fail (no device)
+        // or, should a device be present after all, is not attempted
+        int dev_count = 0;
+        const bool no_device = hipGetDeviceCount(&dev_count) != hipSuccess || dev_count == 0;
+        if (no_device) {
+            const int rc = ts_build_kmap(coords, 64, 3, 1, 0, &m);
+            CHECK(rc != TS_OK && m == nullptr);
+            const int rc2 = ts_build_kmap(coords, 64, 2, 2, 0, &m);
+            CHECK(rc2 != TS_OK && m == nullptr);
+            CHECK(handed_out > 0);
+        }
+        CHECK(ts_set_allocator(nullptr, nullptr, nullptr) == TS_OK);
+        (void)ts_release_cache();
+        CHECK(handed_out == returned);
     }
 
     // ---- measurement helpers

@@ -1029,3 +1029,36 @@ def test_two_part_input_errors():
     with pytest.raises(ts.TsError) as e:
         ts.ts_sparse_conv_prepared2(a, torch.zeros((300, 64), dtype=torch.float16, device="cuda"), pw, kmap)
     assert e.value.code == ts.TS_ERR_SHAPE          # 32 + 64 channels against weights prepared for 64
+
+
+def test_callers_allocator_owns_the_librarys_memory():
+    """ts_set_allocator: with PyTorch's caching allocator behind it the library's maps, temporaries and scratch
+    show up in torch's statistics, results are the ones the library's own pool gives, and everything goes back
+    when the maps are freed; maps made under one setting are released correctly under the other."""
+    coords = _rand_coords(6000, 20000, -30, 30, batches=2)
+    x_h, w_h = features(6001, 20000, 64, np.float16), conv_weights(6002, 27, 64, 96, np.float16)
+    x, w, cd = to_dev(x_h), to_dev(w_h), to_dev(coords)
+    own = ts.ts_build_kmap(cd, 3, 1)
+    want = ts.ts_sparse_conv(x, w, own, dataflow=ts.TS_DATAFLOW_EXPLICIT)
+    torch.cuda.synchronize()
+    before = torch.cuda.memory_allocated()
+    ts.use_torch_allocator(True)
+    try:
+        theirs = ts.ts_build_kmap(cd, 3, 1)
+        down = ts.ts_build_kmap(cd, 2, 2, wait=False)
+        assert torch.cuda.memory_allocated() > before + 20000 * 128      # at least the neighbour table
+        got = ts.ts_sparse_conv(x, w, theirs, dataflow=ts.TS_DATAFLOW_EXPLICIT)
+        assert torch.equal(got, want)
+        assert np.array_equal(gpu_triples(theirs), oracle_map(coords, 3, 1)[2])
+        assert np.array_equal(gpu_triples(down), oracle_map(coords, 2, 2)[2])
+        own.free()                      # a block of the library's pool, released while the caller's allocator is set
+    finally:
+        ts.use_torch_allocator(False)
+    theirs.free()                       # and the other way round
+    down.free()
+    del got
+    torch.cuda.synchronize()
+    ts.ts_release_cache()
+    # what remains allocated in torch: this test's own tensors only (scratch areas taken from torch went back with the cache)
+    assert torch.cuda.memory_allocated() <= before + want.numel() * 2 + 4096
+    check_features(ts.ts_sparse_conv(x, w, ts.ts_build_kmap(cd, 3, 1)), oracle_conv(coords, x_h, w_h, 3, 1), torch.float16, "after the switch back")
