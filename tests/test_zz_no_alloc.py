@@ -74,3 +74,41 @@ def test_limits_are_reported_not_exceeded():
     out = torch.zeros((0, 32), dtype=torch.float16, device="cuda")
     ts.ts_sparse_conv_static(torch.zeros((0, 32), dtype=torch.float16, device="cuda"),
                              torch.zeros((27, 32, 32), dtype=torch.float16, device="cuda"), empty, out)
+
+
+def test_under_graph_capture():
+    """What the entry point is for: recorded into a HIP graph (nothing may allocate there) and replayed, with new
+    features copied in between the replays and other library work in between; every replay equals the eager result."""
+    coords = _coords(9, 4000, 22, batches=2)
+    kmap = ts.ts_build_kmap(to_dev(coords), 3, 1)
+    w = to_dev(conv_weights(91, 27, 64, 64, np.float16))
+    xs = [to_dev(features(92 + i, 4000, 64, np.float16)) for i in range(3)]
+    want = [ts.ts_sparse_conv(x, w, kmap, dataflow=ts.TS_DATAFLOW_FUSED).clone() for x in xs]
+    static_in = xs[0].clone()
+    static_out = torch.zeros((4000, 64), dtype=torch.float16, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ts.ts_sparse_conv_static(static_in, w, kmap, static_out)     # the first call on the device looks the array's address up
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    free_before = torch.cuda.mem_get_info()[0]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ts.ts_sparse_conv_static(static_in, w, kmap, static_out)
+    for rep in range(2):
+        for x, y in zip(xs, want):
+            static_in.copy_(x)
+            static_out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(static_out, y)
+            other = ts.ts_build_kmap(to_dev(coords[:1000]), 3, 1)      # eager library work between the replays
+            ts.ts_sparse_conv_static(to_dev(features(99, 1000, 32, np.float16)), to_dev(conv_weights(98, 27, 32, 32, np.float16)), other,
+                                     torch.zeros((1000, 32), dtype=torch.float16, device="cuda"))
+            torch.cuda.synchronize()
+            other.free()
+            # the eager call above has overwritten the shared array: the graph's own repacking kernel restores it on replay
+    del graph
+    assert torch.cuda.mem_get_info()[0] >= free_before - (64 << 20)    # nothing of note was allocated by capture or replays
+    kmap.free()
