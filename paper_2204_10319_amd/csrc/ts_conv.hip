@@ -515,35 +515,53 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(N
         for (int s0 = 0; s0 < nstage; s0 += DEPTH) static_for<DEPTH>([&](auto dc) __attribute__((always_inline)) { run(s0 + decltype(dc)::value, dc); });
     }
 
-    // lane l holds, per block, output channels 4 * (l / 16) + 0..3 of rows r0 (c2 = 0) and r1 (c2 = 1)
+    // lane l holds, per block, output channels 4 * (l / 16) + 0..3 of rows r0 (c2 = 0) and r1 (c2 = 1).
+    // What the tail adds is asked for in one go per kind (all blocks' bias words, then all blocks' residual
+    // words of a row) and used afterwards: a load placed next to its use costs a round trip per block.
+    half4 bv[NCO];
+#pragma unroll
+    for (int cb = 0; cb < NCO; ++cb) bv[cb] = half4{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
+    if (bias) {
+        // (the pointer is made opaque per tile: loads the compiler can prove the same for every tile move to the
+        // top of the kernel and hold registers through the stage loop, which has none to spare)
+        const _Float16 *bp = bias;
+        asm volatile("" : "+s"(bp));
+#pragma unroll
+        for (int cb = 0; cb < NCO; ++cb) bv[cb] = *reinterpret_cast<const half4 *>(bp + cb0 * 16 + cb * 16 + g * 4);
+    }
 #pragma unroll
     for (int c2 = 0; c2 < 2; ++c2) {
         const int64_t pos = tile * kTileRows + (c2 ? r1 : r0);
         const int64_t row = perm ? perm[pos] : (pos < n_out ? pos : -1);
         if (row < 0) continue;
         const int64_t at = row * cout + cb0 * 16 + g * 4;
+        // the layer's own result, rounded once to fp16 (the accumulators' registers are free from here on) ...
+        half4 v[NCO];
 #pragma unroll
-        for (int cb = 0; cb < NCO; ++cb) {
-            // the layer's own result, rounded once to fp16 ...
-            half4 v = {(_Float16)acc[cb][c2][0], (_Float16)acc[cb][c2][1], (_Float16)acc[cb][c2][2], (_Float16)acc[cb][c2][3]};
-            // ... then, if asked for, what ts_bias_act would do with it: fp32 sum, ReLU, one rounding
-            if (bias || residual || relu) {
-                float f[4] = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
-                if (bias) {
-                    const half4 b = *reinterpret_cast<const half4 *>(bias + cb0 * 16 + cb * 16 + g * 4);
+        for (int cb = 0; cb < NCO; ++cb)
+            v[cb] = half4{(_Float16)acc[cb][c2][0], (_Float16)acc[cb][c2][1], (_Float16)acc[cb][c2][2], (_Float16)acc[cb][c2][3]};
+        // ... then, if asked for, what ts_bias_act would do with it: fp32 sum, ReLU, one rounding
+        if (bias || residual || relu) {
+            half4 rv[NCO];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) f[e] += (float)b[e];
-                }
-                if (residual) {
-                    const half4 r = *reinterpret_cast<const half4 *>(residual + at + cb * 16);
+            for (int cb = 0; cb < NCO; ++cb) rv[cb] = half4{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
+            if (residual) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) f[e] += (float)r[e];
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (_Float16)(relu && f[e] < 0.f ? 0.f : f[e]);
+                for (int cb = 0; cb < NCO; ++cb) rv[cb] = *reinterpret_cast<const half4 *>(residual + at + cb * 16);
             }
-            *reinterpret_cast<half4 *>(out + at + cb * 16) = v;
+#pragma unroll
+            for (int cb = 0; cb < NCO; ++cb) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float f = (float)v[cb][e];
+                    if (bias) f += (float)bv[cb][e];
+                    if (residual) f += (float)rv[cb][e];
+                    v[cb][e] = (_Float16)(relu && f < 0.f ? 0.f : f);
+                }
+            }
         }
+#pragma unroll
+        for (int cb = 0; cb < NCO; ++cb) *reinterpret_cast<half4 *>(out + at + cb * 16) = v[cb];
     }
     if (threadIdx.x == 0) s_tile = ticket;
     __syncthreads();   // the tile's LDS is free; s_tile is set
