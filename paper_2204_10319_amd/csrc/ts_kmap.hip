@@ -279,20 +279,33 @@ __global__ void k_insert(const uint64_t *keys, int64_t n, TableT t, int *status)
     table_insert(t, key, (int32_t)i, status);
 }
 
-// Stride-1 front end in one pass: pack and insert (key -> i).
+// Stride-1 front end in one pass: pack and insert (key -> i).  With `rows` (the neighbour table of a 3x3x3
+// map, 8 16-byte vectors per point) the workgroup also sets its points' rows to "no neighbour": the symmetric
+// search writes hits only, and these stores ride along with a kernel that waits for its atomics anyway
+// instead of tripling what the clearing launch before it has to write.
 template <class TableT>
-__global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, TableT t, int *status, Box box) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    int4 c = coords[i];
-    if (!coord_ok(c) || !in_box(c, box)) {
-        raise_flag(status, ST_RANGE);
-        keys[i] = kEmptyKey;
-        return;
+__global__ void k_pack_insert(const int4 *coords, int64_t n, uint64_t *keys, TableT t, int *status, Box box, int4 *rows) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        const int4 c = coords[i];
+        if (!coord_ok(c) || !in_box(c, box)) {
+            raise_flag(status, ST_RANGE);
+            keys[i] = kEmptyKey;
+        } else {
+            const uint64_t key = pack_key(c.x, c.y, c.z, c.w);
+            keys[i] = key;
+            table_insert(t, key, (int32_t)i, status);
+        }
     }
-    uint64_t key = pack_key(c.x, c.y, c.z, c.w);
-    keys[i] = key;
-    table_insert(t, key, (int32_t)i, status);
+    // (after the insertion: stores issued before it would have to complete before the atomic's answer is seen)
+    if (rows) {
+        const int64_t first = (int64_t)blockIdx.x * blockDim.x * 8, end = n * 8;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int64_t at = first + (int64_t)k * blockDim.x + threadIdx.x;
+            if (at < end) rows[at] = make_int4(-1, -1, -1, -1);
+        }
+    }
 }
 
 // Alg. 3 stages 1-4 in registers: candidate u = p - delta, modular check, boundary check, key of u/s.
@@ -1416,7 +1429,7 @@ int sort_rows(ts_kmap *m) {
 }
 
 // Allocations of the map that depend on n_out only.
-int alloc_outputs(ts_kmap *m, FillArgs *fill) {
+int alloc_outputs(ts_kmap *m, FillArgs *fill, bool rows_cleared_later = false) {
     const int K3 = m->K3;
     m->stride = nbr_stride(K3);
     m->n_blocks = (m->n_out + 63) / 64;
@@ -1429,7 +1442,7 @@ int alloc_outputs(ts_kmap *m, FillArgs *fill) {
         TS_TRY(alloc_n(&m->d_sched, (size_t)kMaxSchedSlices * kSchedWords));
         fill->add(m->d_sched, (size_t)kMaxSchedSlices * kSchedWords * sizeof(int32_t), 0u);
     }
-    if (m->s == 1 && K3 == 27) fill->add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);   // the symmetric probe writes hits only
+    if (m->s == 1 && K3 == 27 && !rows_cleared_later) fill->add(m->d_nbr, (size_t)m->n_out * m->stride * sizeof(int32_t), 0xFFFFFFFFu);   // the symmetric probe writes hits only
     return TS_OK;
 }
 
@@ -1474,13 +1487,15 @@ int build(const int32_t *coords, int64_t N, int K, int s, int transposed, ts_kma
                 early_slot = slot;
             }
         }
-        TS_TRY(alloc_outputs(m, &fill));
+        const bool rows_here = K == 3;   // the insertion kernel clears the neighbour rows of a 3x3x3 map
+        TS_TRY(alloc_outputs(m, &fill, rows_here));
         TS_TRY(make_searched(tmp, opt, N, opt.box.lo, opt.box.hi, &table, &fill));
         TS_TRY(launch_fill(fill));
+        int4 *rows = rows_here ? reinterpret_cast<int4 *>(m->d_nbr) : nullptr;
         if (table.grid)
-            TS_LAUNCH("k_pack_insert_grid", k_pack_insert<Grid>, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, table.g, d_status, opt.box);
+            TS_LAUNCH("k_pack_insert_grid", k_pack_insert<Grid>, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, table.g, d_status, opt.box, rows);
         else
-            TS_LAUNCH("k_pack_insert", k_pack_insert<Table>, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, table.t, d_status, opt.box);
+            TS_LAUNCH("k_pack_insert", k_pack_insert<Table>, per_point, block, reinterpret_cast<const int4 *>(coords), N, given, table.t, d_status, opt.box, rows);
     } else {
         // coarse set: the distinct admissible candidates in ascending order (Alg. 3)
         const int A = (K + s - 1) / s, slots = A * A * A;
