@@ -116,7 +116,7 @@ __device__ __forceinline__ void table_insert(const Table &t, uint64_t key, int32
             raise_flag(status, ST_DUP);
             return;
         }
-        slot = next_slot(slot, t.mask);   // the table is at most half full, so an empty slot exists
+        slot = next_slot(slot, t.mask);   // the table is at most a quarter full, so an empty slot exists
     }
 }
 
@@ -1051,8 +1051,8 @@ int launch_fill(const FillArgs &f) {
 // Allocates the table; its clearing is added to `fill`.
 int make_table(Temps &tmp, int64_t entries, Table *t, FillArgs *fill) {
     uint64_t cap = 1024;
-    while (cap < (uint64_t)(2 * entries)) cap <<= 1;
-    if (cap > (1ull << 27)) return fail(TS_ERR_UNSUPPORTED, "too many points for the hash table");
+    while (cap < (uint64_t)(4 * entries)) cap <<= 1;
+    if (cap > (1ull << 28)) return fail(TS_ERR_UNSUPPORTED, "too many points for the hash table");
     TS_TRY(tmp.get(&t->keys, cap));
     TS_TRY(tmp.get(&t->vals, cap));
     t->mask = (uint32_t)(cap - 1);
