@@ -53,7 +53,10 @@ def kmap_bytes(n, m, k3, table_slots):
     """Algorithmic bytes of the stride-1 map build that is timed (ts_build_kmap, waiting form): coordinates
     in, table init + fill, one 8-byte probe per (point, half of the offsets), and what it writes: one
     4-byte neighbour entry per pair, a bitmask word per row, and the rank bitmaps (12 bytes per offset and
-    64-row block).  The offset-major pair lists are not part of it: they are derived on first use."""
+    64-row block).  The offset-major pair lists are not part of it: they are derived on first use.
+    table_slots is counted as the smallest power of two that keeps the table half empty (2 n or more): the
+    library allocates twice that because shorter probe chains pay for it, which is its choice, not work the
+    method asks for."""
     return 16 * n + 12 * table_slots + 12 * n + (k3 - 1) // 2 * n * 8 + 4 * m + 4 * n + 12 * k3 * ((n + 63) // 64)
 
 
