@@ -64,6 +64,19 @@ def test_kmap_extreme_coordinates():
         _check_map(coords, K, s, tr)
 
 
+@pytest.mark.parametrize("wait", [True, False])
+def test_kmap_rows_start_clean_in_reused_memory(wait):
+    """The neighbour rows of a 3x3x3 map are set to "no neighbour" by the build itself (the symmetric search
+    writes hits only): a dense scene leaves a table full of entries in the library's pool, and a sparse scene of
+    the same size built right after it, most likely into the same block, must show none of them.  Sizes on
+    both sides of a whole number of 256-point workgroups."""
+    for n in (255, 256, 257, 4096, 5000):
+        dense = _rand_coords(7000 + n, n, 0, max(2, int(np.ceil(n ** (1 / 3))) + 1))      # nearly every cell taken
+        _check_map(dense, 3, 1, wait=wait).free()
+        sparse = _rand_coords(7100 + n, n, -60, 60)                                       # hardly any neighbours
+        _check_map(sparse, 3, 1, wait=wait).free()
+
+
 def test_kmap_errors():
     dup = np.array([[0, 1, 2, 3], [0, 5, 5, 5], [0, 1, 2, 3]], dtype=np.int32)
     with pytest.raises(ts.TsError) as e:
