@@ -165,8 +165,9 @@ int ts_identity_kmap(int64_t n, ts_kmap **out_kmap);
  *                 then follows without a search either: every kept candidate of an input is an output,
  *                 whose row number is the rank of its cell among the marked ones.  Larger boxes take the
  *                 hash route.
- *                 TS_SEARCH_HASH: the open-addressing table; a strided build finds its output
- *                 coordinates by sorting the candidates.  TS_SEARCH_GRID: the collision-free
+ *                 TS_SEARCH_HASH: the open-addressing table (a temporary of the build: a power of two
+ *                 of 12-byte slots, four per searched point or more; at most 2^26 points); a strided
+ *                 build finds its output coordinates by sorting the candidates.  TS_SEARCH_GRID: the collision-free
  *                 grid of Sec. 4.4, one int32 cell per coordinate of the box the caller states
  *                 with grid_lo / grid_hi (inclusive bounds of x, y, z over the rows of `coords`) and
  *                 grid_batches (batch indices are below it): one memory access per insertion and per
