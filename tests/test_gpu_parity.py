@@ -509,6 +509,32 @@ def test_transpose_of_a_map_with_boundary(K):
     assert 0 < hit.sum() < coords.shape[0]
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_kmap_random_arguments_all_routes(seed):
+    """Seeded random draws over what a build can be asked: size, extent and sign of the coordinates (dense
+    blobs to scattered points), batches, (K, s, transposed), a boundary, the search route, waiting or not.
+    Every map equals the oracle's, triple for triple."""
+    rng = np.random.Generator(np.random.PCG64(8800 + seed))
+    for case in range(10):
+        K, s, tr = MAP_CASES[int(rng.integers(len(MAP_CASES)))]
+        n = int(rng.choice([1, 2, 63, 64, 65, 129, 300, 1000, 2500]))
+        side = int(rng.integers(max(2, int(np.ceil(n ** (1 / 3))) + 1), 40))
+        lo = int(rng.integers(-30, 10))
+        batches = int(rng.integers(1, 5))
+        while batches * side ** 3 < n:
+            side += 1
+        coords = _rand_coords(int(rng.integers(1 << 30)), n, lo, lo + side, batches=batches)
+        boundary = None
+        if s == 2 and rng.random() < 0.4:
+            boundary = tuple(int(v) for v in rng.integers(1, max(2, (lo + side) // 2 + 2), size=3))
+        route = ["auto", "hash", "grid"][int(rng.integers(3))]
+        wait = bool(rng.integers(2))
+        print(f"seed {seed} case {case}: n={n} side={side} lo={lo} batches={batches} K={K} s={s} tr={tr} "
+              f"boundary={boundary} route={route} wait={wait}", flush=True)
+        _check_map(coords, K, s, tr, grid=grid_of(coords) if route == "grid" else None, boundary=boundary, wait=wait,
+                   search=ts.TS_SEARCH_HASH if route == "hash" else ts.TS_SEARCH_AUTO).free()
+
+
 def test_kmap_boundary_that_cuts_everything():
     coords = _rand_coords(3100, 500, 40, 60)
     for K, s, tr in [(2, 2, False), (3, 2, False), (2, 2, True), (3, 2, True)]:
