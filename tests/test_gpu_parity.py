@@ -907,6 +907,53 @@ def test_fused_epilogue_equals_two_calls(dtype, K, s, transposed, c_in, c_out):
     check_features(ts.ts_sparse_conv_act(x, w, kmap, bias, res, True), y, dtype, "fused epilogue vs oracle", pre_mag=mag)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_layer_random_arguments_against_the_oracle(seed):
+    """Seeded random draws over what a layer can be asked: map kind, point count, channel widths (multiples of
+    32 up to 192, and the narrow 4 / 16-channel inputs the padding path takes), dtype, dataflow, prepared weights
+    or not, and any subset of bias / residual / ReLU.  Every result is held to the oracle's with the layer bounds."""
+    rng = np.random.Generator(np.random.PCG64(9900 + seed))
+    for case in range(6):
+        K, s, tr = [(3, 1, False), (2, 2, False), (2, 2, True), (1, 1, False), (3, 2, False), (3, 2, True)][int(rng.integers(6))]
+        n = int(rng.choice([1, 100, 129, 1000, 4097, 9000]))
+        side = max(int(np.ceil(n ** (1 / 3))) + 1, int(rng.integers(4, 36)))
+        coords = _rand_coords(int(rng.integers(1 << 30)), n, -side // 2, -side // 2 + side, batches=int(rng.integers(1, 3)))
+        dtype = torch.float16 if rng.random() < 0.75 else torch.float32
+        nd = np_dtype(dtype)
+        c_in = int(rng.choice([4, 16, 32, 64, 96, 128, 160, 192]))
+        c_out = int(rng.choice([32, 64, 96, 128, 192]))
+        df = [ts.TS_DATAFLOW_AUTO, ts.TS_DATAFLOW_FUSED, ts.TS_DATAFLOW_EXPLICIT, ts.TS_DATAFLOW_FETCH][int(rng.integers(4))]
+        use_b, use_r, relu, prepared = (bool(rng.integers(2)) for _ in range(4))
+        kmap = ts.ts_build_kmap(to_dev(coords), K, s, tr)
+        x_h = features(int(rng.integers(1 << 30)), kmap.num_in, c_in, nd)
+        w_h = conv_weights(int(rng.integers(1 << 30)), K ** 3, c_in, c_out, nd)
+        b_h = features(int(rng.integers(1 << 30)), 1, c_out, nd).reshape(-1)
+        r_h = features(int(rng.integers(1 << 30)), kmap.num_out, c_out, nd)
+        print(f"seed {seed} case {case}: n={n} side={side} K={K} s={s} tr={tr} {c_in}->{c_out} {dtype} dataflow={df} "
+              f"bias={use_b} residual={use_r} relu={relu} prepared={prepared}", flush=True)
+        x, w = to_dev(x_h), to_dev(w_h)
+        bias = to_dev(b_h) if use_b else None
+        res = to_dev(r_h) if use_r else None
+        if prepared:        # the library's own choice of dataflow, weights repacked once
+            got = ts.ts_sparse_conv_prepared(x, ts.ts_weights_prepare(w), kmap, bias, res, relu)
+        elif use_b or use_r or relu:
+            got = ts.ts_sparse_conv_act(x, w, kmap, bias, res, relu)
+        else:
+            got = ts.ts_sparse_conv(x, w, kmap, dataflow=df)
+        y = oracle.round_to(oracle_conv(coords, x_h, w_h, K, s, tr), nd).astype(np.float64)
+        mag = np.abs(y)
+        if use_b:
+            y = y + b_h.astype(np.float64)[None, :]
+            mag = mag + np.abs(b_h.astype(np.float64))[None, :]
+        if use_r:
+            y = y + r_h.astype(np.float64)
+            mag = mag + np.abs(r_h.astype(np.float64))
+        if relu:
+            y = np.maximum(y, 0.0)
+        check_features(got, y, dtype, f"seed {seed} case {case}", pre_mag=mag if (use_b or use_r or relu) else None)
+        kmap.free()
+
+
 @pytest.mark.parametrize("K", [1, 2, 3])
 @pytest.mark.parametrize("n", [1, 700, 20000])
 def test_transposed_map_derived_from_forward_map(K, n):
